@@ -1,0 +1,240 @@
+"""ctypes front end of the CPU oracle (``mcr_oracle.cpp``).
+
+TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the benchmark's
+CPU-baseline leg call this; the GPU library never does, and nothing here
+imports the GPU package.  All arrays are numpy, host resident; bf16 travels
+as ``uint16`` bit patterns.
+
+Argument marshalling only -- every loop of the operations lives in the C++
+file, which cites the passages of the paper it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+F32 = 0
+BF16 = 1
+SUM = 0
+AVG = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mcr_oracle.cpp")
+_LIB = os.path.join(_HERE, "libmcr_oracle.so")
+
+CXXFLAGS = ["-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+            "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (about a second); returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["g++", *CXXFLAGS, "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_f32_to_bf16.restype = ctypes.c_uint16
+        _lib.orc_f32_to_bf16.argtypes = [ctypes.c_float]
+        _lib.orc_bf16_to_f32.restype = ctypes.c_float
+        _lib.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
+    return _lib
+
+
+def np_dtype(dtype: int):
+    return np.float32 if dtype == F32 else np.uint16
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError(f"oracle {what} rejected its arguments (rc={rc})")
+
+
+def _ptrs(arrs: Sequence[np.ndarray]):
+    for a in arrs:
+        assert a.flags["C_CONTIGUOUS"], "oracle arrays must be contiguous"
+    return (ctypes.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return ctypes.c_void_p(0)
+    assert a.flags["C_CONTIGUOUS"]
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+# ---- bf16 -------------------------------------------------------------------
+def f32_to_bf16(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().orc_f32_to_bf16_array(_p(x), _p(out), ctypes.c_size_t(x.size))
+    return out
+
+
+def bf16_to_f32(h: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape, dtype=np.float32)
+    lib().orc_bf16_to_f32_array(_p(h), _p(out), ctypes.c_size_t(h.size))
+    return out
+
+
+# ---- collectives ------------------------------------------------------------
+def allreduce(bufs: List[np.ndarray], dtype: int, op: int = SUM) -> None:
+    """In place on every array of ``bufs`` (one per rank)."""
+    n = bufs[0].size
+    assert all(b.size == n and b.dtype == np_dtype(dtype) for b in bufs)
+    _check(lib().orc_allreduce(_ptrs(bufs), ctypes.c_size_t(n), dtype, op, len(bufs)), "allreduce")
+
+
+def allreduce_ref64(bufs: List[np.ndarray], dtype: int, op: int = SUM):
+    """(binary64 sum, binary64 sum of magnitudes) per element."""
+    n = bufs[0].size
+    out = np.empty(n, dtype=np.float64)
+    mag = np.empty(n, dtype=np.float64)
+    _check(lib().orc_allreduce_ref64(_ptrs(bufs), ctypes.c_size_t(n), dtype, op, len(bufs),
+                                     _p(out), _p(mag)), "allreduce_ref64")
+    return out, mag
+
+
+def reduce_scatter(ins: List[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
+    P = len(ins)
+    n = ins[0].size
+    if n % P:
+        raise ValueError("count not divisible by P")
+    outs = [np.zeros(n // P, dtype=np_dtype(dtype)) for _ in range(P)]
+    _check(lib().orc_reduce_scatter(_ptrs(outs), _ptrs(ins), ctypes.c_size_t(n), dtype, op, P),
+           "reduce_scatter")
+    return outs
+
+
+def allgather(ins: List[np.ndarray], dtype: int) -> List[np.ndarray]:
+    P = len(ins)
+    m = ins[0].size
+    outs = [np.zeros(P * m, dtype=np_dtype(dtype)) for _ in range(P)]
+    _check(lib().orc_allgather(_ptrs(outs), _ptrs(ins), ctypes.c_size_t(m), dtype, P), "allgather")
+    return outs
+
+
+def alltoall(ins: List[np.ndarray], dtype: int) -> List[np.ndarray]:
+    P = len(ins)
+    n = ins[0].size
+    if n % P:
+        raise ValueError("count not divisible by P")
+    outs = [np.zeros(n, dtype=np_dtype(dtype)) for _ in range(P)]
+    _check(lib().orc_alltoall(_ptrs(outs), _ptrs(ins), ctypes.c_size_t(n), dtype, P), "alltoall")
+    return outs
+
+
+def alltoallv(ins: List[np.ndarray], S: np.ndarray, row_elems: int, dtype: int,
+              outs: Optional[List[np.ndarray]] = None) -> List[np.ndarray]:
+    """``S[p, r]`` rows go from rank p to rank r.  ``outs`` (if given) keeps its
+    rows beyond the received ones; otherwise exact-size outputs are made."""
+    P = len(ins)
+    S = np.ascontiguousarray(S, dtype=np.int64)
+    assert S.shape == (P, P)
+    if outs is None:
+        outs = [np.zeros(int(S[:, r].sum()) * row_elems, dtype=np_dtype(dtype)) for r in range(P)]
+    for p in range(P):
+        assert ins[p].size >= int(S[p].sum()) * row_elems
+    for r in range(P):
+        assert outs[r].size >= int(S[:, r].sum()) * row_elems
+    _check(lib().orc_alltoallv(_ptrs(outs), _ptrs(ins), _p(S), ctypes.c_size_t(row_elems), dtype, P),
+           "alltoallv")
+    return outs
+
+
+# ---- MoE --------------------------------------------------------------------
+def moe_route(ids: np.ndarray, E: int, P: int, C: int):
+    """One rank: returns (slot[T] int32, counts[E] int32, srow[P] int64)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T = ids.size
+    slot = np.empty(T, dtype=np.int32)
+    counts = np.empty(E, dtype=np.int32)
+    srow = np.empty(P, dtype=np.int64)
+    _check(lib().orc_moe_route(_p(ids), T, E, P, C, _p(slot), _p(counts), _p(srow)), "moe_route")
+    return slot, counts, srow
+
+
+def pack(tok: np.ndarray, slot: np.ndarray, row_elems: int, dtype: int, out: np.ndarray) -> np.ndarray:
+    slot = np.ascontiguousarray(slot, dtype=np.int32)
+    _check(lib().orc_pack(_p(out), _p(tok), _p(slot), ctypes.c_int64(slot.size),
+                          ctypes.c_size_t(row_elems), dtype), "pack")
+    return out
+
+
+def unpack(packed: np.ndarray, slot: np.ndarray, gate: Optional[np.ndarray], row_elems: int,
+           dtype: int) -> np.ndarray:
+    slot = np.ascontiguousarray(slot, dtype=np.int32)
+    if gate is not None:
+        gate = np.ascontiguousarray(gate, dtype=np.float32)
+        assert gate.size == slot.size
+    out = np.empty(slot.size * row_elems, dtype=np_dtype(dtype))
+    _check(lib().orc_unpack(_p(out), _p(packed), _p(slot), _p(gate), ctypes.c_int64(slot.size),
+                            ctypes.c_size_t(row_elems), dtype), "unpack")
+    return out
+
+
+# ---- DLRM -------------------------------------------------------------------
+def dlrm_forward(src: List[np.ndarray], n_tables: int, batch: int, dim: int, dtype: int) -> List[np.ndarray]:
+    P = len(src)
+    outs = [np.zeros((batch // P) * n_tables * dim, dtype=np_dtype(dtype)) for _ in range(P)]
+    _check(lib().orc_dlrm_forward(_ptrs(outs), _ptrs(src), n_tables, ctypes.c_int64(batch),
+                                  ctypes.c_size_t(dim), dtype, P), "dlrm_forward")
+    return outs
+
+
+def dlrm_backward(grad_out: List[np.ndarray], n_tables: int, batch: int, dim: int, dtype: int) -> List[np.ndarray]:
+    P = len(grad_out)
+    n_local = [len(range(p, n_tables, P)) for p in range(P)]
+    gsrc = [np.zeros(n_local[p] * batch * dim, dtype=np_dtype(dtype)) for p in range(P)]
+    _check(lib().orc_dlrm_backward(_ptrs(gsrc), _ptrs(grad_out), n_tables, ctypes.c_int64(batch),
+                                   ctypes.c_size_t(dim), dtype, P), "dlrm_backward")
+    return gsrc
+
+
+# ---- tensor fusion ----------------------------------------------------------
+def fuse_plan(numel: Sequence[int], B: int):
+    """Returns (tensor_bucket[int32], tensor_offset[uint64], bucket_numel[uint64])."""
+    numel = np.ascontiguousarray(numel, dtype=np.uint64)
+    n = numel.size
+    tb = np.zeros(max(n, 1), dtype=np.int32)
+    to = np.zeros(max(n, 1), dtype=np.uint64)
+    bn = np.zeros(max(n, 1), dtype=np.uint64)
+    nb = ctypes.c_int32(0)
+    _check(lib().orc_fuse_plan(_p(numel), n, ctypes.c_uint64(B), _p(tb), _p(to), ctypes.byref(nb), _p(bn)),
+           "fuse_plan")
+    return tb[:n].copy(), to[:n].copy(), bn[:nb.value].copy()
+
+
+def fuse(tensors: List[np.ndarray], offsets: Sequence[int], total: int, dtype: int) -> np.ndarray:
+    flat = np.zeros(total, dtype=np_dtype(dtype))
+    numel = np.array([t.size for t in tensors], dtype=np.uint64)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    _check(lib().orc_fuse(_p(flat), _ptrs(tensors), _p(numel), _p(off), len(tensors), dtype), "fuse")
+    return flat
+
+
+def unfuse(flat: np.ndarray, numel: Sequence[int], offsets: Sequence[int], dtype: int) -> List[np.ndarray]:
+    tensors = [np.zeros(int(n), dtype=np_dtype(dtype)) for n in numel]
+    nn = np.ascontiguousarray(numel, dtype=np.uint64)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    _check(lib().orc_unfuse(_ptrs(tensors), _p(flat), _p(nn), _p(off), len(tensors), dtype), "unfuse")
+    return tensors
+
+
+# ---- tuning table -----------------------------------------------------------
+def tune_lookup(sizes: Sequence[int], choice: Sequence[int], nbytes: int) -> int:
+    s = np.ascontiguousarray(sizes, dtype=np.uint64)
+    c = np.ascontiguousarray(choice, dtype=np.int32)
+    return int(lib().orc_tune_lookup(_p(s), _p(c), int(s.size), ctypes.c_uint64(nbytes)))
