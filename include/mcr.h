@@ -1,0 +1,259 @@
+/*
+ * mcr.h -- C ABI of the MI355X-native local data movement and reduction that
+ * sits inside the collectives of MCR-DL's API (paper Sec. IV-A, "High-level
+ * MCR-DL API" listing).
+ *
+ * Model.  The paper's calls are per rank (get_rank, one tensor per call) and
+ * hand the bytes to NCCL/MPI.  Here all P ranks are simulated in one GPU's
+ * memory: every collective takes a HOST array of P DEVICE pointers, one per
+ * rank, and performs the whole P-rank operation in one stream-ordered launch.
+ *
+ * Conventions that hold for every entry point unless stated otherwise:
+ *   - Return value: 0 (MCR_OK) or a negative mcr_status.  On any error nothing
+ *     has been launched and no output has been touched.  Nothing throws or
+ *     aborts.  mcr_strerror() names a code.
+ *   - Pointer arguments named *bufs / *in / *out / *slot / *gate / *flat are
+ *     HOST arrays holding DEVICE addresses; the arrays are read before the
+ *     call returns and may be reused at once.  The device memory they point to
+ *     is owned by the caller and must stay valid until the stream has passed
+ *     the launch.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
+ *     call enqueues and returns; ordering and completion are the stream's.
+ *     This is the paper's non-blocking model (Sec. IV-C: the operation is
+ *     posted to a stream and waited for through an event): the caller records
+ *     an event on `stream` as its work handle.
+ *   - No entry point allocates or frees device memory except mcr_init,
+ *     mcr_finalize, mcr_fuse_plan_create/bind/destroy.
+ *   - P is 1..MCR_MAX_RANKS.  Rank pointer tables travel as kernel arguments.
+ *   - `variant` selects the kernel: a non-negative id from mcr_get_variants,
+ *     or MCR_AUTO, which consults the tuning table (the paper's "auto"
+ *     backend, Sec. IV-A and IV-E) and falls back to a safe choice when the
+ *     shape or the pointer alignment rules the tabled variant out.  An
+ *     explicit variant that cannot handle the shape/alignment gives
+ *     MCR_EVARIANT.
+ *   - Except for mcr_allreduce (in place by definition) inputs and outputs
+ *     must not overlap; overlap is not detected.
+ *   - Element counts are in elements of `dtype`, never bytes.
+ */
+#ifndef MCR_H_
+#define MCR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mcr_ctx mcr_ctx;             /* library-owned: variant registry + tuning table */
+typedef struct mcr_fuse_plan mcr_fuse_plan; /* library-owned: bucket plan + device descriptors */
+
+typedef enum { MCR_F32 = 0, MCR_BF16 = 1 } mcr_dtype;
+
+/* ReduceOp of the API listing.  MCR_AVG is the sum multiplied (in binary32,
+ * before the one final rounding) by the binary32 value 1.0f/P. */
+typedef enum { MCR_SUM = 0, MCR_AVG = 1 } mcr_redop;
+
+typedef enum {
+  MCR_OP_ALLREDUCE = 0,
+  MCR_OP_REDUCE_SCATTER = 1,
+  MCR_OP_ALLGATHER = 2,
+  MCR_OP_ALLTOALL = 3,
+  MCR_OP_ALLTOALLV = 4,
+  MCR_OP_PACK = 5,
+  MCR_OP_UNPACK = 6,
+  MCR_OP_FUSE = 7,
+  MCR_OP_UNFUSE = 8,
+  MCR_OP_ALLREDUCE_MULTI = 9,
+  MCR_OP_MOE_ROUTE = 10,
+  MCR_OP_COUNT = 11
+} mcr_op;
+
+typedef enum {
+  MCR_OK = 0,
+  MCR_EINVAL = -1,   /* null pointer, P out of range, count not divisible by P, negative split, ... */
+  MCR_EDTYPE = -2,   /* unknown dtype */
+  MCR_EOP = -3,      /* unknown reduce op / op id */
+  MCR_EVARIANT = -4, /* unknown variant, or variant not applicable to this shape/alignment */
+  MCR_ESPLIT = -5,   /* host-resident split matrix inconsistent with the declared buffer rows */
+  MCR_EHIP = -6,     /* the HIP runtime reported an error (launch, copy, allocation) */
+  MCR_ENOMEM = -7,   /* host allocation failed */
+  MCR_EIO = -8,      /* tuning-table file could not be read / written / parsed */
+  MCR_ESTATE = -9    /* call order: plan not bound, wrong P for a bound plan, ... */
+} mcr_status;
+
+#define MCR_AUTO (-1)
+#define MCR_NO_DEVICE (-1)
+#define MCR_MAX_RANKS 16
+#define MCR_MAX_EXPERTS 512
+
+/* ---- lifecycle (API listing: init, finalize, synchronize, get_backends) ---- */
+
+/* Creates a context on HIP device `device` (made current for the call).  If the
+ * environment variable MCR_TUNING_TABLE names a readable table file it is
+ * loaded; otherwise the table starts empty (MCR_AUTO then uses built-in
+ * defaults).  *out is written only on success.
+ * device == MCR_NO_DEVICE gives a host-only context that touches no GPU: the
+ * tuning table, mcr_get_variants, mcr_fuse_plan_create/info and all argument
+ * validation work as usual, and any call that would launch or bind returns
+ * MCR_ESTATE instead (after its validation has passed). */
+int mcr_init(mcr_ctx** out, int device);
+
+/* Destroys the context.  Plans created from it must be destroyed first. */
+int mcr_finalize(mcr_ctx* ctx);
+
+/* Blocks the host until `stream` has drained (hipStreamSynchronize). */
+int mcr_synchronize(mcr_ctx* ctx, void* stream);
+
+/* The kernel variants of one op, the analogue of get_backends().  On entry *n is
+ * the capacity of names[]; on return *n is the number of variants, and the
+ * first min(capacity, *n) entries of names[] point to static strings.  The
+ * index in names[] is the variant id. */
+int mcr_get_variants(mcr_ctx* ctx, int op_id, const char** names, int* n);
+
+const char* mcr_strerror(int status);
+
+/* ---- collectives ------------------------------------------------------------ */
+
+/* all_reduce (API listing).  bufs[r], r<P: `count` elements each, reduced in
+ * place: every bufs[r][i] becomes x_0[i] (+) x_1[i] (+) ... (+) x_{P-1}[i], taken left
+ * to right in rank order in binary32 (bf16 widened first, rounded once to
+ * nearest-even at the end).  Every element index is read (all P) and then
+ * written (all P) by one thread, so in-place is race free. */
+int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype,
+                  mcr_redop op, int P, int variant, void* stream);
+
+/* reduce_scatter (API listing; it has no root).  in[p]: `count` elements;
+ * out[r]: count/P elements = slice r of the reduction.  P must divide count. */
+int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
+                       mcr_dtype dtype, mcr_redop op, int P, int variant, void* stream);
+
+/* all_gather (API listing; Table II is its tuning table).  in[p]: `count`
+ * elements; out[r]: P*count elements, out[r][p*count + j] = in[p][j].  Bit copy. */
+int mcr_allgather(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
+                  mcr_dtype dtype, int P, int variant, void* stream);
+
+/* all_to_all_single (API listing; "shuffles the tensor elements themselves"),
+ * equal split.  in[p], out[r]: `count` elements, P divides count, b = count/P:
+ * out[r][p*b + k] = in[p][r*b + k].  Bit copy. */
+int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
+                 mcr_dtype dtype, int P, int variant, void* stream);
+
+/* all_to_allv (API listing) with packed displacements.  The unit is a row of
+ * `row_elems` elements.  splits is P x P row-major int64, splits[p*P + r] = rows
+ * rank p sends to rank r (row p is rank p's scounts, column r is rank r's
+ * rcounts).  sdispl[p][r] = sum_{q<r} splits[p][q], rdispl[r][p] =
+ * sum_{q<p} splits[q][r]:
+ *     out[r] row (rdispl[r][p] + k) = in[p] row (sdispl[p][r] + k),  k < splits[p][r].
+ * Rows of out[r] beyond its received total are left untouched.
+ *   splits_on_device == 0: splits is HOST memory, read before return and
+ *     validated: a negative entry gives MCR_EINVAL; a row sum above in_rows or
+ *     a column sum above out_rows gives MCR_ESPLIT.
+ *   splits_on_device != 0: splits is DEVICE memory (e.g. written by
+ *     mcr_moe_route earlier on the same stream) and is read by the kernel; no
+ *     host synchronisation happens.  The kernel itself skips any row that
+ *     would fall outside in_rows / out_rows and treats negative entries as 0.
+ *   splits == NULL: equal split, every pair exchanges in_rows/P rows (P must
+ *     divide in_rows, and out_rows >= in_rows).
+ * in_rows / out_rows: capacity, in rows, of every in[p] / out[r]. */
+int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const int64_t* splits,
+                  int splits_on_device, size_t in_rows, size_t out_rows, size_t row_elems,
+                  mcr_dtype dtype, int P, int variant, void* stream);
+
+/* ---- MoE dispatch / combine (paper Sec. II-C: routing of tokens to experts and
+ * the combination of the expert outputs each need an Alltoall) -------------------
+ *
+ * mcr_moe_route: for every rank p independently, from top-1 expert ids
+ * expert_ids[p][t], t<T (ids outside [0,E) drop the token):
+ *   pos[t]  = number of earlier tokens of rank p with the same expert
+ *   kept[t] = pos[t] < capacity
+ *   counts[p][e] = min(#tokens of e, capacity); base[e] = sum_{e'<e} counts[p][e']
+ *   slot[p][t] = kept ? base[id] + pos[t] : -1      (row in rank p's packed send buffer)
+ *   splits[p*P + r] = sum of counts[p][e] over the E/P experts living on rank r
+ * so the packed buffer is ordered by (expert, token index), hence by
+ * destination rank.  P must divide E; E <= MCR_MAX_EXPERTS; T < 2^31.
+ * expert_ids, slot, counts: host arrays of P device pointers (T, T, E int32
+ * each); splits: DEVICE memory, P*P int64, fully overwritten. */
+int mcr_moe_route(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P,
+                  int capacity, int32_t* const* slot, int32_t* const* counts, int64_t* splits,
+                  void* stream);
+
+/* mcr_pack, batched over P ranks: out[p] row slot[p][t] = in[p] row t for every t<T
+ * with 0 <= slot[p][t] < out_rows; other rows of out[p] are left untouched. */
+int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot,
+             size_t T, size_t out_rows, size_t row_elems, mcr_dtype dtype, int P, int variant,
+             void* stream);
+
+/* mcr_unpack, batched over P ranks: out[p] row t = in[p] row slot[p][t] if
+ * 0 <= slot[p][t] < in_rows, else all-zero bits.  With gate != NULL (host array of
+ * P device pointers to T binary32 weights) the kept rows are scaled:
+ * out = round_to_dtype(gate[p][t] * f32(in)), one binary32 multiply and one
+ * rounding (the gate-weighted combine). */
+int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot,
+               const float* const* gate, size_t T, size_t in_rows, size_t row_elems,
+               mcr_dtype dtype, int P, int variant, void* stream);
+
+/* ---- tensor fusion (paper Sec. IV-D: small tensors are combined into a fusion
+ * buffer of at most B elements; the wait-time parameter T is not modelled) -------
+ *
+ * Plan: walk numel[0..n_tensors) in order; a tensor larger than bucket_elems
+ * closes the open bucket and is a bucket by itself (never split); otherwise, if
+ * it does not fit in the open bucket, that bucket is closed first; then it is
+ * appended.  Offsets inside a bucket are running sums, no padding. */
+int mcr_fuse_plan_create(mcr_ctx* ctx, const size_t* numel, int n_tensors, size_t bucket_elems,
+                         mcr_dtype dtype, mcr_fuse_plan** out);
+
+/* Any output pointer may be NULL.  bucket_numel needs n_buckets entries,
+ * tensor_bucket and tensor_offset n_tensors entries. */
+int mcr_fuse_plan_info(const mcr_fuse_plan* plan, int* n_buckets, size_t* bucket_numel,
+                       int* tensor_bucket, size_t* tensor_offset);
+
+/* Binds the tensors of P ranks to the plan: tensors is a HOST array of
+ * P*n_tensors DEVICE pointers, rank-major (tensors[p*n_tensors + i]).  The table
+ * is copied to plan-owned device memory synchronously (the call blocks until
+ * the copy is done; it may allocate on its first use or when P grows).  Rebind
+ * whenever an address changes; do not rebind while launches that use the plan
+ * are still in flight. */
+int mcr_fuse_plan_bind(mcr_ctx* ctx, mcr_fuse_plan* plan, void* const* tensors, int P);
+
+/* fuse: flat[p][off_i + j] = tensor_i^p[j] for the tensors of `bucket`, all bound
+ * ranks in one launch.  flat: host array of P device pointers, each with room
+ * for bucket_numel[bucket] elements.  P must equal the bound P. */
+int mcr_fuse(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, void* const* flat, int P,
+             int variant, void* stream);
+
+/* unfuse: the inverse, writes the bound tensors. */
+int mcr_unfuse(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, const void* const* flat, int P,
+               int variant, void* stream);
+
+/* The small-message path (paper Sec. IV-C: concurrency only helps small
+ * messages; Sec. IV-D: fusion exists to avoid many tiny operations): one launch
+ * all-reduces, in place and with the arithmetic of mcr_allreduce, every bound
+ * tensor of `bucket` (or of the whole plan when bucket == -1) across the bound
+ * P ranks, reading and writing the tensors where they lie -- no flat buffer. */
+int mcr_allreduce_multi(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, mcr_redop op,
+                        int variant, void* stream);
+
+int mcr_fuse_plan_destroy(mcr_fuse_plan* plan);
+
+/* ---- static tuning table (paper Sec. IV-E, Table II) ---------------------------
+ * One table per (op, dtype, P): rows (message bytes -> variant), kept sorted by
+ * size.  Lookup takes the row with the largest size not above the message; a
+ * message below the first row takes the first, above the last the last; no rows
+ * gives MCR_EVARIANT from mcr_tune_get (MCR_AUTO then uses its default).
+ * "Message bytes" is one rank's send-buffer size: count*elem for allreduce,
+ * reduce_scatter, allgather, alltoall; in_rows*row bytes for alltoallv;
+ * T*row bytes for pack/unpack; bucket bytes for fuse/unfuse/allreduce_multi. */
+int mcr_tune_set(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int variant);
+int mcr_tune_get(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int* variant);
+int mcr_tune_clear(mcr_ctx* ctx);
+/* Number of rows over all tables (Num_Collectives x Num_Scales x Num_Message_Sizes). */
+int mcr_tune_count(mcr_ctx* ctx, size_t* n_rows);
+/* Text file, one row per line: "<op name> <dtype name> <P> <bytes> <variant name>". */
+int mcr_tune_save(mcr_ctx* ctx, const char* path);
+int mcr_tune_load(mcr_ctx* ctx, const char* path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MCR_H_ */

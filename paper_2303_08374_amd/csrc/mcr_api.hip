@@ -1,0 +1,608 @@
+// C ABI: argument validation, variant selection (explicit or from the static
+// tuning table, the paper's "auto" backend of Sec. IV-A / IV-E), fusion plans,
+// and the tuning table itself.  No kernel lives here.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <type_traits>
+
+#include "mcr_internal.hpp"
+
+namespace mcr {
+
+const char* const kStreamVariantNames[SV_COUNT] = {"scalar", "v1", "v2", "v4", "v2nt", "v4nt", "pv2", "pv2nt"};
+
+namespace {
+
+const char* const kOpNames[MCR_OP_COUNT] = {"allreduce", "reduce_scatter", "allgather", "alltoall",
+                                            "alltoallv", "pack", "unpack", "fuse",
+                                            "unfuse", "allreduce_multi", "moe_route"};
+const char* const kDtypeNames[2] = {"f32", "bf16"};
+const char* const kRouteVariantNames[1] = {"wave_ballot"};
+
+bool valid_dtype(int d) { return d == MCR_F32 || d == MCR_BF16; }
+bool valid_redop(int o) { return o == MCR_SUM || o == MCR_AVG; }
+bool valid_P(int P) { return P >= 1 && P <= MCR_MAX_RANKS; }
+int n_variants(int op) { return op == MCR_OP_MOE_ROUTE ? 1 : SV_COUNT; }
+
+bool elem_aligned(const void* p, int dtype) {
+  return (reinterpret_cast<uintptr_t>(p) & (elem_bytes(dtype) - 1)) == 0;
+}
+
+// Copies a host array of P device pointers into a kernel-argument table.
+// Returns false on a null entry (when `need`), or one not aligned to the element.
+template <class Tab, class Ptr>
+bool fill_tab(Tab& tab, Ptr const* arr, int P, int dtype_for_align, bool need, bool* all16) {
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) tab.p[i] = nullptr;
+  if (!arr) return false;
+  for (int p = 0; p < P; ++p) {
+    if (need && arr[p] == nullptr) return false;
+    if (dtype_for_align >= 0 && !elem_aligned(arr[p], dtype_for_align)) return false;
+    if (all16 && !aligned16(arr[p])) *all16 = false;
+    typedef typename std::remove_reference<decltype(tab.p[0])>::type Slot;
+    tab.p[p] = (Slot)arr[p];
+  }
+  return true;
+}
+
+// Table lookup: floor-to-row rule.  Returns -1 when there is no table for the key.
+int table_lookup(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes) {
+  std::lock_guard<std::mutex> lock(ctx->mu);
+  auto it = ctx->tables.find(TuneKey{op, dtype, P});
+  if (it == ctx->tables.end() || it->second.empty()) return -1;
+  const auto& rows = it->second;
+  int pick = rows.front().second;
+  for (const auto& row : rows) {
+    if (row.first <= bytes) pick = row.second; else break;
+  }
+  return pick;
+}
+
+// Built-in choice when the table has nothing: a plain 16-byte-per-thread launch for
+// small messages (least latency), four vectors per thread for large ones.
+int default_variant(size_t bytes) { return bytes >= (size_t(1) << 20) ? SV_V4 : SV_V1; }
+
+// Resolves `variant` for a streaming op.  vec_ok: the shape and alignment allow
+// the 128-bit variants.
+int resolve_variant(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes, bool vec_ok, int variant, int* out) {
+  if (variant == MCR_AUTO) {
+    if (!vec_ok) { *out = SV_SCALAR; return MCR_OK; }
+    int v = table_lookup(ctx, op, dtype, P, bytes);
+    if (v < 0 || v >= SV_COUNT) v = default_variant(bytes);
+    *out = v;
+    return MCR_OK;
+  }
+  if (variant < 0 || variant >= SV_COUNT) return MCR_EVARIANT;
+  if (variant != SV_SCALAR && !vec_ok) return MCR_EVARIANT;
+  *out = variant;
+  return MCR_OK;
+}
+
+// A host-only context (device < 0) validates, plans and tunes but never launches.
+int set_device(mcr_ctx* ctx) {
+  if (ctx->device < 0) return MCR_ESTATE;
+  return hip_status(hipSetDevice(ctx->device));
+}
+
+}  // namespace
+}  // namespace mcr
+
+using namespace mcr;
+
+extern "C" {
+
+const char* mcr_strerror(int status) {
+  switch (status) {
+    case MCR_OK: return "ok";
+    case MCR_EINVAL: return "invalid argument";
+    case MCR_EDTYPE: return "unknown dtype";
+    case MCR_EOP: return "unknown op";
+    case MCR_EVARIANT: return "unknown or inapplicable variant";
+    case MCR_ESPLIT: return "split matrix exceeds the declared buffer rows";
+    case MCR_EHIP: return "HIP runtime error";
+    case MCR_ENOMEM: return "out of host memory";
+    case MCR_EIO: return "tuning table file error";
+    case MCR_ESTATE: return "call not valid in this state";
+  }
+  return "unknown status";
+}
+
+int mcr_init(mcr_ctx** out, int device) {
+  if (!out || device < MCR_NO_DEVICE) return MCR_EINVAL;
+  if (device != MCR_NO_DEVICE) {
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess) return MCR_EHIP;
+    if (device >= count) return MCR_EINVAL;
+    if (hipSetDevice(device) != hipSuccess) return MCR_EHIP;
+  }
+  mcr_ctx* ctx = new (std::nothrow) mcr_ctx;
+  if (!ctx) return MCR_ENOMEM;
+  ctx->device = device;
+  int cus = 0;
+  if (device != MCR_NO_DEVICE &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
+    ctx->num_cus = cus;
+  const char* path = std::getenv("MCR_TUNING_TABLE");
+  if (path && *path) (void)mcr_tune_load(ctx, path);   // an unreadable file leaves the table empty
+  *out = ctx;
+  return MCR_OK;
+}
+
+int mcr_finalize(mcr_ctx* ctx) {
+  if (!ctx) return MCR_EINVAL;
+  delete ctx;
+  return MCR_OK;
+}
+
+int mcr_synchronize(mcr_ctx* ctx, void* stream) {
+  if (!ctx) return MCR_EINVAL;
+  return hip_status(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+}
+
+int mcr_get_variants(mcr_ctx* ctx, int op_id, const char** names, int* n) {
+  if (!ctx || !n) return MCR_EINVAL;
+  if (op_id < 0 || op_id >= MCR_OP_COUNT) return MCR_EOP;
+  const int have = n_variants(op_id);
+  const int cap = *n;
+  if (names) {
+    for (int i = 0; i < have && i < cap; ++i)
+      names[i] = (op_id == MCR_OP_MOE_ROUTE) ? kRouteVariantNames[i] : kStreamVariantNames[i];
+  }
+  *n = have;
+  return MCR_OK;
+}
+
+// ---- collectives ----------------------------------------------------------------
+int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, mcr_redop op, int P,
+                  int variant, void* stream) {
+  if (!ctx || !bufs || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (!valid_redop(op)) return MCR_EOP;
+  PtrTab tab;
+  bool all16 = true;
+  if (!fill_tab(tab, bufs, P, dtype, count > 0, &all16)) return MCR_EINVAL;
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_allreduce(ctx, tab, count, dtype, op, P, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype,
+                       mcr_redop op, int P, int variant, void* stream) {
+  if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (!valid_redop(op)) return MCR_EOP;
+  if (count % static_cast<size_t>(P) != 0) return MCR_EINVAL;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, count > 0, &all16) || !fill_tab(ti, in, P, dtype, count > 0, &all16)) return MCR_EINVAL;
+  const bool vec_ok = all16 && ((count / P) % per_vec(dtype) == 0);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_REDUCE_SCATTER, dtype, P, count * elem_bytes(dtype), vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_reduce_scatter(ctx, to, ti, count, dtype, op, P, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_allgather(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype, int P,
+                  int variant, void* stream) {
+  if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, count > 0, &all16) || !fill_tab(ti, in, P, dtype, count > 0, &all16)) return MCR_EINVAL;
+  const bool vec_ok = all16 && (count % per_vec(dtype) == 0);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLGATHER, dtype, P, count * elem_bytes(dtype), vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_allgather(ctx, to, ti, count, dtype, P, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype, int P,
+                 int variant, void* stream) {
+  if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (count % static_cast<size_t>(P) != 0) return MCR_EINVAL;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, count > 0, &all16) || !fill_tab(ti, in, P, dtype, count > 0, &all16)) return MCR_EINVAL;
+  const bool vec_ok = all16 && ((count / P) % per_vec(dtype) == 0);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLTOALL, dtype, P, count * elem_bytes(dtype), vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_alltoall(ctx, to, ti, count, dtype, P, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const int64_t* splits,
+                  int splits_on_device, size_t in_rows, size_t out_rows, size_t row_elems, mcr_dtype dtype, int P,
+                  int variant, void* stream) {
+  if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  int64_t equal[MCR_MAX_RANKS * MCR_MAX_RANKS];
+  const int64_t* host = nullptr;
+  const int64_t* dev = nullptr;
+  if (!splits) {
+    if (in_rows % static_cast<size_t>(P) != 0 || out_rows < in_rows) return MCR_EINVAL;
+    for (int i = 0; i < P * P; ++i) equal[i] = static_cast<int64_t>(in_rows / P);
+    host = equal;
+  } else if (splits_on_device) {
+    dev = splits;
+  } else {
+    host = splits;
+    for (int i = 0; i < P * P; ++i)
+      if (host[i] < 0) return MCR_EINVAL;
+    for (int p = 0; p < P; ++p) {
+      uint64_t rs = 0, cs = 0;
+      for (int q = 0; q < P; ++q) {
+        rs += static_cast<uint64_t>(host[p * P + q]);
+        cs += static_cast<uint64_t>(host[q * P + p]);
+      }
+      if (rs > in_rows || cs > out_rows) return MCR_ESPLIT;
+    }
+  }
+  const bool any = in_rows > 0 && out_rows > 0 && row_elems > 0;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, in, P, dtype, any, &all16)) return MCR_EINVAL;
+  if (!any) return MCR_OK;
+  const bool vec_ok = all16 && (row_bytes % 16 == 0);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLTOALLV, dtype, P, in_rows * row_bytes, vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_alltoallv(ctx, to, ti, host, dev, in_rows, out_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P,
+                          v, static_cast<hipStream_t>(stream));
+}
+
+// ---- MoE ------------------------------------------------------------------------
+int mcr_moe_route(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P, int capacity,
+                  int32_t* const* slot, int32_t* const* counts, int64_t* splits, void* stream) {
+  if (!ctx || !expert_ids || !slot || !counts || !splits || !valid_P(P)) return MCR_EINVAL;
+  if (T < 0 || E < 1 || E > MCR_MAX_EXPERTS || capacity < 0 || E % P != 0) return MCR_EINVAL;
+  if (reinterpret_cast<uintptr_t>(splits) & 7u) return MCR_EINVAL;
+  CPtrTab ti;
+  PtrTab ts, tc;
+  // dtype code MCR_F32 stands for "4-byte aligned" here
+  if (!fill_tab(ti, expert_ids, P, MCR_F32, T > 0, nullptr) || !fill_tab(ts, slot, P, MCR_F32, T > 0, nullptr) ||
+      !fill_tab(tc, counts, P, MCR_F32, true, nullptr))
+    return MCR_EINVAL;
+  int rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_moe_route(ctx, ti, T, E, P, capacity, ts, tc, splits, static_cast<hipStream_t>(stream));
+}
+
+int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot, size_t T,
+             size_t out_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !out || !in || !slot || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (row_elems > (size_t(1) << 28)) return MCR_EINVAL;
+  const bool any = T > 0 && row_elems > 0;
+  PtrTab to;
+  CPtrTab ti, tsl;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, any && out_rows > 0, &all16) || !fill_tab(ti, in, P, dtype, any, &all16) ||
+      !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
+    return MCR_EINVAL;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  const bool vec_ok = all16 && (row_bytes % 16 == 0);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_PACK, dtype, P, T * row_bytes, vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any || out_rows == 0) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_pack(ctx, to, ti, tsl, T, out_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P, v,
+                     static_cast<hipStream_t>(stream));
+}
+
+int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot,
+               const float* const* gate, size_t T, size_t in_rows, size_t row_elems, mcr_dtype dtype, int P,
+               int variant, void* stream) {
+  if (!ctx || !out || !in || !slot || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (row_elems > (size_t(1) << 28)) return MCR_EINVAL;
+  const bool any = T > 0 && row_elems > 0;
+  PtrTab to;
+  CPtrTab ti, tsl, tg;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, in, P, dtype, any && in_rows > 0, &all16) ||
+      !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
+    return MCR_EINVAL;
+  if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  const bool vec_ok = all16 && (row_bytes % 16 == 0);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_UNPACK, dtype, P, T * row_bytes, vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_unpack(ctx, to, ti, tsl, gate ? &tg : nullptr, T, in_rows, row_elems, dtype, P, v,
+                       static_cast<hipStream_t>(stream));
+}
+
+// ---- tensor fusion ---------------------------------------------------------------
+static void plan_free_device(mcr_fuse_plan* plan) {
+  if (plan->d_numel) (void)hipFree(plan->d_numel);
+  if (plan->d_offset) (void)hipFree(plan->d_offset);
+  if (plan->d_chunk_start) (void)hipFree(plan->d_chunk_start);
+  if (plan->d_chunk_tensor) (void)hipFree(plan->d_chunk_tensor);
+  if (plan->d_ptrs) (void)hipFree(plan->d_ptrs);
+  plan->d_numel = plan->d_offset = nullptr;
+  plan->d_chunk_start = plan->d_chunk_tensor = nullptr;
+  plan->d_ptrs = nullptr;
+}
+
+int mcr_fuse_plan_create(mcr_ctx* ctx, const size_t* numel, int n_tensors, size_t bucket_elems, mcr_dtype dtype,
+                         mcr_fuse_plan** out) {
+  if (!ctx || !out || n_tensors < 0 || bucket_elems == 0 || (n_tensors > 0 && !numel)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  mcr_fuse_plan* plan = new (std::nothrow) mcr_fuse_plan;
+  if (!plan) return MCR_ENOMEM;
+  plan->ctx = ctx;
+  plan->dtype = dtype;
+  plan->n_tensors = n_tensors;
+  plan->bucket_elems = bucket_elems;
+  plan->numel.assign(numel, numel + n_tensors);
+  plan->offset.resize(n_tensors);
+  plan->tensor_bucket.resize(n_tensors);
+  plan->bucket_first.push_back(0);
+  // greedy, order preserving: a tensor that does not fit closes the open bucket; an
+  // oversize tensor sits alone
+  size_t fill = 0;
+  int count_in_open = 0;
+  for (int i = 0; i < n_tensors; ++i) {
+    const size_t n = plan->numel[i];
+    const bool oversize = n > bucket_elems;
+    if (count_in_open > 0 && (oversize || fill + n > bucket_elems)) {
+      plan->bucket_numel.push_back(fill);
+      plan->bucket_first.push_back(i);
+      fill = 0;
+      count_in_open = 0;
+    }
+    plan->tensor_bucket[i] = static_cast<int>(plan->bucket_numel.size());
+    plan->offset[i] = fill;
+    fill += n;
+    ++count_in_open;
+    if (oversize) {
+      plan->bucket_numel.push_back(fill);
+      plan->bucket_first.push_back(i + 1);
+      fill = 0;
+      count_in_open = 0;
+    }
+  }
+  if (count_in_open > 0) {
+    plan->bucket_numel.push_back(fill);
+    plan->bucket_first.push_back(n_tensors);
+  }
+  plan->n_buckets = static_cast<int>(plan->bucket_numel.size());
+  // chunk tables
+  const size_t ce = kChunkBytes / elem_bytes(dtype);
+  plan->chunk_start.resize(n_tensors + 1);
+  std::vector<uint32_t> chunk_tensor;
+  uint64_t chunks = 0;
+  for (int i = 0; i < n_tensors; ++i) {
+    plan->chunk_start[i] = static_cast<uint32_t>(chunks);
+    const uint64_t nc = (plan->numel[i] + ce - 1) / ce;
+    chunks += nc;
+    if (chunks > 0x7fffffffull) { delete plan; return MCR_EINVAL; }
+    chunk_tensor.insert(chunk_tensor.end(), nc, static_cast<uint32_t>(i));
+  }
+  plan->chunk_start[n_tensors] = static_cast<uint32_t>(chunks);
+  if (ctx->device < 0) {   // host-only context: the plan can be inspected, not launched
+    *out = plan;
+    return MCR_OK;
+  }
+  if (set_device(ctx) != MCR_OK) { delete plan; return MCR_EHIP; }
+  std::vector<uint64_t> h_numel(plan->numel.begin(), plan->numel.end());
+  std::vector<uint64_t> h_off(plan->offset.begin(), plan->offset.end());
+  bool ok = true;
+  auto up = [&](auto** dptr, const void* src, size_t bytes) {
+    if (!ok) return;
+    if (hipMalloc(reinterpret_cast<void**>(dptr), bytes ? bytes : 16) != hipSuccess) { ok = false; return; }
+    if (bytes && hipMemcpy(*dptr, src, bytes, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+  };
+  up(&plan->d_numel, h_numel.data(), h_numel.size() * 8);
+  up(&plan->d_offset, h_off.data(), h_off.size() * 8);
+  up(&plan->d_chunk_start, plan->chunk_start.data(), plan->chunk_start.size() * 4);
+  up(&plan->d_chunk_tensor, chunk_tensor.data(), chunk_tensor.size() * 4);
+  if (!ok) {
+    plan_free_device(plan);
+    delete plan;
+    return MCR_EHIP;
+  }
+  *out = plan;
+  return MCR_OK;
+}
+
+int mcr_fuse_plan_info(const mcr_fuse_plan* plan, int* n_buckets, size_t* bucket_numel, int* tensor_bucket,
+                       size_t* tensor_offset) {
+  if (!plan) return MCR_EINVAL;
+  if (n_buckets) *n_buckets = plan->n_buckets;
+  if (bucket_numel) std::copy(plan->bucket_numel.begin(), plan->bucket_numel.end(), bucket_numel);
+  if (tensor_bucket) std::copy(plan->tensor_bucket.begin(), plan->tensor_bucket.end(), tensor_bucket);
+  if (tensor_offset) std::copy(plan->offset.begin(), plan->offset.end(), tensor_offset);
+  return MCR_OK;
+}
+
+int mcr_fuse_plan_bind(mcr_ctx* ctx, mcr_fuse_plan* plan, void* const* tensors, int P) {
+  if (!ctx || !plan || plan->ctx != ctx || !valid_P(P)) return MCR_EINVAL;
+  const size_t n = static_cast<size_t>(plan->n_tensors);
+  if (n > 0 && !tensors) return MCR_EINVAL;
+  for (size_t k = 0; k < n * P; ++k) {
+    const size_t i = k % n;
+    if (plan->numel[i] > 0 && (tensors[k] == nullptr || !elem_aligned(tensors[k], plan->dtype))) return MCR_EINVAL;
+  }
+  int rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  if (P > plan->alloc_P) {
+    if (plan->d_ptrs) (void)hipFree(plan->d_ptrs);
+    plan->d_ptrs = nullptr;
+    plan->alloc_P = 0;
+    if (hipMalloc(reinterpret_cast<void**>(&plan->d_ptrs), std::max<size_t>(n * P * sizeof(void*), 16)) != hipSuccess)
+      return MCR_EHIP;
+    plan->alloc_P = P;
+  }
+  if (n > 0 && hipMemcpy(plan->d_ptrs, tensors, n * P * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)
+    return MCR_EHIP;
+  plan->h_ptrs.assign(tensors, tensors + n * P);
+  plan->bound_P = P;
+  return MCR_OK;
+}
+
+static int fuse_common(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, void* const* flat, int P, int variant,
+                       void* stream, bool unfuse) {
+  if (!ctx || !plan || plan->ctx != ctx || !flat || !valid_P(P)) return MCR_EINVAL;
+  if (bucket < 0 || bucket >= plan->n_buckets) return MCR_EINVAL;
+  if (plan->bound_P == 0 || plan->bound_P != P) return MCR_ESTATE;
+  PtrTab tf;
+  if (!fill_tab(tf, flat, P, plan->dtype, plan->bucket_numel[bucket] > 0, nullptr)) return MCR_EINVAL;
+  int v;
+  int rc = resolve_variant(ctx, unfuse ? MCR_OP_UNFUSE : MCR_OP_FUSE, plan->dtype, P,
+                           plan->bucket_numel[bucket] * elem_bytes(plan->dtype), true, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_fuse(ctx, plan, bucket, tf, unfuse, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_fuse(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, void* const* flat, int P, int variant,
+             void* stream) {
+  return fuse_common(ctx, plan, bucket, flat, P, variant, stream, false);
+}
+
+int mcr_unfuse(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, const void* const* flat, int P, int variant,
+               void* stream) {
+  return fuse_common(ctx, plan, bucket, const_cast<void* const*>(flat), P, variant, stream, true);
+}
+
+int mcr_allreduce_multi(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, mcr_redop op, int variant,
+                        void* stream) {
+  if (!ctx || !plan || plan->ctx != ctx) return MCR_EINVAL;
+  if (bucket < -1 || bucket >= plan->n_buckets) return MCR_EINVAL;
+  if (!valid_redop(op)) return MCR_EOP;
+  if (plan->bound_P == 0) return MCR_ESTATE;
+  const int t0 = bucket < 0 ? 0 : plan->bucket_first[bucket];
+  const int t1 = bucket < 0 ? plan->n_tensors : plan->bucket_first[bucket + 1];
+  size_t elems = 0;
+  for (int i = t0; i < t1; ++i) elems += plan->numel[i];
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE_MULTI, plan->dtype, plan->bound_P, elems * elem_bytes(plan->dtype),
+                           true, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_allreduce_multi(ctx, plan, t0, t1, op, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_fuse_plan_destroy(mcr_fuse_plan* plan) {
+  if (!plan) return MCR_EINVAL;
+  if (plan->ctx && plan->ctx->device >= 0) (void)hipSetDevice(plan->ctx->device);
+  plan_free_device(plan);
+  delete plan;
+  return MCR_OK;
+}
+
+// ---- tuning table -----------------------------------------------------------------
+int mcr_tune_set(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int variant) {
+  if (!ctx || !valid_P(P)) return MCR_EINVAL;
+  if (op_id < 0 || op_id >= MCR_OP_COUNT) return MCR_EOP;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (variant < 0 || variant >= n_variants(op_id)) return MCR_EVARIANT;
+  std::lock_guard<std::mutex> lock(ctx->mu);
+  auto& rows = ctx->tables[TuneKey{op_id, dtype, P}];
+  auto it = std::lower_bound(rows.begin(), rows.end(), bytes,
+                             [](const std::pair<size_t, int>& r, size_t b) { return r.first < b; });
+  if (it != rows.end() && it->first == bytes) it->second = variant;
+  else rows.insert(it, std::make_pair(bytes, variant));
+  return MCR_OK;
+}
+
+int mcr_tune_get(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int* variant) {
+  if (!ctx || !variant || !valid_P(P)) return MCR_EINVAL;
+  if (op_id < 0 || op_id >= MCR_OP_COUNT) return MCR_EOP;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  const int v = table_lookup(ctx, op_id, dtype, P, bytes);
+  if (v < 0) return MCR_EVARIANT;
+  *variant = v;
+  return MCR_OK;
+}
+
+int mcr_tune_clear(mcr_ctx* ctx) {
+  if (!ctx) return MCR_EINVAL;
+  std::lock_guard<std::mutex> lock(ctx->mu);
+  ctx->tables.clear();
+  return MCR_OK;
+}
+
+int mcr_tune_count(mcr_ctx* ctx, size_t* n_rows) {
+  if (!ctx || !n_rows) return MCR_EINVAL;
+  std::lock_guard<std::mutex> lock(ctx->mu);
+  size_t n = 0;
+  for (const auto& kv : ctx->tables) n += kv.second.size();
+  *n_rows = n;
+  return MCR_OK;
+}
+
+int mcr_tune_save(mcr_ctx* ctx, const char* path) {
+  if (!ctx || !path) return MCR_EINVAL;
+  std::FILE* f = std::fopen(path, "w");
+  if (!f) return MCR_EIO;
+  std::lock_guard<std::mutex> lock(ctx->mu);
+  std::fprintf(f, "# op dtype P bytes variant\n");
+  for (const auto& kv : ctx->tables) {
+    for (const auto& row : kv.second) {
+      const char* vname = kv.first.op == MCR_OP_MOE_ROUTE ? kRouteVariantNames[row.second] : kStreamVariantNames[row.second];
+      std::fprintf(f, "%s %s %d %zu %s\n", kOpNames[kv.first.op], kDtypeNames[kv.first.dtype], kv.first.P, row.first, vname);
+    }
+  }
+  const bool bad = std::ferror(f) != 0;
+  if (std::fclose(f) != 0 || bad) return MCR_EIO;
+  return MCR_OK;
+}
+
+int mcr_tune_load(mcr_ctx* ctx, const char* path) {
+  if (!ctx || !path) return MCR_EINVAL;
+  std::FILE* f = std::fopen(path, "r");
+  if (!f) return MCR_EIO;
+  // parse everything first; the table changes only if the whole file is good
+  struct Row { int op, dtype, P; size_t bytes; int variant; };
+  std::vector<Row> parsed;
+  char line[512];
+  bool ok = true;
+  while (ok && std::fgets(line, sizeof line, f)) {
+    char* s = line;
+    while (*s == ' ' || *s == '\t') ++s;
+    if (*s == '#' || *s == '\n' || *s == '\r' || *s == 0) continue;
+    char op[64], dt[16], var[32];
+    int P;
+    unsigned long long bytes;
+    if (std::sscanf(s, "%63s %15s %d %llu %31s", op, dt, &P, &bytes, var) != 5) { ok = false; break; }
+    Row r{-1, -1, P, static_cast<size_t>(bytes), -1};
+    for (int i = 0; i < MCR_OP_COUNT; ++i) if (!std::strcmp(op, kOpNames[i])) r.op = i;
+    for (int i = 0; i < 2; ++i) if (!std::strcmp(dt, kDtypeNames[i])) r.dtype = i;
+    if (r.op >= 0) {
+      for (int i = 0; i < n_variants(r.op); ++i) {
+        const char* vname = r.op == MCR_OP_MOE_ROUTE ? kRouteVariantNames[i] : kStreamVariantNames[i];
+        if (!std::strcmp(var, vname)) r.variant = i;
+      }
+    }
+    if (r.op < 0 || r.dtype < 0 || r.variant < 0 || !valid_P(P)) ok = false;
+    else parsed.push_back(r);
+  }
+  std::fclose(f);
+  if (!ok) return MCR_EIO;
+  for (const Row& r : parsed) {
+    const int rc = mcr_tune_set(ctx, r.op, static_cast<mcr_dtype>(r.dtype), r.P, r.bytes, r.variant);
+    if (rc != MCR_OK) return rc;
+  }
+  return MCR_OK;
+}
+
+}  // extern "C"

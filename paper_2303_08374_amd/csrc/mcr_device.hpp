@@ -1,0 +1,106 @@
+// Device-side helpers shared by the gfx950 kernels: 128-bit access types, bf16
+// widening / rounding, the rank pointer table.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mcr.h"
+
+namespace mcr {
+
+constexpr int kBlock = 256;   // 4 wavefronts of 64 lanes
+constexpr int kWave = 64;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Rank pointer table, passed by value as a kernel argument (16 x 8 bytes).
+struct PtrTab {
+  void* p[MCR_MAX_RANKS];
+};
+struct CPtrTab {
+  const void* p[MCR_MAX_RANKS];
+};
+
+// 128-bit global access.  NT = nontemporal (streaming) hint.
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const void* base, size_t vec_index) {
+  const u32x4* p = reinterpret_cast<const u32x4*>(base) + vec_index;
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void store16(void* base, size_t vec_index, u32x4 v) {
+  u32x4* p = reinterpret_cast<u32x4*>(base) + vec_index;
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// bf16 <-> binary32.  A bf16 is the upper half of a binary32 pattern.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Round to nearest even by adding the bias 0x7fff + (lsb of the kept part) and
+// truncating; NaN is kept NaN by forcing the quiet bit.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t nan = (u >> 16) | 0x0040u;
+  return (f != f) ? nan : rounded;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (f32_to_bf16_rne(lo) & 0xffffu) | (f32_to_bf16_rne(hi) << 16);
+}
+
+// Element traits: how many elements one 128-bit vector holds and how a vector
+// is widened to / narrowed from binary32 lanes.
+template <int DT> struct Elem;
+template <> struct Elem<MCR_F32> {
+  static constexpr int kBytes = 4;
+  static constexpr int kPerVec = 4;
+  typedef float scalar_t;
+  __device__ static __forceinline__ void widen(u32x4 v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  __device__ static __forceinline__ u32x4 narrow(const float (&f)[4]) {
+    u32x4 v;
+    v.x = __float_as_uint(f[0]); v.y = __float_as_uint(f[1]);
+    v.z = __float_as_uint(f[2]); v.w = __float_as_uint(f[3]);
+    return v;
+  }
+  __device__ static __forceinline__ float load1(const void* b, size_t i) {
+    return reinterpret_cast<const float*>(b)[i];
+  }
+  __device__ static __forceinline__ void store1(void* b, size_t i, float f) {
+    reinterpret_cast<float*>(b)[i] = f;
+  }
+};
+template <> struct Elem<MCR_BF16> {
+  static constexpr int kBytes = 2;
+  static constexpr int kPerVec = 8;
+  typedef uint16_t scalar_t;
+  __device__ static __forceinline__ void widen(u32x4 v, float (&f)[8]) {
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+  }
+  __device__ static __forceinline__ u32x4 narrow(const float (&f)[8]) {
+    u32x4 v;
+    v.x = pack_bf16x2(f[0], f[1]); v.y = pack_bf16x2(f[2], f[3]);
+    v.z = pack_bf16x2(f[4], f[5]); v.w = pack_bf16x2(f[6], f[7]);
+    return v;
+  }
+  __device__ static __forceinline__ float load1(const void* b, size_t i) {
+    return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(b)[i]) << 16);
+  }
+  __device__ static __forceinline__ void store1(void* b, size_t i, float f) {
+    reinterpret_cast<uint16_t*>(b)[i] = static_cast<uint16_t>(f32_to_bf16_rne(f));
+  }
+};
+
+// Lanes of this wavefront with a lower lane id.
+__device__ __forceinline__ uint64_t lanemask_lt() {
+  const unsigned lane = __lane_id();
+  return (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+}
+
+}  // namespace mcr

@@ -1,0 +1,71 @@
+// Compile-time dispatch over rank count, element type and launch shape.
+#pragma once
+#include <type_traits>
+
+#include "mcr_internal.hpp"
+
+namespace mcr {
+
+template <int N> using Int = std::integral_constant<int, N>;
+template <bool B> using Bool = std::integral_constant<bool, B>;
+
+// f(Int<P>) for P in 1..16
+template <class F>
+inline int dispatch_ranks(int P, F&& f) {
+  switch (P) {
+    case 1: return f(Int<1>{});   case 2: return f(Int<2>{});   case 3: return f(Int<3>{});
+    case 4: return f(Int<4>{});   case 5: return f(Int<5>{});   case 6: return f(Int<6>{});
+    case 7: return f(Int<7>{});   case 8: return f(Int<8>{});   case 9: return f(Int<9>{});
+    case 10: return f(Int<10>{}); case 11: return f(Int<11>{}); case 12: return f(Int<12>{});
+    case 13: return f(Int<13>{}); case 14: return f(Int<14>{}); case 15: return f(Int<15>{});
+    case 16: return f(Int<16>{});
+  }
+  return MCR_EINVAL;
+}
+
+template <class F>
+inline int dispatch_dtype(int dtype, F&& f) {
+  if (dtype == MCR_F32) return f(Int<MCR_F32>{});
+  if (dtype == MCR_BF16) return f(Int<MCR_BF16>{});
+  return MCR_EDTYPE;
+}
+
+// f(Int<U>, Bool<NT>, Bool<PERSIST>) for the vector launch shapes
+template <class F>
+inline int dispatch_shape(int variant, F&& f) {
+  switch (variant) {
+    case SV_V1: return f(Int<1>{}, Bool<false>{}, Bool<false>{});
+    case SV_V2: return f(Int<2>{}, Bool<false>{}, Bool<false>{});
+    case SV_V4: return f(Int<4>{}, Bool<false>{}, Bool<false>{});
+    case SV_V2NT: return f(Int<2>{}, Bool<true>{}, Bool<false>{});
+    case SV_V4NT: return f(Int<4>{}, Bool<true>{}, Bool<false>{});
+    case SV_PV2: return f(Int<2>{}, Bool<false>{}, Bool<true>{});
+    case SV_PV2NT: return f(Int<2>{}, Bool<true>{}, Bool<true>{});
+  }
+  return MCR_EVARIANT;
+}
+
+inline int shape_unroll(int variant) {
+  switch (variant) {
+    case SV_V1: return 1;
+    case SV_V2: case SV_V2NT: case SV_PV2: case SV_PV2NT: return 2;
+    case SV_V4: case SV_V4NT: return 4;
+  }
+  return 1;
+}
+inline bool shape_persistent(int variant) { return variant == SV_PV2 || variant == SV_PV2NT; }
+
+// Workgroups along x for `nvec` vectors per slice and `slices` slices in y/z.
+inline unsigned grid_x(const mcr_ctx* ctx, size_t nvec, int variant, size_t slices) {
+  const size_t per_block = static_cast<size_t>(shape_unroll(variant)) * kBlock;
+  size_t blocks = (nvec + per_block - 1) / per_block;
+  if (blocks == 0) blocks = 1;
+  if (shape_persistent(variant)) {
+    size_t cap = static_cast<size_t>(ctx->num_cus) * 8 / (slices ? slices : 1);
+    if (cap == 0) cap = 1;
+    if (blocks > cap) blocks = cap;
+  }
+  return static_cast<unsigned>(blocks);
+}
+
+}  // namespace mcr

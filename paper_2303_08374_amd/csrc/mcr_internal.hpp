@@ -1,0 +1,105 @@
+// Host-side internals: context, variant ids, launcher prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <map>
+#include <mutex>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "../../include/mcr.h"
+#include "mcr_device.hpp"
+
+namespace mcr {
+
+// Launch shapes of the streaming kernels.  The same list serves allreduce,
+// reduce_scatter, allgather, alltoall, alltoallv, pack, unpack, fuse, unfuse
+// and allreduce_multi: "scalar" moves one element per thread and accepts any
+// alignment; "vN" moves N 128-bit vectors per thread, a workgroup covering
+// N*256 consecutive vectors; "nt" adds the nontemporal hint to loads and
+// stores; "pv" is a fixed grid of a few workgroups per compute unit that
+// strides over the index space.
+enum StreamVariant {
+  SV_SCALAR = 0,
+  SV_V1 = 1,
+  SV_V2 = 2,
+  SV_V4 = 3,
+  SV_V2NT = 4,
+  SV_V4NT = 5,
+  SV_PV2 = 6,
+  SV_PV2NT = 7,
+  SV_COUNT = 8
+};
+extern const char* const kStreamVariantNames[SV_COUNT];
+
+struct TuneKey {
+  int op, dtype, P;
+  bool operator<(const TuneKey& o) const {
+    return std::tie(op, dtype, P) < std::tie(o.op, o.dtype, o.P);
+  }
+};
+
+}  // namespace mcr
+
+struct mcr_ctx {
+  int device = 0;
+  int num_cus = 256;
+  std::mutex mu;                                                      // guards `tables`
+  std::map<mcr::TuneKey, std::vector<std::pair<size_t, int>>> tables; // sorted by bytes
+};
+
+struct mcr_fuse_plan {
+  mcr_ctx* ctx = nullptr;
+  int dtype = 0;
+  int n_tensors = 0;
+  int n_buckets = 0;
+  size_t bucket_elems = 0;
+  std::vector<size_t> numel, offset;        // per tensor; offset inside its bucket
+  std::vector<int> tensor_bucket;
+  std::vector<size_t> bucket_numel;
+  std::vector<int> bucket_first;            // n_buckets+1: first tensor of each bucket
+  std::vector<uint32_t> chunk_start;        // n_tensors+1: prefix of per-tensor chunk counts
+  // device mirrors
+  uint64_t* d_numel = nullptr;              // n_tensors
+  uint64_t* d_offset = nullptr;             // n_tensors
+  uint32_t* d_chunk_start = nullptr;        // n_tensors+1
+  uint32_t* d_chunk_tensor = nullptr;       // per chunk: the tensor it belongs to
+  void** d_ptrs = nullptr;                  // bound_P * n_tensors, rank-major
+  int bound_P = 0;
+  int alloc_P = 0;
+  std::vector<void*> h_ptrs;                // host copy of the bound table (alignment checks)
+};
+
+namespace mcr {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_bytes(int dtype) { return dtype == MCR_F32 ? 4 : 2; }
+inline int per_vec(int dtype) { return dtype == MCR_F32 ? 4 : 8; }
+
+// Elements one workgroup covers per tensor chunk in the multi-tensor kernels
+// (fuse / unfuse / allreduce_multi): 256 threads x 4 vectors of 16 bytes.
+constexpr uint32_t kChunkBytes = 256 * 4 * 16;
+
+// Every launcher returns MCR_OK or MCR_EHIP and assumes validated arguments.
+int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int variant, hipStream_t);
+int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int op, int P, int variant, hipStream_t);
+int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
+int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
+int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits, const int64_t* dev_splits,
+                     size_t in_rows, size_t out_rows, size_t row_bytes, int elem_b, int P, int variant, hipStream_t);
+int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot, const PtrTab& counts,
+                     int64_t* splits, hipStream_t);
+int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows, size_t row_bytes,
+                int elem_b, int P, int variant, hipStream_t);
+int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, const CPtrTab* gate, size_t T,
+                  size_t in_rows, size_t row_elems, int dtype, int P, int variant, hipStream_t);
+int launch_fuse(mcr_ctx*, const mcr_fuse_plan*, int bucket, const PtrTab& flat, bool unfuse, int variant, hipStream_t);
+int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan*, int t0, int t1, int op, int variant, hipStream_t);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? MCR_OK : MCR_EHIP; }
+inline int launch_status() { return hip_status(hipGetLastError()); }
+
+}  // namespace mcr

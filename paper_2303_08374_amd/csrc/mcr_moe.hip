@@ -1,0 +1,274 @@
+// MoE token dispatch / combine around the Alltoall (paper Sec. II-C): routing
+// (histogram + capacity clamp + exclusive scan -> pack slots and the split
+// matrix), pack (row scatter by slot), unpack / gate-weighted combine (row
+// gather by slot).
+#include "mcr_dispatch.hpp"
+
+namespace mcr {
+namespace {
+
+// ---- routing ---------------------------------------------------------------------
+// One workgroup of 16 wavefronts per rank.  Wave w owns a contiguous run of
+// tokens, so "earlier token" means: earlier wave, or earlier 64-token step of
+// this wave, or lower lane in this step.  Within a step the lanes holding the
+// same expert id are found with one ballot per id bit; a lane's position is
+// the popcount of that mask below it.  Pass 1 counts per (wave, expert) in
+// LDS; a scan over waves turns the counts into each wave's starting position;
+// pass 2 replays the steps and emits slots.  Integer work on a few KB: bound
+// by latency, not bandwidth.
+constexpr int kRouteWaves = 16;
+constexpr int kRouteBlock = kRouteWaves * kWave;
+
+__device__ __forceinline__ uint64_t same_id_mask(int id, bool valid, int nbits) {
+  uint64_t mask = __ballot(valid);
+  for (int b = 0; b < nbits; ++b) {
+    const bool bit = (id >> b) & 1;
+    const uint64_t vote = __ballot(valid && bit);
+    mask &= bit ? vote : ~vote;
+  }
+  return mask;
+}
+
+__global__ void __launch_bounds__(kRouteBlock)
+moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* splits, int T, int E,
+                 int P, int C, int nbits) {
+  __shared__ int wave_cnt[kRouteWaves][MCR_MAX_EXPERTS];   // count, then running start position
+  __shared__ int ebase[MCR_MAX_EXPERTS];                   // first slot of each expert
+  __shared__ int ecnt[MCR_MAX_EXPERTS];                    // kept tokens of each expert
+  const int rank = blockIdx.x;
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[rank]);
+  int32_t* slot = static_cast<int32_t*>(slot_tab.p[rank]);
+  int32_t* counts = static_cast<int32_t*>(counts_tab.p[rank]);
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const uint64_t below = lanemask_lt();
+
+  for (int i = tid; i < kRouteWaves * E; i += kRouteBlock) wave_cnt[i / E][i % E] = 0;
+  __syncthreads();
+
+  // tokens of this wave: [t_begin, t_end), a multiple of 64 long except at the very end
+  const int steps_total = (T + kWave - 1) / kWave;
+  const int steps_per_wave = (steps_total + kRouteWaves - 1) / kRouteWaves;
+  const int s_begin = wave * steps_per_wave;
+  const int s_end = min(steps_total, s_begin + steps_per_wave);
+
+  for (int s = s_begin; s < s_end; ++s) {
+    const int t = s * kWave + lane;
+    const int id = (t < T) ? ids[t] : -1;
+    const bool valid = id >= 0 && id < E;
+    const uint64_t mask = same_id_mask(id, valid, nbits);
+    if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);   // lowest lane of the group
+  }
+  __syncthreads();
+
+  // per expert: exclusive scan over waves, then clamp the total to the capacity
+  for (int e = tid; e < E; e += kRouteBlock) {
+    int run = 0;
+    for (int w = 0; w < kRouteWaves; ++w) {
+      const int c = wave_cnt[w][e];
+      wave_cnt[w][e] = run;
+      run += c;
+    }
+    ecnt[e] = min(run, C);
+  }
+  __syncthreads();
+  // exclusive scan of the kept counts over experts (E <= 512: one wave, 64 at a time)
+  if (wave == 0) {
+    int carry = 0;
+    for (int e0 = 0; e0 < E; e0 += kWave) {
+      const int e = e0 + lane;
+      const int c = (e < E) ? ecnt[e] : 0;
+      int incl = c;
+      for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+      }
+      if (e < E) {
+        ebase[e] = carry + incl - c;
+        counts[e] = c;
+      }
+      carry += __shfl(incl, kWave - 1);
+    }
+  }
+  __syncthreads();
+  if (tid < P) {
+    const int per = E / P;
+    int64_t a = 0;
+    for (int e = tid * per; e < (tid + 1) * per; ++e) a += ecnt[e];
+    splits[static_cast<size_t>(rank) * P + tid] = a;
+  }
+
+  for (int s = s_begin; s < s_end; ++s) {
+    const int t = s * kWave + lane;
+    const int id = (t < T) ? ids[t] : -1;
+    const bool valid = id >= 0 && id < E;
+    const uint64_t mask = same_id_mask(id, valid, nbits);
+    int out = -1;
+    if (valid) {
+      const int pos = wave_cnt[wave][id] + __popcll(mask & below);
+      if (pos < C) out = ebase[id] + pos;
+    }
+    // every lane has read the running position before the group's first lane moves it on
+    __builtin_amdgcn_wave_barrier();
+    if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);
+    __builtin_amdgcn_wave_barrier();
+    if (t < T) slot[t] = out;
+  }
+}
+
+// ---- pack / unpack -----------------------------------------------------------------
+// A row is `upr` units; `tpr` threads (a power of two <= 256) share a row, so a
+// workgroup covers 256/tpr rows.  blockIdx.y = rank.
+template <int UB> struct RowUnit;
+template <> struct RowUnit<16> { typedef u32x4 type; };
+template <> struct RowUnit<4> { typedef uint32_t type; };
+template <> struct RowUnit<2> { typedef uint16_t type; };
+
+template <int UB, bool NT>
+__global__ void __launch_bounds__(kBlock)
+pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows, uint32_t upr,
+            uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  const unsigned rank = blockIdx.y;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[rank]);
+  const U* src = static_cast<const U*>(in.p[rank]);
+  U* dst = static_cast<U*>(out.p[rank]);
+  const uint32_t rows_per_block = kBlock >> tpr_shift;
+  const size_t t = static_cast<size_t>(blockIdx.x) * rows_per_block + (threadIdx.x >> tpr_shift);
+  if (t >= T) return;
+  const int32_t s = slot[t];
+  if (s < 0 || static_cast<size_t>(s) >= out_rows) return;
+  const U* srow = src + t * upr;
+  U* drow = dst + static_cast<size_t>(s) * upr;
+  for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+    U v;
+    if constexpr (NT) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
+    if constexpr (NT) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
+  }
+}
+
+template <int DT> __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float g) {
+  using E = Elem<DT>;
+  float f[E::kPerVec];
+  E::widen(v, f);
+#pragma unroll
+  for (int k = 0; k < E::kPerVec; ++k) f[k] = g * f[k];
+  return E::narrow(f);
+}
+
+// GATE: 0 = plain gather, 1 = scale kept rows by gate[t].
+template <int DT, int UB, bool NT, bool GATE>
+__global__ void __launch_bounds__(kBlock)
+unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t T, size_t in_rows,
+              uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  const unsigned rank = blockIdx.y;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[rank]);
+  const U* src = static_cast<const U*>(in.p[rank]);
+  U* dst = static_cast<U*>(out.p[rank]);
+  const uint32_t rows_per_block = kBlock >> tpr_shift;
+  const size_t t = static_cast<size_t>(blockIdx.x) * rows_per_block + (threadIdx.x >> tpr_shift);
+  if (t >= T) return;
+  const int32_t s = slot[t];
+  const bool kept = s >= 0 && static_cast<size_t>(s) < in_rows;
+  U* drow = dst + t * upr;
+  if (!kept) {
+    U z = {};
+    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+      if constexpr (NT) __builtin_nontemporal_store(z, drow + c); else drow[c] = z;
+    }
+    return;
+  }
+  const U* srow = src + static_cast<size_t>(s) * upr;
+  float g = 1.0f;
+  if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[rank])[t];
+  for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+    U v;
+    if constexpr (NT) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
+    if constexpr (GATE) {
+      if constexpr (UB == 16) {
+        v = scale_vec<DT>(v, g);
+      } else {
+        // one element per unit
+        float x;
+        if constexpr (DT == MCR_F32) x = __uint_as_float(static_cast<uint32_t>(v));
+        else x = __uint_as_float(static_cast<uint32_t>(v) << 16);
+        const float y = g * x;
+        if constexpr (DT == MCR_F32) v = static_cast<U>(__float_as_uint(y));
+        else v = static_cast<U>(f32_to_bf16_rne(y));
+      }
+    }
+    if constexpr (NT) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
+  }
+}
+
+struct RowShape {
+  uint32_t upr, tpr, shift;
+  unsigned blocks;
+};
+inline RowShape row_shape(size_t T, size_t units_per_row) {
+  RowShape s;
+  s.upr = static_cast<uint32_t>(units_per_row);
+  s.shift = 0;
+  while ((1u << s.shift) < s.upr && s.shift < 8) ++s.shift;   // tpr = min(256, pow2 >= upr)
+  s.tpr = 1u << s.shift;
+  const size_t rows_per_block = kBlock >> s.shift;
+  s.blocks = static_cast<unsigned>((T + rows_per_block - 1) / rows_per_block);
+  if (s.blocks == 0) s.blocks = 1;
+  return s;
+}
+
+inline bool variant_nt(int variant) { return variant == SV_V2NT || variant == SV_V4NT || variant == SV_PV2NT; }
+
+}  // namespace
+
+int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot,
+                     const PtrTab& counts, int64_t* splits, hipStream_t stream) {
+  int nbits = 0;
+  while ((1 << nbits) < E) ++nbits;
+  hipLaunchKernelGGL(moe_route_kernel, dim3(P), dim3(kRouteBlock), 0, stream, ids, slot, counts, splits, T, E,
+                     P, capacity, nbits);
+  return launch_status();
+}
+
+int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows,
+                size_t row_bytes, int elem_b, int P, int variant, hipStream_t stream) {
+  if (T == 0 || row_bytes == 0) return MCR_OK;
+  if (variant == SV_SCALAR) {
+    const RowShape s = row_shape(T, row_bytes / elem_b);
+    if (elem_b == 4)
+      hipLaunchKernelGGL((pack_kernel<4, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+    else
+      hipLaunchKernelGGL((pack_kernel<2, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+    return launch_status();
+  }
+  const RowShape s = row_shape(T, row_bytes / 16);
+  if (variant_nt(variant))
+    hipLaunchKernelGGL((pack_kernel<16, true>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+  else
+    hipLaunchKernelGGL((pack_kernel<16, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+  return launch_status();
+}
+
+int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, const CPtrTab* gate,
+                  size_t T, size_t in_rows, size_t row_elems, int dtype, int P, int variant, hipStream_t stream) {
+  if (T == 0 || row_elems == 0) return MCR_OK;
+  CPtrTab g;
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
+  const bool nt = variant_nt(variant);
+  return dispatch_dtype(dtype, [&](auto dt) {
+    constexpr int DT = decltype(dt)::value;
+    constexpr int EB = Elem<DT>::kBytes;
+    auto go = [&](auto ub, auto ntc, auto gc) {
+      constexpr int UB = decltype(ub)::value;
+      const RowShape s = row_shape(T, row_elems * EB / UB);
+      hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntc)::value, decltype(gc)::value>), dim3(s.blocks, P),
+                         dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);
+      return launch_status();
+    };
+    if (variant == SV_SCALAR) return gate ? go(Int<EB>{}, Bool<false>{}, Bool<true>{}) : go(Int<EB>{}, Bool<false>{}, Bool<false>{});
+    if (nt) return gate ? go(Int<16>{}, Bool<true>{}, Bool<true>{}) : go(Int<16>{}, Bool<true>{}, Bool<false>{});
+    return gate ? go(Int<16>{}, Bool<false>{}, Bool<true>{}) : go(Int<16>{}, Bool<false>{}, Bool<false>{});
+  });
+}
+
+}  // namespace mcr

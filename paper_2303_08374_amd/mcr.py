@@ -1,0 +1,243 @@
+"""Thin ctypes binding of libmcr.so (see include/mcr.h for the contract of every call).
+
+Argument marshalling only: each function has the name and argument order of its C
+entry point, turns torch tensors into device addresses, passes torch's current HIP
+stream unless told otherwise, and raises :class:`McrError` on a non-zero status.
+There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Union
+
+F32, BF16 = 0, 1
+SUM, AVG = 0, 1
+AUTO = -1
+MAX_RANKS = 16
+MAX_EXPERTS = 512
+
+OP_ALLREDUCE, OP_REDUCE_SCATTER, OP_ALLGATHER, OP_ALLTOALL, OP_ALLTOALLV = 0, 1, 2, 3, 4
+OP_PACK, OP_UNPACK, OP_FUSE, OP_UNFUSE, OP_ALLREDUCE_MULTI, OP_MOE_ROUTE = 5, 6, 7, 8, 9, 10
+OP_NAMES = ["allreduce", "reduce_scatter", "allgather", "alltoall", "alltoallv", "pack", "unpack",
+            "fuse", "unfuse", "allreduce_multi", "moe_route"]
+
+OK, EINVAL, EDTYPE, EOP, EVARIANT, ESPLIT, EHIP, ENOMEM, EIO, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8, -9
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmcr.so")
+
+Ptr = Union[int, "torch.Tensor"]  # noqa: F821
+
+
+class McrError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Opens libmcr.so; raises if it has not been built (python -m paper_2303_08374_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2303_08374_amd.build`; "
+                              "there is no fallback path")
+        _lib = ctypes.CDLL(LIB_PATH)
+        _lib.mcr_strerror.restype = ctypes.c_char_p
+        _lib.mcr_strerror.argtypes = [ctypes.c_int]
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().mcr_strerror(status).decode()
+
+
+mcr_strerror = strerror
+
+
+def _addr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _ptr_array(xs: Optional[Sequence[Ptr]]):
+    if xs is None:
+        return None
+    return (ctypes.c_void_p * len(xs))(*[_addr(x) for x in xs])
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise McrError(rc, what)
+
+
+_sz = ctypes.c_size_t
+
+
+# ---- lifecycle -----------------------------------------------------------------------------
+def mcr_init(device: int = 0) -> ctypes.c_void_p:
+    ctx = ctypes.c_void_p()
+    _check(lib().mcr_init(ctypes.byref(ctx), device), "mcr_init")
+    return ctx
+
+
+def mcr_finalize(ctx) -> None:
+    _check(lib().mcr_finalize(ctx), "mcr_finalize")
+
+
+def mcr_synchronize(ctx, stream=None) -> None:
+    _check(lib().mcr_synchronize(ctx, _stream(stream)), "mcr_synchronize")
+
+
+def mcr_get_variants(ctx, op_id: int) -> List[str]:
+    n = ctypes.c_int(64)
+    names = (ctypes.c_char_p * 64)()
+    _check(lib().mcr_get_variants(ctx, op_id, names, ctypes.byref(n)), "mcr_get_variants")
+    return [names[i].decode() for i in range(n.value)]
+
+
+# ---- collectives ---------------------------------------------------------------------------
+def mcr_allreduce(ctx, bufs: Sequence[Ptr], count: int, dtype: int, op: int, P: int, variant: int = AUTO,
+                  stream=None) -> None:
+    _check(lib().mcr_allreduce(ctx, _ptr_array(bufs), _sz(count), dtype, op, P, variant, _stream(stream)),
+           "mcr_allreduce")
+
+
+def mcr_reduce_scatter(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, op: int, P: int,
+                       variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_reduce_scatter(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, op, P, variant,
+                                    _stream(stream)), "mcr_reduce_scatter")
+
+
+def mcr_allgather(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, P: int,
+                  variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_allgather(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, variant,
+                               _stream(stream)), "mcr_allgather")
+
+
+def mcr_alltoall(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, P: int,
+                 variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_alltoall(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, variant,
+                              _stream(stream)), "mcr_alltoall")
+
+
+def mcr_alltoallv(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], splits, splits_on_device: bool, in_rows: int,
+                  out_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    """``splits``: None (equal split), a device tensor / address (splits_on_device=True), or a host
+    sequence of P*P integers, row-major."""
+    keep = None
+    if splits is None:
+        sp = ctypes.c_void_p(0)
+    elif splits_on_device:
+        sp = ctypes.c_void_p(_addr(splits))
+    else:
+        flat = [int(v) for row in splits for v in (row if hasattr(row, "__len__") else [row])]
+        keep = (ctypes.c_int64 * len(flat))(*flat)
+        sp = ctypes.cast(keep, ctypes.c_void_p)
+    _check(lib().mcr_alltoallv(ctx, _ptr_array(out), _ptr_array(inp), sp, int(bool(splits_on_device)),
+                               _sz(in_rows), _sz(out_rows), _sz(row_elems), dtype, P, variant, _stream(stream)),
+           "mcr_alltoallv")
+
+
+# ---- MoE -----------------------------------------------------------------------------------
+def mcr_moe_route(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
+                  counts: Sequence[Ptr], splits: Ptr, stream=None) -> None:
+    _check(lib().mcr_moe_route(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
+                               ctypes.c_void_p(_addr(splits)), _stream(stream)), "mcr_moe_route")
+
+
+def mcr_pack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr], T: int, out_rows: int, row_elems: int,
+             dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_pack(ctx, _ptr_array(out), _ptr_array(inp), _ptr_array(slot), _sz(T), _sz(out_rows),
+                          _sz(row_elems), dtype, P, variant, _stream(stream)), "mcr_pack")
+
+
+def mcr_unpack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr], gate: Optional[Sequence[Ptr]], T: int,
+               in_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_unpack(ctx, _ptr_array(out), _ptr_array(inp), _ptr_array(slot), _ptr_array(gate), _sz(T),
+                            _sz(in_rows), _sz(row_elems), dtype, P, variant, _stream(stream)), "mcr_unpack")
+
+
+# ---- tensor fusion -------------------------------------------------------------------------
+def mcr_fuse_plan_create(ctx, numel: Sequence[int], bucket_elems: int, dtype: int) -> ctypes.c_void_p:
+    arr = (ctypes.c_size_t * max(len(numel), 1))(*[int(n) for n in numel])
+    plan = ctypes.c_void_p()
+    _check(lib().mcr_fuse_plan_create(ctx, arr, len(numel), _sz(bucket_elems), dtype, ctypes.byref(plan)),
+           "mcr_fuse_plan_create")
+    return plan
+
+
+def mcr_fuse_plan_info(plan, n_tensors: int):
+    """Returns (bucket_numel, tensor_bucket, tensor_offset) as Python lists."""
+    nb = ctypes.c_int(0)
+    _check(lib().mcr_fuse_plan_info(plan, ctypes.byref(nb), None, None, None), "mcr_fuse_plan_info")
+    bn = (ctypes.c_size_t * max(nb.value, 1))()
+    tb = (ctypes.c_int * max(n_tensors, 1))()
+    to = (ctypes.c_size_t * max(n_tensors, 1))()
+    _check(lib().mcr_fuse_plan_info(plan, ctypes.byref(nb), bn, tb, to), "mcr_fuse_plan_info")
+    return list(bn[:nb.value]), list(tb[:n_tensors]), list(to[:n_tensors])
+
+
+def mcr_fuse_plan_bind(ctx, plan, tensors: Sequence[Ptr], P: int) -> None:
+    """``tensors``: P*n_tensors entries, rank-major."""
+    _check(lib().mcr_fuse_plan_bind(ctx, plan, _ptr_array(tensors), P), "mcr_fuse_plan_bind")
+
+
+def mcr_fuse(ctx, plan, bucket: int, flat: Sequence[Ptr], P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_fuse(ctx, plan, bucket, _ptr_array(flat), P, variant, _stream(stream)), "mcr_fuse")
+
+
+def mcr_unfuse(ctx, plan, bucket: int, flat: Sequence[Ptr], P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_unfuse(ctx, plan, bucket, _ptr_array(flat), P, variant, _stream(stream)), "mcr_unfuse")
+
+
+def mcr_allreduce_multi(ctx, plan, bucket: int, op: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_allreduce_multi(ctx, plan, bucket, op, variant, _stream(stream)), "mcr_allreduce_multi")
+
+
+def mcr_fuse_plan_destroy(plan) -> None:
+    _check(lib().mcr_fuse_plan_destroy(plan), "mcr_fuse_plan_destroy")
+
+
+# ---- tuning table --------------------------------------------------------------------------
+def mcr_tune_set(ctx, op_id: int, dtype: int, P: int, nbytes: int, variant: int) -> None:
+    _check(lib().mcr_tune_set(ctx, op_id, dtype, P, _sz(nbytes), variant), "mcr_tune_set")
+
+
+def mcr_tune_get(ctx, op_id: int, dtype: int, P: int, nbytes: int) -> int:
+    v = ctypes.c_int(-1)
+    _check(lib().mcr_tune_get(ctx, op_id, dtype, P, _sz(nbytes), ctypes.byref(v)), "mcr_tune_get")
+    return v.value
+
+
+def mcr_tune_clear(ctx) -> None:
+    _check(lib().mcr_tune_clear(ctx), "mcr_tune_clear")
+
+
+def mcr_tune_count(ctx) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().mcr_tune_count(ctx, ctypes.byref(n)), "mcr_tune_count")
+    return n.value
+
+
+def mcr_tune_save(ctx, path: str) -> None:
+    _check(lib().mcr_tune_save(ctx, path.encode()), "mcr_tune_save")
+
+
+def mcr_tune_load(ctx, path: str) -> None:
+    _check(lib().mcr_tune_load(ctx, path.encode()), "mcr_tune_load")

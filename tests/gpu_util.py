@@ -1,0 +1,71 @@
+"""Helpers for the GPU parity tests: host numpy <-> device torch buffers (torch is used for
+device memory only), a shared library context, bitwise comparison."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2303_08374_amd import mcr
+
+_ctx = None
+
+
+def ctx():
+    global _ctx
+    if _ctx is None:
+        _ctx = mcr.mcr_init(0)
+    return _ctx
+
+
+def to_dev(a: np.ndarray) -> torch.Tensor:
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t: torch.Tensor, like: np.dtype) -> np.ndarray:
+    a = t.cpu().numpy()
+    if np.dtype(like) == np.uint16:
+        a = a.view(np.uint16)
+    return a
+
+
+def dev_empty(n: int, dtype: int, fill=None) -> torch.Tensor:
+    td = torch.float32 if dtype == mcr.F32 else torch.int16
+    t = torch.empty(n, dtype=td, device="cuda")
+    if fill is not None:
+        t.fill_(fill)
+    return t
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+def assert_bits_equal(got: np.ndarray, exp: np.ndarray, what=""):
+    g = np.ascontiguousarray(got).view(np.uint8)
+    e = np.ascontiguousarray(exp).view(np.uint8)
+    assert g.shape == e.shape, (what, g.shape, e.shape)
+    if not np.array_equal(g, e):
+        es = exp.dtype.itemsize
+        bad = np.nonzero((g.reshape(-1, es) != e.reshape(-1, es)).any(axis=1))[0]
+        raise AssertionError(f"{what}: {bad.size} of {exp.size} elements differ, first at {bad[:5].tolist()}: "
+                             f"got {got.reshape(-1)[bad[:5]]} expected {exp.reshape(-1)[bad[:5]]}")
+
+
+def assert_reduced_equal(got: np.ndarray, exp: np.ndarray, dtype: int, what=""):
+    """Reduced outputs: bit-equal except that a NaN only has to be a NaN."""
+    if dtype == mcr.F32:
+        gn, en = np.isnan(got), np.isnan(exp)
+    else:
+        isnan = lambda h: ((h & 0x7F80) == 0x7F80) & ((h & 0x7F) != 0)
+        gn, en = isnan(got), isnan(exp)
+    assert np.array_equal(gn, en), f"{what}: NaN positions differ"
+    assert_bits_equal(np.where(gn, 0, got).astype(got.dtype), np.where(en, 0, exp).astype(exp.dtype), what)
+
+
+VEC_VARIANTS = [1, 2, 3, 4, 5, 6, 7]
+ALL_VARIANTS = [0] + VEC_VARIANTS
+NPDT = {mcr.F32: np.float32, mcr.BF16: np.uint16}
+EB = {mcr.F32: 4, mcr.BF16: 2}
+assert (oracle.F32, oracle.BF16, oracle.SUM, oracle.AVG) == (mcr.F32, mcr.BF16, mcr.SUM, mcr.AVG)

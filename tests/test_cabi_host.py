@@ -1,0 +1,202 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host logic (argument validation, tuning table, bucket plan) behaves as the header
+says.  A host-only context (MCR_NO_DEVICE) is used, so no kernel is ever launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2303_08374_amd import inputs, mcr
+from tests import golden_io as gio
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mcr.h")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = mcr.mcr_init(-1)
+    yield c
+    mcr.mcr_finalize(c)
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mcr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 25 and "mcr_allreduce" in names and "mcr_alltoallv" in names
+    lib = mcr.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/mcr.h but not exported by libmcr.so"
+
+
+def test_binding_has_the_same_names():
+    for n in declared_symbols():
+        assert hasattr(mcr, n), f"the Python binding lacks {n}"
+
+
+def test_strerror_and_variants(ctx):
+    assert mcr.strerror(0) == "ok"
+    for code in range(-9, 0):
+        assert mcr.strerror(code) not in ("ok", "unknown status")
+    for op in range(10):
+        v = mcr.mcr_get_variants(ctx, op)
+        assert v[0] == "scalar" and len(v) == len(set(v)) == 8
+    assert mcr.mcr_get_variants(ctx, mcr.OP_MOE_ROUTE) == ["wave_ballot"]
+    with pytest.raises(mcr.McrError) as e:
+        mcr.mcr_get_variants(ctx, 99)
+    assert e.value.status == mcr.EOP
+
+
+def _status(fn, *a, **k):
+    try:
+        fn(*a, **k)
+    except mcr.McrError as e:
+        return e.status
+    return 0
+
+
+A16 = [0x10000 * (i + 1) for i in range(16)]       # fake, 16-byte aligned device addresses (never dereferenced)
+
+
+def test_validation_errors(ctx):
+    S = mcr
+    # a fully valid call passes validation and then stops at the host-only context
+    assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, S.SUM, 4, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, 7, S.SUM, 4, S.AUTO, 0) == S.EDTYPE
+    assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, 9, 4, S.AUTO, 0) == S.EOP
+    assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, S.SUM, 0, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_allreduce, ctx, A16[:4] + A16, 1024, S.F32, S.SUM, 17, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_allreduce, ctx, [A16[0], 0], 1024, S.F32, S.SUM, 2, S.AUTO, 0) == S.EINVAL      # null rank buffer
+    assert _status(S.mcr_allreduce, ctx, [A16[0], A16[1] + 2], 8, S.F32, S.SUM, 2, S.AUTO, 0) == S.EINVAL  # not element aligned
+    assert _status(S.mcr_allreduce, ctx, A16[:2], 8, S.F32, S.SUM, 2, 99, 0) == S.EVARIANT
+    assert _status(S.mcr_allreduce, ctx, [A16[0], A16[1] + 4], 8, S.F32, S.SUM, 2, 3, 0) == S.EVARIANT    # vector variant, misaligned
+    assert _status(S.mcr_allreduce, ctx, [A16[0], A16[1] + 4], 8, S.F32, S.SUM, 2, S.AUTO, 0) == S.ESTATE  # AUTO falls back
+    # count must divide by P
+    assert _status(S.mcr_reduce_scatter, ctx, A16[:3], A16[3:6], 10, S.F32, S.SUM, 3, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_alltoall, ctx, A16[:3], A16[3:6], 10, S.BF16, 3, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_reduce_scatter, ctx, A16[:3], A16[3:6], 12, S.F32, S.SUM, 3, S.AUTO, 0) == S.ESTATE
+    # slices of 1 element cannot use a 128-bit variant
+    assert _status(S.mcr_reduce_scatter, ctx, A16[:3], A16[3:6], 3, S.F32, S.SUM, 3, 1, 0) == S.EVARIANT
+    assert _status(S.mcr_allgather, ctx, A16[:2], A16[2:4], 3, S.BF16, 2, 2, 0) == S.EVARIANT
+    # alltoallv: negative split, row/column sums against the declared rows, equal split divisibility
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[1, -1], [0, 0]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 4], [0, 0]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 0], [4, 0]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 3], [3, 5]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], None, False, 7, 8, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[1, 1], [1, 1]], False, 8, 8, 3, S.BF16, 2, 3, 0) == S.EVARIANT
+    # MoE routing
+    assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 6, 4, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL      # P does not divide E
+    assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 1024, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL  # too many experts
+    assert _status(S.mcr_moe_route, ctx, A16[:2], -1, 4, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL
+    assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 4, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.ESTATE
+    # pack / unpack
+    assert _status(S.mcr_pack, ctx, A16[:1], A16[1:2], [0], 8, 8, 4, S.F32, 1, S.AUTO, 0) == S.EINVAL           # null slot
+    assert _status(S.mcr_unpack, ctx, A16[:1], A16[1:2], A16[2:3], None, 8, 8, 3, S.F32, 1, 1, 0) == S.EVARIANT
+    assert _status(S.mcr_unpack, ctx, A16[:1], A16[1:2], A16[2:3], A16[3:4], 8, 8, 4, S.F32, 1, S.AUTO, 0) == S.ESTATE
+
+
+def test_null_context_is_rejected():
+    assert _status(mcr.mcr_allreduce, None, A16[:2], 8, mcr.F32, mcr.SUM, 2, mcr.AUTO, 0) == mcr.EINVAL
+    assert _status(mcr.mcr_tune_set, None, 0, 0, 8, 4096, 1) == mcr.EINVAL
+
+
+# ------------------------------------------------------------------- tuning table
+def test_tuning_table_reproduces_table2(ctx, tmp_path):
+    """Table II of the paper as a fixture: three 'backends' stand for three variants."""
+    mcr.mcr_tune_clear(ctx)
+    rows = [s.split() for s in gio.lines("table2_allgather.txt")]
+    backend_to_variant = {"MVAPICH2-GDR": 1, "NCCL": 3, "SCCL": 6}
+    for size, backend in reversed(rows):                       # insertion order must not matter
+        mcr.mcr_tune_set(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, int(size), backend_to_variant[backend])
+    sizes = [int(r[0]) for r in rows]
+    choice = [backend_to_variant[r[1]] for r in rows]
+    for probe in [1, 255, 256, 257, 2048, 4095, 4096, 4097, 8192, 16383, 16384, 32768, 1 << 30]:
+        assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, probe) == oracle.tune_lookup(sizes, choice, probe)
+    assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 4095) == 1
+    assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 4096) == 3
+    assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 100) == 1          # below the first row
+    assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 1 << 40) == 6      # above the last row
+    # other keys have no table
+    assert _status(mcr.mcr_tune_get, ctx, mcr.OP_ALLGATHER, mcr.BF16, 8, 4096) == mcr.EVARIANT
+    assert _status(mcr.mcr_tune_get, ctx, mcr.OP_ALLGATHER, mcr.F32, 4, 4096) == mcr.EVARIANT
+    # entry count = collectives x scales x message sizes
+    assert mcr.mcr_tune_count(ctx) == 1 * 1 * 8
+    mcr.mcr_tune_set(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 4096, 2)                  # overwrite, no new row
+    assert mcr.mcr_tune_count(ctx) == 8 and mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 5000) == 2
+    for P in (2, 4):
+        for size in sizes:
+            mcr.mcr_tune_set(ctx, mcr.OP_ALLREDUCE, mcr.BF16, P, size, 4)
+    assert mcr.mcr_tune_count(ctx) == 8 + 1 * 2 * 8
+    # save / load round trip
+    path = str(tmp_path / "table.txt")
+    mcr.mcr_tune_save(ctx, path)
+    other = mcr.mcr_init(-1)
+    try:
+        mcr.mcr_tune_load(other, path)
+        assert mcr.mcr_tune_count(other) == 24
+        for probe in [1, 300, 4096, 9000, 1 << 20]:
+            assert mcr.mcr_tune_get(other, mcr.OP_ALLGATHER, mcr.F32, 8, probe) == mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, probe)
+            assert mcr.mcr_tune_get(other, mcr.OP_ALLREDUCE, mcr.BF16, 4, probe) == 4
+    finally:
+        mcr.mcr_finalize(other)
+    # a malformed file changes nothing
+    bad = tmp_path / "bad.txt"
+    bad.write_text("allgather f32 8 4096 v4\nallgather f32 8 oops v4\n")
+    assert _status(mcr.mcr_tune_load, ctx, str(bad)) == mcr.EIO
+    assert mcr.mcr_tune_count(ctx) == 24
+    assert _status(mcr.mcr_tune_load, ctx, str(tmp_path / "missing.txt")) == mcr.EIO
+    assert _status(mcr.mcr_tune_set, ctx, 0, 0, 8, 4096, 99) == mcr.EVARIANT
+    assert _status(mcr.mcr_tune_set, ctx, 99, 0, 8, 4096, 1) == mcr.EOP
+    mcr.mcr_tune_clear(ctx)
+    assert mcr.mcr_tune_count(ctx) == 0
+
+
+def test_shipped_tuning_table_is_well_formed(ctx):
+    """The table measured on MI355X that ships with the package loads, and holds a row for
+    every (op, dtype, size) cell of the sweep at P=8."""
+    path = os.path.join(ROOT, "paper_2303_08374_amd", "tuning", "mi355x.tbl")
+    if not os.path.exists(path):
+        pytest.skip("no shipped table yet")
+    mcr.mcr_tune_clear(ctx)
+    mcr.mcr_tune_load(ctx, path)
+    n_ops, n_dtypes, n_sizes = len(inputs.SWEEP_OPS), len(inputs.SWEEP_DTYPES), len(inputs.SWEEP_BYTES)
+    assert mcr.mcr_tune_count(ctx) >= n_ops * n_dtypes * n_sizes
+    for op in range(4):
+        for dt in (mcr.F32, mcr.BF16):
+            for b in inputs.SWEEP_BYTES:
+                assert 0 <= mcr.mcr_tune_get(ctx, op, dt, inputs.SWEEP_P, b) < 8
+    mcr.mcr_tune_clear(ctx)
+
+
+# ---------------------------------------------------------------------- bucket plan
+def test_fuse_plan_matches_oracle_and_fixture(ctx):
+    g = gio.keyed_ints("fuse_plan_case.txt")
+    plan = mcr.mcr_fuse_plan_create(ctx, g["numel"], g["B"][0], mcr.BF16)
+    bn, tb, to = mcr.mcr_fuse_plan_info(plan, len(g["numel"]))
+    mcr.mcr_fuse_plan_destroy(plan)
+    assert bn == g["bucket_numel"] and tb == g["tensor_bucket"] and to == g["tensor_offset"]
+    w = inputs.GradBucketWorkload()
+    rng = np.random.Generator(np.random.Philox(key=3))
+    cases = [(w.numel(), w.bucket_elems), (w.numel()[::-1], w.bucket_elems), ([], 10), ([5], 5), ([6], 5),
+             ([0, 0, 3, 0], 2)]
+    cases += [(rng.integers(1, 50, size=40).tolist(), int(B)) for B in (1, 7, 49, 50, 1000)]
+    for numel, B in cases:
+        plan = mcr.mcr_fuse_plan_create(ctx, numel, B, mcr.F32)
+        bn, tb, to = mcr.mcr_fuse_plan_info(plan, len(numel))
+        otb, oto, obn = oracle.fuse_plan(numel, B)
+        assert bn == obn.tolist() and tb == otb.tolist() and to == oto.tolist(), (numel[:8], B)
+        # a host-only context cannot bind or launch
+        assert _status(mcr.mcr_fuse_plan_bind, ctx, plan, [A16[0]] * max(len(numel), 1), 1) in (mcr.ESTATE, mcr.EINVAL)
+        assert _status(mcr.mcr_allreduce_multi, ctx, plan, -1, mcr.SUM, mcr.AUTO, 0) == mcr.ESTATE
+        mcr.mcr_fuse_plan_destroy(plan)
+    assert _status(mcr.mcr_fuse_plan_create, ctx, [1, 2], 0, mcr.F32) == mcr.EINVAL
+    assert _status(mcr.mcr_fuse_plan_create, ctx, [1, 2], 4, 5) == mcr.EDTYPE

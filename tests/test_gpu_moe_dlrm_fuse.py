@@ -1,0 +1,357 @@
+"""GPU parity of MoE routing / pack / unpack / combine, the DLRM embedding shuffle and tensor
+fusion against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2303_08374_amd import inputs, mcr
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+# ------------------------------------------------------------------------ routing
+def _route_gpu(ids_per_rank, E, C):
+    P = len(ids_per_rank)
+    T = len(ids_per_rank[0])
+    d_ids = [_i32(x) for x in ids_per_rank]
+    d_slot = [torch.full((max(T, 1),), -77, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_cnt = [torch.full((E,), -77, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_S = torch.full((P * P,), -77, dtype=torch.int64, device="cuda")
+    mcr.mcr_moe_route(gu.ctx(), d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+    gu.sync()
+    return [s.cpu().numpy()[:T] for s in d_slot], [c.cpu().numpy() for c in d_cnt], d_S.cpu().numpy().reshape(P, P)
+
+
+@pytest.mark.parametrize("T", [0, 1, 63, 64, 65, 1000, 16384, 20001])
+@pytest.mark.parametrize("E,P", [(1, 1), (4, 2), (64, 16), (512, 8), (48, 3)])
+def test_moe_route_matches_oracle(T, E, P):
+    g = np.random.Generator(np.random.Philox(key=T * 1000 + E))
+    for C in (0, 1, max(1, int(np.ceil(1.25 * T / E))), 1 << 30):
+        ids = [g.integers(0, E, size=T).astype(np.int32) for _ in range(P)]
+        if T > 10:
+            ids[0][::7] = -1                # out-of-range ids are dropped
+            ids[P - 1][3] = E
+            ids[P - 1][:] = np.where(g.random(T) < 0.7, 0, ids[P - 1])     # a very hot expert
+        slot, cnt, S = _route_gpu(ids, E, C)
+        for p in range(P):
+            es, ec, er = oracle.moe_route(ids[p], E, P, C)
+            assert np.array_equal(slot[p], es), (T, E, P, C, p)
+            assert np.array_equal(cnt[p], ec), (T, E, P, C, p)
+            assert np.array_equal(S[p], er), (T, E, P, C, p)
+
+
+def test_moe_route_zipf_workload():
+    w = inputs.MoEWorkload()
+    for permute in (False, True):
+        ids = [w.ids(p, permute) for p in range(w.P)]
+        slot, cnt, S = _route_gpu(ids, w.E, w.C)
+        for p in range(w.P):
+            es, ec, er = oracle.moe_route(ids[p], w.E, w.P, w.C)
+            assert np.array_equal(slot[p], es) and np.array_equal(cnt[p], ec) and np.array_equal(S[p], er)
+
+
+# ----------------------------------------------------------------- pack / unpack
+@pytest.mark.parametrize("dtype,w", [(mcr.F32, 1), (mcr.F32, 4), (mcr.F32, 128), (mcr.BF16, 5), (mcr.BF16, 8),
+                                      (mcr.BF16, 2048), (mcr.BF16, 24), (mcr.F32, 1028)])
+def test_pack_unpack_combine(dtype, w):
+    P, T, E = 3, 777, 12
+    g = np.random.Generator(np.random.Philox(key=w))
+    ids = [g.integers(0, E, size=T).astype(np.int32) for _ in range(P)]
+    routes = [oracle.moe_route(ids[p], E, P, 40) for p in range(P)]
+    slots = [r[0] for r in routes]
+    out_rows = max(int(r[1].sum()) for r in routes) + 1
+    toks = [inputs.normal(T * w, 800 + w, p, bf16=(dtype == mcr.BF16)) for p in range(P)]
+    gates = [inputs.uniform01(T, 900 + w, p) for p in range(P)]
+    fillv = 0x1111 if dtype == mcr.BF16 else 3.5
+    exp_packed, exp_plain, exp_comb = [], [], []
+    for p in range(P):
+        buf = np.full(out_rows * w, fillv, dtype=gu.NPDT[dtype])
+        oracle.pack(toks[p], slots[p], w, dtype, buf)
+        exp_packed.append(buf)
+        exp_plain.append(oracle.unpack(buf, slots[p], None, w, dtype))
+        exp_comb.append(oracle.unpack(buf, slots[p], gates[p], w, dtype))
+    vec_ok = (w * gu.EB[dtype]) % 16 == 0
+    d_slot = [_i32(s) for s in slots]
+    d_gate = [torch.from_numpy(x).cuda() for x in gates]
+    for variant in [mcr.AUTO, 0] + ([1, 5] if vec_ok else []):
+        d_tok = [gu.to_dev(t) for t in toks]
+        d_packed = [gu.to_dev(np.full(out_rows * w, fillv, dtype=gu.NPDT[dtype])) for _ in range(P)]
+        mcr.mcr_pack(gu.ctx(), d_packed, d_tok, d_slot, T, out_rows, w, dtype, P, variant)
+        d_plain = [gu.dev_empty(T * w, dtype, 1) for _ in range(P)]
+        d_comb = [gu.dev_empty(T * w, dtype, 1) for _ in range(P)]
+        mcr.mcr_unpack(gu.ctx(), d_plain, d_packed, d_slot, None, T, out_rows, w, dtype, P, variant)
+        mcr.mcr_unpack(gu.ctx(), d_comb, d_packed, d_slot, d_gate, T, out_rows, w, dtype, P, variant)
+        gu.sync()
+        for p in range(P):
+            gu.assert_bits_equal(gu.to_host(d_packed[p], gu.NPDT[dtype]), exp_packed[p], f"pack w={w} v={variant}")
+            gu.assert_bits_equal(gu.to_host(d_plain[p], gu.NPDT[dtype]), exp_plain[p], f"unpack w={w} v={variant}")
+            gu.assert_bits_equal(gu.to_host(d_comb[p], gu.NPDT[dtype]), exp_comb[p], f"combine w={w} v={variant}")
+
+
+def test_pack_skips_slots_beyond_capacity():
+    T, w = 10, 4
+    slot = np.array([0, 5, 2, 99, -1, 1, 3, 4, 7, -5], dtype=np.int32)      # 99 and 7 exceed out_rows=6
+    tok = np.arange(T * w, dtype=np.float32)
+    d_out = [gu.dev_empty(6 * w, mcr.F32, -1.0)]
+    mcr.mcr_pack(gu.ctx(), d_out, [gu.to_dev(tok)], [_i32(slot)], T, 6, w, mcr.F32, 1, mcr.AUTO)
+    gu.sync()
+    got = gu.to_host(d_out[0], np.float32).reshape(6, w)
+    for t, s in enumerate(slot):
+        if 0 <= s < 6:
+            assert np.array_equal(got[s], tok.reshape(T, w)[t])
+
+
+def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None):
+    """route -> pack -> alltoallv(S, device resident) -> [identity experts] -> alltoallv(S^T) ->
+    gate-weighted combine, each stage compared with the oracle."""
+    P, T, H, E, C = w.P, w.T, w.H, w.E, w.C
+    ids = [w.ids(p, permute) for p in range(P)]
+    toks = [w.tokens(p) for p in range(P)]
+    gates = [w.gate(p) for p in range(P)]
+    send_rows, recv_rows = T, w.recv_rows
+    # device side
+    d_ids = [_i32(x) for x in ids]
+    d_tok = [gu.to_dev(t) for t in toks]
+    d_gate = [torch.from_numpy(x).cuda() for x in gates]
+    d_slot = [torch.empty(T, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_cnt = [torch.empty(E, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_S = torch.empty(P * P, dtype=torch.int64, device="cuda")
+    d_packed = [gu.dev_empty(send_rows * H, mcr.BF16, 0) for _ in range(P)]
+    d_recv = [gu.dev_empty(recv_rows * H, mcr.BF16, 0) for _ in range(P)]
+    d_back = [gu.dev_empty(send_rows * H, mcr.BF16, 0) for _ in range(P)]
+    d_out = [gu.dev_empty(T * H, mcr.BF16, 1) for _ in range(P)]
+    c = gu.ctx()
+    mcr.mcr_moe_route(c, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+    mcr.mcr_pack(c, d_packed, d_tok, d_slot, T, send_rows, H, mcr.BF16, P)
+    mcr.mcr_alltoallv(c, d_recv, d_packed, d_S, True, send_rows, recv_rows, H, mcr.BF16, P)
+    d_ST = d_S.view(P, P).t().contiguous()            # a 2 KB device-side transpose by torch: plumbing
+    mcr.mcr_alltoallv(c, d_back, d_recv, d_ST, True, recv_rows, send_rows, H, mcr.BF16, P)
+    mcr.mcr_unpack(c, d_out, d_back, d_slot, d_gate, T, send_rows, H, mcr.BF16, P)
+    gu.sync()
+    # oracle side
+    routes = [oracle.moe_route(ids[p], E, P, C) for p in range(P)]
+    S = np.stack([r[2] for r in routes])
+    assert np.array_equal(d_S.cpu().numpy().reshape(P, P), S)
+    packed = []
+    for p in range(P):
+        buf = np.zeros(send_rows * H, dtype=np.uint16)
+        oracle.pack(toks[p], routes[p][0], H, oracle.BF16, buf)
+        packed.append(buf)
+    recv = [np.zeros(recv_rows * H, dtype=np.uint16) for _ in range(P)]
+    oracle.alltoallv(packed, S, H, oracle.BF16, recv)
+    back = [np.zeros(send_rows * H, dtype=np.uint16) for _ in range(P)]
+    oracle.alltoallv(recv, S.T.copy(), H, oracle.BF16, back)
+    for p in (check_ranks if check_ranks is not None else range(P)):
+        assert np.array_equal(d_slot[p].cpu().numpy(), routes[p][0])
+        gu.assert_bits_equal(gu.to_host(d_packed[p], np.uint16), packed[p], f"packed r={p}")
+        gu.assert_bits_equal(gu.to_host(d_recv[p], np.uint16), recv[p], f"recv r={p}")
+        gu.assert_bits_equal(gu.to_host(d_back[p], np.uint16), back[p], f"back r={p}")
+        exp = oracle.unpack(back[p], routes[p][0], gates[p], H, oracle.BF16)
+        gu.assert_bits_equal(gu.to_host(d_out[p], np.uint16), exp, f"combine r={p}")
+
+
+def test_moe_pipeline_small():
+    _moe_pipeline(inputs.MoEWorkload(P=4, T=1000, H=72, E=8))
+    _moe_pipeline(inputs.MoEWorkload(P=2, T=333, H=7, E=6), permute=True)     # rows not a multiple of 16 bytes
+
+
+def test_moe_pipeline_config3_full_size():
+    """P=16, T=16384, H=2048 bf16, E=64, Zipf(1.2), capacity 320: every stage, every rank."""
+    _moe_pipeline(inputs.MoEWorkload())
+
+
+# ---------------------------------------------------------------------------- DLRM
+def _dlrm_maps(w: inputs.DLRMWorkload):
+    """Index maps for one rank's local permute between the alltoallv receive order
+    [(owner, local) table order][b] and the batch-major layout [b][table]."""
+    bl = w.batch // w.P
+    order = [t for p in range(w.P) for t in w.tables_on(p)]          # receive order of tables
+    pos = {t: k for k, t in enumerate(order)}
+    b = np.arange(bl)[:, None]
+    t = np.arange(w.n_tables)[None, :]
+    recv_row = np.vectorize(pos.get)(t) * bl + b                      # [bl, n_tables] -> row in recv
+    return recv_row.reshape(-1).astype(np.int32)
+
+
+def _dlrm_roundtrip(w: inputs.DLRMWorkload, payload="normal"):
+    P, NT, D, B = w.P, w.n_tables, w.dim, w.batch
+    bl = B // P
+    src = []
+    for p in range(P):
+        if payload == "normal":
+            src.append(w.pooled(p))
+        else:   # closed form: value = table * 2^14 + global batch index + column / 256
+            tabs = w.tables_on(p)
+            v = np.empty((len(tabs), B, D), dtype=np.float32)
+            for li, t in enumerate(tabs):
+                v[li] = (t * (1 << 14) + np.arange(B))[:, None] + np.arange(D)[None, :] / 256.0
+            src.append(v.reshape(-1))
+    S = w.splits()
+    # the send buffer of rank p must be ordered by destination: [r][local table][b]; the pooled
+    # source is [local table][B] = [local table][r][b], so this is itself an equal-block shuffle
+    # of rows; done here with the same pack primitive (slot = destination-major row index).
+    c = gu.ctx()
+    n_local = [len(w.tables_on(p)) for p in range(P)]
+    max_rows = max(n_local) * B
+    send_slot = []
+    for p in range(P):
+        lt, r, b = np.meshgrid(np.arange(n_local[p]), np.arange(P), np.arange(bl), indexing="ij")
+        s = (r * n_local[p] + lt) * bl + b
+        full = np.full(max_rows, -1, dtype=np.int32)
+        full[: s.size] = s.reshape(-1)
+        send_slot.append(full)
+    d_src = [gu.to_dev(np.concatenate([s, np.zeros(max_rows * D - s.size, dtype=np.float32)])) for s in src]
+    d_send = [gu.dev_empty(max_rows * D, mcr.F32, 0) for _ in range(P)]
+    d_recv = [gu.dev_empty(NT * bl * D, mcr.F32, 0) for _ in range(P)]
+    d_out = [gu.dev_empty(bl * NT * D, mcr.F32, 0) for _ in range(P)]
+    d_sslot = [_i32(s) for s in send_slot]
+    perm = _dlrm_maps(w)
+    d_perm = [_i32(perm) for _ in range(P)]
+    mcr.mcr_pack(c, d_send, d_src, d_sslot, max_rows, max_rows, D, mcr.F32, P)
+    mcr.mcr_alltoallv(c, d_recv, d_send, S, False, max_rows, NT * bl, D, mcr.F32, P)
+    mcr.mcr_unpack(c, d_out, d_recv, d_perm, None, bl * NT, NT * bl, D, mcr.F32, P)
+    gu.sync()
+    exp = oracle.dlrm_forward(src, NT, B, D, oracle.F32)
+    for r in range(P):
+        gu.assert_bits_equal(gu.to_host(d_out[r], np.float32), exp[r], f"dlrm fwd r={r}")
+    if payload != "normal":
+        for r in range(P):
+            o = gu.to_host(d_out[r], np.float32).reshape(bl, NT, D)
+            b, t, col = np.meshgrid(np.arange(bl), np.arange(NT), np.arange(D), indexing="ij")
+            assert np.array_equal(o, (t * (1 << 14) + r * bl + b + col / 256.0).astype(np.float32))
+    # backward: the inverse permutation.  grad_out [bl][NT] -> recv order (pack with the same map),
+    # alltoallv with S^T, then back to table-major (unpack with the send map).
+    d_grecv = [gu.dev_empty(NT * bl * D, mcr.F32, 0) for _ in range(P)]
+    d_gsend = [gu.dev_empty(max_rows * D, mcr.F32, 0) for _ in range(P)]
+    d_gsrc = [gu.dev_empty(max_rows * D, mcr.F32, 0) for _ in range(P)]
+    mcr.mcr_pack(c, d_grecv, d_out, d_perm, bl * NT, NT * bl, D, mcr.F32, P)
+    mcr.mcr_alltoallv(c, d_gsend, d_grecv, S.T.copy(), False, NT * bl, max_rows, D, mcr.F32, P)
+    mcr.mcr_unpack(c, d_gsrc, d_gsend, d_sslot, None, max_rows, max_rows, D, mcr.F32, P)
+    gu.sync()
+    gexp = oracle.dlrm_backward(exp, NT, B, D, oracle.F32)
+    for p in range(P):
+        got = gu.to_host(d_gsrc[p], np.float32)[: src[p].size]
+        gu.assert_bits_equal(got, gexp[p], f"dlrm bwd r={p}")
+        gu.assert_bits_equal(got, src[p], f"dlrm bwd(fwd) r={p}")
+
+
+def test_dlrm_small_closed_form():
+    _dlrm_roundtrip(inputs.DLRMWorkload(P=4, n_tables=10, dim=8, batch=64), payload="closed")
+
+
+def test_dlrm_config4_full_size():
+    """P=8, 26 tables x [16384, 128] fp32 round-robin, batch-sharded output [2048, 26, 128]."""
+    _dlrm_roundtrip(inputs.DLRMWorkload(), payload="normal")
+    _dlrm_roundtrip(inputs.DLRMWorkload(), payload="closed")
+
+
+# ------------------------------------------------------------------- tensor fusion
+def _fusion_case(numel, B, dtype, P, seed, variants):
+    c = gu.ctx()
+    plan = mcr.mcr_fuse_plan_create(c, numel, B, dtype)
+    try:
+        bn, tb, to = mcr.mcr_fuse_plan_info(plan, len(numel))
+        otb, oto, obn = oracle.fuse_plan(numel, B)
+        assert bn == obn.tolist() and tb == otb.tolist() and to == oto.tolist()
+        bf = dtype == mcr.BF16
+        host = [[inputs.normal(n, seed, p, i, std=1e-3, bf16=bf) for i, n in enumerate(numel)] for p in range(P)]
+        # tensors live at odd offsets inside one arena per rank so that some are only element-aligned
+        def arena(p):
+            offs, cur = [], 1
+            for n in numel:
+                offs.append(cur)
+                cur += n + (1 if n % 2 else 0)
+            a = np.zeros(cur + 8, dtype=gu.NPDT[dtype])
+            for i, n in enumerate(numel):
+                a[offs[i]: offs[i] + n] = host[p][i]
+            return a, offs
+        for variant in variants:
+            arenas, views = [], []
+            for p in range(P):
+                a, offs = arena(p)
+                d = gu.to_dev(a)
+                arenas.append(d)
+                views += [d[offs[i]: offs[i] + numel[i]] for i in range(len(numel))]
+            mcr.mcr_fuse_plan_bind(c, plan, views, P)
+            for k in range(len(bn)):
+                idx = [i for i in range(len(numel)) if tb[i] == k]
+                flats = [gu.dev_empty(bn[k] + 3, dtype, 0) for _ in range(P)]
+                fviews = [f[1:1 + bn[k]] if (k % 2) else f[:bn[k]] for f in flats]     # odd buckets: misaligned flat
+                mcr.mcr_fuse(c, plan, k, fviews, P, variant)
+                gu.sync()
+                for p in range(P):
+                    exp = oracle.fuse([host[p][i] for i in idx], [to[i] for i in idx], bn[k], dtype)
+                    gu.assert_bits_equal(gu.to_host(fviews[p], gu.NPDT[dtype]), exp, f"fuse k={k} v={variant}")
+                # reduce the flat buckets, then unfuse into the tensors
+                mcr.mcr_allreduce(c, fviews, bn[k], dtype, mcr.AVG, P, mcr.AUTO)
+                mcr.mcr_unfuse(c, plan, k, fviews, P, variant)
+            gu.sync()
+            exp_t = [[t.copy() for t in host[p]] for p in range(P)]
+            for i in range(len(numel)):
+                oracle.allreduce([exp_t[p][i] for p in range(P)], dtype, oracle.AVG)
+            for p in range(P):
+                for i in range(len(numel)):
+                    gu.assert_reduced_equal(gu.to_host(views[p * len(numel) + i], gu.NPDT[dtype]), exp_t[p][i], dtype,
+                                            f"fuse->allreduce->unfuse t={i} v={variant}")
+            # the fused small-message path must give the same tensors without a flat buffer
+            arenas2, views2 = [], []
+            for p in range(P):
+                a, offs = arena(p)
+                d = gu.to_dev(a)
+                arenas2.append(d)
+                views2 += [d[offs[i]: offs[i] + numel[i]] for i in range(len(numel))]
+            mcr.mcr_fuse_plan_bind(c, plan, views2, P)
+            mcr.mcr_allreduce_multi(c, plan, -1, mcr.AVG, variant)
+            gu.sync()
+            for p in range(P):
+                for i in range(len(numel)):
+                    gu.assert_reduced_equal(gu.to_host(views2[p * len(numel) + i], gu.NPDT[dtype]), exp_t[p][i], dtype,
+                                            f"allreduce_multi t={i} v={variant}")
+                # nothing outside the tensors was written
+                a, offs = arena(p)
+                got = gu.to_host(arenas2[p], gu.NPDT[dtype])
+                mask = np.ones(a.size, dtype=bool)
+                for i, n in enumerate(numel):
+                    mask[offs[i]: offs[i] + n] = False
+                assert np.array_equal(got[mask], a[mask])
+    finally:
+        mcr.mcr_fuse_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("dtype", [mcr.F32, mcr.BF16])
+def test_fusion_odd_sizes(dtype):
+    _fusion_case([1, 3, 7, 8191, 2, 64, 20000, 5, 4096, 8192, 16385], 9000, dtype, P=3, seed=1000, variants=[mcr.AUTO, 0, 3, 5])
+
+
+def test_fusion_scaled_down_gpt_list():
+    w = inputs.GradBucketWorkload(layers=2, hidden=64, ffn=256, vocab=1000, bucket_elems=30000)
+    _fusion_case(w.numel(), w.bucket_elems, mcr.BF16, P=8, seed=w.seed, variants=[mcr.AUTO])
+
+
+def test_allreduce_multi_single_bucket():
+    """bucket >= 0 reduces only that bucket's tensors."""
+    numel = [100, 200, 5000, 50]
+    c = gu.ctx()
+    plan = mcr.mcr_fuse_plan_create(c, numel, 300, mcr.F32)
+    try:
+        bn, tb, to = mcr.mcr_fuse_plan_info(plan, len(numel))
+        P = 2
+        host = [[inputs.normal(n, 1100, p, i) for i, n in enumerate(numel)] for p in range(P)]
+        dev = [[gu.to_dev(t) for t in host[p]] for p in range(P)]
+        mcr.mcr_fuse_plan_bind(c, plan, [t for p in range(P) for t in dev[p]], P)
+        mcr.mcr_allreduce_multi(c, plan, 0, mcr.SUM, mcr.AUTO)
+        gu.sync()
+        for i in range(len(numel)):
+            exp = [host[p][i].copy() for p in range(P)]
+            if tb[i] == 0:
+                oracle.allreduce(exp, oracle.F32, oracle.SUM)
+            for p in range(P):
+                gu.assert_bits_equal(gu.to_host(dev[p][i], np.float32), exp[p], f"bucket-0 only t={i}")
+    finally:
+        mcr.mcr_fuse_plan_destroy(plan)
