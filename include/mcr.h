@@ -246,6 +246,10 @@ int mcr_fuse_plan_destroy(mcr_fuse_plan* plan);
  * T*row bytes for pack/unpack; bucket bytes for fuse/unfuse/allreduce_multi. */
 int mcr_tune_set(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int variant);
 int mcr_tune_get(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int* variant);
+/* What MCR_AUTO would choose for this key and size: the table's row if there is one, else
+ * the built-in default; the scalar variant when vec_ok == 0 (shape or alignment rules the
+ * 128-bit variants out). */
+int mcr_auto_variant(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int vec_ok, int* variant);
 int mcr_tune_clear(mcr_ctx* ctx);
 /* Number of rows over all tables (Num_Collectives x Num_Scales x Num_Message_Sizes). */
 int mcr_tune_count(mcr_ctx* ctx, size_t* n_rows);

@@ -1,0 +1,90 @@
+// all_reduce over P rank buffers in one GPU's memory (API listing of the paper).
+//
+// A streaming sum: every element index is read from all P buffers with 128-bit
+// loads, summed in rank order in binary32, optionally scaled by 1/P, rounded
+// once, and written back to all P buffers with 128-bit stores.  The thread that
+// reads an index is the only one that writes it, so in place has no race.
+// Bound by HBM bandwidth: (P-1) adds per 2*P*s bytes.
+#include "mcr_reduce_tile.hpp"
+
+namespace mcr {
+namespace {
+
+template <int DT, int P, int U, bool NTL, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale) {
+  using E = Elem<DT>;
+  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
+  CPtrTab in;
+#pragma unroll
+  for (int p = 0; p < P; ++p) in.p[p] = bufs.p[p];
+  const size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
+  if (tile < nvec) {
+    u32x4 out[U];
+    const bool full = tile + kTile <= nvec;
+    if (full) reduce_tile<DT, P, U, NTL, true>(in, 0, tile, nvec, scale, do_scale != 0, out);
+    else reduce_tile<DT, P, U, NTL, false>(in, 0, tile, nvec, scale, do_scale != 0, out);
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+        if (full || idx < nvec) store16<NTS>(bufs.p[p], idx, out[u]);
+      }
+    }
+  }
+  // elements past the last whole vector
+  const size_t done = nvec * E::kPerVec;
+  if (blockIdx.x == 0 && done + threadIdx.x < count) {
+    const size_t i = done + threadIdx.x;
+    const float y = reduce_scalar<DT>(in, i, P, scale, do_scale != 0);
+#pragma unroll
+    for (int p = 0; p < P; ++p) E::store1(bufs.p[p], i, y);
+  }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kBlock)
+allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int do_scale) {
+  using E = Elem<DT>;
+  CPtrTab in;
+  for (int p = 0; p < MCR_MAX_RANKS; ++p) in.p[p] = bufs.p[p];
+  const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += step) {
+    const float y = reduce_scalar<DT>(in, i, P, scale, do_scale != 0);
+    for (int p = 0; p < P; ++p) E::store1(bufs.p[p], i, y);
+  }
+}
+
+}  // namespace
+
+int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P,
+                     int variant, hipStream_t stream) {
+  if (count == 0) return MCR_OK;
+  const float scale = 1.0f / static_cast<float>(P);
+  const int do_scale = (op == MCR_AVG) ? 1 : 0;
+  if (variant == SV_SCALAR) {
+    return dispatch_dtype(dtype, [&](auto dt) {
+      constexpr int DT = decltype(dt)::value;
+      hipLaunchKernelGGL((allreduce_scalar<DT>), dim3(scalar_grid(count)), dim3(kBlock), 0, stream,
+                         bufs, count, P, scale, do_scale);
+      return launch_status();
+    });
+  }
+  const size_t nvec = count / per_vec(dtype);
+  const unsigned gx = grid_x(nvec, variant);
+  return dispatch_dtype(dtype, [&](auto dt) {
+    return dispatch_ranks(P, [&](auto pp) {
+      return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
+        constexpr int DT = decltype(dt)::value;
+        constexpr int kP = decltype(pp)::value;
+        constexpr int U = decltype(uu)::value;
+        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value>),
+                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, do_scale);
+        return launch_status();
+      });
+    });
+  });
+}
+
+}  // namespace mcr

@@ -12,7 +12,8 @@
 
 namespace mcr {
 
-const char* const kStreamVariantNames[SV_COUNT] = {"scalar", "v1", "v2", "v4", "v2nt", "v4nt", "pv2", "pv2nt"};
+const char* const kStreamVariantNames[AG_COUNT] = {"scalar", "v1", "v2", "v4", "v1nt", "v2nt", "v4nt", "v1ln", "v2ln", "v4ln",
+                                                   "v1sn", "v2sn", "v4sn", "sc4", "sc8", "sc16"};
 
 namespace {
 
@@ -25,7 +26,7 @@ const char* const kRouteVariantNames[1] = {"wave_ballot"};
 bool valid_dtype(int d) { return d == MCR_F32 || d == MCR_BF16; }
 bool valid_redop(int o) { return o == MCR_SUM || o == MCR_AVG; }
 bool valid_P(int P) { return P >= 1 && P <= MCR_MAX_RANKS; }
-int n_variants(int op) { return op == MCR_OP_MOE_ROUTE ? 1 : SV_COUNT; }
+int n_variants(int op) { return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : SV_COUNT; }
 
 bool elem_aligned(const void* p, int dtype) {
   return (reinterpret_cast<uintptr_t>(p) & (elem_bytes(dtype) - 1)) == 0;
@@ -70,11 +71,11 @@ int resolve_variant(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes, bool v
   if (variant == MCR_AUTO) {
     if (!vec_ok) { *out = SV_SCALAR; return MCR_OK; }
     int v = table_lookup(ctx, op, dtype, P, bytes);
-    if (v < 0 || v >= SV_COUNT) v = default_variant(bytes);
+    if (v < 0 || v >= n_variants(op)) v = default_variant(bytes);
     *out = v;
     return MCR_OK;
   }
-  if (variant < 0 || variant >= SV_COUNT) return MCR_EVARIANT;
+  if (variant < 0 || variant >= n_variants(op)) return MCR_EVARIANT;
   if (variant != SV_SCALAR && !vec_ok) return MCR_EVARIANT;
   *out = variant;
   return MCR_OK;
@@ -532,6 +533,14 @@ int mcr_tune_get(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, 
   if (v < 0) return MCR_EVARIANT;
   *variant = v;
   return MCR_OK;
+}
+
+int mcr_auto_variant(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, int vec_ok, int* variant) {
+  if (!ctx || !variant || !valid_P(P)) return MCR_EINVAL;
+  if (op_id < 0 || op_id >= MCR_OP_COUNT) return MCR_EOP;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (op_id == MCR_OP_MOE_ROUTE) { *variant = 0; return MCR_OK; }
+  return resolve_variant(ctx, op_id, dtype, P, bytes, vec_ok != 0, MCR_AUTO, variant);
 }
 
 int mcr_tune_clear(mcr_ctx* ctx) {

@@ -26,8 +26,9 @@ __device__ __forceinline__ void store_unit(void* base, size_t i, T v) {
 }
 
 // ---- all_gather -----------------------------------------------------------------
-// blockIdx.y = source rank p; its m units land at offset p*m of every output.
-template <int UB, int P, int U, bool NT, bool PERSIST>
+// Classic form.  blockIdx.y = source rank p; its m units land at offset p*m of every
+// output: one load, P stores per thread.
+template <int UB, int P, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 allgather_kernel(PtrTab out, CPtrTab in, size_t m) {
   typedef typename Unit<UB>::type T;
@@ -35,55 +36,72 @@ allgather_kernel(PtrTab out, CPtrTab in, size_t m) {
   const unsigned p = blockIdx.y;
   const void* src = in.p[p];
   const size_t off = static_cast<size_t>(p) * m;
-  size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
   const size_t step = static_cast<size_t>(gridDim.x) * kTile;
-  while (tile < m) {
+  for (size_t tile = static_cast<size_t>(blockIdx.x) * kTile; tile < m; tile += step) {
     T v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-      if (idx < m) v[u] = load_unit<NT, T>(src, idx);
+      if (idx < m) v[u] = load_unit<NTL, T>(src, idx);
     }
 #pragma unroll
     for (int r = 0; r < P; ++r) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-        if (idx < m) store_unit<NT, T>(out.p[r], off + idx, v[u]);
+        if (idx < m) store_unit<NTS, T>(out.p[r], off + idx, v[u]);
       }
     }
-    if (!PERSIST) break;
-    tile += step;
   }
 }
 
+// Super-chunk form.  P simultaneous write streams cost the memory system more than
+// one, so the message of each source is cut into super-chunks of `bpc` workgroup
+// tiles, and the workgroups are numbered [source p (y)] [super-chunk] [destination
+// r] [tile]: in dispatch order the chip copies one super-chunk to destination 0,
+// then the same super-chunk to destination 1, ...  Re-reads of the super-chunk are
+// served by the last-level cache (plain loads); the stores are nontemporal so they
+// do not push it out.  HBM traffic stays at one read and P writes per unit.
+__global__ void __launch_bounds__(kBlock)
+allgather_superchunk_kernel(PtrTab out, CPtrTab in, size_t mvec, unsigned bpc, unsigned P) {
+  const unsigned p = blockIdx.y;
+  const unsigned per_sc = P * bpc;
+  const size_t sc = blockIdx.x / per_sc;
+  const unsigned rem = blockIdx.x - static_cast<unsigned>(sc * per_sc);
+  const unsigned r = rem / bpc, j = rem - r * bpc;
+  const size_t idx = (sc * bpc + j) * static_cast<size_t>(kBlock) + threadIdx.x;
+  if (idx >= mvec) return;
+  const u32x4 v = load16<false>(in.p[p], idx);
+  store16<true>(out.p[r], static_cast<size_t>(p) * mvec + idx, v);
+}
+
 // ---- all_to_all_single, equal split ---------------------------------------------
-// blockIdx.y = destination r, blockIdx.z = source p; block (p -> r) is b units.
-template <int UB, int U, bool NT, bool PERSIST>
+// blockIdx.y = source p, blockIdx.z = destination r; block (p -> r) is b units.  In
+// dispatch order (x, then y, then z) each output buffer is written front to back
+// while the reads hop between sources: writes are the side that is sensitive to
+// many interleaved streams.
+template <int UB, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 alltoall_kernel(PtrTab out, CPtrTab in, size_t b) {
   typedef typename Unit<UB>::type T;
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
-  const unsigned r = blockIdx.y, p = blockIdx.z;
+  const unsigned p = blockIdx.y, r = blockIdx.z;
   const void* src = in.p[p];
   void* dst = out.p[r];
   const size_t soff = static_cast<size_t>(r) * b, doff = static_cast<size_t>(p) * b;
-  size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
   const size_t step = static_cast<size_t>(gridDim.x) * kTile;
-  while (tile < b) {
+  for (size_t tile = static_cast<size_t>(blockIdx.x) * kTile; tile < b; tile += step) {
     T v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-      if (idx < b) v[u] = load_unit<NT, T>(src, soff + idx);
+      if (idx < b) v[u] = load_unit<NTL, T>(src, soff + idx);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-      if (idx < b) store_unit<NT, T>(dst, doff + idx, v[u]);
+      if (idx < b) store_unit<NTS, T>(dst, doff + idx, v[u]);
     }
-    if (!PERSIST) break;
-    tile += step;
   }
 }
 
@@ -152,7 +170,7 @@ __device__ __forceinline__ void build_tables(A2AVTables& t, const SplitArg& hs, 
 }
 
 // upr = units per row; shift >= 0 when upr is a power of two.
-template <int UB, int U, bool NT, bool DEV>
+template <int UB, int U, bool NTL, bool NTS, bool DEV>
 __global__ void __launch_bounds__(kBlock)
 alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, uint32_t upr,
                  int shift, uint64_t in_rows, uint64_t out_rows) {
@@ -192,7 +210,7 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
         const uint64_t drow = static_cast<uint64_t>(t.rdispl[lo]) + (g - static_cast<uint64_t>(t.rowstart[lo]));
         ok[u] = srow < in_rows && drow < out_rows;
         if (ok[u]) {
-          v[u] = load_unit<NT, T>(t.in[p], srow * upr + c);
+          v[u] = load_unit<NTL, T>(t.in[p], srow * upr + c);
           dptr[u] = t.out[r];
           didx[u] = drow * upr + c;
         }
@@ -200,7 +218,7 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (ok[u]) store_unit<NT, T>(dptr[u], didx[u], v[u]);
+      if (ok[u]) store_unit<NTS, T>(dptr[u], didx[u], v[u]);
     }
   }
 }
@@ -221,7 +239,7 @@ inline unsigned capped_blocks(size_t units, size_t per_block, size_t cap) {
 
 }  // namespace
 
-int launch_allgather(mcr_ctx* ctx, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P,
+int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P,
                      int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   if (variant == SV_SCALAR) {
@@ -229,42 +247,54 @@ int launch_allgather(mcr_ctx* ctx, const PtrTab& out, const CPtrTab& in, size_t 
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int kP = decltype(pp)::value;
       if (dtype == MCR_F32)
-        hipLaunchKernelGGL((allgather_kernel<4, kP, 1, false, true>), dim3(gx, P), dim3(kBlock), 0, stream, out, in, count);
+        hipLaunchKernelGGL((allgather_kernel<4, kP, 1, false, false>), dim3(gx, P), dim3(kBlock), 0, stream, out, in, count);
       else
-        hipLaunchKernelGGL((allgather_kernel<2, kP, 1, false, true>), dim3(gx, P), dim3(kBlock), 0, stream, out, in, count);
+        hipLaunchKernelGGL((allgather_kernel<2, kP, 1, false, false>), dim3(gx, P), dim3(kBlock), 0, stream, out, in, count);
       return launch_status();
     });
   }
   const size_t mvec = count / per_vec(dtype);
-  const unsigned gx = grid_x(ctx, mvec, variant, P);
+  if (variant >= AG_SC4 && variant <= AG_SC16) {
+    const size_t sc_bytes = (variant == AG_SC4 ? 4u : variant == AG_SC8 ? 8u : 16u) << 20;
+    const size_t nblk = (mvec + kBlock - 1) / kBlock;                    // tiles of 4 KiB per source
+    size_t bpc = sc_bytes / (kBlock * 16);
+    if (bpc > nblk) bpc = nblk;
+    const size_t nsc = (nblk + bpc - 1) / bpc;
+    const size_t gx = nsc * bpc * static_cast<size_t>(P);
+    if (gx > 0x7fffffffull) return MCR_EVARIANT;
+    hipLaunchKernelGGL(allgather_superchunk_kernel, dim3(static_cast<unsigned>(gx), P), dim3(kBlock), 0, stream, out, in,
+                       mvec, static_cast<unsigned>(bpc), static_cast<unsigned>(P));
+    return launch_status();
+  }
+  const unsigned gx = grid_x(mvec, variant);
   return dispatch_ranks(P, [&](auto pp) {
-    return dispatch_shape(variant, [&](auto uu, auto nt, auto ps) {
+    return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
       constexpr int kP = decltype(pp)::value;
       constexpr int U = decltype(uu)::value;
-      hipLaunchKernelGGL((allgather_kernel<16, kP, U, decltype(nt)::value, decltype(ps)::value>),
+      hipLaunchKernelGGL((allgather_kernel<16, kP, U, decltype(ntl)::value, decltype(nts)::value>),
                          dim3(gx, P), dim3(kBlock), 0, stream, out, in, mvec);
       return launch_status();
     });
   });
 }
 
-int launch_alltoall(mcr_ctx* ctx, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P,
+int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P,
                     int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
     const unsigned gx = capped_blocks(b, kBlock, 1u << 16);
     if (dtype == MCR_F32)
-      hipLaunchKernelGGL((alltoall_kernel<4, 1, false, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
+      hipLaunchKernelGGL((alltoall_kernel<4, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     else
-      hipLaunchKernelGGL((alltoall_kernel<2, 1, false, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
+      hipLaunchKernelGGL((alltoall_kernel<2, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     return launch_status();
   }
   const size_t bvec = b / per_vec(dtype);
-  const unsigned gx = grid_x(ctx, bvec, variant, static_cast<size_t>(P) * P);
-  return dispatch_shape(variant, [&](auto uu, auto nt, auto ps) {
+  const unsigned gx = grid_x(bvec, variant);
+  return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
     constexpr int U = decltype(uu)::value;
-    hipLaunchKernelGGL((alltoall_kernel<16, U, decltype(nt)::value, decltype(ps)::value>),
+    hipLaunchKernelGGL((alltoall_kernel<16, U, decltype(ntl)::value, decltype(nts)::value>),
                        dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, bvec);
     return launch_status();
   });
@@ -287,30 +317,30 @@ int launch_alltoallv(mcr_ctx* ctx, const PtrTab& out, const CPtrTab& in, const i
   if (total_rows == 0 || row_bytes == 0) return MCR_OK;
   const bool dev = host_splits == nullptr;
 
-  auto go = [&](auto ub, auto uu, auto nt, size_t cap) {
+  auto go = [&](auto ub, auto uu, auto ntl, auto nts, size_t cap) {
     constexpr int UB = decltype(ub)::value;
     constexpr int U = decltype(uu)::value;
-    constexpr bool NT = decltype(nt)::value;
+    constexpr bool NTL = decltype(ntl)::value;
+    constexpr bool NTS = decltype(nts)::value;
     const uint64_t upr = row_bytes / UB;
     const unsigned gx = capped_blocks(total_rows * upr, static_cast<size_t>(U) * kBlock, cap);
     const int shift = log2_exact(upr);
     if (dev)
-      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NT, true>), dim3(gx), dim3(kBlock), 0, stream, out, in, hs,
+      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx), dim3(kBlock), 0, stream, out, in, hs,
                          dev_splits, P, static_cast<uint32_t>(upr), shift, static_cast<uint64_t>(in_rows),
                          static_cast<uint64_t>(out_rows));
     else
-      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NT, false>), dim3(gx), dim3(kBlock), 0, stream, out, in, hs,
+      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, false>), dim3(gx), dim3(kBlock), 0, stream, out, in, hs,
                          dev_splits, P, static_cast<uint32_t>(upr), shift, static_cast<uint64_t>(in_rows),
                          static_cast<uint64_t>(out_rows));
     return launch_status();
   };
   if (variant == SV_SCALAR) {
     const size_t cap = static_cast<size_t>(ctx->num_cus) * 32;
-    if (elem_b == 4) return go(Int<4>{}, Int<1>{}, Bool<false>{}, cap);
-    return go(Int<2>{}, Int<1>{}, Bool<false>{}, cap);
+    if (elem_b == 4) return go(Int<4>{}, Int<1>{}, Bool<false>{}, Bool<false>{}, cap);
+    return go(Int<2>{}, Int<1>{}, Bool<false>{}, Bool<false>{}, cap);
   }
-  const size_t cap = shape_persistent(variant) ? static_cast<size_t>(ctx->num_cus) * 8 : (1u << 30);
-  return dispatch_shape(variant, [&](auto uu, auto nt, auto) { return go(Int<16>{}, uu, nt, cap); });
+  return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) { return go(Int<16>{}, uu, ntl, nts, size_t(1) << 30); });
 }
 
 }  // namespace mcr

@@ -30,41 +30,50 @@ inline int dispatch_dtype(int dtype, F&& f) {
   return MCR_EDTYPE;
 }
 
-// f(Int<U>, Bool<NT>, Bool<PERSIST>) for the vector launch shapes
+// f(Int<U>, Bool<NT loads>, Bool<NT stores>) for the vector launch shapes
 template <class F>
 inline int dispatch_shape(int variant, F&& f) {
   switch (variant) {
     case SV_V1: return f(Int<1>{}, Bool<false>{}, Bool<false>{});
     case SV_V2: return f(Int<2>{}, Bool<false>{}, Bool<false>{});
     case SV_V4: return f(Int<4>{}, Bool<false>{}, Bool<false>{});
-    case SV_V2NT: return f(Int<2>{}, Bool<true>{}, Bool<false>{});
-    case SV_V4NT: return f(Int<4>{}, Bool<true>{}, Bool<false>{});
-    case SV_PV2: return f(Int<2>{}, Bool<false>{}, Bool<true>{});
-    case SV_PV2NT: return f(Int<2>{}, Bool<true>{}, Bool<true>{});
+    case SV_V1NT: return f(Int<1>{}, Bool<true>{}, Bool<true>{});
+    case SV_V2NT: return f(Int<2>{}, Bool<true>{}, Bool<true>{});
+    case SV_V4NT: return f(Int<4>{}, Bool<true>{}, Bool<true>{});
+    case SV_V1LN: return f(Int<1>{}, Bool<true>{}, Bool<false>{});
+    case SV_V2LN: return f(Int<2>{}, Bool<true>{}, Bool<false>{});
+    case SV_V4LN: return f(Int<4>{}, Bool<true>{}, Bool<false>{});
+    case SV_V1SN: return f(Int<1>{}, Bool<false>{}, Bool<true>{});
+    case SV_V2SN: return f(Int<2>{}, Bool<false>{}, Bool<true>{});
+    case SV_V4SN: return f(Int<4>{}, Bool<false>{}, Bool<true>{});
   }
   return MCR_EVARIANT;
 }
 
+// f(Bool<NT loads>, Bool<NT stores>): the cache hint of a shape, for kernels with a fixed unroll
+template <class F>
+inline int dispatch_hint(int variant, F&& f) {
+  switch (variant) {
+    case SV_V1NT: case SV_V2NT: case SV_V4NT: return f(Bool<true>{}, Bool<true>{});
+    case SV_V1LN: case SV_V2LN: case SV_V4LN: return f(Bool<true>{}, Bool<false>{});
+    case SV_V1SN: case SV_V2SN: case SV_V4SN: return f(Bool<false>{}, Bool<true>{});
+  }
+  return f(Bool<false>{}, Bool<false>{});
+}
+
 inline int shape_unroll(int variant) {
   switch (variant) {
-    case SV_V1: return 1;
-    case SV_V2: case SV_V2NT: case SV_PV2: case SV_PV2NT: return 2;
-    case SV_V4: case SV_V4NT: return 4;
+    case SV_V2: case SV_V2NT: case SV_V2LN: case SV_V2SN: return 2;
+    case SV_V4: case SV_V4NT: case SV_V4LN: case SV_V4SN: return 4;
   }
   return 1;
 }
-inline bool shape_persistent(int variant) { return variant == SV_PV2 || variant == SV_PV2NT; }
 
-// Workgroups along x for `nvec` vectors per slice and `slices` slices in y/z.
-inline unsigned grid_x(const mcr_ctx* ctx, size_t nvec, int variant, size_t slices) {
+// Workgroups along x for `nvec` vectors per slice.
+inline unsigned grid_x(size_t nvec, int variant) {
   const size_t per_block = static_cast<size_t>(shape_unroll(variant)) * kBlock;
   size_t blocks = (nvec + per_block - 1) / per_block;
   if (blocks == 0) blocks = 1;
-  if (shape_persistent(variant)) {
-    size_t cap = static_cast<size_t>(ctx->num_cus) * 8 / (slices ? slices : 1);
-    if (cap == 0) cap = 1;
-    if (blocks > cap) blocks = cap;
-  }
   return static_cast<unsigned>(blocks);
 }
 

@@ -21,7 +21,7 @@ struct PlanDev {
 };
 
 // UNFUSE = false: flat[off + j] = tensor[j];  true: tensor[j] = flat[off + j].  blockIdx.y = rank.
-template <int EB, bool UNFUSE, bool NT, bool FORCE_SCALAR>
+template <int EB, bool UNFUSE, bool NTL, bool NTS, bool FORCE_SCALAR>
 __global__ void __launch_bounds__(kBlock)
 fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
   const uint32_t c = first_chunk + blockIdx.x;
@@ -45,12 +45,12 @@ fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
-      if (idx < nv) v[u] = load16<NT>(src, idx);
+      if (idx < nv) v[u] = load16<NTL>(src, idx);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
-      if (idx < nv) store16<NT>(dst, idx, v[u]);
+      if (idx < nv) store16<NTS>(dst, idx, v[u]);
     }
     done = static_cast<uint64_t>(nv) * W;
   }
@@ -60,7 +60,7 @@ fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
 }
 
 // All-reduce of one chunk of one tensor across the bound ranks, in place.
-template <int DT, int P, bool NT, bool FORCE_SCALAR>
+template <int DT, int P, bool NTL, bool NTS, bool FORCE_SCALAR>
 __global__ void __launch_bounds__(kBlock)
 allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int do_scale) {
   using E = Elem<DT>;
@@ -83,13 +83,14 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int do_scal
     const uint32_t nv = static_cast<uint32_t>(ne / W);
     u32x4 v[4][P];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t idx = u * kBlock + threadIdx.x;
-      if (idx < nv) {
+    for (int p = 0; p < P; ++p) {            // rank-major issue order, as in all_reduce
 #pragma unroll
-        for (int p = 0; p < P; ++p) v[u][p] = load16<NT>(base[p], idx);
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t idx = u * kBlock + threadIdx.x;
+        if (idx < nv) v[u][p] = load16<NTL>(base[p], idx);
       }
     }
+    u32x4 y[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
@@ -107,9 +108,15 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int do_scal
 #pragma unroll
           for (int k = 0; k < W; ++k) acc[k] = acc[k] * scale;
         }
-        const u32x4 y = E::narrow(acc);
+        y[u] = E::narrow(acc);
+      }
+    }
 #pragma unroll
-        for (int p = 0; p < P; ++p) store16<NT>(base[p], idx, y);
+    for (int p = 0; p < P; ++p) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t idx = u * kBlock + threadIdx.x;
+        if (idx < nv) store16<NTS>(base[p], idx, y[u]);
       }
     }
     done = static_cast<uint64_t>(nv) * W;
@@ -135,8 +142,6 @@ inline PlanDev plan_dev(const mcr_fuse_plan* plan) {
   return d;
 }
 
-inline bool variant_nt(int variant) { return variant == SV_V2NT || variant == SV_V4NT || variant == SV_PV2NT; }
-
 }  // namespace
 
 int launch_fuse(mcr_ctx*, const mcr_fuse_plan* plan, int bucket, const PtrTab& flat, bool unfuse, int variant,
@@ -146,15 +151,15 @@ int launch_fuse(mcr_ctx*, const mcr_fuse_plan* plan, int bucket, const PtrTab& f
   if (c1 == c0) return MCR_OK;
   const PlanDev d = plan_dev(plan);
   const dim3 grid(c1 - c0, plan->bound_P);
-  auto go = [&](auto eb, auto un, auto nt, auto fs) {
-    hipLaunchKernelGGL((fuse_kernel<decltype(eb)::value, decltype(un)::value, decltype(nt)::value, decltype(fs)::value>),
+  auto go = [&](auto eb, auto un, auto ntl, auto nts, auto fs) {
+    hipLaunchKernelGGL((fuse_kernel<decltype(eb)::value, decltype(un)::value, decltype(ntl)::value, decltype(nts)::value,
+                                    decltype(fs)::value>),
                        grid, dim3(kBlock), 0, stream, d, flat, c0);
     return launch_status();
   };
   auto by_shape = [&](auto eb, auto un) {
-    if (variant == SV_SCALAR) return go(eb, un, Bool<false>{}, Bool<true>{});
-    if (variant_nt(variant)) return go(eb, un, Bool<true>{}, Bool<false>{});
-    return go(eb, un, Bool<false>{}, Bool<false>{});
+    if (variant == SV_SCALAR) return go(eb, un, Bool<false>{}, Bool<false>{}, Bool<true>{});
+    return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(eb, un, ntl, nts, Bool<false>{}); });
   };
   if (plan->dtype == MCR_F32) return unfuse ? by_shape(Int<4>{}, Bool<true>{}) : by_shape(Int<4>{}, Bool<false>{});
   return unfuse ? by_shape(Int<2>{}, Bool<true>{}) : by_shape(Int<2>{}, Bool<false>{});
@@ -172,13 +177,15 @@ int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, 
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int DT = decltype(dt)::value;
       constexpr int kP = decltype(pp)::value;
-      if (variant == SV_SCALAR)
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, do_scale);
-      else if (variant_nt(variant))
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, do_scale);
-      else
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, do_scale);
-      return launch_status();
+      if (variant == SV_SCALAR) {
+        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, do_scale);
+        return launch_status();
+      }
+      return dispatch_hint(variant, [&](auto ntl, auto nts) {
+        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false>), dim3(c1 - c0),
+                           dim3(kBlock), 0, stream, d, c0, scale, do_scale);
+        return launch_status();
+      });
     });
   });
 }

@@ -15,25 +15,24 @@
 
 namespace mcr {
 
-// Launch shapes of the streaming kernels.  The same list serves allreduce,
-// reduce_scatter, allgather, alltoall, alltoallv, pack, unpack, fuse, unfuse
-// and allreduce_multi: "scalar" moves one element per thread and accepts any
-// alignment; "vN" moves N 128-bit vectors per thread, a workgroup covering
-// N*256 consecutive vectors; "nt" adds the nontemporal hint to loads and
-// stores; "pv" is a fixed grid of a few workgroups per compute unit that
-// strides over the index space.
+// Launch shapes of the streaming kernels, shared by every op but moe_route.
+// "scalar" moves one element per thread and accepts any alignment; "vN" moves N
+// 128-bit vectors per thread, a workgroup of 256 threads covering N*256
+// consecutive vectors.  The suffix is the cache hint: "nt" = nontemporal loads
+// and stores, "ln" = nontemporal loads only, "sn" = nontemporal stores only.
 enum StreamVariant {
   SV_SCALAR = 0,
-  SV_V1 = 1,
-  SV_V2 = 2,
-  SV_V4 = 3,
-  SV_V2NT = 4,
-  SV_V4NT = 5,
-  SV_PV2 = 6,
-  SV_PV2NT = 7,
-  SV_COUNT = 8
+  SV_V1 = 1, SV_V2 = 2, SV_V4 = 3,
+  SV_V1NT = 4, SV_V2NT = 5, SV_V4NT = 6,
+  SV_V1LN = 7, SV_V2LN = 8, SV_V4LN = 9,
+  SV_V1SN = 10, SV_V2SN = 11, SV_V4SN = 12,
+  SV_COUNT = 13
 };
-extern const char* const kStreamVariantNames[SV_COUNT];
+// all_gather only: "scN" walks the message in super-chunks of N MiB per source and
+// copies each super-chunk to one destination after the other, so that at any
+// moment the chip streams from one source region into one destination region.
+enum AllgatherVariant { AG_SC4 = 13, AG_SC8 = 14, AG_SC16 = 15, AG_COUNT = 16 };
+extern const char* const kStreamVariantNames[AG_COUNT];
 
 struct TuneKey {
   int op, dtype, P;

@@ -123,7 +123,7 @@ template <> struct RowUnit<16> { typedef u32x4 type; };
 template <> struct RowUnit<4> { typedef uint32_t type; };
 template <> struct RowUnit<2> { typedef uint16_t type; };
 
-template <int UB, bool NT>
+template <int UB, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows, uint32_t upr,
             uint32_t tpr, uint32_t tpr_shift) {
@@ -141,8 +141,8 @@ pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows,
   U* drow = dst + static_cast<size_t>(s) * upr;
   for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
     U v;
-    if constexpr (NT) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
-    if constexpr (NT) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
+    if constexpr (NTL) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
+    if constexpr (NTS) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
   }
 }
 
@@ -156,7 +156,7 @@ template <int DT> __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float g) {
 }
 
 // GATE: 0 = plain gather, 1 = scale kept rows by gate[t].
-template <int DT, int UB, bool NT, bool GATE>
+template <int DT, int UB, bool NTL, bool NTS, bool GATE>
 __global__ void __launch_bounds__(kBlock)
 unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t T, size_t in_rows,
               uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
@@ -174,7 +174,7 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
   if (!kept) {
     U z = {};
     for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
-      if constexpr (NT) __builtin_nontemporal_store(z, drow + c); else drow[c] = z;
+      if constexpr (NTS) __builtin_nontemporal_store(z, drow + c); else drow[c] = z;
     }
     return;
   }
@@ -183,7 +183,7 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
   if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[rank])[t];
   for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
     U v;
-    if constexpr (NT) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
+    if constexpr (NTL) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
     if constexpr (GATE) {
       if constexpr (UB == 16) {
         v = scale_vec<DT>(v, g);
@@ -197,7 +197,7 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
         else v = static_cast<U>(f32_to_bf16_rne(y));
       }
     }
-    if constexpr (NT) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
+    if constexpr (NTS) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
   }
 }
 
@@ -217,8 +217,6 @@ inline RowShape row_shape(size_t T, size_t units_per_row) {
   return s;
 }
 
-inline bool variant_nt(int variant) { return variant == SV_V2NT || variant == SV_V4NT || variant == SV_PV2NT; }
-
 }  // namespace
 
 int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot,
@@ -236,17 +234,17 @@ int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& s
   if (variant == SV_SCALAR) {
     const RowShape s = row_shape(T, row_bytes / elem_b);
     if (elem_b == 4)
-      hipLaunchKernelGGL((pack_kernel<4, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+      hipLaunchKernelGGL((pack_kernel<4, false, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
     else
-      hipLaunchKernelGGL((pack_kernel<2, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+      hipLaunchKernelGGL((pack_kernel<2, false, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
     return launch_status();
   }
   const RowShape s = row_shape(T, row_bytes / 16);
-  if (variant_nt(variant))
-    hipLaunchKernelGGL((pack_kernel<16, true>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
-  else
-    hipLaunchKernelGGL((pack_kernel<16, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
-  return launch_status();
+  return dispatch_hint(variant, [&](auto ntl, auto nts) {
+    hipLaunchKernelGGL((pack_kernel<16, decltype(ntl)::value, decltype(nts)::value>), dim3(s.blocks, P), dim3(kBlock), 0,
+                       stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+    return launch_status();
+  });
 }
 
 int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, const CPtrTab* gate,
@@ -254,20 +252,21 @@ int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab&
   if (T == 0 || row_elems == 0) return MCR_OK;
   CPtrTab g;
   for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
-  const bool nt = variant_nt(variant);
   return dispatch_dtype(dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
-    auto go = [&](auto ub, auto ntc, auto gc) {
+    auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
       constexpr int UB = decltype(ub)::value;
       const RowShape s = row_shape(T, row_elems * EB / UB);
-      hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntc)::value, decltype(gc)::value>), dim3(s.blocks, P),
-                         dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);
+      hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
+                         dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);
       return launch_status();
     };
-    if (variant == SV_SCALAR) return gate ? go(Int<EB>{}, Bool<false>{}, Bool<true>{}) : go(Int<EB>{}, Bool<false>{}, Bool<false>{});
-    if (nt) return gate ? go(Int<16>{}, Bool<true>{}, Bool<true>{}) : go(Int<16>{}, Bool<true>{}, Bool<false>{});
-    return gate ? go(Int<16>{}, Bool<false>{}, Bool<true>{}) : go(Int<16>{}, Bool<false>{}, Bool<false>{});
+    if (variant == SV_SCALAR)
+      return gate ? go(Int<EB>{}, Bool<false>{}, Bool<false>{}, Bool<true>{}) : go(Int<EB>{}, Bool<false>{}, Bool<false>{}, Bool<false>{});
+    return dispatch_hint(variant, [&](auto ntl, auto nts) {
+      return gate ? go(Int<16>{}, ntl, nts, Bool<true>{}) : go(Int<16>{}, ntl, nts, Bool<false>{});
+    });
   });
 }
 

@@ -1,0 +1,66 @@
+// The streaming sum shared by all_reduce and reduce_scatter: one tile of U*256
+// consecutive 128-bit vectors, read from all P rank buffers and summed left to
+// right in rank order in binary32, starting from rank 0's value.
+#pragma once
+#include "mcr_dispatch.hpp"
+
+namespace mcr {
+
+// All U*P loads are issued before the first add, stream by stream (rank-major):
+// a wavefront then asks each rank buffer for U pieces in a row, which the memory
+// system serves better than a round-robin over the P buffers.
+template <int DT, int P, int U, bool NTL, bool FULL>
+__device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off, size_t tile,
+                                            size_t nvec, float scale, bool do_scale,
+                                            u32x4 (&out)[U]) {
+  using E = Elem<DT>;
+  constexpr int W = E::kPerVec;
+  u32x4 v[U][P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+      if (FULL || idx < nvec) v[u][p] = load16<NTL>(in.p[p], in_vec_off + idx);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+    if (FULL || idx < nvec) {
+      float acc[W];
+      E::widen(v[u][0], acc);
+#pragma unroll
+      for (int p = 1; p < P; ++p) {
+        float x[W];
+        E::widen(v[u][p], x);
+#pragma unroll
+        for (int k = 0; k < W; ++k) acc[k] = acc[k] + x[k];
+      }
+      if (do_scale) {
+#pragma unroll
+        for (int k = 0; k < W; ++k) acc[k] = acc[k] * scale;
+      }
+      out[u] = E::narrow(acc);
+    }
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ float reduce_scalar(const CPtrTab& in, size_t i, int P, float scale,
+                                               bool do_scale) {
+  using E = Elem<DT>;
+  float acc = E::load1(in.p[0], i);
+  for (int p = 1; p < P; ++p) acc = acc + E::load1(in.p[p], i);
+  if (do_scale) acc = acc * scale;
+  return acc;
+}
+
+inline unsigned scalar_grid(size_t n) {
+  size_t blocks = (n + kBlock - 1) / kBlock;
+  if (blocks == 0) blocks = 1;
+  if (blocks > (1u << 20)) blocks = 1u << 20;   // grid-stride beyond that
+  return static_cast<unsigned>(blocks);
+}
+
+}  // namespace mcr

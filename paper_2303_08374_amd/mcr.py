@@ -225,6 +225,12 @@ def mcr_tune_get(ctx, op_id: int, dtype: int, P: int, nbytes: int) -> int:
     return v.value
 
 
+def mcr_auto_variant(ctx, op_id: int, dtype: int, P: int, nbytes: int, vec_ok: bool = True) -> int:
+    v = ctypes.c_int(-1)
+    _check(lib().mcr_auto_variant(ctx, op_id, dtype, P, _sz(nbytes), int(vec_ok), ctypes.byref(v)), "mcr_auto_variant")
+    return v.value
+
+
 def mcr_tune_clear(ctx) -> None:
     _check(lib().mcr_tune_clear(ctx), "mcr_tune_clear")
 

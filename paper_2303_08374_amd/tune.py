@@ -1,0 +1,104 @@
+"""The tuning suite (paper Sec. IV-E and V-B): micro-benchmarks every kernel variant of every
+op over the message-size sweep, picks the variant with the least time per (op, dtype, P,
+size) and writes the static tuning table that MCR_AUTO consults.
+
+    python -m paper_2303_08374_amd.tune [--out paper_2303_08374_amd/tuning/mi355x.tbl]
+                                        [--report gpurun_out/tune_report.json]
+
+One table cell = one batch of identical launches on one stream over cold buffers, mean time
+per launch.  Ties go to the lower variant id.  Besides the per-size ("fine", the paper's
+MCR-DL-T) table the report holds the best single variant per op ("coarse", the paper's
+MCR-DL) and the gap between the two.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+import torch
+
+from . import inputs, mcr, sweep
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+DEFAULT_TABLE = os.path.join(HERE, "tuning", "mi355x.tbl")
+
+
+def reps_for(alg_bytes: int) -> int:
+    # about 160 GiB of traffic per batch (tens of milliseconds), between 5 and 50 launches
+    return int(max(5, min(50, (160 << 30) // max(alg_bytes, 1))))
+
+
+def run(out_path: str, report_path: str | None, P: int, max_bytes: int, arena_gib: float, verbose: bool = True):
+    ctx = mcr.mcr_init(0)
+    mcr.mcr_tune_clear(ctx)
+    sizes = [m for m in inputs.SWEEP_BYTES if m <= max_bytes]
+    cells = sweep.make_cells(P, inputs.SWEEP_OPS, inputs.SWEEP_DTYPES, sizes)
+    need = max(c.footprint for c in cells)
+    arena = sweep.Arena(max(int(arena_gib * (1 << 30)), need + (1 << 20)))
+    names = mcr.mcr_get_variants(ctx, mcr.OP_ALLGATHER)                  # the longest list; a prefix serves the others
+    report = {"P": P, "variants": names, "cells": {}}
+    for cell in cells:
+        n_var = len(mcr.mcr_get_variants(ctx, sweep.OPS[cell.op]))
+        variants = list(range(1, n_var))             # the 128-bit variants; scalar is only the fallback
+        reps = reps_for(cell.alg_bytes)
+        times = {}
+        for v in variants:
+            cell.launch(ctx, arena.take(cell.footprint), v)              # first-launch effects out of the way
+            ms = sweep.time_launches(lambda: cell.launch(ctx, arena.take(cell.footprint), v), reps)
+            times[v] = ms
+        # least time wins; anything within 2 % of it counts as a tie and the lowest id is taken,
+        # so that launch-bound sizes do not pick a variant by noise
+        floor = min(times.values())
+        best = min(v for v in variants if times[v] <= floor * 1.02)
+        mcr.mcr_tune_set(ctx, sweep.OPS[cell.op], sweep.DTYPES[cell.dtype], P, cell.M, best)
+        report["cells"][cell.key] = {
+            "alg_bytes": cell.alg_bytes, "best": names[best],
+            "us": {names[v]: round(times[v] * 1e3, 3) for v in variants},
+            "GBps": {names[v]: round(cell.alg_bytes / (times[v] * 1e-3) / 1e9, 1) for v in variants},
+        }
+        if verbose:
+            print(f"{cell.key:34s} best={names[best]:6s} {times[best]*1e3:10.2f} us "
+                  f"{cell.alg_bytes / (times[best] * 1e-3) / 1e9:8.1f} GB/s", flush=True)
+    # coarse (one variant per op and dtype) versus fine (one per size)
+    coarse = {}
+    for op in inputs.SWEEP_OPS:
+        variants = list(range(1, len(mcr.mcr_get_variants(ctx, sweep.OPS[op]))))
+        for dt in inputs.SWEEP_DTYPES:
+            keys = [c.key for c in cells if c.op == op and c.dtype == dt]
+            tot = {v: sum(report["cells"][k]["us"][names[v]] for k in keys) for v in variants}
+            fine = sum(min(report["cells"][k]["us"].values()) for k in keys)
+            bv = min(variants, key=lambda v: (tot[v], v))
+            coarse[f"{op}/{dt}"] = {"variant": names[bv], "sum_us": round(tot[bv], 2), "fine_sum_us": round(fine, 2),
+                                    "fine_gain": round(tot[bv] / fine, 4)}
+    report["coarse_vs_fine"] = coarse
+    os.makedirs(os.path.dirname(out_path), exist_ok=True)
+    mcr.mcr_tune_save(ctx, out_path)
+    if report_path:
+        os.makedirs(os.path.dirname(report_path) or ".", exist_ok=True)
+        with open(report_path, "w") as f:
+            json.dump(report, f, indent=1)
+    n = mcr.mcr_tune_count(ctx)
+    mcr.mcr_finalize(ctx)
+    return n, report
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=DEFAULT_TABLE)
+    ap.add_argument("--report", default=None)
+    ap.add_argument("--ranks", type=int, default=inputs.SWEEP_P)
+    ap.add_argument("--max-bytes", type=int, default=inputs.SWEEP_BYTES[-1])
+    ap.add_argument("--arena-gib", type=float, default=4.0)
+    a = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        print("the tuning suite needs a GPU", file=sys.stderr)
+        return 2
+    n, _ = run(a.out, a.report, a.ranks, a.max_bytes, a.arena_gib)
+    print(f"wrote {n} rows to {a.out}")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -64,8 +64,9 @@ def assert_reduced_equal(got: np.ndarray, exp: np.ndarray, dtype: int, what=""):
     assert_bits_equal(np.where(gn, 0, got).astype(got.dtype), np.where(en, 0, exp).astype(exp.dtype), what)
 
 
-VEC_VARIANTS = [1, 2, 3, 4, 5, 6, 7]
+VEC_VARIANTS = list(range(1, 13))          # every 128-bit launch shape
 ALL_VARIANTS = [0] + VEC_VARIANTS
+ALLGATHER_EXTRA = [13, 14, 15]             # super-chunk forms of all_gather
 NPDT = {mcr.F32: np.float32, mcr.BF16: np.uint16}
 EB = {mcr.F32: 4, mcr.BF16: 2}
 assert (oracle.F32, oracle.BF16, oracle.SUM, oracle.AVG) == (mcr.F32, mcr.BF16, mcr.SUM, mcr.AVG)

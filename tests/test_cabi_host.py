@@ -48,7 +48,7 @@ def test_strerror_and_variants(ctx):
         assert mcr.strerror(code) not in ("ok", "unknown status")
     for op in range(10):
         v = mcr.mcr_get_variants(ctx, op)
-        assert v[0] == "scalar" and len(v) == len(set(v)) == 8
+        assert v[0] == "scalar" and len(v) == len(set(v)) == (16 if op == mcr.OP_ALLGATHER else 13)
     assert mcr.mcr_get_variants(ctx, mcr.OP_MOE_ROUTE) == ["wave_ballot"]
     with pytest.raises(mcr.McrError) as e:
         mcr.mcr_get_variants(ctx, 99)
@@ -114,7 +114,7 @@ def test_tuning_table_reproduces_table2(ctx, tmp_path):
     """Table II of the paper as a fixture: three 'backends' stand for three variants."""
     mcr.mcr_tune_clear(ctx)
     rows = [s.split() for s in gio.lines("table2_allgather.txt")]
-    backend_to_variant = {"MVAPICH2-GDR": 1, "NCCL": 3, "SCCL": 6}
+    backend_to_variant = {"MVAPICH2-GDR": 1, "NCCL": 3, "SCCL": 14}
     for size, backend in reversed(rows):                       # insertion order must not matter
         mcr.mcr_tune_set(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, int(size), backend_to_variant[backend])
     sizes = [int(r[0]) for r in rows]
@@ -124,7 +124,7 @@ def test_tuning_table_reproduces_table2(ctx, tmp_path):
     assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 4095) == 1
     assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 4096) == 3
     assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 100) == 1          # below the first row
-    assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 1 << 40) == 6      # above the last row
+    assert mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, 1 << 40) == 14     # above the last row
     # other keys have no table
     assert _status(mcr.mcr_tune_get, ctx, mcr.OP_ALLGATHER, mcr.BF16, 8, 4096) == mcr.EVARIANT
     assert _status(mcr.mcr_tune_get, ctx, mcr.OP_ALLGATHER, mcr.F32, 4, 4096) == mcr.EVARIANT
@@ -173,7 +173,7 @@ def test_shipped_tuning_table_is_well_formed(ctx):
     for op in range(4):
         for dt in (mcr.F32, mcr.BF16):
             for b in inputs.SWEEP_BYTES:
-                assert 0 <= mcr.mcr_tune_get(ctx, op, dt, inputs.SWEEP_P, b) < 8
+                assert 0 <= mcr.mcr_tune_get(ctx, op, dt, inputs.SWEEP_P, b) < 16
     mcr.mcr_tune_clear(ctx)
 
 

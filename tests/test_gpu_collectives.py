@@ -132,8 +132,15 @@ def test_allreduce_on_side_stream():
 
 
 # --------------------------------------------------- reduce_scatter / all_gather / all_to_all
-def _variants_for(vec_ok):
-    return [mcr.AUTO] + (gu.ALL_VARIANTS if vec_ok else [0])
+def _variants_for(vec_ok, extra=()):
+    return [mcr.AUTO] + (gu.ALL_VARIANTS + list(extra) if vec_ok else [0])
+
+
+def test_variant_lists_match_the_library():
+    for op in range(10):
+        names = mcr.mcr_get_variants(gu.ctx(), op)
+        want = len(gu.ALL_VARIANTS) + (len(gu.ALLGATHER_EXTRA) if op == mcr.OP_ALLGATHER else 0)
+        assert len(names) == want, (op, names)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -166,7 +173,7 @@ def test_allgather(dtype, P):
     for m in (1, 7, 8, 1032, 9 * 1024 + 8):
         host = _make(P, m, dtype, seed=300 + P, dist="uniform")
         exp = oracle.allgather(host, dtype)
-        for variant in _variants_for(m % W == 0):
+        for variant in _variants_for(m % W == 0, gu.ALLGATHER_EXTRA):
             dev_in = [gu.to_dev(h) for h in host]
             dev_out = [gu.dev_empty(P * m, dtype, 0) for _ in range(P)]
             mcr.mcr_allgather(gu.ctx(), dev_out, dev_in, m, dtype, P, variant)
@@ -174,6 +181,20 @@ def test_allgather(dtype, P):
             for r in range(P):
                 gu.assert_bits_equal(gu.to_host(dev_out[r], gu.NPDT[dtype]), exp[r],
                                      f"allgather dt={dtype} P={P} m={m} v={variant} r={r}")
+
+
+def test_allgather_superchunk_spans_several_superchunks():
+    """5 MiB + a ragged tail per rank: two 4 MiB super-chunks, the second partial."""
+    P, dtype = 4, mcr.F32
+    m = (5 << 20) // 4 + 1028
+    host = _make(P, m, dtype, seed=333, dist="uniform")
+    exp = oracle.allgather(host, dtype)
+    for variant in gu.ALLGATHER_EXTRA:
+        dev_out = [gu.dev_empty(P * m, dtype, 0) for _ in range(P)]
+        mcr.mcr_allgather(gu.ctx(), dev_out, [gu.to_dev(h) for h in host], m, dtype, P, variant)
+        gu.sync()
+        for r in range(P):
+            gu.assert_bits_equal(gu.to_host(dev_out[r], np.float32), exp[r], f"superchunk v={variant} r={r}")
 
 
 def test_allgather_preserves_nan_payloads():
@@ -263,7 +284,7 @@ def test_alltoallv_skewed_large():
     host = [inputs.normal(in_rows * w, 600, p, bf16=True) for p in range(P)]
     exp = [np.zeros(out_rows * w, dtype=np.uint16) for _ in range(P)]
     oracle.alltoallv(host, S, w, dtype, exp)
-    for variant in (mcr.AUTO, 3, 6):
+    for variant in (mcr.AUTO, 3, 6, 12):
         dev_out = [gu.dev_empty(out_rows * w, dtype, 0) for _ in range(P)]
         mcr.mcr_alltoallv(gu.ctx(), dev_out, [gu.to_dev(h) for h in host], torch.from_numpy(S).cuda(), True, in_rows,
                           out_rows, w, dtype, P, variant)
