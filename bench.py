@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--cells-out", default=None, help="write the per-cell table (JSON) here")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-stages", action="store_true",
+                    help="skip the application-shaped workloads (small allreduce, MoE, DLRM, gradient buckets)")
     ap.add_argument("--cpu-max-bytes", type=int, default=128 << 20)
     ap.add_argument("--calibrate", action="store_true",
                     help="finish with three plain 1 GiB copies (alltoall at P=1): the known-size kernel that "
@@ -227,6 +229,9 @@ def main():
         "messages_ge_16MiB_frac_of_peak": large_summary,
         "smallest_message_us": small_us,
     }
+    if not args.no_stages:
+        from paper_2303_08374_amd import workloads
+        out["stages"] = workloads.run_all(ctx)
     if args.calibrate:
         n = (1 << 30) // 4
         src = arena.base

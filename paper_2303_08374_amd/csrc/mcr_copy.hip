@@ -106,128 +106,63 @@ alltoall_kernel(PtrTab out, CPtrTab in, size_t b) {
 }
 
 // ---- all_to_allv -----------------------------------------------------------------
-// All rows of all senders form one flat sequence in send order (sender p, then
-// destination r, then row k); pair i = p*P + r owns rows [rowstart[i],
-// rowstart[i+1]).  Work is dealt out over that flat sequence in units, so the
-// load per workgroup is even no matter how skewed the split matrix is.  Every
-// workgroup rebuilds the displacement tables in LDS from the P*P split matrix
-// (host matrix passed by value, or device matrix read here: no host sync).
+// blockIdx.y = sender p, blockIdx.z = receiver r, blockIdx.x = tile of the pair's
+// rows.  With packed displacements the rows of one pair are contiguous on both
+// sides, so a pair is a plain linear copy of S[p][r]*upr units from
+//   in[p]  + sdispl[p][r]*upr    (sdispl = sum of row p of S left of r)
+// to out[r] + rdispl[r][p]*upr   (rdispl = sum of column r of S above p),
+// and every workgroup derives its two displacements itself from at most 2*(P-1)
+// entries of S with uniform loads: no table, no search, no division per thread.
+// S comes by value (host matrix) or is read from device memory (no host sync).
+// In dispatch order the chip walks one pair after the other: one read stream
+// and one write stream at a time.  Skew costs nothing but workgroups that find
+// their tile beyond the pair's end and leave at once; pairs longer than the
+// grid are covered by striding.
 struct SplitArg {
   int64_t s[MCR_MAX_RANKS * MCR_MAX_RANKS];
 };
 
-struct A2AVTables {
-  int64_t S[MCR_MAX_RANKS * MCR_MAX_RANKS];
-  int64_t rowstart[MCR_MAX_RANKS * MCR_MAX_RANKS + 1];
-  int64_t rdispl[MCR_MAX_RANKS * MCR_MAX_RANKS];
-  int64_t rowsum[MCR_MAX_RANKS];
-  int64_t sendbase[MCR_MAX_RANKS];
-  const void* in[MCR_MAX_RANKS];
-  void* out[MCR_MAX_RANKS];
-};
-
-template <bool DEV>
-__device__ __forceinline__ void build_tables(A2AVTables& t, const SplitArg& hs, const int64_t* ds,
-                                             const PtrTab& out, const CPtrTab& in, int P,
-                                             uint64_t in_rows) {
-  const int tid = threadIdx.x;
-  const int PP = P * P;
-  if (tid < PP) {
-    // a device matrix is untrusted: negative -> 0, and no pair can carry more rows than a
-    // send buffer holds, which also bounds the loop below
-    int64_t s = DEV ? ds[tid] : hs.s[tid];
-    if (s < 0) s = 0;
-    if (static_cast<uint64_t>(s) > in_rows) s = static_cast<int64_t>(in_rows);
-    t.S[tid] = s;
-  }
-  if (tid < P) {
-    t.in[tid] = in.p[tid];
-    t.out[tid] = out.p[tid];
-  }
-  __syncthreads();
-  if (tid < P) {
-    int64_t a = 0;
-    for (int r = 0; r < P; ++r) a += t.S[tid * P + r];
-    t.rowsum[tid] = a;
-  }
-  __syncthreads();
-  if (tid < P) {
-    int64_t a = 0;
-    for (int q = 0; q < tid; ++q) a += t.rowsum[q];
-    t.sendbase[tid] = a;
-  }
-  __syncthreads();
-  if (tid < PP) {
-    const int p = tid / P, r = tid % P;
-    int64_t sd = 0, rd = 0;
-    for (int q = 0; q < r; ++q) sd += t.S[p * P + q];
-    for (int q = 0; q < p; ++q) rd += t.S[q * P + r];
-    t.rowstart[tid] = t.sendbase[p] + sd;
-    t.rdispl[tid] = rd;
-    if (tid == PP - 1) t.rowstart[PP] = t.sendbase[p] + sd + t.S[tid];
-  }
-  __syncthreads();
+// A split entry as the kernel uses it: a device matrix is untrusted, so negative
+// counts as 0 and nothing exceeds the rows a send buffer holds.
+__device__ __forceinline__ uint64_t clamp_split(int64_t s, uint64_t in_rows) {
+  if (s < 0) return 0;
+  return static_cast<uint64_t>(s) > in_rows ? in_rows : static_cast<uint64_t>(s);
 }
 
-// upr = units per row; shift >= 0 when upr is a power of two.
 template <int UB, int U, bool NTL, bool NTS, bool DEV>
 __global__ void __launch_bounds__(kBlock)
-alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, uint32_t upr,
-                 int shift, uint64_t in_rows, uint64_t out_rows) {
+alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, uint64_t upr,
+                 uint64_t in_rows, uint64_t out_rows) {
   typedef typename Unit<UB>::type T;
-  __shared__ A2AVTables t;
-  build_tables<DEV>(t, hs, ds, out, in, P, in_rows);
-  const int PP = P * P;
-  const uint64_t total = static_cast<uint64_t>(t.rowstart[PP]) * upr;
   constexpr uint64_t kTile = static_cast<uint64_t>(U) * kBlock;
+  const int p = blockIdx.y, r = blockIdx.z;
+  const int64_t* S = DEV ? ds : hs.s;
+  uint64_t rows = clamp_split(S[p * P + r], in_rows);
+  if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;      // the common early exit
+  uint64_t sdispl = 0, rdispl = 0;
+  for (int q = 0; q < r; ++q) sdispl += clamp_split(S[p * P + q], in_rows);
+  for (int q = 0; q < p; ++q) rdispl += clamp_split(S[q * P + r], in_rows);
+  // rows that would leave either buffer are not copied
+  if (sdispl >= in_rows || rdispl >= out_rows) return;
+  if (rows > in_rows - sdispl) rows = in_rows - sdispl;
+  if (rows > out_rows - rdispl) rows = out_rows - rdispl;
+  const uint64_t n = rows * upr;
+  const T* src = static_cast<const T*>(in.p[p]) + sdispl * upr;
+  T* dst = static_cast<T*>(out.p[r]) + rdispl * upr;
   const uint64_t step = static_cast<uint64_t>(gridDim.x) * kTile;
-  for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < total; tile += step) {
+  for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < n; tile += step) {
     T v[U];
-    void* dptr[U];
-    uint64_t didx[U];
-    bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-      ok[u] = idx < total;
-      if (ok[u]) {
-        uint64_t g, c;
-        if (shift >= 0) {
-          g = idx >> shift;
-          c = idx & (upr - 1u);
-        } else {
-          g = idx / upr;
-          c = idx - g * upr;
-        }
-        // last pair whose first row is <= g
-        int lo = 0, hi = PP;   // invariant: rowstart[lo] <= g < rowstart[hi]
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (static_cast<uint64_t>(t.rowstart[mid]) <= g) lo = mid; else hi = mid;
-        }
-        const int p = lo / P, r = lo - p * P;
-        const uint64_t srow = g - static_cast<uint64_t>(t.sendbase[p]);
-        const uint64_t drow = static_cast<uint64_t>(t.rdispl[lo]) + (g - static_cast<uint64_t>(t.rowstart[lo]));
-        ok[u] = srow < in_rows && drow < out_rows;
-        if (ok[u]) {
-          v[u] = load_unit<NTL, T>(t.in[p], srow * upr + c);
-          dptr[u] = t.out[r];
-          didx[u] = drow * upr + c;
-        }
-      }
+      if (idx < n) v[u] = load_unit<NTL, T>(src, idx);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (ok[u]) store_unit<NTS, T>(dptr[u], didx[u], v[u]);
+      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+      if (idx < n) store_unit<NTS, T>(dst, idx, v[u]);
     }
   }
-}
-
-inline int log2_exact(uint64_t x) {
-  if (x == 0 || (x & (x - 1))) return -1;
-  int s = 0;
-  while ((x >> s) != 1) ++s;
-  return s;
 }
 
 inline unsigned capped_blocks(size_t units, size_t per_block, size_t cap) {
@@ -300,47 +235,45 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
   });
 }
 
-int launch_alltoallv(mcr_ctx* ctx, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits,
+int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits,
                      const int64_t* dev_splits, size_t in_rows, size_t out_rows, size_t row_bytes,
                      int elem_b, int P, int variant, hipStream_t stream) {
   SplitArg hs;
-  uint64_t total_rows = 0;
   for (int i = 0; i < MCR_MAX_RANKS * MCR_MAX_RANKS; ++i) hs.s[i] = 0;
+  // rows of the longest pair: exact for a host matrix, the buffer bound for a device one
+  uint64_t max_pair = 0;
   if (host_splits) {
     for (int i = 0; i < P * P; ++i) {
       hs.s[i] = host_splits[i];
-      total_rows += static_cast<uint64_t>(host_splits[i]);
+      if (static_cast<uint64_t>(host_splits[i]) > max_pair) max_pair = static_cast<uint64_t>(host_splits[i]);
     }
   } else {
-    total_rows = static_cast<uint64_t>(P) * in_rows;   // upper bound; the kernel knows the real total
+    max_pair = in_rows < out_rows ? in_rows : out_rows;
   }
-  if (total_rows == 0 || row_bytes == 0) return MCR_OK;
+  if (max_pair == 0 || row_bytes == 0) return MCR_OK;
   const bool dev = host_splits == nullptr;
 
-  auto go = [&](auto ub, auto uu, auto ntl, auto nts, size_t cap) {
+  auto go = [&](auto ub, auto uu, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     constexpr int U = decltype(uu)::value;
     constexpr bool NTL = decltype(ntl)::value;
     constexpr bool NTS = decltype(nts)::value;
     const uint64_t upr = row_bytes / UB;
-    const unsigned gx = capped_blocks(total_rows * upr, static_cast<size_t>(U) * kBlock, cap);
-    const int shift = log2_exact(upr);
+    // a device matrix usually fills a fraction of the bound: cap the tiles per pair, longer pairs stride
+    const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock, dev ? 1024 : 65535 * 16);
     if (dev)
-      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx), dim3(kBlock), 0, stream, out, in, hs,
-                         dev_splits, P, static_cast<uint32_t>(upr), shift, static_cast<uint64_t>(in_rows),
-                         static_cast<uint64_t>(out_rows));
+      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
+                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows));
     else
-      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, false>), dim3(gx), dim3(kBlock), 0, stream, out, in, hs,
-                         dev_splits, P, static_cast<uint32_t>(upr), shift, static_cast<uint64_t>(in_rows),
-                         static_cast<uint64_t>(out_rows));
+      hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
+                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows));
     return launch_status();
   };
   if (variant == SV_SCALAR) {
-    const size_t cap = static_cast<size_t>(ctx->num_cus) * 32;
-    if (elem_b == 4) return go(Int<4>{}, Int<1>{}, Bool<false>{}, Bool<false>{}, cap);
-    return go(Int<2>{}, Int<1>{}, Bool<false>{}, Bool<false>{}, cap);
+    if (elem_b == 4) return go(Int<4>{}, Int<4>{}, Bool<false>{}, Bool<false>{});
+    return go(Int<2>{}, Int<4>{}, Bool<false>{}, Bool<false>{});
   }
-  return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) { return go(Int<16>{}, uu, ntl, nts, size_t(1) << 30); });
+  return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) { return go(Int<16>{}, uu, ntl, nts); });
 }
 
 }  // namespace mcr

@@ -1,0 +1,245 @@
+"""Device-side drivers of the application-shaped workloads: the small allreduce, MoE token
+dispatch/combine, the DLRM embedding shuffle and dense gradient buckets.  Each returns
+per-stage times measured with events on the launch stream, with the algorithmic bytes of the
+stage (bytes that must be read plus written once).
+
+They stand in for the paper's DS-MoE, DLRM and Megatron-DeepSpeed runs (Sec. V-A4), whose
+models and datasets are not needed for the data movement itself.  Inputs are generated on the
+device here (timing only; the parity tests use the host generators of ``inputs``).
+"""
+from __future__ import annotations
+
+from typing import Dict, List
+
+import numpy as np
+import torch
+
+from . import inputs, mcr
+
+
+def _events(n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _stage_report(names, alg_bytes, ev_rows):
+    """ev_rows: one list of len(names)+1 events per repetition."""
+    out = {}
+    for i, name in enumerate(names):
+        ms = sorted(r[i].elapsed_time(r[i + 1]) for r in ev_rows)
+        med = ms[len(ms) // 2]
+        out[name] = {"us": round(med * 1e3, 2), "alg_bytes": int(alg_bytes[i]),
+                     "GBps": round(alg_bytes[i] / (med * 1e-3) / 1e9, 1) if alg_bytes[i] else None}
+    tot = sorted(r[0].elapsed_time(r[-1]) for r in ev_rows)
+    med = tot[len(tot) // 2]
+    out["end_to_end"] = {"us": round(med * 1e3, 2), "alg_bytes": int(sum(alg_bytes)),
+                         "GBps": round(sum(alg_bytes) / (med * 1e-3) / 1e9, 1)}
+    return out
+
+
+# ---- workload 1 ---------------------------------------------------------------------------
+def allreduce_small(ctx, reps: int = 50) -> Dict:
+    """P=4, 2^20 fp32 per rank (32 MiB of traffic per call).  `cold`: 32 buffer sets in rotation
+    (512 MiB, beyond the last-level cache); `warm`: the same buffers every time (cache resident,
+    not an HBM figure)."""
+    w = inputs.AllreduceSmall()
+    sets = 32
+    arena = torch.empty(sets * w.P * w.n, dtype=torch.float32, device="cuda").normal_()
+    base = arena.data_ptr()
+    ptrs = [[base + (s * w.P + p) * w.n * 4 for p in range(w.P)] for s in range(sets)]
+    alg = 2 * w.P * w.n * 4
+    out = {}
+    for label, pick in (("cold", lambda i: ptrs[i % sets]), ("warm", lambda i: ptrs[0])):
+        for i in range(sets):
+            mcr.mcr_allreduce(ctx, pick(i), w.n, mcr.F32, mcr.SUM, w.P)
+        e = _events(2)
+        e[0].record()
+        for i in range(reps):
+            mcr.mcr_allreduce(ctx, pick(i), w.n, mcr.F32, mcr.SUM, w.P)
+        e[1].record()
+        e[1].synchronize()
+        ms = e[0].elapsed_time(e[1]) / reps
+        out[label] = {"us": round(ms * 1e3, 2), "alg_bytes": alg, "GBps": round(alg / (ms * 1e-3) / 1e9, 1)}
+        arena.normal_()
+    return out
+
+
+# ---- workload 3 ---------------------------------------------------------------------------
+def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoEWorkload()) -> Dict:
+    P, T, H, E, C = w.P, w.T, w.H, w.E, w.C
+    row = H * 2
+    d_ids = [torch.from_numpy(w.ids(p)).cuda() for p in range(P)]
+    d_tok = [torch.empty(T * H, dtype=torch.bfloat16, device="cuda").normal_() for _ in range(P)]
+    d_gate = [torch.rand(T, dtype=torch.float32, device="cuda") for _ in range(P)]
+    d_slot = [torch.empty(T, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_cnt = [torch.empty(E, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_S = torch.empty(P * P, dtype=torch.int64, device="cuda")
+    mk = lambda rows: [torch.zeros(rows * H, dtype=torch.bfloat16, device="cuda") for _ in range(P)]
+    d_packed, d_recv, d_back, d_out = mk(T), mk(w.recv_rows), mk(T), mk(T)
+    rows = []
+    for it in range(reps + 2):
+        e = _events(6)
+        e[0].record()
+        mcr.mcr_moe_route(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+        e[1].record()
+        mcr.mcr_pack(ctx, d_packed, d_tok, d_slot, T, T, H, mcr.BF16, P)
+        e[2].record()
+        mcr.mcr_alltoallv(ctx, d_recv, d_packed, d_S, True, T, w.recv_rows, H, mcr.BF16, P)
+        d_ST = d_S.view(P, P).t().contiguous()
+        e[3].record()
+        mcr.mcr_alltoallv(ctx, d_back, d_recv, d_ST, True, w.recv_rows, T, H, mcr.BF16, P)
+        e[4].record()
+        mcr.mcr_unpack(ctx, d_out, d_back, d_slot, d_gate, T, T, H, mcr.BF16, P)
+        e[5].record()
+        if it >= 2:
+            rows.append(e)
+    torch.cuda.synchronize()
+    kept = int(d_S.sum().item())
+    alg = [0,                                  # routing: a few KB of integers, latency bound
+           2 * kept * row + P * T * 4,         # pack: kept rows read and written, slots read
+           2 * kept * row,                     # dispatch alltoallv
+           2 * kept * row,                     # return alltoallv
+           kept * row + P * T * row + P * T * 8]   # combine: kept rows read, all T rows written, slot + gate read
+    rep = _stage_report(["route", "pack", "alltoallv_dispatch", "alltoallv_return", "unpack_combine"], alg, rows)
+    rep["kept_rows"] = kept
+    rep["kept_fraction"] = round(kept / (P * T), 4)
+    return rep
+
+
+# ---- workload 4 ---------------------------------------------------------------------------
+def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorkload(), sets: int = 3) -> Dict:
+    """Forward: pooled [T_p, B, D] -> destination-major send order (pack) -> alltoallv ->
+    [B/P, n_tables, D] (unpack with the table permutation).  Backward: the inverse chain.
+    `sets` independent buffer sets are used in rotation so that a stage does not find its
+    input in the last-level cache."""
+    P, NT, D, B = w.P, w.n_tables, w.dim, w.batch
+    bl = B // P
+    n_local = [len(w.tables_on(p)) for p in range(P)]
+    max_rows = max(n_local) * B
+    S = w.splits()
+    send_slot = []
+    for p in range(P):
+        lt, r, b = np.meshgrid(np.arange(n_local[p]), np.arange(P), np.arange(bl), indexing="ij")
+        full = np.full(max_rows, -1, dtype=np.int32)
+        full[: lt.size] = ((r * n_local[p] + lt) * bl + b).reshape(-1)
+        send_slot.append(torch.from_numpy(full).cuda())
+    order = [t for p in range(P) for t in w.tables_on(p)]
+    pos = np.empty(NT, dtype=np.int64)
+    pos[order] = np.arange(NT)
+    perm = (pos[None, :] * bl + np.arange(bl)[:, None]).reshape(-1).astype(np.int32)
+    d_perm = [torch.from_numpy(perm).cuda() for _ in range(P)]
+    f32 = lambda rows: [torch.empty(rows * D, dtype=torch.float32, device="cuda").normal_() for _ in range(P)]
+    bufs = [dict(src=f32(max_rows), send=f32(max_rows), recv=f32(NT * bl), out=f32(bl * NT), grecv=f32(NT * bl),
+                 gsend=f32(max_rows), gsrc=f32(max_rows)) for _ in range(sets)]
+    ST = S.T.copy()
+    rows = []
+    for it in range(reps + sets):
+        x = bufs[it % sets]
+        e = _events(7)
+        e[0].record()
+        mcr.mcr_pack(ctx, x["send"], x["src"], send_slot, max_rows, max_rows, D, mcr.F32, P)
+        e[1].record()
+        mcr.mcr_alltoallv(ctx, x["recv"], x["send"], S, False, max_rows, NT * bl, D, mcr.F32, P)
+        e[2].record()
+        mcr.mcr_unpack(ctx, x["out"], x["recv"], d_perm, None, bl * NT, NT * bl, D, mcr.F32, P)
+        e[3].record()
+        mcr.mcr_pack(ctx, x["grecv"], x["out"], d_perm, bl * NT, NT * bl, D, mcr.F32, P)
+        e[4].record()
+        mcr.mcr_alltoallv(ctx, x["gsend"], x["grecv"], ST, False, NT * bl, max_rows, D, mcr.F32, P)
+        e[5].record()
+        mcr.mcr_unpack(ctx, x["gsrc"], x["gsend"], send_slot, None, max_rows, max_rows, D, mcr.F32, P)
+        e[6].record()
+        if it >= sets:
+            rows.append(e)
+    torch.cuda.synchronize()
+    data = NT * B * D * 4                                   # 208 MiB of pooled rows
+    pad = (P * max_rows - NT * B) * D * 4                   # zero rows written for the ranks that own fewer tables
+    alg = [2 * data + P * max_rows * 4, 2 * data, 2 * data + NT * B * 4,
+           2 * data + NT * B * 4, 2 * data, 2 * data + pad + P * max_rows * 4]
+    return _stage_report(["fwd_pack_send_order", "fwd_alltoallv", "fwd_unpack_permute",
+                          "bwd_pack_permute", "bwd_alltoallv", "bwd_unpack_table_order"], alg, rows)
+
+
+# ---- workload 5 ---------------------------------------------------------------------------
+def grad_buckets(ctx, reps: int = 3, w: inputs.GradBucketWorkload = inputs.GradBucketWorkload()) -> Dict:
+    """bf16 gradients of the GPT-style list on P ranks.  Three ways to all-reduce (average) them:
+    per bucket fuse -> allreduce(flat) -> unfuse; the fused multi-tensor allreduce in one launch
+    over the whole list; and one allreduce launch per tensor (no fusion)."""
+    P = w.P
+    numel = w.numel()
+    total = sum(numel)
+    plan = mcr.mcr_fuse_plan_create(ctx, numel, w.bucket_elems, mcr.BF16)
+    try:
+        bn, tb, to = mcr.mcr_fuse_plan_info(plan, len(numel))
+        arenas = [torch.empty(total, dtype=torch.bfloat16, device="cuda").normal_(0.0, w.std) for _ in range(P)]
+        offs = np.concatenate([[0], np.cumsum(numel)[:-1]]).tolist()
+        ptrs = [arenas[p].data_ptr() + offs[i] * 2 for p in range(P) for i in range(len(numel))]
+        mcr.mcr_fuse_plan_bind(ctx, plan, ptrs, P)
+        flats = [torch.empty(max(bn), dtype=torch.bfloat16, device="cuda") for _ in range(P)]
+        s = 2
+        rows_pipe, rows_multi, rows_each = [], [], []
+        for it in range(reps + 1):
+            e = _events(2)
+            stage_ev = []
+            e[0].record()
+            for k in range(len(bn)):
+                se = _events(4)
+                se[0].record()
+                mcr.mcr_fuse(ctx, plan, k, flats, P)
+                se[1].record()
+                mcr.mcr_allreduce(ctx, flats, bn[k], mcr.BF16, mcr.AVG, P)
+                se[2].record()
+                mcr.mcr_unfuse(ctx, plan, k, flats, P)
+                se[3].record()
+                stage_ev.append(se)
+            e[1].record()
+            if it >= 1:
+                rows_pipe.append((e, stage_ev))
+        for it in range(reps + 1):
+            e = _events(2)
+            e[0].record()
+            mcr.mcr_allreduce_multi(ctx, plan, -1, mcr.AVG)
+            e[1].record()
+            if it >= 1:
+                rows_multi.append(e)
+        for it in range(reps + 1):
+            e = _events(2)
+            e[0].record()
+            for i, n in enumerate(numel):
+                mcr.mcr_allreduce(ctx, [ptrs[p * len(numel) + i] for p in range(P)], n, mcr.BF16, mcr.AVG, P)
+            e[1].record()
+            if it >= 1:
+                rows_each.append(e)
+        torch.cuda.synchronize()
+        minimum = 2 * P * total * s                          # read every gradient once, write it once
+        med = lambda xs: sorted(xs)[len(xs) // 2]
+        rep = {}
+        for name, idx, alg in (("fuse", 0, 2 * P * total * s), ("allreduce_flat", 1, 2 * P * total * s),
+                               ("unfuse", 2, 2 * P * total * s)):
+            ms = med([sum(se[idx].elapsed_time(se[idx + 1]) for se in stage_ev) for _, stage_ev in rows_pipe])
+            rep[name] = {"us": round(ms * 1e3, 1), "alg_bytes": alg, "GBps": round(alg / (ms * 1e-3) / 1e9, 1)}
+        ms = med([e[0].elapsed_time(e[1]) for e, _ in rows_pipe])
+        rep["pipeline_fuse_allreduce_unfuse"] = {"us": round(ms * 1e3, 1), "launches": 3 * len(bn), "traffic_bytes": 3 * minimum,
+                                                 "GBps_of_minimum": round(minimum / (ms * 1e-3) / 1e9, 1),
+                                                 "GBps_of_traffic": round(3 * minimum / (ms * 1e-3) / 1e9, 1)}
+        ms = med([e[0].elapsed_time(e[1]) for e in rows_multi])
+        rep["allreduce_multi_one_launch"] = {"us": round(ms * 1e3, 1), "launches": 1, "alg_bytes": minimum,
+                                             "GBps": round(minimum / (ms * 1e-3) / 1e9, 1)}
+        ms = med([e[0].elapsed_time(e[1]) for e in rows_each])
+        rep["allreduce_per_tensor"] = {"us": round(ms * 1e3, 1), "launches": len(numel), "alg_bytes": minimum,
+                                       "GBps": round(minimum / (ms * 1e-3) / 1e9, 1)}
+        rep["tensors"], rep["buckets"], rep["elements_per_rank"] = len(numel), len(bn), total
+        return rep
+    finally:
+        mcr.mcr_fuse_plan_destroy(plan)
+
+
+def run_all(ctx) -> Dict:
+    out = {"allreduce_small": allreduce_small(ctx)}
+    torch.cuda.empty_cache()
+    out["moe_dispatch_combine"] = moe_dispatch_combine(ctx)
+    torch.cuda.empty_cache()
+    out["dlrm_shuffle"] = dlrm_shuffle(ctx)
+    torch.cuda.empty_cache()
+    out["grad_buckets"] = grad_buckets(ctx)
+    torch.cuda.empty_cache()
+    return out
