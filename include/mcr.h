@@ -66,7 +66,10 @@ typedef enum {
   MCR_OP_UNFUSE = 8,
   MCR_OP_ALLREDUCE_MULTI = 9,
   MCR_OP_MOE_ROUTE = 10,
-  MCR_OP_COUNT = 11
+  MCR_OP_MOE_DISPATCH = 11,
+  MCR_OP_MOE_COMBINE = 12,
+  MCR_OP_DLRM_SHUFFLE = 13,
+  MCR_OP_COUNT = 14
 } mcr_op;
 
 typedef enum {
@@ -192,6 +195,40 @@ int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_
 int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot,
                const float* const* gate, size_t T, size_t in_rows, size_t row_elems,
                mcr_dtype dtype, int P, int variant, void* stream);
+
+/* ---- pipelines fused across op boundaries ----------------------------------------
+ * One address space lets a row go straight from where it is to where it is needed;
+ * each call below writes bit for bit what the chain of calls it replaces writes, for
+ * split matrices as mcr_moe_route produces them (entries within [0, T]).
+ *
+ * mcr_moe_dispatch = mcr_pack followed by mcr_alltoallv(splits on device): for every rank
+ * p and token t with 0 <= slot[p][t] < T, the token row is written to row
+ * rdispl[r][p] + (slot - sdispl[p][r]) of recv[r], r being the rank whose block of rank
+ * p's packed order holds that slot.  Rows that would fall outside recv_rows are skipped;
+ * other rows of recv are left untouched.  splits: DEVICE memory, P*P int64. */
+int mcr_moe_dispatch(mcr_ctx* ctx, void* const* recv, const void* const* tokens,
+                     const int32_t* const* slot, const int64_t* splits, size_t T, size_t recv_rows,
+                     size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream);
+
+/* mcr_moe_combine = mcr_alltoallv(transposed splits) followed by mcr_unpack with a gate:
+ * out[p] row t = round_to_dtype(gate[p][t] * f32(row of expert_out[r] that token t was
+ * dispatched to)), all-zero bits for a dropped token.  expert_out[r] has the layout of
+ * recv[r] above (the experts' outputs, row for row).  gate may be NULL (no scaling). */
+int mcr_moe_combine(mcr_ctx* ctx, void* const* out, const void* const* expert_out,
+                    const int32_t* const* slot, const float* const* gate, const int64_t* splits,
+                    size_t T, size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant,
+                    void* stream);
+
+/* mcr_dlrm_shuffle: the embedding shuffle of paper Sec. II-D as one row permutation.
+ * n_tables tables, table t on rank t mod P as its local table t div P.
+ *   backward == 0: in[p] is [T_p][batch][dim] (table-major pooled rows), out[r] is
+ *     [batch/P][n_tables][dim]; out[r][b][t][:] = in[t mod P][t div P][r*(batch/P) + b][:].
+ *   backward != 0: the inverse (gradients): in[r] is [batch/P][n_tables][dim], out[p] is
+ *     [T_p][batch][dim].
+ * P must divide batch.  Equals pack + all_to_allv + unpack of the same rows. */
+int mcr_dlrm_shuffle(mcr_ctx* ctx, void* const* out, const void* const* in, int n_tables,
+                     size_t batch, size_t dim, mcr_dtype dtype, int P, int backward, int variant,
+                     void* stream);
 
 /* ---- tensor fusion (paper Sec. IV-D: small tensors are combined into a fusion
  * buffer of at most B elements; the wait-time parameter T is not modelled) -------

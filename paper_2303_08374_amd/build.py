@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmcr.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["mcr_api.hip", "mcr_allreduce.hip", "mcr_reduce_scatter.hip", "mcr_copy.hip", "mcr_moe.hip", "mcr_fuse.hip"]
+SOURCES = ["mcr_api.hip", "mcr_allreduce.hip", "mcr_reduce_scatter.hip", "mcr_copy.hip", "mcr_moe.hip", "mcr_fuse.hip", "mcr_fused.hip"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler otherwise forms packed
 # binary32 instructions from ordinary float code.
@@ -38,7 +38,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 6) -> str:
+def build(jobs: int = 7) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(_compile, SOURCES))

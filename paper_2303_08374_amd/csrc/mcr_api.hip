@@ -19,7 +19,8 @@ namespace {
 
 const char* const kOpNames[MCR_OP_COUNT] = {"allreduce", "reduce_scatter", "allgather", "alltoall",
                                             "alltoallv", "pack", "unpack", "fuse",
-                                            "unfuse", "allreduce_multi", "moe_route"};
+                                            "unfuse", "allreduce_multi", "moe_route", "moe_dispatch",
+                                            "moe_combine", "dlrm_shuffle"};
 const char* const kDtypeNames[2] = {"f32", "bf16"};
 const char* const kRouteVariantNames[1] = {"wave_ballot"};
 
@@ -328,6 +329,86 @@ int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int3
   if ((rc = set_device(ctx)) != MCR_OK) return rc;
   return launch_unpack(ctx, to, ti, tsl, gate ? &tg : nullptr, T, in_rows, row_elems, dtype, P, v,
                        static_cast<hipStream_t>(stream));
+}
+
+// ---- fused pipelines ---------------------------------------------------------------
+int mcr_moe_dispatch(mcr_ctx* ctx, void* const* recv, const void* const* tokens, const int32_t* const* slot,
+                     const int64_t* splits, size_t T, size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P,
+                     int variant, void* stream) {
+  if (!ctx || !recv || !tokens || !slot || !splits || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull || (reinterpret_cast<uintptr_t>(splits) & 7u)) return MCR_EINVAL;
+  const bool any = T > 0 && row_elems > 0 && recv_rows > 0;
+  PtrTab to;
+  CPtrTab ti, tsl;
+  bool all16 = true;
+  if (!fill_tab(to, recv, P, dtype, any, &all16) || !fill_tab(ti, tokens, P, dtype, any, &all16) ||
+      !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
+    return MCR_EINVAL;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_MOE_DISPATCH, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_moe_dispatch(ctx, to, ti, tsl, splits, T, recv_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P, v,
+                             static_cast<hipStream_t>(stream));
+}
+
+int mcr_moe_combine(mcr_ctx* ctx, void* const* out, const void* const* expert_out, const int32_t* const* slot,
+                    const float* const* gate, const int64_t* splits, size_t T, size_t recv_rows, size_t row_elems,
+                    mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !out || !expert_out || !slot || !splits || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull || (reinterpret_cast<uintptr_t>(splits) & 7u)) return MCR_EINVAL;
+  const bool any = T > 0 && row_elems > 0;
+  PtrTab to;
+  CPtrTab ti, tsl, tg;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, expert_out, P, dtype, any && recv_rows > 0, &all16) ||
+      !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
+    return MCR_EINVAL;
+  if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_MOE_COMBINE, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_moe_combine(ctx, to, ti, tsl, gate ? &tg : nullptr, splits, T, recv_rows, row_elems, dtype, P, v,
+                            static_cast<hipStream_t>(stream));
+}
+
+int mcr_dlrm_shuffle(mcr_ctx* ctx, void* const* out, const void* const* in, int n_tables, size_t batch, size_t dim,
+                     mcr_dtype dtype, int P, int backward, int variant, void* stream) {
+  if (!ctx || !out || !in || !valid_P(P) || n_tables < 0) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (batch % static_cast<size_t>(P) != 0 || dim > (size_t(1) << 28)) return MCR_EINVAL;
+  const bool any = n_tables > 0 && batch > 0 && dim > 0;
+  // a rank that owns no table (n_tables < P) has an empty table-major buffer and may pass NULL
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) { to.p[i] = nullptr; ti.p[i] = nullptr; }
+  for (int p = 0; p < P; ++p) {
+    const bool owns = p < n_tables;
+    const bool need_out = any && (backward ? owns : true);
+    const bool need_in = any && (backward ? true : owns);
+    if ((need_out && !out[p]) || (need_in && !in[p])) return MCR_EINVAL;
+    if (!elem_aligned(out[p], dtype) || !elem_aligned(in[p], dtype)) return MCR_EINVAL;
+    if ((need_out && !aligned16(out[p])) || (need_in && !aligned16(in[p]))) all16 = false;
+    to.p[p] = out[p];
+    ti.p[p] = in[p];
+  }
+  const size_t row_bytes = dim * elem_bytes(dtype);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_DLRM_SHUFFLE, dtype, P, (batch / P) * n_tables * row_bytes,
+                           all16 && row_bytes % 16 == 0, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_dlrm_shuffle(ctx, to, ti, n_tables, batch, row_bytes, static_cast<int>(elem_bytes(dtype)), P, backward != 0,
+                             v, static_cast<hipStream_t>(stream));
 }
 
 // ---- tensor fusion ---------------------------------------------------------------

@@ -260,7 +260,7 @@ int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64
     constexpr bool NTS = decltype(nts)::value;
     const uint64_t upr = row_bytes / UB;
     // a device matrix usually fills a fraction of the bound: cap the tiles per pair, longer pairs stride
-    const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock, dev ? 1024 : 65535 * 16);
+    const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock, dev ? 256 : 65535 * 16);
     if (dev)
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
                          hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows));

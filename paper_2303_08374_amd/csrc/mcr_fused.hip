@@ -1,0 +1,296 @@
+// Pipelines fused across op boundaries, which one address space allows and a
+// library-per-operation runtime does not:
+//   moe_dispatch  = pack + all_to_allv      (token rows go straight to their row in the
+//                                            destination rank's receive buffer)
+//   moe_combine   = all_to_allv(S^T) + gate-weighted unpack
+//                                           (each token row is fetched from where the expert
+//                                            left it on the destination rank and scaled)
+//   dlrm_shuffle  = pack + all_to_allv + unpack of the embedding shuffle, forward or
+//                   backward, as one row permutation across the rank buffers
+// Each produces bit for bit what the unfused chain produces (paper Sec. II-C and II-D
+// describe the chains), at 2 row transfers instead of 4 to 6.
+#include "mcr_dispatch.hpp"
+
+namespace mcr {
+namespace {
+
+template <int UB> struct RowUnit;
+template <> struct RowUnit<16> { typedef u32x4 type; };
+template <> struct RowUnit<4> { typedef uint32_t type; };
+template <> struct RowUnit<2> { typedef uint16_t type; };
+
+template <bool NT, class U> __device__ __forceinline__ U ldu(const U* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT, class U> __device__ __forceinline__ void stu(U* p, U v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// Displacements of sender `p` for every receiver r, from the device split matrix:
+//   sd[r] = sum_{q<r} S[p][q]  (sd[P] = rows rank p sends in all)
+//   rd[r] = sum_{q<p} S[q][r]  (first row of rank p's block in receiver r's buffer)
+// Entries are untrusted: negative counts as 0, nothing exceeds `cap` rows.
+struct PairTables {
+  int64_t sd[MCR_MAX_RANKS + 1];
+  int64_t rd[MCR_MAX_RANKS];
+};
+__device__ __forceinline__ int64_t clamp_rows(int64_t s, int64_t cap) { return s < 0 ? 0 : (s > cap ? cap : s); }
+
+__device__ __forceinline__ void build_pair_tables(PairTables& t, const int64_t* S, int p, int P, int64_t cap) {
+  const int r = threadIdx.x;
+  if (r <= P) {
+    int64_t a = 0;
+    for (int q = 0; q < r; ++q) a += clamp_rows(S[p * P + q], cap);
+    t.sd[r] = a;
+  }
+  if (r < P) {
+    int64_t a = 0;
+    for (int q = 0; q < p; ++q) a += clamp_rows(S[q * P + r], cap);
+    t.rd[r] = a;
+  }
+  __syncthreads();
+}
+
+// Receiver of packed row s of this sender, and its row in that receiver's buffer; false if the
+// slot is not a row this sender owns or the row would leave the receive buffer.
+__device__ __forceinline__ bool locate(const PairTables& t, int P, int64_t s, int64_t send_rows, uint64_t recv_rows,
+                                       int* r_out, uint64_t* row_out) {
+  if (s < 0 || s >= t.sd[P] || s >= send_rows) return false;
+  int r = 0;
+  for (int q = 1; q < P; ++q) r += (t.sd[q] <= s) ? 1 : 0;     // sd is non-decreasing
+  const uint64_t row = static_cast<uint64_t>(t.rd[r] + (s - t.sd[r]));
+  if (row >= recv_rows) return false;
+  *r_out = r;
+  *row_out = row;
+  return true;
+}
+
+constexpr int kRowsPerBlock = 8;   // token rows one workgroup walks (amortises the table build)
+constexpr int kRowsInFlight = 4;   // rows whose loads are issued before the first store
+
+// blockIdx.y = sender p.  tpr threads (power of two) share a row of upr units.
+template <int UB, bool NTL, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+moe_dispatch_kernel(PtrTab recv, CPtrTab tok, CPtrTab slot_tab, const int64_t* S, int P, size_t T,
+                    uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  __shared__ PairTables tab;
+  const int p = blockIdx.y;
+  build_pair_tables(tab, S, p, P, static_cast<int64_t>(T));
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  const U* src = static_cast<const U*>(tok.p[p]);
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
+    const U* srow[kRowsInFlight];
+    U* drow[kRowsInFlight];
+    bool ok[kRowsInFlight];
+#pragma unroll
+    for (int j = 0; j < kRowsInFlight; ++j) {
+      const size_t t = t0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
+      int r = 0;
+      uint64_t row = 0;
+      ok[j] = t < T && locate(tab, P, slot[t], static_cast<int64_t>(T), recv_rows, &r, &row);
+      srow[j] = src + t * upr;
+      drow[j] = ok[j] ? static_cast<U*>(recv.p[r]) + row * upr : nullptr;
+    }
+    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+      U v[kRowsInFlight];
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j)
+        if (ok[j]) v[j] = ldu<NTL, U>(srow[j] + c);
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j)
+        if (ok[j]) stu<NTS, U>(drow[j] + c, v[j]);
+    }
+  }
+}
+
+template <int DT, int UB, class U> __device__ __forceinline__ U scale_unit(U v, float g) {
+  if constexpr (UB == 16) {
+    using E = Elem<DT>;
+    float f[E::kPerVec];
+    E::widen(v, f);
+#pragma unroll
+    for (int k = 0; k < E::kPerVec; ++k) f[k] = g * f[k];
+    return E::narrow(f);
+  } else {
+    // one element per unit
+    float x;
+    if constexpr (DT == MCR_F32) x = __uint_as_float(static_cast<uint32_t>(v));
+    else x = __uint_as_float(static_cast<uint32_t>(v) << 16);
+    const float y = g * x;
+    if constexpr (DT == MCR_F32) return static_cast<U>(__float_as_uint(y));
+    else return static_cast<U>(f32_to_bf16_rne(y));
+  }
+}
+
+// out[p] row t = gate[p][t] * (row of expert_out[r] that token t was dispatched to), zeros if dropped.
+template <int DT, int UB, bool NTL, bool NTS, bool GATE>
+__global__ void __launch_bounds__(kBlock)
+moe_combine_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gate_tab, const int64_t* S, int P,
+                   size_t T, uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  __shared__ PairTables tab;
+  const int p = blockIdx.y;
+  build_pair_tables(tab, S, p, P, static_cast<int64_t>(T));
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  U* dst = static_cast<U*>(out.p[p]);
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
+    const U* srow[kRowsInFlight];
+    U* drow[kRowsInFlight];
+    bool live[kRowsInFlight], kept[kRowsInFlight];
+    float g[kRowsInFlight];
+#pragma unroll
+    for (int j = 0; j < kRowsInFlight; ++j) {
+      const size_t t = t0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
+      int r = 0;
+      uint64_t row = 0;
+      live[j] = t < T;
+      kept[j] = live[j] && locate(tab, P, slot[t], static_cast<int64_t>(T), recv_rows, &r, &row);
+      srow[j] = kept[j] ? static_cast<const U*>(expert_out.p[r]) + row * upr : nullptr;
+      drow[j] = dst + t * upr;
+      g[j] = 1.0f;
+      if constexpr (GATE) {
+        if (kept[j]) g[j] = static_cast<const float*>(gate_tab.p[p])[t];
+      }
+    }
+    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+      U v[kRowsInFlight];
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j) {
+        v[j] = U{};
+        if (kept[j]) v[j] = ldu<NTL, U>(srow[j] + c);
+      }
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j) {
+        if (!live[j]) continue;
+        U y = v[j];
+        if constexpr (GATE) {
+          if (kept[j]) y = scale_unit<DT, UB, U>(y, g[j]);
+        }
+        stu<NTS, U>(drow[j] + c, y);
+      }
+    }
+  }
+}
+
+// DLRM shuffle.  Table t lives on rank t mod P as local table t div P; the table-major side is
+// [T_p][batch][dim], the batch-major side [batch/P][n_tables][dim].  blockIdx.y = rank r of the
+// batch-major side; rows j = b*n_tables + t of that side are walked in order.
+//   forward : batch[r] row j  = table[t mod P] row (t div P)*batch + r*bl + b
+//   backward: table[t mod P] row (...)        = batch[r] row j
+template <int UB, bool NTL, bool NTS, bool BWD>
+__global__ void __launch_bounds__(kBlock)
+dlrm_shuffle_kernel(PtrTab dst_tab, CPtrTab src_tab, uint32_t n_tables, uint64_t batch, uint32_t P, uint32_t upr,
+                    uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  const uint32_t r = blockIdx.y;
+  const uint64_t bl = batch / P;
+  const uint64_t rows = bl * n_tables;
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const uint64_t j = static_cast<uint64_t>(blockIdx.x) * rows_per_pass + (threadIdx.x >> tpr_shift);
+  if (j >= rows) return;
+  const uint64_t b = j / n_tables;
+  const uint32_t t = static_cast<uint32_t>(j - b * n_tables);
+  const uint32_t owner = t % P, local = t / P;
+  const uint64_t trow = static_cast<uint64_t>(local) * batch + static_cast<uint64_t>(r) * bl + b;
+  const U* s;
+  U* d;
+  if constexpr (BWD) {
+    s = static_cast<const U*>(src_tab.p[r]) + j * upr;
+    d = static_cast<U*>(dst_tab.p[owner]) + trow * upr;
+  } else {
+    s = static_cast<const U*>(src_tab.p[owner]) + trow * upr;
+    d = static_cast<U*>(dst_tab.p[r]) + j * upr;
+  }
+  for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) stu<NTS, U>(d + c, ldu<NTL, U>(s + c));
+}
+
+struct RowShape {
+  uint32_t upr, tpr, shift, rows_per_pass;
+};
+inline RowShape row_shape(size_t units_per_row) {
+  RowShape s;
+  s.upr = static_cast<uint32_t>(units_per_row);
+  s.shift = 0;
+  while ((1u << s.shift) < s.upr && s.shift < 8) ++s.shift;   // tpr = min(256, pow2 >= upr)
+  s.tpr = 1u << s.shift;
+  s.rows_per_pass = kBlock >> s.shift;
+  return s;
+}
+inline unsigned blocks_for(size_t rows, size_t rows_per_block) {
+  size_t b = (rows + rows_per_block - 1) / rows_per_block;
+  return static_cast<unsigned>(b ? b : 1);
+}
+
+}  // namespace
+
+int launch_moe_dispatch(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& slot, const int64_t* splits,
+                        size_t T, size_t recv_rows, size_t row_bytes, int elem_b, int P, int variant, hipStream_t stream) {
+  if (T == 0 || row_bytes == 0) return MCR_OK;
+  auto go = [&](auto ub, auto ntl, auto nts) {
+    constexpr int UB = decltype(ub)::value;
+    const RowShape s = row_shape(row_bytes / UB);
+    const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
+    hipLaunchKernelGGL((moe_dispatch_kernel<UB, decltype(ntl)::value, decltype(nts)::value>), dim3(gx, P), dim3(kBlock), 0,
+                       stream, recv, tok, slot, splits, P, T, static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+    return launch_status();
+  };
+  if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
+  return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(Int<16>{}, ntl, nts); });
+}
+
+int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& slot, const CPtrTab* gate,
+                       const int64_t* splits, size_t T, size_t recv_rows, size_t row_elems, int dtype, int P, int variant,
+                       hipStream_t stream) {
+  if (T == 0 || row_elems == 0) return MCR_OK;
+  CPtrTab g;
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
+  return dispatch_dtype(dtype, [&](auto dt) {
+    constexpr int DT = decltype(dt)::value;
+    constexpr int EB = Elem<DT>::kBytes;
+    auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
+      constexpr int UB = decltype(ub)::value;
+      const RowShape s = row_shape(row_elems * EB / UB);
+      const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
+      hipLaunchKernelGGL((moe_combine_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
+                         dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, slot, g, splits, P, T,
+                         static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+      return launch_status();
+    };
+    if (variant == SV_SCALAR)
+      return gate ? go(Int<EB>{}, Bool<false>{}, Bool<false>{}, Bool<true>{}) : go(Int<EB>{}, Bool<false>{}, Bool<false>{}, Bool<false>{});
+    return dispatch_hint(variant, [&](auto ntl, auto nts) {
+      return gate ? go(Int<16>{}, ntl, nts, Bool<true>{}) : go(Int<16>{}, ntl, nts, Bool<false>{});
+    });
+  });
+}
+
+int launch_dlrm_shuffle(mcr_ctx*, const PtrTab& dst, const CPtrTab& src, int n_tables, size_t batch, size_t row_bytes,
+                        int elem_b, int P, bool backward, int variant, hipStream_t stream) {
+  const size_t rows = (batch / P) * static_cast<size_t>(n_tables);
+  if (rows == 0 || row_bytes == 0) return MCR_OK;
+  auto go = [&](auto ub, auto ntl, auto nts) {
+    constexpr int UB = decltype(ub)::value;
+    const RowShape s = row_shape(row_bytes / UB);
+    const unsigned gx = blocks_for(rows, s.rows_per_pass);
+    if (backward)
+      hipLaunchKernelGGL((dlrm_shuffle_kernel<UB, decltype(ntl)::value, decltype(nts)::value, true>), dim3(gx, P), dim3(kBlock),
+                         0, stream, dst, src, static_cast<uint32_t>(n_tables), static_cast<uint64_t>(batch),
+                         static_cast<uint32_t>(P), s.upr, s.tpr, s.shift);
+    else
+      hipLaunchKernelGGL((dlrm_shuffle_kernel<UB, decltype(ntl)::value, decltype(nts)::value, false>), dim3(gx, P), dim3(kBlock),
+                         0, stream, dst, src, static_cast<uint32_t>(n_tables), static_cast<uint64_t>(batch),
+                         static_cast<uint32_t>(P), s.upr, s.tpr, s.shift);
+    return launch_status();
+  };
+  if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
+  return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(Int<16>{}, ntl, nts); });
+}
+
+}  // namespace mcr

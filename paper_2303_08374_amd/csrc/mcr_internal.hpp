@@ -97,6 +97,13 @@ int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab&
                   size_t in_rows, size_t row_elems, int dtype, int P, int variant, hipStream_t);
 int launch_fuse(mcr_ctx*, const mcr_fuse_plan*, int bucket, const PtrTab& flat, bool unfuse, int variant, hipStream_t);
 int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan*, int t0, int t1, int op, int variant, hipStream_t);
+int launch_moe_dispatch(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& slot, const int64_t* splits, size_t T,
+                        size_t recv_rows, size_t row_bytes, int elem_b, int P, int variant, hipStream_t);
+int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& slot, const CPtrTab* gate,
+                       const int64_t* splits, size_t T, size_t recv_rows, size_t row_elems, int dtype, int P, int variant,
+                       hipStream_t);
+int launch_dlrm_shuffle(mcr_ctx*, const PtrTab& dst, const CPtrTab& src, int n_tables, size_t batch, size_t row_bytes,
+                        int elem_b, int P, bool backward, int variant, hipStream_t);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MCR_OK : MCR_EHIP; }
 inline int launch_status() { return hip_status(hipGetLastError()); }

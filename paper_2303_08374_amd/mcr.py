@@ -19,8 +19,9 @@ MAX_EXPERTS = 512
 
 OP_ALLREDUCE, OP_REDUCE_SCATTER, OP_ALLGATHER, OP_ALLTOALL, OP_ALLTOALLV = 0, 1, 2, 3, 4
 OP_PACK, OP_UNPACK, OP_FUSE, OP_UNFUSE, OP_ALLREDUCE_MULTI, OP_MOE_ROUTE = 5, 6, 7, 8, 9, 10
+OP_MOE_DISPATCH, OP_MOE_COMBINE, OP_DLRM_SHUFFLE = 11, 12, 13
 OP_NAMES = ["allreduce", "reduce_scatter", "allgather", "alltoall", "alltoallv", "pack", "unpack",
-            "fuse", "unfuse", "allreduce_multi", "moe_route"]
+            "fuse", "unfuse", "allreduce_multi", "moe_route", "moe_dispatch", "moe_combine", "dlrm_shuffle"]
 
 OK, EINVAL, EDTYPE, EOP, EVARIANT, ESPLIT, EHIP, ENOMEM, EIO, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8, -9
 
@@ -171,6 +172,28 @@ def mcr_unpack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr],
                in_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
     _check(lib().mcr_unpack(ctx, _ptr_array(out), _ptr_array(inp), _ptr_array(slot), _ptr_array(gate), _sz(T),
                             _sz(in_rows), _sz(row_elems), dtype, P, variant, _stream(stream)), "mcr_unpack")
+
+
+# ---- fused pipelines -----------------------------------------------------------------------
+def mcr_moe_dispatch(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], slot: Sequence[Ptr], splits: Ptr, T: int,
+                     recv_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_moe_dispatch(ctx, _ptr_array(recv), _ptr_array(tokens), _ptr_array(slot),
+                                  ctypes.c_void_p(_addr(splits)), _sz(T), _sz(recv_rows), _sz(row_elems), dtype, P,
+                                  variant, _stream(stream)), "mcr_moe_dispatch")
+
+
+def mcr_moe_combine(ctx, out: Sequence[Ptr], expert_out: Sequence[Ptr], slot: Sequence[Ptr],
+                    gate: Optional[Sequence[Ptr]], splits: Ptr, T: int, recv_rows: int, row_elems: int, dtype: int,
+                    P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_moe_combine(ctx, _ptr_array(out), _ptr_array(expert_out), _ptr_array(slot), _ptr_array(gate),
+                                 ctypes.c_void_p(_addr(splits)), _sz(T), _sz(recv_rows), _sz(row_elems), dtype, P,
+                                 variant, _stream(stream)), "mcr_moe_combine")
+
+
+def mcr_dlrm_shuffle(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], n_tables: int, batch: int, dim: int, dtype: int,
+                     P: int, backward: bool = False, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_dlrm_shuffle(ctx, _ptr_array(out), _ptr_array(inp), n_tables, _sz(batch), _sz(dim), dtype, P,
+                                  int(bool(backward)), variant, _stream(stream)), "mcr_dlrm_shuffle")
 
 
 # ---- tensor fusion -------------------------------------------------------------------------

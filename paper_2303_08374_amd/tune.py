@@ -19,7 +19,7 @@ import sys
 
 import torch
 
-from . import inputs, mcr, sweep
+from . import inputs, mcr, sweep, workloads
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 DEFAULT_TABLE = os.path.join(HERE, "tuning", "mi355x.tbl")
@@ -28,6 +28,58 @@ DEFAULT_TABLE = os.path.join(HERE, "tuning", "mi355x.tbl")
 def reps_for(alg_bytes: int) -> int:
     # about 160 GiB of traffic per batch (tens of milliseconds), between 5 and 50 launches
     return int(max(5, min(50, (160 << 30) // max(alg_bytes, 1))))
+
+
+def tune_workload_ops(ctx, verbose: bool = True):
+    """One table row per (op, dtype, P) of the ops the application-shaped workloads use beyond the
+    swept collectives: all_to_allv, pack, unpack (MoE: bf16, P=16; DLRM: fp32, P=8), fuse, unfuse and
+    the fused multi-tensor allreduce (gradient buckets: bf16, P=8).  Every stage of a workload is an
+    independent launch timed on its own, so one run with all stages on variant v gives v's time for
+    each of them."""
+    n_var = len(mcr.mcr_get_variants(ctx, mcr.OP_ALLTOALLV))
+    names = mcr.mcr_get_variants(ctx, mcr.OP_ALLTOALLV)
+    variants = list(range(1, n_var))
+    moe, dlrm, gb = inputs.MoEWorkload(), inputs.DLRMWorkload(), inputs.GradBucketWorkload()
+    plans = [
+        # (label, runner, {op id: [stage names]}, dtype, P, table bytes)
+        ("moe", lambda vv: workloads.moe_dispatch_combine(ctx, reps=5, variants=vv),
+         {mcr.OP_PACK: ["pack"], mcr.OP_ALLTOALLV: ["alltoallv_dispatch", "alltoallv_return"], mcr.OP_UNPACK: ["unpack_combine"],
+          mcr.OP_MOE_DISPATCH: ["fused/moe_dispatch"], mcr.OP_MOE_COMBINE: ["fused/moe_combine"]},
+         mcr.BF16, moe.P, moe.T * moe.H * 2),
+        ("dlrm", lambda vv: workloads.dlrm_shuffle(ctx, reps=5, variants=vv),
+         {mcr.OP_PACK: ["fwd_pack_send_order", "bwd_pack_permute"], mcr.OP_ALLTOALLV: ["fwd_alltoallv", "bwd_alltoallv"],
+          mcr.OP_UNPACK: ["fwd_unpack_permute", "bwd_unpack_table_order"],
+          mcr.OP_DLRM_SHUFFLE: ["fused/fwd_dlrm_shuffle", "fused/bwd_dlrm_shuffle"]},
+         mcr.F32, dlrm.P, (dlrm.batch // dlrm.P) * dlrm.n_tables * dlrm.dim * 4),
+        ("grad_buckets", lambda vv: workloads.grad_buckets(ctx, reps=2, variants=vv, per_tensor=False),
+         {mcr.OP_FUSE: ["fuse"], mcr.OP_UNFUSE: ["unfuse"], mcr.OP_ALLREDUCE_MULTI: ["allreduce_multi_one_launch"]},
+         mcr.BF16, gb.P, 1 << 20),
+    ]
+    key_of = {mcr.OP_PACK: "pack", mcr.OP_ALLTOALLV: "alltoallv", mcr.OP_UNPACK: "unpack", mcr.OP_FUSE: "fuse",
+              mcr.OP_UNFUSE: "unfuse", mcr.OP_ALLREDUCE_MULTI: "allreduce_multi", mcr.OP_MOE_DISPATCH: "moe_dispatch",
+              mcr.OP_MOE_COMBINE: "moe_combine", mcr.OP_DLRM_SHUFFLE: "dlrm_shuffle"}
+
+    def stage_us(rep, path):
+        for part in path.split("/"):
+            rep = rep[part]
+        return rep["us"]
+    report = {}
+    for label, runner, ops, dtype, P, nbytes in plans:
+        times = {op: {} for op in ops}
+        for v in variants:
+            rep = runner({key_of[op]: v for op in ops})
+            for op, stages in ops.items():
+                times[op][v] = sum(stage_us(rep, st) for st in stages)
+            torch.cuda.empty_cache()
+        for op in ops:
+            floor = min(times[op].values())
+            best = min(v for v in variants if times[op][v] <= floor * 1.02)
+            mcr.mcr_tune_set(ctx, op, dtype, P, nbytes, best)
+            report[f"{label}/{mcr.OP_NAMES[op]}"] = {"best": names[best], "us": {names[v]: round(t, 1) for v, t in times[op].items()}}
+            if verbose:
+                print(f"{label}/{mcr.OP_NAMES[op]:18s} best={names[best]:6s} " +
+                      " ".join(f"{names[v]}={t:.0f}" for v, t in times[op].items()), flush=True)
+    return report
 
 
 def run(out_path: str, report_path: str | None, P: int, max_bytes: int, arena_gib: float, verbose: bool = True):
@@ -73,6 +125,7 @@ def run(out_path: str, report_path: str | None, P: int, max_bytes: int, arena_gi
             coarse[f"{op}/{dt}"] = {"variant": names[bv], "sum_us": round(tot[bv], 2), "fine_sum_us": round(fine, 2),
                                     "fine_gain": round(tot[bv] / fine, 4)}
     report["coarse_vs_fine"] = coarse
+    report["workload_ops"] = tune_workload_ops(ctx, verbose)
     os.makedirs(os.path.dirname(out_path), exist_ok=True)
     mcr.mcr_tune_save(ctx, out_path)
     if report_path:

@@ -9,12 +9,17 @@ device here (timing only; the parity tests use the host generators of ``inputs``
 """
 from __future__ import annotations
 
-from typing import Dict, List
+from typing import Dict, List, Optional
 
 import numpy as np
 import torch
 
 from . import inputs, mcr
+
+
+def _v(variants: Optional[Dict[str, int]], key: str) -> int:
+    """Variant for one stage: MCR_AUTO unless the tuning suite asks for a specific one."""
+    return mcr.AUTO if not variants else variants.get(key, mcr.AUTO)
 
 
 def _events(n):
@@ -64,7 +69,8 @@ def allreduce_small(ctx, reps: int = 50) -> Dict:
 
 
 # ---- workload 3 ---------------------------------------------------------------------------
-def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoEWorkload()) -> Dict:
+def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoEWorkload(),
+                         variants: Optional[Dict[str, int]] = None) -> Dict:
     P, T, H, E, C = w.P, w.T, w.H, w.E, w.C
     row = H * 2
     d_ids = [torch.from_numpy(w.ids(p)).cuda() for p in range(P)]
@@ -81,14 +87,14 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
         e[0].record()
         mcr.mcr_moe_route(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
         e[1].record()
-        mcr.mcr_pack(ctx, d_packed, d_tok, d_slot, T, T, H, mcr.BF16, P)
+        mcr.mcr_pack(ctx, d_packed, d_tok, d_slot, T, T, H, mcr.BF16, P, _v(variants, "pack"))
         e[2].record()
-        mcr.mcr_alltoallv(ctx, d_recv, d_packed, d_S, True, T, w.recv_rows, H, mcr.BF16, P)
+        mcr.mcr_alltoallv(ctx, d_recv, d_packed, d_S, True, T, w.recv_rows, H, mcr.BF16, P, _v(variants, "alltoallv"))
         d_ST = d_S.view(P, P).t().contiguous()
         e[3].record()
-        mcr.mcr_alltoallv(ctx, d_back, d_recv, d_ST, True, w.recv_rows, T, H, mcr.BF16, P)
+        mcr.mcr_alltoallv(ctx, d_back, d_recv, d_ST, True, w.recv_rows, T, H, mcr.BF16, P, _v(variants, "alltoallv"))
         e[4].record()
-        mcr.mcr_unpack(ctx, d_out, d_back, d_slot, d_gate, T, T, H, mcr.BF16, P)
+        mcr.mcr_unpack(ctx, d_out, d_back, d_slot, d_gate, T, T, H, mcr.BF16, P, _v(variants, "unpack"))
         e[5].record()
         if it >= 2:
             rows.append(e)
@@ -102,11 +108,30 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     rep = _stage_report(["route", "pack", "alltoallv_dispatch", "alltoallv_return", "unpack_combine"], alg, rows)
     rep["kept_rows"] = kept
     rep["kept_fraction"] = round(kept / (P * T), 4)
+    # the same result with the fused calls: tokens go straight into the receive buffers and come
+    # straight back out of them (identity experts in between)
+    rows = []
+    for it in range(reps + 2):
+        e = _events(4)
+        e[0].record()
+        mcr.mcr_moe_route(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+        e[1].record()
+        mcr.mcr_moe_dispatch(ctx, d_recv, d_tok, d_slot, d_S, T, w.recv_rows, H, mcr.BF16, P, _v(variants, "moe_dispatch"))
+        e[2].record()
+        mcr.mcr_moe_combine(ctx, d_out, d_recv, d_slot, d_gate, d_S, T, w.recv_rows, H, mcr.BF16, P, _v(variants, "moe_combine"))
+        e[3].record()
+        if it >= 2:
+            rows.append(e)
+    torch.cuda.synchronize()
+    falg = [0, 2 * kept * row + P * T * 4, kept * row + P * T * row + P * T * 8]
+    rep["fused"] = _stage_report(["route", "moe_dispatch", "moe_combine"], falg, rows)
+    rep["fused"]["speedup_vs_chain"] = round(rep["end_to_end"]["us"] / rep["fused"]["end_to_end"]["us"], 2)
     return rep
 
 
 # ---- workload 4 ---------------------------------------------------------------------------
-def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorkload(), sets: int = 3) -> Dict:
+def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorkload(), sets: int = 3,
+                 variants: Optional[Dict[str, int]] = None) -> Dict:
     """Forward: pooled [T_p, B, D] -> destination-major send order (pack) -> alltoallv ->
     [B/P, n_tables, D] (unpack with the table permutation).  Backward: the inverse chain.
     `sets` independent buffer sets are used in rotation so that a stage does not find its
@@ -136,17 +161,17 @@ def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorklo
         x = bufs[it % sets]
         e = _events(7)
         e[0].record()
-        mcr.mcr_pack(ctx, x["send"], x["src"], send_slot, max_rows, max_rows, D, mcr.F32, P)
+        mcr.mcr_pack(ctx, x["send"], x["src"], send_slot, max_rows, max_rows, D, mcr.F32, P, _v(variants, "pack"))
         e[1].record()
-        mcr.mcr_alltoallv(ctx, x["recv"], x["send"], S, False, max_rows, NT * bl, D, mcr.F32, P)
+        mcr.mcr_alltoallv(ctx, x["recv"], x["send"], S, False, max_rows, NT * bl, D, mcr.F32, P, _v(variants, "alltoallv"))
         e[2].record()
-        mcr.mcr_unpack(ctx, x["out"], x["recv"], d_perm, None, bl * NT, NT * bl, D, mcr.F32, P)
+        mcr.mcr_unpack(ctx, x["out"], x["recv"], d_perm, None, bl * NT, NT * bl, D, mcr.F32, P, _v(variants, "unpack"))
         e[3].record()
-        mcr.mcr_pack(ctx, x["grecv"], x["out"], d_perm, bl * NT, NT * bl, D, mcr.F32, P)
+        mcr.mcr_pack(ctx, x["grecv"], x["out"], d_perm, bl * NT, NT * bl, D, mcr.F32, P, _v(variants, "pack"))
         e[4].record()
-        mcr.mcr_alltoallv(ctx, x["gsend"], x["grecv"], ST, False, NT * bl, max_rows, D, mcr.F32, P)
+        mcr.mcr_alltoallv(ctx, x["gsend"], x["grecv"], ST, False, NT * bl, max_rows, D, mcr.F32, P, _v(variants, "alltoallv"))
         e[5].record()
-        mcr.mcr_unpack(ctx, x["gsrc"], x["gsend"], send_slot, None, max_rows, max_rows, D, mcr.F32, P)
+        mcr.mcr_unpack(ctx, x["gsrc"], x["gsend"], send_slot, None, max_rows, max_rows, D, mcr.F32, P, _v(variants, "unpack"))
         e[6].record()
         if it >= sets:
             rows.append(e)
@@ -155,12 +180,29 @@ def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorklo
     pad = (P * max_rows - NT * B) * D * 4                   # zero rows written for the ranks that own fewer tables
     alg = [2 * data + P * max_rows * 4, 2 * data, 2 * data + NT * B * 4,
            2 * data + NT * B * 4, 2 * data, 2 * data + pad + P * max_rows * 4]
-    return _stage_report(["fwd_pack_send_order", "fwd_alltoallv", "fwd_unpack_permute",
-                          "bwd_pack_permute", "bwd_alltoallv", "bwd_unpack_table_order"], alg, rows)
+    rep = _stage_report(["fwd_pack_send_order", "fwd_alltoallv", "fwd_unpack_permute",
+                         "bwd_pack_permute", "bwd_alltoallv", "bwd_unpack_table_order"], alg, rows)
+    # the fused single-pass shuffle
+    rows = []
+    for it in range(reps + sets):
+        x = bufs[it % sets]
+        e = _events(3)
+        e[0].record()
+        mcr.mcr_dlrm_shuffle(ctx, x["out"], x["src"], NT, B, D, mcr.F32, P, False, _v(variants, "dlrm_shuffle"))
+        e[1].record()
+        mcr.mcr_dlrm_shuffle(ctx, x["gsrc"], x["out"], NT, B, D, mcr.F32, P, True, _v(variants, "dlrm_shuffle"))
+        e[2].record()
+        if it >= sets:
+            rows.append(e)
+    torch.cuda.synchronize()
+    rep["fused"] = _stage_report(["fwd_dlrm_shuffle", "bwd_dlrm_shuffle"], [2 * data, 2 * data], rows)
+    rep["fused"]["speedup_vs_chain"] = round(rep["end_to_end"]["us"] / rep["fused"]["end_to_end"]["us"], 2)
+    return rep
 
 
 # ---- workload 5 ---------------------------------------------------------------------------
-def grad_buckets(ctx, reps: int = 3, w: inputs.GradBucketWorkload = inputs.GradBucketWorkload()) -> Dict:
+def grad_buckets(ctx, reps: int = 3, w: inputs.GradBucketWorkload = inputs.GradBucketWorkload(),
+                 variants: Optional[Dict[str, int]] = None, per_tensor: bool = True) -> Dict:
     """bf16 gradients of the GPT-style list on P ranks.  Three ways to all-reduce (average) them:
     per bucket fuse -> allreduce(flat) -> unfuse; the fused multi-tensor allreduce in one launch
     over the whole list; and one allreduce launch per tensor (no fusion)."""
@@ -184,11 +226,11 @@ def grad_buckets(ctx, reps: int = 3, w: inputs.GradBucketWorkload = inputs.GradB
             for k in range(len(bn)):
                 se = _events(4)
                 se[0].record()
-                mcr.mcr_fuse(ctx, plan, k, flats, P)
+                mcr.mcr_fuse(ctx, plan, k, flats, P, _v(variants, "fuse"))
                 se[1].record()
                 mcr.mcr_allreduce(ctx, flats, bn[k], mcr.BF16, mcr.AVG, P)
                 se[2].record()
-                mcr.mcr_unfuse(ctx, plan, k, flats, P)
+                mcr.mcr_unfuse(ctx, plan, k, flats, P, _v(variants, "unfuse"))
                 se[3].record()
                 stage_ev.append(se)
             e[1].record()
@@ -197,11 +239,11 @@ def grad_buckets(ctx, reps: int = 3, w: inputs.GradBucketWorkload = inputs.GradB
         for it in range(reps + 1):
             e = _events(2)
             e[0].record()
-            mcr.mcr_allreduce_multi(ctx, plan, -1, mcr.AVG)
+            mcr.mcr_allreduce_multi(ctx, plan, -1, mcr.AVG, _v(variants, "allreduce_multi"))
             e[1].record()
             if it >= 1:
                 rows_multi.append(e)
-        for it in range(reps + 1):
+        for it in range(reps + 1 if per_tensor else 0):
             e = _events(2)
             e[0].record()
             for i, n in enumerate(numel):
@@ -224,11 +266,50 @@ def grad_buckets(ctx, reps: int = 3, w: inputs.GradBucketWorkload = inputs.GradB
         ms = med([e[0].elapsed_time(e[1]) for e in rows_multi])
         rep["allreduce_multi_one_launch"] = {"us": round(ms * 1e3, 1), "launches": 1, "alg_bytes": minimum,
                                              "GBps": round(minimum / (ms * 1e-3) / 1e9, 1)}
-        ms = med([e[0].elapsed_time(e[1]) for e in rows_each])
-        rep["allreduce_per_tensor"] = {"us": round(ms * 1e3, 1), "launches": len(numel), "alg_bytes": minimum,
-                                       "GBps": round(minimum / (ms * 1e-3) / 1e9, 1)}
+        if per_tensor:
+            ms = med([e[0].elapsed_time(e[1]) for e in rows_each])
+            rep["allreduce_per_tensor"] = {"us": round(ms * 1e3, 1), "launches": len(numel), "alg_bytes": minimum,
+                                           "GBps": round(minimum / (ms * 1e-3) / 1e9, 1)}
         rep["tensors"], rep["buckets"], rep["elements_per_rank"] = len(numel), len(bn), total
         return rep
+    finally:
+        mcr.mcr_fuse_plan_destroy(plan)
+
+
+def small_tensor_path(ctx, reps: int = 5, w: inputs.GradBucketWorkload = inputs.GradBucketWorkload()) -> Dict:
+    """The small-message path on its own: only the gradients of at most 8192 elements (LayerNorm
+    weights and biases, linear biases: 194 tensors of 4-16 KiB per rank), averaged over P ranks
+    either with one launch per tensor or with the fused multi-tensor launch."""
+    P = w.P
+    numel = [n for n in w.numel() if n <= 8192]
+    total = sum(numel)
+    plan = mcr.mcr_fuse_plan_create(ctx, numel, 1 << 40, mcr.BF16)
+    try:
+        arenas = [torch.empty(total, dtype=torch.bfloat16, device="cuda").normal_(0.0, w.std) for _ in range(P)]
+        offs = np.concatenate([[0], np.cumsum(numel)[:-1]]).tolist()
+        ptrs = [arenas[p].data_ptr() + offs[i] * 2 for p in range(P) for i in range(len(numel))]
+        mcr.mcr_fuse_plan_bind(ctx, plan, ptrs, P)
+        per_tensor = [[ptrs[p * len(numel) + i] for p in range(P)] for i in range(len(numel))]
+        t_multi, t_each = [], []
+        for it in range(reps + 1):
+            e = _events(3)
+            e[0].record()
+            mcr.mcr_allreduce_multi(ctx, plan, -1, mcr.AVG)
+            e[1].record()
+            for i, n in enumerate(numel):
+                mcr.mcr_allreduce(ctx, per_tensor[i], n, mcr.BF16, mcr.AVG, P)
+            e[2].record()
+            e[2].synchronize()
+            if it >= 1:
+                t_multi.append(e[0].elapsed_time(e[1]))
+                t_each.append(e[1].elapsed_time(e[2]))
+        med = lambda xs: sorted(xs)[len(xs) // 2]
+        alg = 2 * P * total * 2
+        return {"tensors": len(numel), "bytes_per_rank": total * 2, "alg_bytes": alg,
+                "allreduce_multi_one_launch_us": round(med(t_multi) * 1e3, 2),
+                "allreduce_per_tensor_us": round(med(t_each) * 1e3, 2),
+                "launches_saved": len(numel) - 1,
+                "speedup": round(med(t_each) / med(t_multi), 1)}
     finally:
         mcr.mcr_fuse_plan_destroy(plan)
 
@@ -241,5 +322,7 @@ def run_all(ctx) -> Dict:
     out["dlrm_shuffle"] = dlrm_shuffle(ctx)
     torch.cuda.empty_cache()
     out["grad_buckets"] = grad_buckets(ctx)
+    torch.cuda.empty_cache()
+    out["small_tensor_path"] = small_tensor_path(ctx)
     torch.cuda.empty_cache()
     return out

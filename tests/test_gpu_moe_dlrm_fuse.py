@@ -107,7 +107,7 @@ def test_pack_skips_slots_beyond_capacity():
             assert np.array_equal(got[s], tok.reshape(T, w)[t])
 
 
-def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None):
+def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None, fused_variant=mcr.AUTO):
     """route -> pack -> alltoallv(S, device resident) -> [identity experts] -> alltoallv(S^T) ->
     gate-weighted combine, each stage compared with the oracle."""
     P, T, H, E, C = w.P, w.T, w.H, w.E, w.C
@@ -147,6 +147,14 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None):
     oracle.alltoallv(packed, S, H, oracle.BF16, recv)
     back = [np.zeros(send_rows * H, dtype=np.uint16) for _ in range(P)]
     oracle.alltoallv(recv, S.T.copy(), H, oracle.BF16, back)
+    # the fused forms: dispatch = pack + alltoallv, combine = alltoallv(S^T) + gate-weighted unpack
+    f_recv = [gu.dev_empty(recv_rows * H, mcr.BF16, 0) for _ in range(P)]
+    f_out = [gu.dev_empty(T * H, mcr.BF16, 1) for _ in range(P)]
+    f_plain = [gu.dev_empty(T * H, mcr.BF16, 1) for _ in range(P)]
+    mcr.mcr_moe_dispatch(c, f_recv, d_tok, d_slot, d_S, T, recv_rows, H, mcr.BF16, P, fused_variant)
+    mcr.mcr_moe_combine(c, f_out, f_recv, d_slot, d_gate, d_S, T, recv_rows, H, mcr.BF16, P, fused_variant)
+    mcr.mcr_moe_combine(c, f_plain, f_recv, d_slot, None, d_S, T, recv_rows, H, mcr.BF16, P, fused_variant)
+    gu.sync()
     for p in (check_ranks if check_ranks is not None else range(P)):
         assert np.array_equal(d_slot[p].cpu().numpy(), routes[p][0])
         gu.assert_bits_equal(gu.to_host(d_packed[p], np.uint16), packed[p], f"packed r={p}")
@@ -154,11 +162,19 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None):
         gu.assert_bits_equal(gu.to_host(d_back[p], np.uint16), back[p], f"back r={p}")
         exp = oracle.unpack(back[p], routes[p][0], gates[p], H, oracle.BF16)
         gu.assert_bits_equal(gu.to_host(d_out[p], np.uint16), exp, f"combine r={p}")
+        gu.assert_bits_equal(gu.to_host(f_recv[p], np.uint16), recv[p], f"fused dispatch r={p}")
+        gu.assert_bits_equal(gu.to_host(f_out[p], np.uint16), exp, f"fused combine r={p}")
+        gu.assert_bits_equal(gu.to_host(f_plain[p], np.uint16), oracle.unpack(back[p], routes[p][0], None, H, oracle.BF16),
+                             f"fused combine without gate r={p}")
 
 
 def test_moe_pipeline_small():
     _moe_pipeline(inputs.MoEWorkload(P=4, T=1000, H=72, E=8))
     _moe_pipeline(inputs.MoEWorkload(P=2, T=333, H=7, E=6), permute=True)     # rows not a multiple of 16 bytes
+    for v in (0, 1, 4, 7, 10):
+        _moe_pipeline(inputs.MoEWorkload(P=4, T=1000, H=72, E=8), fused_variant=v)
+    _moe_pipeline(inputs.MoEWorkload(P=16, T=100, H=8, E=16, capacity_factor=0.5))   # heavy dropping, one-vector rows
+    _moe_pipeline(inputs.MoEWorkload(P=1, T=65, H=16, E=3))
 
 
 def test_moe_pipeline_config3_full_size():
@@ -239,10 +255,40 @@ def _dlrm_roundtrip(w: inputs.DLRMWorkload, payload="normal"):
         got = gu.to_host(d_gsrc[p], np.float32)[: src[p].size]
         gu.assert_bits_equal(got, gexp[p], f"dlrm bwd r={p}")
         gu.assert_bits_equal(got, src[p], f"dlrm bwd(fwd) r={p}")
+    # the fused single-pass shuffle, forward and backward
+    for variant in (mcr.AUTO, 0, 1, 5, 8, 11):
+        f_out = [gu.dev_empty(bl * NT * D, mcr.F32, 0) for _ in range(P)]
+        f_src = [gu.dev_empty(max(src[p].size, 4), mcr.F32, 0) for p in range(P)]
+        mcr.mcr_dlrm_shuffle(c, f_out, d_src, NT, B, D, mcr.F32, P, False, variant)
+        mcr.mcr_dlrm_shuffle(c, f_src, f_out, NT, B, D, mcr.F32, P, True, variant)
+        gu.sync()
+        for r in range(P):
+            gu.assert_bits_equal(gu.to_host(f_out[r], np.float32), exp[r], f"fused dlrm fwd v={variant} r={r}")
+            gu.assert_bits_equal(gu.to_host(f_src[r], np.float32)[: src[r].size], gexp[r], f"fused dlrm bwd v={variant} r={r}")
 
 
 def test_dlrm_small_closed_form():
     _dlrm_roundtrip(inputs.DLRMWorkload(P=4, n_tables=10, dim=8, batch=64), payload="closed")
+
+
+def test_dlrm_fused_odd_shapes():
+    """Fewer tables than ranks (some ranks own none), rows that are not a multiple of 16 bytes, bf16."""
+    for P, NT, D, B, dtype in ((4, 3, 5, 16, mcr.F32), (8, 26, 12, 64, mcr.BF16), (1, 2, 8, 7, mcr.F32), (3, 7, 128, 9, mcr.BF16)):
+        bf = dtype == mcr.BF16
+        n_local = [len(range(p, NT, P)) for p in range(P)]
+        src = [inputs.normal(max(n_local[p] * B * D, 0), 1300 + NT, p, bf16=bf) for p in range(P)]
+        exp = oracle.dlrm_forward(src, NT, B, D, dtype)
+        gexp = oracle.dlrm_backward(exp, NT, B, D, dtype)
+        d_src = [gu.to_dev(s) if s.size else gu.dev_empty(8, dtype, 0) for s in src]
+        for variant in (mcr.AUTO, 0):
+            f_out = [gu.dev_empty((B // P) * NT * D, dtype, 0) for _ in range(P)]
+            f_back = [gu.dev_empty(max(s.size, 8), dtype, 0) for s in src]
+            mcr.mcr_dlrm_shuffle(gu.ctx(), f_out, d_src, NT, B, D, dtype, P, False, variant)
+            mcr.mcr_dlrm_shuffle(gu.ctx(), f_back, f_out, NT, B, D, dtype, P, True, variant)
+            gu.sync()
+            for r in range(P):
+                gu.assert_bits_equal(gu.to_host(f_out[r], gu.NPDT[dtype]), exp[r], f"fwd P={P} NT={NT} D={D} v={variant}")
+                gu.assert_bits_equal(gu.to_host(f_back[r], gu.NPDT[dtype])[: src[r].size], gexp[r], f"bwd P={P} NT={NT} D={D}")
 
 
 def test_dlrm_config4_full_size():
