@@ -107,6 +107,38 @@ def allreduce_ref64(bufs: List[np.ndarray], dtype: int, op: int = SUM):
     return out, mag
 
 
+def reduce(bufs: List[np.ndarray], dtype: int, op: int, root: int) -> None:
+    """In place on ``bufs[root]`` only."""
+    n = bufs[0].size
+    _check(lib().orc_reduce(_ptrs(bufs), ctypes.c_size_t(n), dtype, op, len(bufs), root), "reduce")
+
+
+def bcast(bufs: List[np.ndarray], dtype: int, root: int) -> None:
+    n = bufs[0].size
+    _check(lib().orc_bcast(_ptrs(bufs), ctypes.c_size_t(n), dtype, len(bufs), root), "bcast")
+
+
+def gatherv(ins: List[np.ndarray], counts: Sequence[int], dtype: int) -> np.ndarray:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    out = np.zeros(int(c.sum()), dtype=np_dtype(dtype))
+    _check(lib().orc_gatherv(_p(out), _ptrs(ins), _p(c), dtype, len(ins)), "gatherv")
+    return out
+
+
+def scatterv(root_in: np.ndarray, counts: Sequence[int], dtype: int) -> List[np.ndarray]:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    outs = [np.zeros(int(n), dtype=np_dtype(dtype)) for n in c]
+    _check(lib().orc_scatterv(_ptrs(outs), _p(root_in), _p(c), dtype, len(outs)), "scatterv")
+    return outs
+
+
+def allgatherv(ins: List[np.ndarray], counts: Sequence[int], dtype: int) -> List[np.ndarray]:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    outs = [np.zeros(int(c.sum()), dtype=np_dtype(dtype)) for _ in ins]
+    _check(lib().orc_allgatherv(_ptrs(outs), _ptrs(ins), _p(c), dtype, len(ins)), "allgatherv")
+    return outs
+
+
 def reduce_scatter(ins: List[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
     P = len(ins)
     n = ins[0].size

@@ -147,6 +147,67 @@ int orc_allreduce_ref64(const void* const* bufs, size_t n, int dtype, int op, in
   return 0;
 }
 
+// ---- reduce (API listing, reduce) : only the root's buffer receives the result --
+int orc_reduce(void* const* bufs, size_t n, int dtype, int op, int P, int root) {
+  if (!bufs || P < 1 || root < 0 || root >= P || bad_dtype(dtype) || bad_op(op)) return -1;
+  for (size_t i = 0; i < n; ++i) {
+    const float y = reduce_at(bufs, i, dtype, op, P);
+    store_elem(bufs[root], i, dtype, y);
+  }
+  return 0;
+}
+
+// ---- bcast (API listing, bcast) : every buffer becomes a bit copy of the root's --
+int orc_bcast(void* const* bufs, size_t n, int dtype, int P, int root) {
+  if (!bufs || P < 1 || root < 0 || root >= P || bad_dtype(dtype)) return -1;
+  const size_t s = elem_bytes(dtype);
+  for (int r = 0; r < P; ++r) {
+    if (r == root) continue;
+    for (size_t i = 0; i < n; ++i)
+      std::memcpy(static_cast<char*>(bufs[r]) + i * s, static_cast<const char*>(bufs[root]) + i * s, s);
+  }
+  return 0;
+}
+
+// ---- gatherv / scatterv / all_gatherv (API listing) with packed displacements ----
+// counts[p] elements belong to rank p; displ[p] = sum_{q<p} counts[q].
+//   gatherv   : root_out[displ[p] + j] = in[p][j]
+//   scatterv  : out[r][j] = root_in[displ[r] + j]
+//   allgatherv: out[r][displ[p] + j] = in[p][j] for every r
+// gather / scatter are the equal-count cases.
+int orc_gatherv(void* root_out, const void* const* in, const uint64_t* counts, int dtype, int P) {
+  if (!in || !counts || P < 1 || bad_dtype(dtype)) return -1;
+  const size_t s = elem_bytes(dtype);
+  uint64_t displ = 0;
+  for (int p = 0; p < P; ++p) {
+    for (uint64_t j = 0; j < counts[p]; ++j)
+      std::memcpy(static_cast<char*>(root_out) + (displ + j) * s, static_cast<const char*>(in[p]) + j * s, s);
+    displ += counts[p];
+  }
+  return 0;
+}
+
+int orc_scatterv(void* const* out, const void* root_in, const uint64_t* counts, int dtype, int P) {
+  if (!out || !counts || P < 1 || bad_dtype(dtype)) return -1;
+  const size_t s = elem_bytes(dtype);
+  uint64_t displ = 0;
+  for (int r = 0; r < P; ++r) {
+    for (uint64_t j = 0; j < counts[r]; ++j)
+      std::memcpy(static_cast<char*>(out[r]) + j * s, static_cast<const char*>(root_in) + (displ + j) * s, s);
+    displ += counts[r];
+  }
+  return 0;
+}
+
+int orc_allgatherv(void* const* out, const void* const* in, const uint64_t* counts, int dtype, int P) {
+  if (!out || !in || !counts || P < 1 || bad_dtype(dtype)) return -1;
+  for (int r = 0; r < P; ++r) {
+    const int rc = orc_gatherv(out[r], in, counts, dtype, P);
+    if (rc != 0) return rc;
+  }
+  return 0;
+}
+
 // ---- reduce_scatter (API listing, reduce_scatter; the root it prints is ------
 // a slip, there is none) : rank r receives slice r of the reduction.
 int orc_reduce_scatter(void* const* out, const void* const* in, size_t n, int dtype,

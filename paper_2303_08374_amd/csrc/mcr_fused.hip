@@ -55,11 +55,22 @@ __device__ __forceinline__ void build_pair_tables(PairTables& t, const int64_t* 
 
 // Receiver of packed row s of this sender, and its row in that receiver's buffer; false if the
 // slot is not a row this sender owns or the row would leave the receive buffer.
+// WAVE: every lane of the wavefront asks about the same row (a row is at least 64 threads wide),
+// so lane q compares sd[q] once and a ballot counts the receivers that start at or below s,
+// instead of every lane walking the table.
+template <bool WAVE>
 __device__ __forceinline__ bool locate(const PairTables& t, int P, int64_t s, int64_t send_rows, uint64_t recv_rows,
                                        int* r_out, uint64_t* row_out) {
-  if (s < 0 || s >= t.sd[P] || s >= send_rows) return false;
   int r = 0;
-  for (int q = 1; q < P; ++q) r += (t.sd[q] <= s) ? 1 : 0;     // sd is non-decreasing
+  if constexpr (WAVE) {
+    const int lane = __lane_id();
+    const bool below = lane >= 1 && lane < P && t.sd[lane] <= s;
+    r = __popcll(__ballot(below));
+  }
+  if (s < 0 || s >= t.sd[P] || s >= send_rows) return false;
+  if constexpr (!WAVE) {
+    for (int q = 1; q < P; ++q) r += (t.sd[q] <= s) ? 1 : 0;     // sd is non-decreasing
+  }
   const uint64_t row = static_cast<uint64_t>(t.rd[r] + (s - t.sd[r]));
   if (row >= recv_rows) return false;
   *r_out = r;
@@ -67,11 +78,28 @@ __device__ __forceinline__ bool locate(const PairTables& t, int P, int64_t s, in
   return true;
 }
 
-constexpr int kRowsPerBlock = 8;   // token rows one workgroup walks (amortises the table build)
+constexpr int kRowsPerBlock = 32;   // token rows one workgroup walks (amortises the table build); <= 64
 constexpr int kRowsInFlight = 4;   // rows whose loads are issued before the first store
 
+// When a row is at least a wavefront wide, every wave fetches the slots of all the rows it will
+// walk with one coalesced load (lane k holds the slot of the wave's k-th row) and hands them out
+// by shuffle, so the row loop has no dependent slot load in it.
+template <bool WAVE>
+__device__ __forceinline__ int32_t prefetch_slots(const int32_t* slot, size_t t0, uint32_t rows_per_pass,
+                                                  uint32_t tpr_shift, size_t T) {
+  if constexpr (!WAVE) return -1;
+  const unsigned lane = __lane_id();
+  const size_t t = t0 + static_cast<size_t>(lane) * rows_per_pass + (threadIdx.x >> tpr_shift);
+  return (lane < kRowsPerBlock && t < T) ? slot[t] : -1;
+}
+template <bool WAVE>
+__device__ __forceinline__ int64_t row_slot(const int32_t* slot, int32_t my_slot, int k, size_t t, size_t T) {
+  if constexpr (WAVE) return __shfl(my_slot, k);
+  return t < T ? slot[t] : -1;
+}
+
 // blockIdx.y = sender p.  tpr threads (power of two) share a row of upr units.
-template <int UB, bool NTL, bool NTS>
+template <int UB, bool NTL, bool NTS, bool WAVE>
 __global__ void __launch_bounds__(kBlock)
 moe_dispatch_kernel(PtrTab recv, CPtrTab tok, CPtrTab slot_tab, const int64_t* S, int P, size_t T,
                     uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
@@ -83,6 +111,7 @@ moe_dispatch_kernel(PtrTab recv, CPtrTab tok, CPtrTab slot_tab, const int64_t* S
   const U* src = static_cast<const U*>(tok.p[p]);
   const uint32_t rows_per_pass = kBlock >> tpr_shift;
   const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  const int32_t my_slot = prefetch_slots<WAVE>(slot, t0, rows_per_pass, tpr_shift, T);
   for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
     const U* srow[kRowsInFlight];
     U* drow[kRowsInFlight];
@@ -92,7 +121,8 @@ moe_dispatch_kernel(PtrTab recv, CPtrTab tok, CPtrTab slot_tab, const int64_t* S
       const size_t t = t0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
       int r = 0;
       uint64_t row = 0;
-      ok[j] = t < T && locate(tab, P, slot[t], static_cast<int64_t>(T), recv_rows, &r, &row);
+      const int64_t sl = row_slot<WAVE>(slot, my_slot, k0 + j, t, T);       // -1: no such token
+      ok[j] = locate<WAVE>(tab, P, sl, static_cast<int64_t>(T), recv_rows, &r, &row);
       srow[j] = src + t * upr;
       drow[j] = ok[j] ? static_cast<U*>(recv.p[r]) + row * upr : nullptr;
     }
@@ -128,7 +158,7 @@ template <int DT, int UB, class U> __device__ __forceinline__ U scale_unit(U v, 
 }
 
 // out[p] row t = gate[p][t] * (row of expert_out[r] that token t was dispatched to), zeros if dropped.
-template <int DT, int UB, bool NTL, bool NTS, bool GATE>
+template <int DT, int UB, bool NTL, bool NTS, bool GATE, bool WAVE>
 __global__ void __launch_bounds__(kBlock)
 moe_combine_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gate_tab, const int64_t* S, int P,
                    size_t T, uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
@@ -140,6 +170,7 @@ moe_combine_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gat
   U* dst = static_cast<U*>(out.p[p]);
   const uint32_t rows_per_pass = kBlock >> tpr_shift;
   const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  const int32_t my_slot = prefetch_slots<WAVE>(slot, t0, rows_per_pass, tpr_shift, T);
   for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
     const U* srow[kRowsInFlight];
     U* drow[kRowsInFlight];
@@ -151,7 +182,8 @@ moe_combine_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gat
       int r = 0;
       uint64_t row = 0;
       live[j] = t < T;
-      kept[j] = live[j] && locate(tab, P, slot[t], static_cast<int64_t>(T), recv_rows, &r, &row);
+      const int64_t sl = row_slot<WAVE>(slot, my_slot, k0 + j, t, T);
+      kept[j] = locate<WAVE>(tab, P, sl, static_cast<int64_t>(T), recv_rows, &r, &row);
       srow[j] = kept[j] ? static_cast<const U*>(expert_out.p[r]) + row * upr : nullptr;
       drow[j] = dst + t * upr;
       g[j] = 1.0f;
@@ -237,8 +269,12 @@ int launch_moe_dispatch(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const 
     constexpr int UB = decltype(ub)::value;
     const RowShape s = row_shape(row_bytes / UB);
     const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
-    hipLaunchKernelGGL((moe_dispatch_kernel<UB, decltype(ntl)::value, decltype(nts)::value>), dim3(gx, P), dim3(kBlock), 0,
-                       stream, recv, tok, slot, splits, P, T, static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+    if (s.tpr >= kWave)
+      hipLaunchKernelGGL((moe_dispatch_kernel<UB, decltype(ntl)::value, decltype(nts)::value, true>), dim3(gx, P), dim3(kBlock),
+                         0, stream, recv, tok, slot, splits, P, T, static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+    else
+      hipLaunchKernelGGL((moe_dispatch_kernel<UB, decltype(ntl)::value, decltype(nts)::value, false>), dim3(gx, P), dim3(kBlock),
+                         0, stream, recv, tok, slot, splits, P, T, static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
     return launch_status();
   };
   if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
@@ -258,9 +294,14 @@ int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, c
       constexpr int UB = decltype(ub)::value;
       const RowShape s = row_shape(row_elems * EB / UB);
       const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
-      hipLaunchKernelGGL((moe_combine_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
-                         dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, slot, g, splits, P, T,
-                         static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+      if (s.tpr >= kWave)
+        hipLaunchKernelGGL((moe_combine_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value, true>),
+                           dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, slot, g, splits, P, T,
+                           static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+      else
+        hipLaunchKernelGGL((moe_combine_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value, false>),
+                           dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, slot, g, splits, P, T,
+                           static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
       return launch_status();
     };
     if (variant == SV_SCALAR)

@@ -26,6 +26,10 @@ MUTANTS = [
      "float acc = load_elem(bufs[P - 1], i, dtype);\n  for (int p = 1; p < P; ++p) {\n    acc = acc + load_elem(bufs[P - 1 - p], i, dtype);"),
     ("avg_divides", "acc = acc * scale;", "acc = acc / static_cast<float>(P);"),
     ("allreduce_writes_rank0_only", "for (int r = 0; r < P; ++r) store_elem(bufs[r], i, dtype, y);", "store_elem(bufs[0], i, dtype, y);"),
+    ("reduce_writes_everyone", "    store_elem(bufs[root], i, dtype, y);\n  }\n  return 0;\n}\n\n// ---- bcast", "    for (int r = 0; r < P; ++r) store_elem(bufs[r], i, dtype, y);\n  }\n  return 0;\n}\n\n// ---- bcast"),
+    ("bcast_from_rank0", "static_cast<const char*>(bufs[root]) + i * s, s);", "static_cast<const char*>(bufs[0]) + i * s, s);"),
+    ("gatherv_displ_not_advanced", "    displ += counts[p];\n  }\n  return 0;\n}\n\nint orc_scatterv", "    displ += counts[0];\n  }\n  return 0;\n}\n\nint orc_scatterv"),
+    ("scatterv_ignores_displ", "static_cast<const char*>(root_in) + (displ + j) * s, s);", "static_cast<const char*>(root_in) + j * s, s);"),
     ("rs_wrong_slice", "reduce_at(in, static_cast<size_t>(r) * b + j, dtype, op, P);", "reduce_at(in, j, dtype, op, P);"),
     ("allgather_transposed", "static_cast<char*>(out[r]) + (static_cast<size_t>(p) * m + j) * s,\n                    static_cast<const char*>(in[p]) + j * s, s);",
      "static_cast<char*>(out[r]) + (static_cast<size_t>(r) * m + j) * s,\n                    static_cast<const char*>(in[p]) + j * s, s);"),

@@ -155,6 +155,58 @@ def check_allreduce_bruteforce_p2():
                     assert np.array_equal(bits32(out)[~nan], bits32(expect)[~nan])
 
 
+# ====================== rooted and vector collectives ==========================
+def check_reduce_and_bcast():
+    for dtype in (F32, BF16):
+        P, n = 5, 333
+        bufs = inputs.rank_buffers(P, n, seed=71, dist="normal", bf16=(dtype == BF16))
+        for root in (0, 3):
+            full = [b.copy() for b in bufs]
+            oracle.allreduce(full, dtype, AVG)
+            red = [b.copy() for b in bufs]
+            oracle.reduce(red, dtype, AVG, root)
+            for r in range(P):
+                # the root holds what all_reduce gives everyone; the others are untouched
+                assert np.array_equal(red[r], full[r] if r == root else bufs[r])
+            bc = [b.copy() for b in bufs]
+            oracle.bcast(bc, dtype, root)
+            for r in range(P):
+                assert np.array_equal(bc[r], bufs[root])
+    # closed form
+    bufs = [np.full(10, p + 1, dtype=np.float32) for p in range(4)]
+    oracle.reduce(bufs, F32, SUM, 2)
+    assert (bufs[2] == 10).all() and (bufs[0] == 1).all() and (bufs[3] == 4).all()
+
+
+def check_gatherv_scatterv_allgatherv():
+    # hand-worked: counts 2,0,3 -> displacements 0,2,2
+    ins = [np.array([1, 2], dtype=np.float32), np.zeros(0, dtype=np.float32), np.array([7, 8, 9], dtype=np.float32)]
+    g = oracle.gatherv(ins, [2, 0, 3], F32)
+    assert g.tolist() == [1, 2, 7, 8, 9]
+    sc = oracle.scatterv(g, [2, 0, 3], F32)
+    assert [x.tolist() for x in sc] == [[1, 2], [], [7, 8, 9]]
+    ag = oracle.allgatherv(ins, [2, 0, 3], F32)
+    assert all(a.tolist() == [1, 2, 7, 8, 9] for a in ag)
+    rng = np.random.Generator(np.random.Philox(key=72))
+    for dtype in (F32, BF16):
+        for P in (1, 3, 8):
+            counts = rng.integers(0, 50, size=P).tolist()
+            ins = [inputs.uniform_pm1(c, 73, p, bf16=(dtype == BF16)) for p, c in enumerate(counts)]
+            g = oracle.gatherv(ins, counts, dtype)
+            assert np.array_equal(g, np.concatenate(ins))                     # numpy's concatenation
+            back = oracle.scatterv(g, counts, dtype)
+            for p in range(P):
+                assert np.array_equal(back[p], ins[p])                        # scatterv inverts gatherv
+            for a in oracle.allgatherv(ins, counts, dtype):
+                assert np.array_equal(a, g)
+            # equal counts: all_gatherv is all_gather
+            eq = [inputs.uniform_pm1(17, 74, p, bf16=(dtype == BF16)) for p in range(P)]
+            a1 = oracle.allgatherv(eq, [17] * P, dtype)
+            a2 = oracle.allgather(eq, dtype)
+            for r in range(P):
+                assert np.array_equal(a1[r], a2[r])
+
+
 # ========================= reduce_scatter / all_gather =========================
 def check_rs_ag_compose():
     for dtype in (F32, BF16):
