@@ -163,6 +163,39 @@ int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const i
                   int splits_on_device, size_t in_rows, size_t out_rows, size_t row_elems,
                   mcr_dtype dtype, int P, int variant, void* stream);
 
+/* ---- rooted and vector collectives (API listing: reduce, bcast, gather, scatter, gatherv,
+ * scatterv, all_gatherv; the paper names the vectored ones as what other frameworks lack,
+ * Sec. I).  Displacements are packed: displ[p] = sum_{q<p} counts[q].  Counts are in
+ * elements.  MCR_AUTO looks these up under MCR_OP_ALLREDUCE (reduce) and MCR_OP_ALLTOALLV
+ * (the others), whose kernels they run on. ------------------------------------------------- */
+
+/* reduce: bufs[root][i] = x_0[i] (+) ... (+) x_{P-1}[i] with the arithmetic of mcr_allreduce; the
+ * other buffers are read only. */
+int mcr_reduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, mcr_redop op,
+               int root, int P, int variant, void* stream);
+
+/* bcast: bufs[r][i] = bufs[root][i] for every r != root.  Bit copy. */
+int mcr_bcast(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, int root, int P,
+              int variant, void* stream);
+
+/* gather / gatherv: out (the root's receive buffer, DEVICE memory, sum of counts elements)
+ * [displ[p] + j] = in[p][j], j < counts[p] (gather: every count is `count`).  counts: HOST
+ * array of P.  in[p] may be NULL where counts[p] == 0. */
+int mcr_gather(mcr_ctx* ctx, void* out, const void* const* in, size_t count, mcr_dtype dtype,
+               int P, int variant, void* stream);
+int mcr_gatherv(mcr_ctx* ctx, void* out, const void* const* in, const size_t* counts,
+                mcr_dtype dtype, int P, int variant, void* stream);
+
+/* scatter / scatterv: out[r][j] = in (the root's send buffer)[displ[r] + j], j < counts[r]. */
+int mcr_scatter(mcr_ctx* ctx, void* const* out, const void* in, size_t count, mcr_dtype dtype,
+                int P, int variant, void* stream);
+int mcr_scatterv(mcr_ctx* ctx, void* const* out, const void* in, const size_t* counts,
+                 mcr_dtype dtype, int P, int variant, void* stream);
+
+/* all_gatherv (it has no root): out[r][displ[p] + j] = in[p][j] for every r. */
+int mcr_allgatherv(mcr_ctx* ctx, void* const* out, const void* const* in, const size_t* counts,
+                   mcr_dtype dtype, int P, int variant, void* stream);
+
 /* ---- MoE dispatch / combine (paper Sec. II-C: routing of tokens to experts and
  * the combination of the expert outputs each need an Alltoall) -------------------
  *

@@ -4,6 +4,8 @@
 // loads, summed in rank order in binary32, optionally scaled by 1/P, rounded
 // once, and written back to all P buffers with 128-bit stores.  The thread that
 // reads an index is the only one that writes it, so in place has no race.
+// reduce (rooted) is the same kernel with the stores to all but the root's
+// buffer switched off (root >= 0).
 // Bound by HBM bandwidth: (P-1) adds per 2*P*s bytes.
 #include "mcr_reduce_tile.hpp"
 
@@ -12,7 +14,7 @@ namespace {
 
 template <int DT, int P, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
-allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale) {
+allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale, int root) {
   using E = Elem<DT>;
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
   CPtrTab in;
@@ -29,7 +31,7 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale)
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-        if (full || idx < nvec) store16<NTS>(bufs.p[p], idx, out[u]);
+        if ((full || idx < nvec) && (root < 0 || root == p)) store16<NTS>(bufs.p[p], idx, out[u]);
       }
     }
   }
@@ -39,26 +41,28 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale)
     const size_t i = done + threadIdx.x;
     const float y = reduce_scalar<DT>(in, i, P, scale, do_scale != 0);
 #pragma unroll
-    for (int p = 0; p < P; ++p) E::store1(bufs.p[p], i, y);
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
   }
 }
 
 template <int DT>
 __global__ void __launch_bounds__(kBlock)
-allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int do_scale) {
+allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int do_scale, int root) {
   using E = Elem<DT>;
   CPtrTab in;
   for (int p = 0; p < MCR_MAX_RANKS; ++p) in.p[p] = bufs.p[p];
   const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
   for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += step) {
     const float y = reduce_scalar<DT>(in, i, P, scale, do_scale != 0);
-    for (int p = 0; p < P; ++p) E::store1(bufs.p[p], i, y);
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
   }
 }
 
 }  // namespace
 
-int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P,
+int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int root,
                      int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   const float scale = 1.0f / static_cast<float>(P);
@@ -67,7 +71,7 @@ int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int 
     return dispatch_dtype(dtype, [&](auto dt) {
       constexpr int DT = decltype(dt)::value;
       hipLaunchKernelGGL((allreduce_scalar<DT>), dim3(scalar_grid(count)), dim3(kBlock), 0, stream,
-                         bufs, count, P, scale, do_scale);
+                         bufs, count, P, scale, do_scale, root);
       return launch_status();
     });
   }
@@ -80,7 +84,7 @@ int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int 
         constexpr int kP = decltype(pp)::value;
         constexpr int U = decltype(uu)::value;
         hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value>),
-                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, do_scale);
+                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, do_scale, root);
         return launch_status();
       });
     });

@@ -88,6 +88,35 @@ int set_device(mcr_ctx* ctx) {
   return hip_status(hipSetDevice(ctx->device));
 }
 
+// Common tail of the vector collectives: counts[i] elements per block; the split matrix is built by
+// `fill(S, rows)` from counts expressed in rows of `row_elems` elements (one 128-bit vector when
+// every count and pointer allows it, else one element).
+template <class Fill>
+int vector_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool all16, const size_t* counts, int n_counts,
+                      mcr_dtype dtype, int P, int same_src, int variant, void* stream, Fill fill) {
+  const size_t W = per_vec(dtype);
+  bool vec_ok = all16;
+  size_t total = 0, biggest = 0;
+  for (int i = 0; i < n_counts; ++i) {
+    if (counts[i] % W != 0) vec_ok = false;
+    total += counts[i];
+    if (counts[i] > biggest) biggest = counts[i];
+  }
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLTOALLV, dtype, P, biggest * elem_bytes(dtype), vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (total == 0) return MCR_OK;
+  const size_t row_elems = (v == SV_SCALAR) ? 1 : W;
+  int64_t S[MCR_MAX_RANKS * MCR_MAX_RANKS];
+  for (int i = 0; i < P * P; ++i) S[i] = 0;
+  fill(S, row_elems);
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  // every buffer is bounded by the whole payload: the split matrix is ours, so the bounds never bind
+  const size_t rows = total / row_elems;
+  return launch_alltoallv(ctx, to, ti, S, nullptr, rows, rows, row_elems * elem_bytes(dtype),
+                          static_cast<int>(elem_bytes(dtype)), P, same_src, v, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 }  // namespace mcr
 
@@ -169,7 +198,7 @@ int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype
   int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
   if (rc != MCR_OK) return rc;
   if ((rc = set_device(ctx)) != MCR_OK) return rc;
-  return launch_allreduce(ctx, tab, count, dtype, op, P, v, static_cast<hipStream_t>(stream));
+  return launch_allreduce(ctx, tab, count, dtype, op, P, -1, v, static_cast<hipStream_t>(stream));
 }
 
 int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype,
@@ -263,7 +292,123 @@ int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const i
   if (rc != MCR_OK) return rc;
   if ((rc = set_device(ctx)) != MCR_OK) return rc;
   return launch_alltoallv(ctx, to, ti, host, dev, in_rows, out_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P,
-                          v, static_cast<hipStream_t>(stream));
+                          0, v, static_cast<hipStream_t>(stream));
+}
+
+// ---- rooted and vector collectives (API listing: reduce, bcast, gather(v), scatter(v),
+// all_gatherv).  reduce is the all_reduce kernel storing to the root only; the others are
+// all_to_allv with a split matrix that has one column (gather), one row (scatter) or constant
+// rows and a common source block (all_gatherv, bcast). ---------------------------------------
+int mcr_reduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, mcr_redop op, int root, int P,
+               int variant, void* stream) {
+  if (!ctx || !bufs || !valid_P(P) || root < 0 || root >= P) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (!valid_redop(op)) return MCR_EOP;
+  PtrTab tab;
+  bool all16 = true;
+  if (!fill_tab(tab, bufs, P, dtype, count > 0, &all16)) return MCR_EINVAL;
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_allreduce(ctx, tab, count, dtype, op, P, root, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_bcast(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, int root, int P, int variant,
+              void* stream) {
+  if (!ctx || !bufs || !valid_P(P) || root < 0 || root >= P) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, bufs, P, dtype, count > 0, &all16) || !fill_tab(ti, bufs, P, dtype, count > 0, nullptr)) return MCR_EINVAL;
+  const size_t counts[1] = {count};
+  return vector_collective(ctx, to, ti, all16, counts, 1, dtype, P, 1, variant, stream, [&](int64_t* S, size_t re) {
+    for (int r = 0; r < P; ++r)
+      if (r != root) S[root * P + r] = static_cast<int64_t>(count / re);
+  });
+}
+
+int mcr_gatherv(mcr_ctx* ctx, void* out, const void* const* in, const size_t* counts, mcr_dtype dtype, int P,
+                int variant, void* stream) {
+  if (!ctx || !in || !counts || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  size_t total = 0;
+  for (int p = 0; p < P; ++p) total += counts[p];
+  if (total > 0 && (!out || !elem_aligned(out, dtype))) return MCR_EINVAL;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = aligned16(out);
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) { to.p[i] = nullptr; ti.p[i] = nullptr; }
+  to.p[0] = out;                                        // the root is "receiver 0" of the split matrix
+  for (int p = 0; p < P; ++p) {
+    if (counts[p] > 0 && (!in[p] || !elem_aligned(in[p], dtype))) return MCR_EINVAL;
+    if (counts[p] > 0 && !aligned16(in[p])) all16 = false;
+    ti.p[p] = in[p];
+  }
+  return vector_collective(ctx, to, ti, all16, counts, P, dtype, P, 0, variant, stream, [&](int64_t* S, size_t re) {
+    for (int p = 0; p < P; ++p) S[p * P + 0] = static_cast<int64_t>(counts[p] / re);
+  });
+}
+
+int mcr_gather(mcr_ctx* ctx, void* out, const void* const* in, size_t count, mcr_dtype dtype, int P, int variant,
+               void* stream) {
+  if (!valid_P(P)) return MCR_EINVAL;
+  size_t counts[MCR_MAX_RANKS];
+  for (int p = 0; p < P; ++p) counts[p] = count;
+  return mcr_gatherv(ctx, out, in, counts, dtype, P, variant, stream);
+}
+
+int mcr_scatterv(mcr_ctx* ctx, void* const* out, const void* in, const size_t* counts, mcr_dtype dtype, int P,
+                 int variant, void* stream) {
+  if (!ctx || !out || !counts || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  size_t total = 0;
+  for (int p = 0; p < P; ++p) total += counts[p];
+  if (total > 0 && (!in || !elem_aligned(in, dtype))) return MCR_EINVAL;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = aligned16(in);
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) { to.p[i] = nullptr; ti.p[i] = nullptr; }
+  ti.p[0] = in;                                         // the root is "sender 0" of the split matrix
+  for (int r = 0; r < P; ++r) {
+    if (counts[r] > 0 && (!out[r] || !elem_aligned(out[r], dtype))) return MCR_EINVAL;
+    if (counts[r] > 0 && !aligned16(out[r])) all16 = false;
+    to.p[r] = out[r];
+  }
+  return vector_collective(ctx, to, ti, all16, counts, P, dtype, P, 0, variant, stream, [&](int64_t* S, size_t re) {
+    for (int r = 0; r < P; ++r) S[0 * P + r] = static_cast<int64_t>(counts[r] / re);
+  });
+}
+
+int mcr_scatter(mcr_ctx* ctx, void* const* out, const void* in, size_t count, mcr_dtype dtype, int P, int variant,
+                void* stream) {
+  if (!valid_P(P)) return MCR_EINVAL;
+  size_t counts[MCR_MAX_RANKS];
+  for (int p = 0; p < P; ++p) counts[p] = count;
+  return mcr_scatterv(ctx, out, in, counts, dtype, P, variant, stream);
+}
+
+int mcr_allgatherv(mcr_ctx* ctx, void* const* out, const void* const* in, const size_t* counts, mcr_dtype dtype,
+                   int P, int variant, void* stream) {
+  if (!ctx || !out || !in || !counts || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  size_t total = 0;
+  for (int p = 0; p < P; ++p) total += counts[p];
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, total > 0, &all16)) return MCR_EINVAL;
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) ti.p[i] = nullptr;
+  for (int p = 0; p < P; ++p) {
+    if (counts[p] > 0 && (!in[p] || !elem_aligned(in[p], dtype))) return MCR_EINVAL;
+    if (counts[p] > 0 && !aligned16(in[p])) all16 = false;
+    ti.p[p] = in[p];
+  }
+  return vector_collective(ctx, to, ti, all16, counts, P, dtype, P, 1, variant, stream, [&](int64_t* S, size_t re) {
+    for (int p = 0; p < P; ++p)
+      for (int r = 0; r < P; ++r) S[p * P + r] = static_cast<int64_t>(counts[p] / re);
+  });
 }
 
 // ---- MoE ------------------------------------------------------------------------

@@ -117,7 +117,8 @@ alltoall_kernel(PtrTab out, CPtrTab in, size_t b) {
 // In dispatch order the chip walks one pair after the other: one read stream
 // and one write stream at a time.  Skew costs nothing but workgroups that find
 // their tile beyond the pair's end and leave at once; pairs longer than the
-// grid are covered by striding.
+// grid are covered by striding.  gather(v), scatter(v), all_gatherv and bcast
+// are this kernel with a one-column, one-row or row-constant split matrix.
 struct SplitArg {
   int64_t s[MCR_MAX_RANKS * MCR_MAX_RANKS];
 };
@@ -132,7 +133,7 @@ __device__ __forceinline__ uint64_t clamp_split(int64_t s, uint64_t in_rows) {
 template <int UB, int U, bool NTL, bool NTS, bool DEV>
 __global__ void __launch_bounds__(kBlock)
 alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, uint64_t upr,
-                 uint64_t in_rows, uint64_t out_rows) {
+                 uint64_t in_rows, uint64_t out_rows, int same_src) {
   typedef typename Unit<UB>::type T;
   constexpr uint64_t kTile = static_cast<uint64_t>(U) * kBlock;
   const int p = blockIdx.y, r = blockIdx.z;
@@ -140,7 +141,9 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
   uint64_t rows = clamp_split(S[p * P + r], in_rows);
   if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;      // the common early exit
   uint64_t sdispl = 0, rdispl = 0;
-  for (int q = 0; q < r; ++q) sdispl += clamp_split(S[p * P + q], in_rows);
+  // same_src: every receiver gets the sender's rows from row 0 on (all_gatherv, bcast)
+  if (!same_src)
+    for (int q = 0; q < r; ++q) sdispl += clamp_split(S[p * P + q], in_rows);
   for (int q = 0; q < p; ++q) rdispl += clamp_split(S[q * P + r], in_rows);
   // rows that would leave either buffer are not copied
   if (sdispl >= in_rows || rdispl >= out_rows) return;
@@ -237,7 +240,7 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
 
 int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits,
                      const int64_t* dev_splits, size_t in_rows, size_t out_rows, size_t row_bytes,
-                     int elem_b, int P, int variant, hipStream_t stream) {
+                     int elem_b, int P, int same_src, int variant, hipStream_t stream) {
   SplitArg hs;
   for (int i = 0; i < MCR_MAX_RANKS * MCR_MAX_RANKS; ++i) hs.s[i] = 0;
   // rows of the longest pair: exact for a host matrix, the buffer bound for a device one
@@ -263,10 +266,10 @@ int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64
     const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock, dev ? 256 : 65535 * 16);
     if (dev)
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
-                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows));
+                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src);
     else
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
-                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows));
+                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src);
     return launch_status();
   };
   if (variant == SV_SCALAR) {

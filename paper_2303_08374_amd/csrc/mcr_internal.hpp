@@ -83,12 +83,12 @@ inline int per_vec(int dtype) { return dtype == MCR_F32 ? 4 : 8; }
 constexpr uint32_t kChunkBytes = 256 * 4 * 16;
 
 // Every launcher returns MCR_OK or MCR_EHIP and assumes validated arguments.
-int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int variant, hipStream_t);
+int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int root, int variant, hipStream_t);
 int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int op, int P, int variant, hipStream_t);
 int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
 int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
 int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits, const int64_t* dev_splits,
-                     size_t in_rows, size_t out_rows, size_t row_bytes, int elem_b, int P, int variant, hipStream_t);
+                     size_t in_rows, size_t out_rows, size_t row_bytes, int elem_b, int P, int same_src, int variant, hipStream_t);
 int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot, const PtrTab& counts,
                      int64_t* splits, hipStream_t);
 int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows, size_t row_bytes,

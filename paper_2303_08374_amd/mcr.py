@@ -155,6 +155,48 @@ def mcr_alltoallv(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], splits, splits_on
            "mcr_alltoallv")
 
 
+# ---- rooted and vector collectives ---------------------------------------------------------
+def _counts(counts: Sequence[int]):
+    return (ctypes.c_size_t * len(counts))(*[int(c) for c in counts])
+
+
+def mcr_reduce(ctx, bufs: Sequence[Ptr], count: int, dtype: int, op: int, root: int, P: int, variant: int = AUTO,
+               stream=None) -> None:
+    _check(lib().mcr_reduce(ctx, _ptr_array(bufs), _sz(count), dtype, op, root, P, variant, _stream(stream)), "mcr_reduce")
+
+
+def mcr_bcast(ctx, bufs: Sequence[Ptr], count: int, dtype: int, root: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_bcast(ctx, _ptr_array(bufs), _sz(count), dtype, root, P, variant, _stream(stream)), "mcr_bcast")
+
+
+def mcr_gather(ctx, out: Ptr, inp: Sequence[Ptr], count: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_gather(ctx, ctypes.c_void_p(_addr(out)), _ptr_array(inp), _sz(count), dtype, P, variant,
+                            _stream(stream)), "mcr_gather")
+
+
+def mcr_gatherv(ctx, out: Ptr, inp: Sequence[Ptr], counts: Sequence[int], dtype: int, P: int, variant: int = AUTO,
+                stream=None) -> None:
+    _check(lib().mcr_gatherv(ctx, ctypes.c_void_p(_addr(out)), _ptr_array(inp), _counts(counts), dtype, P, variant,
+                             _stream(stream)), "mcr_gatherv")
+
+
+def mcr_scatter(ctx, out: Sequence[Ptr], inp: Ptr, count: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_scatter(ctx, _ptr_array(out), ctypes.c_void_p(_addr(inp)), _sz(count), dtype, P, variant,
+                             _stream(stream)), "mcr_scatter")
+
+
+def mcr_scatterv(ctx, out: Sequence[Ptr], inp: Ptr, counts: Sequence[int], dtype: int, P: int, variant: int = AUTO,
+                 stream=None) -> None:
+    _check(lib().mcr_scatterv(ctx, _ptr_array(out), ctypes.c_void_p(_addr(inp)), _counts(counts), dtype, P, variant,
+                              _stream(stream)), "mcr_scatterv")
+
+
+def mcr_allgatherv(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], counts: Sequence[int], dtype: int, P: int,
+                   variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_allgatherv(ctx, _ptr_array(out), _ptr_array(inp), _counts(counts), dtype, P, variant,
+                                _stream(stream)), "mcr_allgatherv")
+
+
 # ---- MoE -----------------------------------------------------------------------------------
 def mcr_moe_route(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
                   counts: Sequence[Ptr], splits: Ptr, stream=None) -> None:

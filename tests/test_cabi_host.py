@@ -93,6 +93,17 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 3], [3, 5]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESTATE
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], None, False, 7, 8, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[1, 1], [1, 1]], False, 8, 8, 3, S.BF16, 2, 3, 0) == S.EVARIANT
+    # rooted and vector collectives
+    assert _status(S.mcr_reduce, ctx, A16[:4], 64, S.F32, S.SUM, 4, 4, S.AUTO, 0) == S.EINVAL                 # root out of range
+    assert _status(S.mcr_reduce, ctx, A16[:4], 64, S.F32, S.SUM, 3, 4, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_bcast, ctx, A16[:4], 64, S.BF16, -1, 4, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_bcast, ctx, A16[:4], 7, S.BF16, 0, 4, 1, 0) == S.EVARIANT                            # 7 bf16 is not a multiple of 16 bytes
+    assert _status(S.mcr_gatherv, ctx, A16[0], A16[1:3], [8, 8], S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_gatherv, ctx, A16[0], [A16[1], 0], [8, 8], S.F32, 2, S.AUTO, 0) == S.EINVAL            # null sender with a non-zero count
+    assert _status(S.mcr_gatherv, ctx, A16[0], [A16[1], 0], [8, 0], S.F32, 2, S.AUTO, 0) == S.ESTATE            # ... but fine with count 0
+    assert _status(S.mcr_scatterv, ctx, A16[1:3], 0, [8, 8], S.F32, 2, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_allgatherv, ctx, A16[:2], A16[2:4], [3, 8], S.F32, 2, 2, 0) == S.EVARIANT
+    assert _status(S.mcr_allgatherv, ctx, A16[:2], A16[2:4], [0, 0], S.F32, 2, S.AUTO, 0) == 0                   # nothing to move
     # MoE routing
     assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 6, 4, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL      # P does not divide E
     assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 1024, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL  # too many experts

@@ -1,0 +1,108 @@
+"""GPU parity of the rooted and vector collectives (reduce, bcast, gather(v), scatter(v),
+all_gatherv) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2303_08374_amd import inputs, mcr
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DTYPES = [mcr.F32, mcr.BF16]
+
+
+def _bufs(P, n, dtype, seed):
+    return inputs.rank_buffers(P, n, seed, "normal", bf16=(dtype == mcr.BF16))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("P", [1, 2, 5, 8, 16])
+def test_reduce_to_root(dtype, P):
+    for count in (1, 7, 4096, 13319):
+        host = _bufs(P, count, dtype, 1400 + P)
+        for root in sorted({0, P - 1, P // 2}):
+            for op in (mcr.SUM, mcr.AVG):
+                exp = [h.copy() for h in host]
+                oracle.reduce(exp, dtype, op, root)
+                for variant in (mcr.AUTO, 0, 1, 6, 9):
+                    dev = [gu.to_dev(h) for h in host]
+                    mcr.mcr_reduce(gu.ctx(), dev, count, dtype, op, root, P, variant)
+                    gu.sync()
+                    for r in range(P):
+                        gu.assert_reduced_equal(gu.to_host(dev[r], gu.NPDT[dtype]), exp[r], dtype,
+                                                f"reduce dt={dtype} P={P} n={count} root={root} op={op} v={variant} r={r}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("P", [1, 3, 8, 16])
+def test_bcast(dtype, P):
+    for count in (1, 5, 8, 4104, 70000):
+        host = _bufs(P, count, dtype, 1500 + P)
+        vec_ok = count % (4 if dtype == mcr.F32 else 8) == 0
+        for root in sorted({0, P - 1}):
+            exp = [h.copy() for h in host]
+            oracle.bcast(exp, dtype, root)
+            for variant in [mcr.AUTO, 0] + ([1, 4, 12] if vec_ok else []):
+                dev = [gu.to_dev(h) for h in host]
+                mcr.mcr_bcast(gu.ctx(), dev, count, dtype, root, P, variant)
+                gu.sync()
+                for r in range(P):
+                    gu.assert_bits_equal(gu.to_host(dev[r], gu.NPDT[dtype]), exp[r], f"bcast P={P} n={count} root={root} v={variant}")
+
+
+def _count_sets(P, W, rng):
+    yield [W * int(c) for c in rng.integers(0, 600, size=P)]               # 128-bit friendly, some may be 0
+    yield [int(c) for c in rng.integers(0, 50, size=P)]                    # arbitrary: element path
+    yield [0] * P
+    yield [W * 1000] * P                                                   # equal counts (gather / scatter)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("P", [1, 2, 7, 16])
+def test_gatherv_scatterv_allgatherv(dtype, P):
+    W = 4 if dtype == mcr.F32 else 8
+    rng = np.random.Generator(np.random.Philox(key=1600 + P))
+    bf = dtype == mcr.BF16
+    for counts in _count_sets(P, W, rng):
+        total = sum(counts)
+        vec_ok = all(c % W == 0 for c in counts)
+        ins = [inputs.uniform_pm1(c, 1601, p, bf16=bf) for p, c in enumerate(counts)]
+        g_exp = oracle.gatherv(ins, counts, dtype)
+        ag_exp = oracle.allgatherv(ins, counts, dtype)
+        d_ins = [gu.to_dev(x) if x.size else gu.dev_empty(8, dtype, 0) for x in ins]
+        for variant in [mcr.AUTO, 0] + ([1, 5, 9] if vec_ok else []):
+            d_g = gu.dev_empty(total + 8, dtype, 0)
+            mcr.mcr_gatherv(gu.ctx(), d_g, d_ins, counts, dtype, P, variant)
+            d_ag = [gu.dev_empty(total + 8, dtype, 0) for _ in range(P)]
+            mcr.mcr_allgatherv(gu.ctx(), d_ag, d_ins, counts, dtype, P, variant)
+            d_sc = [gu.dev_empty(c + 8, dtype, 0) for c in counts]
+            mcr.mcr_scatterv(gu.ctx(), d_sc, d_g, counts, dtype, P, variant)
+            gu.sync()
+            got = gu.to_host(d_g, gu.NPDT[dtype])
+            gu.assert_bits_equal(got[:total], g_exp, f"gatherv P={P} v={variant}")
+            assert (got[total:] == 0).all()                                  # nothing past the payload is written
+            for r in range(P):
+                a = gu.to_host(d_ag[r], gu.NPDT[dtype])
+                gu.assert_bits_equal(a[:total], ag_exp[r], f"allgatherv P={P} v={variant} r={r}")
+                assert (a[total:] == 0).all()
+                s = gu.to_host(d_sc[r], gu.NPDT[dtype])
+                gu.assert_bits_equal(s[:counts[r]], ins[r], f"scatterv(gatherv) P={P} v={variant} r={r}")
+                assert (s[counts[r]:] == 0).all()
+        if not vec_ok:
+            with pytest.raises(mcr.McrError) as e:
+                mcr.mcr_gatherv(gu.ctx(), gu.dev_empty(total + 8, dtype, 0), d_ins, counts, dtype, P, 1)
+            assert e.value.status == mcr.EVARIANT
+
+
+def test_gather_scatter_equal_counts():
+    P, n, dtype = 8, 4096, mcr.F32
+    ins = _bufs(P, n, dtype, 1700)
+    d_out = gu.dev_empty(P * n, dtype, 0)
+    mcr.mcr_gather(gu.ctx(), d_out, [gu.to_dev(x) for x in ins], n, dtype, P)
+    d_back = [gu.dev_empty(n, dtype, 0) for _ in range(P)]
+    mcr.mcr_scatter(gu.ctx(), d_back, d_out, n, dtype, P)
+    gu.sync()
+    gu.assert_bits_equal(gu.to_host(d_out, np.float32), oracle.allgather(ins, dtype)[0], "gather = a row of all_gather")
+    sc_exp = oracle.scatterv(np.concatenate(ins), [n] * P, dtype)
+    for r in range(P):
+        gu.assert_bits_equal(gu.to_host(d_back[r], np.float32), sc_exp[r], "scatter")
