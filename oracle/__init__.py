@@ -21,6 +21,9 @@ F32 = 0
 BF16 = 1
 SUM = 0
 AVG = 1
+MAX = 2
+MIN = 3
+PROD = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mcr_oracle.cpp")

@@ -28,7 +28,7 @@
 namespace {
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
-enum { OP_SUM = 0, OP_AVG = 1 };
+enum { OP_SUM = 0, OP_AVG = 1, OP_MAX = 2, OP_MIN = 3, OP_PROD = 4 };
 
 // bf16 is the upper half of a binary32 pattern.
 inline float bf16_bits_to_float(uint16_t h) {
@@ -83,13 +83,25 @@ inline void store_elem(void* base, size_t i, int dtype, float v) {
 inline size_t elem_bytes(int dtype) { return dtype == DT_F32 ? 4u : 2u; }
 
 inline bool bad_dtype(int dtype) { return dtype != DT_F32 && dtype != DT_BF16; }
-inline bool bad_op(int op) { return op != OP_SUM && op != OP_AVG; }
+inline bool bad_op(int op) { return op < OP_SUM || op > OP_PROD; }
+
+// One step of the ReduceOp chain (API listing: all_reduce / reduce / reduce_scatter take a
+// ReduceOp).  MAX and MIN let a NaN through from either side, so a NaN anywhere in the chain
+// reaches the result; between equal values (+0 and -0 included) the earlier rank's value stays.
+inline float combine(float acc, float x, int op) {
+  switch (op) {
+    case OP_MAX: return (x > acc || x != x) ? x : acc;
+    case OP_MIN: return (x < acc || x != x) ? x : acc;
+    case OP_PROD: return acc * x;
+    default: return acc + x;
+  }
+}
 
 // Reduction of element i over ranks 0..P-1, canonical order.
 inline float reduce_at(const void* const* bufs, size_t i, int dtype, int op, int P) {
   float acc = load_elem(bufs[0], i, dtype);
   for (int p = 1; p < P; ++p) {
-    acc = acc + load_elem(bufs[p], i, dtype);
+    acc = combine(acc, load_elem(bufs[p], i, dtype), op);
   }
   if (op == OP_AVG) {
     const float scale = 1.0f / static_cast<float>(P);

@@ -30,6 +30,9 @@ MUTANTS = [
     ("bcast_from_rank0", "static_cast<const char*>(bufs[root]) + i * s, s);", "static_cast<const char*>(bufs[0]) + i * s, s);"),
     ("gatherv_displ_not_advanced", "    displ += counts[p];\n  }\n  return 0;\n}\n\nint orc_scatterv", "    displ += counts[0];\n  }\n  return 0;\n}\n\nint orc_scatterv"),
     ("scatterv_ignores_displ", "static_cast<const char*>(root_in) + (displ + j) * s, s);", "static_cast<const char*>(root_in) + j * s, s);"),
+    ("max_is_min", "case OP_MAX: return (x > acc || x != x) ? x : acc;", "case OP_MAX: return (x < acc || x != x) ? x : acc;"),
+    ("min_drops_nan", "case OP_MIN: return (x < acc || x != x) ? x : acc;", "case OP_MIN: return (x < acc) ? x : acc;"),
+    ("prod_adds", "case OP_PROD: return acc * x;", "case OP_PROD: return acc + x;"),
     ("rs_wrong_slice", "reduce_at(in, static_cast<size_t>(r) * b + j, dtype, op, P);", "reduce_at(in, j, dtype, op, P);"),
     ("allgather_transposed", "static_cast<char*>(out[r]) + (static_cast<size_t>(p) * m + j) * s,\n                    static_cast<const char*>(in[p]) + j * s, s);",
      "static_cast<char*>(out[r]) + (static_cast<size_t>(r) * m + j) * s,\n                    static_cast<const char*>(in[p]) + j * s, s);"),

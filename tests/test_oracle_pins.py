@@ -80,6 +80,39 @@ def check_allreduce_golden():
                 assert bits32(b)[0] == bits32([gio.f32_from_token(exp)])[0], (s, hex(bits32(b)[0]))
 
 
+def check_reduce_ops_golden_and_closed_form():
+    ops = {"max": oracle.MAX, "min": oracle.MIN, "prod": oracle.PROD}
+    for s in gio.lines("reduce_op_cases.txt"):
+        op, vals, exp = [t.strip() for t in s.split("|")]
+        bufs = [np.array([gio.f32_from_token(t)], dtype=np.float32) for t in vals.split()]
+        with np.errstate(all="ignore"):
+            oracle.allreduce(bufs, F32, ops[op])
+        for b in bufs:
+            if exp == "nan":
+                assert np.isnan(b[0]), s
+            else:
+                assert bits32(b)[0] == bits32([gio.f32_from_token(exp)])[0], (s, hex(bits32(b)[0]))
+    # numpy's reductions on NaN-free data; small-integer products are exact
+    for dtype in (F32, BF16):
+        P = 6
+        bufs = inputs.rank_buffers(P, 5000, seed=81, dist="normal", bf16=(dtype == BF16))
+        wide = np.stack([b if dtype == F32 else inputs.bf16_bits_to_f32(b) for b in bufs])
+        for op, ref in ((oracle.MAX, wide.max(axis=0)), (oracle.MIN, wide.min(axis=0))):
+            got = [b.copy() for b in bufs]
+            oracle.allreduce(got, dtype, op)
+            g = got[2] if dtype == F32 else inputs.bf16_bits_to_f32(got[2])
+            assert np.array_equal(g, ref)
+    i = np.arange(1000)
+    bufs = [((i + p) % 3 + 1).astype(np.float32) for p in range(5)]          # factors 1..3, product <= 243
+    expect = np.prod(np.stack(bufs).astype(np.int64), axis=0)
+    oracle.allreduce(bufs, F32, oracle.PROD)
+    assert np.array_equal(bufs[4], expect.astype(np.float32))
+    # reduce_scatter and reduce take the same ops
+    bufs = inputs.rank_buffers(4, 64, seed=82)
+    rs = oracle.reduce_scatter(bufs, F32, oracle.MAX)
+    assert np.array_equal(np.concatenate(rs), np.stack(bufs).max(axis=0))
+
+
 def check_allreduce_closed_form():
     # small integers are exact in binary32 (and here in bf16) under any association
     for dtype in (F32, BF16):
