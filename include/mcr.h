@@ -50,9 +50,11 @@ typedef struct mcr_fuse_plan mcr_fuse_plan; /* library-owned: bucket plan + devi
 
 typedef enum { MCR_F32 = 0, MCR_BF16 = 1 } mcr_dtype;
 
-/* ReduceOp of the API listing.  MCR_AVG is the sum multiplied (in binary32,
- * before the one final rounding) by the binary32 value 1.0f/P. */
-typedef enum { MCR_SUM = 0, MCR_AVG = 1 } mcr_redop;
+/* ReduceOp of the API listing; every op runs as a left-to-right chain in rank order in
+ * binary32 with one final rounding.  MCR_AVG is the sum multiplied (before that rounding) by
+ * the binary32 value 1.0f/P.  MCR_MAX / MCR_MIN let a NaN through from either side, and
+ * between equal values (+0 and -0 included) the earlier rank's value stays. */
+typedef enum { MCR_SUM = 0, MCR_AVG = 1, MCR_MAX = 2, MCR_MIN = 3, MCR_PROD = 4 } mcr_redop;
 
 typedef enum {
   MCR_OP_ALLREDUCE = 0,

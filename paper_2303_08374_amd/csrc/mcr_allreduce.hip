@@ -14,7 +14,7 @@ namespace {
 
 template <int DT, int P, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
-allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale, int root) {
+allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root) {
   using E = Elem<DT>;
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
   CPtrTab in;
@@ -24,8 +24,8 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale,
   if (tile < nvec) {
     u32x4 out[U];
     const bool full = tile + kTile <= nvec;
-    if (full) reduce_tile<DT, P, U, NTL, true>(in, 0, tile, nvec, scale, do_scale != 0, out);
-    else reduce_tile<DT, P, U, NTL, false>(in, 0, tile, nvec, scale, do_scale != 0, out);
+    if (full) reduce_tile<DT, P, U, NTL, true>(in, 0, tile, nvec, scale, op, out);
+    else reduce_tile<DT, P, U, NTL, false>(in, 0, tile, nvec, scale, op, out);
 #pragma unroll
     for (int p = 0; p < P; ++p) {
 #pragma unroll
@@ -39,7 +39,7 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale,
   const size_t done = nvec * E::kPerVec;
   if (blockIdx.x == 0 && done + threadIdx.x < count) {
     const size_t i = done + threadIdx.x;
-    const float y = reduce_scalar<DT>(in, i, P, scale, do_scale != 0);
+    const float y = reduce_scalar<DT>(in, i, P, scale, op);
 #pragma unroll
     for (int p = 0; p < P; ++p)
       if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
@@ -48,13 +48,13 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int do_scale,
 
 template <int DT>
 __global__ void __launch_bounds__(kBlock)
-allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int do_scale, int root) {
+allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int op, int root) {
   using E = Elem<DT>;
   CPtrTab in;
   for (int p = 0; p < MCR_MAX_RANKS; ++p) in.p[p] = bufs.p[p];
   const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
   for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += step) {
-    const float y = reduce_scalar<DT>(in, i, P, scale, do_scale != 0);
+    const float y = reduce_scalar<DT>(in, i, P, scale, op);
     for (int p = 0; p < P; ++p)
       if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
   }
@@ -66,12 +66,11 @@ int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int 
                      int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   const float scale = 1.0f / static_cast<float>(P);
-  const int do_scale = (op == MCR_AVG) ? 1 : 0;
   if (variant == SV_SCALAR) {
     return dispatch_dtype(dtype, [&](auto dt) {
       constexpr int DT = decltype(dt)::value;
       hipLaunchKernelGGL((allreduce_scalar<DT>), dim3(scalar_grid(count)), dim3(kBlock), 0, stream,
-                         bufs, count, P, scale, do_scale, root);
+                         bufs, count, P, scale, op, root);
       return launch_status();
     });
   }
@@ -84,7 +83,7 @@ int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int 
         constexpr int kP = decltype(pp)::value;
         constexpr int U = decltype(uu)::value;
         hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value>),
-                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, do_scale, root);
+                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root);
         return launch_status();
       });
     });

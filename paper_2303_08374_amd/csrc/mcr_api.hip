@@ -25,7 +25,7 @@ const char* const kDtypeNames[2] = {"f32", "bf16"};
 const char* const kRouteVariantNames[1] = {"wave_ballot"};
 
 bool valid_dtype(int d) { return d == MCR_F32 || d == MCR_BF16; }
-bool valid_redop(int o) { return o == MCR_SUM || o == MCR_AVG; }
+bool valid_redop(int o) { return o >= MCR_SUM && o <= MCR_PROD; }
 bool valid_P(int P) { return P >= 1 && P <= MCR_MAX_RANKS; }
 int n_variants(int op) { return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : SV_COUNT; }
 

@@ -97,6 +97,17 @@ template <> struct Elem<MCR_BF16> {
   }
 };
 
+// One step of the ReduceOp chain.  MAX and MIN let a NaN through from either side; between
+// equal values the accumulated (earlier rank's) one stays.  `op` is uniform over the launch.
+__device__ __forceinline__ float combine(float acc, float x, int op) {
+  switch (op) {
+    case MCR_MAX: return (x > acc || x != x) ? x : acc;
+    case MCR_MIN: return (x < acc || x != x) ? x : acc;
+    case MCR_PROD: return acc * x;
+    default: return acc + x;
+  }
+}
+
 // Lanes of this wavefront with a lower lane id.
 __device__ __forceinline__ uint64_t lanemask_lt() {
   const unsigned lane = __lane_id();

@@ -62,7 +62,7 @@ fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
 // All-reduce of one chunk of one tensor across the bound ranks, in place.
 template <int DT, int P, bool NTL, bool NTS, bool FORCE_SCALAR>
 __global__ void __launch_bounds__(kBlock)
-allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int do_scale) {
+allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
   using E = Elem<DT>;
   constexpr int W = E::kPerVec;
   constexpr uint64_t CE = kChunkBytes / E::kBytes;
@@ -102,9 +102,9 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int do_scal
           float x[W];
           E::widen(v[u][p], x);
 #pragma unroll
-          for (int k = 0; k < W; ++k) acc[k] = acc[k] + x[k];
+          for (int k = 0; k < W; ++k) acc[k] = combine(acc[k], x[k], op);
         }
-        if (do_scale) {
+        if (op == MCR_AVG) {
 #pragma unroll
           for (int k = 0; k < W; ++k) acc[k] = acc[k] * scale;
         }
@@ -124,8 +124,8 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int do_scal
   for (uint64_t e = done + threadIdx.x; e < ne; e += kBlock) {
     float acc = E::load1(base[0], e);
 #pragma unroll
-    for (int p = 1; p < P; ++p) acc = acc + E::load1(base[p], e);
-    if (do_scale) acc = acc * scale;
+    for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(base[p], e), op);
+    if (op == MCR_AVG) acc = acc * scale;
 #pragma unroll
     for (int p = 0; p < P; ++p) E::store1(base[p], e, acc);
   }
@@ -172,18 +172,17 @@ int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, 
   const PlanDev d = plan_dev(plan);
   const int P = plan->bound_P;
   const float scale = 1.0f / static_cast<float>(P);
-  const int do_scale = (op == MCR_AVG) ? 1 : 0;
   return dispatch_dtype(plan->dtype, [&](auto dt) {
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int DT = decltype(dt)::value;
       constexpr int kP = decltype(pp)::value;
       if (variant == SV_SCALAR) {
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, do_scale);
+        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
         return launch_status();
       }
       return dispatch_hint(variant, [&](auto ntl, auto nts) {
         hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false>), dim3(c1 - c0),
-                           dim3(kBlock), 0, stream, d, c0, scale, do_scale);
+                           dim3(kBlock), 0, stream, d, c0, scale, op);
         return launch_status();
       });
     });

@@ -10,7 +10,7 @@ namespace {
 // blockIdx.y = destination rank r; slice r of every input is bvec vectors long.
 template <int DT, int P, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
-reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int do_scale) {
+reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
   const unsigned r = blockIdx.y;
   void* dst = out.p[r];
@@ -19,8 +19,8 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int do_scal
   if (tile >= bvec) return;
   u32x4 res[U];
   const bool full = tile + kTile <= bvec;
-  if (full) reduce_tile<DT, P, U, NTL, true>(in, off, tile, bvec, scale, do_scale != 0, res);
-  else reduce_tile<DT, P, U, NTL, false>(in, off, tile, bvec, scale, do_scale != 0, res);
+  if (full) reduce_tile<DT, P, U, NTL, true>(in, off, tile, bvec, scale, op, res);
+  else reduce_tile<DT, P, U, NTL, false>(in, off, tile, bvec, scale, op, res);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
@@ -30,13 +30,13 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int do_scal
 
 template <int DT>
 __global__ void __launch_bounds__(kBlock)
-reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, int P, float scale, int do_scale) {
+reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, int P, float scale, int op) {
   using E = Elem<DT>;
   const unsigned r = blockIdx.y;
   void* dst = out.p[r];
   const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
   for (size_t j = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; j < b; j += step) {
-    const float y = reduce_scalar<DT>(in, static_cast<size_t>(r) * b + j, P, scale, do_scale != 0);
+    const float y = reduce_scalar<DT>(in, static_cast<size_t>(r) * b + j, P, scale, op);
     E::store1(dst, j, y);
   }
 }
@@ -47,13 +47,12 @@ int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t
                           int op, int P, int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   const float scale = 1.0f / static_cast<float>(P);
-  const int do_scale = (op == MCR_AVG) ? 1 : 0;
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
     return dispatch_dtype(dtype, [&](auto dt) {
       constexpr int DT = decltype(dt)::value;
       hipLaunchKernelGGL((reduce_scatter_scalar<DT>), dim3(scalar_grid(b), P), dim3(kBlock), 0, stream,
-                         out, in, b, P, scale, do_scale);
+                         out, in, b, P, scale, op);
       return launch_status();
     });
   }
@@ -66,7 +65,7 @@ int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t
         constexpr int kP = decltype(pp)::value;
         constexpr int U = decltype(uu)::value;
         hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value>),
-                           dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, do_scale);
+                           dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, op);
         return launch_status();
       });
     });

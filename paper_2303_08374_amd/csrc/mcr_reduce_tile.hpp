@@ -1,6 +1,7 @@
 // The streaming sum shared by all_reduce and reduce_scatter: one tile of U*256
 // consecutive 128-bit vectors, read from all P rank buffers and summed left to
-// right in rank order in binary32, starting from rank 0's value.
+// right in rank order in binary32, starting from rank 0's value (or combined with
+// max / min / product, the other ReduceOps).
 #pragma once
 #include "mcr_dispatch.hpp"
 
@@ -11,7 +12,7 @@ namespace mcr {
 // system serves better than a round-robin over the P buffers.
 template <int DT, int P, int U, bool NTL, bool FULL>
 __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off, size_t tile,
-                                            size_t nvec, float scale, bool do_scale,
+                                            size_t nvec, float scale, int op,
                                             u32x4 (&out)[U]) {
   using E = Elem<DT>;
   constexpr int W = E::kPerVec;
@@ -35,9 +36,9 @@ __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off
         float x[W];
         E::widen(v[u][p], x);
 #pragma unroll
-        for (int k = 0; k < W; ++k) acc[k] = acc[k] + x[k];
+        for (int k = 0; k < W; ++k) acc[k] = combine(acc[k], x[k], op);
       }
-      if (do_scale) {
+      if (op == MCR_AVG) {
 #pragma unroll
         for (int k = 0; k < W; ++k) acc[k] = acc[k] * scale;
       }
@@ -48,11 +49,11 @@ __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off
 
 template <int DT>
 __device__ __forceinline__ float reduce_scalar(const CPtrTab& in, size_t i, int P, float scale,
-                                               bool do_scale) {
+                                               int op) {
   using E = Elem<DT>;
   float acc = E::load1(in.p[0], i);
-  for (int p = 1; p < P; ++p) acc = acc + E::load1(in.p[p], i);
-  if (do_scale) acc = acc * scale;
+  for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(in.p[p], i), op);
+  if (op == MCR_AVG) acc = acc * scale;
   return acc;
 }
 

@@ -12,7 +12,7 @@ import os
 from typing import List, Optional, Sequence, Union
 
 F32, BF16 = 0, 1
-SUM, AVG = 0, 1
+SUM, AVG, MAX, MIN, PROD = 0, 1, 2, 3, 4
 AUTO = -1
 MAX_RANKS = 16
 MAX_EXPERTS = 512

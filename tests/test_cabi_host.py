@@ -72,6 +72,7 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, S.SUM, 4, S.AUTO, 0) == S.ESTATE
     assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, 7, S.SUM, 4, S.AUTO, 0) == S.EDTYPE
     assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, 9, 4, S.AUTO, 0) == S.EOP
+    assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, S.PROD, 4, S.AUTO, 0) == S.ESTATE
     assert _status(S.mcr_allreduce, ctx, A16[:4], 1024, S.F32, S.SUM, 0, S.AUTO, 0) == S.EINVAL
     assert _status(S.mcr_allreduce, ctx, A16[:4] + A16, 1024, S.F32, S.SUM, 17, S.AUTO, 0) == S.EINVAL
     assert _status(S.mcr_allreduce, ctx, [A16[0], 0], 1024, S.F32, S.SUM, 2, S.AUTO, 0) == S.EINVAL      # null rank buffer

@@ -327,3 +327,55 @@ def test_alltoallv_device_splits_out_of_bounds_are_skipped():
     assert np.array_equal(o1[:2], host[0].reshape(in_rows, w)[2:4])
     # rank 1's four rows land after rank 0's claimed four; only one fits in the 5-row buffer
     assert np.array_equal(o1[4], host[1].reshape(in_rows, w)[0]) and (o1[2:4] == -1).all()
+
+
+# ------------------------------------------------------------------ other ReduceOps
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("op", [mcr.MAX, mcr.MIN, mcr.PROD])
+def test_max_min_prod(dtype, op):
+    """all_reduce, reduce_scatter, reduce and the fused multi-tensor all_reduce with the other
+    ReduceOps; NaNs, infinities and signed zeros sprinkled into the inputs."""
+    P, b = 5, 2056
+    n = P * b
+    host = _make(P, n, dtype, seed=900 + op, dist="uniform")
+    specials = np.array([0x7FC00000, 0x7F800000, 0xFF800000, 0x00000000, 0x80000000], dtype=np.uint32).view(np.float32)
+    sp = specials if dtype == mcr.F32 else inputs.f32_bits_to_bf16_trunc(specials)
+    g = np.random.Generator(np.random.Philox(key=901))
+    for p in range(P):
+        idx = g.integers(0, n, size=40)
+        host[p][idx] = sp[g.integers(0, len(sp), size=40)]
+    with np.errstate(all="ignore"):
+        exp_ar = [h.copy() for h in host]
+        oracle.allreduce(exp_ar, dtype, op)
+        exp_rs = oracle.reduce_scatter(host, dtype, op)
+        exp_red = [h.copy() for h in host]
+        oracle.reduce(exp_red, dtype, op, 2)
+    for variant in (mcr.AUTO, 0, 2, 6):
+        dev = [gu.to_dev(h) for h in host]
+        mcr.mcr_allreduce(gu.ctx(), dev, n, dtype, op, P, variant)
+        d_in = [gu.to_dev(h) for h in host]
+        d_rs = [gu.dev_empty(b, dtype, 0) for _ in range(P)]
+        mcr.mcr_reduce_scatter(gu.ctx(), d_rs, d_in, n, dtype, op, P, variant)
+        d_red = [gu.to_dev(h) for h in host]
+        mcr.mcr_reduce(gu.ctx(), d_red, n, dtype, op, 2, P, variant)
+        gu.sync()
+        for r in range(P):
+            gu.assert_reduced_equal(gu.to_host(dev[r], gu.NPDT[dtype]), exp_ar[r], dtype, f"allreduce op={op} v={variant}")
+            gu.assert_reduced_equal(gu.to_host(d_rs[r], gu.NPDT[dtype]), exp_rs[r], dtype, f"reduce_scatter op={op} v={variant}")
+            gu.assert_reduced_equal(gu.to_host(d_red[r], gu.NPDT[dtype]), exp_red[r], dtype, f"reduce op={op} v={variant}")
+    # fused multi-tensor path
+    numel = [100, 4096, 37, 9000]
+    plan = mcr.mcr_fuse_plan_create(gu.ctx(), numel, 1 << 30, dtype)
+    try:
+        th = [[inputs.uniform_pm1(m, 902, p, i, bf16=(dtype == mcr.BF16)) for i, m in enumerate(numel)] for p in range(P)]
+        td = [[gu.to_dev(t) for t in th[p]] for p in range(P)]
+        mcr.mcr_fuse_plan_bind(gu.ctx(), plan, [t for p in range(P) for t in td[p]], P)
+        mcr.mcr_allreduce_multi(gu.ctx(), plan, -1, op)
+        gu.sync()
+        for i in range(len(numel)):
+            e = [th[p][i].copy() for p in range(P)]
+            oracle.allreduce(e, dtype, op)
+            for p in range(P):
+                gu.assert_reduced_equal(gu.to_host(td[p][i], gu.NPDT[dtype]), e[p], dtype, f"multi op={op} t={i}")
+    finally:
+        mcr.mcr_fuse_plan_destroy(plan)
