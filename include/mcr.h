@@ -308,6 +308,20 @@ int mcr_allreduce_multi(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, mcr
 
 int mcr_fuse_plan_destroy(mcr_fuse_plan* plan);
 
+/* ---- diagnostic: what the dispatch layer costs (paper Sec. V-B compares the runtime with a
+ * C-level micro-benchmark of the same operation and reports 5 % overhead for small, 1 % for
+ * large messages).  Runs `iters` back-to-back all_to_all_single operations on `stream` twice:
+ * through mcr_alltoall with MCR_AUTO (validation, table lookup, pointer-table marshalling,
+ * launch) and as bare launches of the kernel that call resolves to, each followed by one
+ * stream synchronisation; reports the best of three rounds as microseconds per operation:
+ * us_auto / us_direct from the first call to the end of the synchronisation (what an
+ * application sees), host_us_auto / host_us_direct (either may be NULL) up to the return of
+ * the last enqueueing call (the CPU cost per call, exact while the hardware queue has room).
+ * Arguments as for mcr_alltoall; the buffers are overwritten. */
+int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
+                          mcr_dtype dtype, int P, int iters, void* stream, double* us_auto,
+                          double* us_direct, double* host_us_auto, double* host_us_direct);
+
 /* ---- static tuning table (paper Sec. IV-E, Table II) ---------------------------
  * One table per (op, dtype, P): rows (message bytes -> variant), kept sorted by
  * size.  Lookup takes the row with the largest size not above the message; a

@@ -12,7 +12,7 @@
 namespace mcr {
 namespace {
 
-template <int DT, int P, int U, bool NTL, bool NTS>
+template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
 __global__ void __launch_bounds__(kBlock)
 allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root) {
   using E = Elem<DT>;
@@ -24,8 +24,8 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int r
   if (tile < nvec) {
     u32x4 out[U];
     const bool full = tile + kTile <= nvec;
-    if (full) reduce_tile<DT, P, U, NTL, true>(in, 0, tile, nvec, scale, op, out);
-    else reduce_tile<DT, P, U, NTL, false>(in, 0, tile, nvec, scale, op, out);
+    if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, 0, tile, nvec, scale, op, out);
+    else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, 0, tile, nvec, scale, op, out);
 #pragma unroll
     for (int p = 0; p < P; ++p) {
 #pragma unroll
@@ -78,11 +78,18 @@ int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int 
   const unsigned gx = grid_x(nvec, variant);
   return dispatch_dtype(dtype, [&](auto dt) {
     return dispatch_ranks(P, [&](auto pp) {
+      constexpr int DT = decltype(dt)::value;
+      constexpr int kP = decltype(pp)::value;
+      if (op > MCR_AVG) {
+        return dispatch_unroll(variant, [&](auto uu) {
+          hipLaunchKernelGGL((allreduce_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx), dim3(kBlock), 0,
+                             stream, bufs, nvec, count, scale, op, root);
+          return launch_status();
+        });
+      }
       return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
-        constexpr int DT = decltype(dt)::value;
-        constexpr int kP = decltype(pp)::value;
         constexpr int U = decltype(uu)::value;
-        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value>),
+        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
                            dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root);
         return launch_status();
       });

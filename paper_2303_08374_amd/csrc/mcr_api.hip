@@ -2,6 +2,7 @@
 // tuning table, the paper's "auto" backend of Sec. IV-A / IV-E), fusion plans,
 // and the tuning table itself.  No kernel lives here.
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -733,6 +734,58 @@ int mcr_fuse_plan_destroy(mcr_fuse_plan* plan) {
   if (plan->ctx && plan->ctx->device >= 0) (void)hipSetDevice(plan->ctx->device);
   plan_free_device(plan);
   delete plan;
+  return MCR_OK;
+}
+
+// ---- dispatch overhead (paper Sec. V-B: the runtime's overhead over a C-level benchmark) ------
+int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype, int P,
+                          int iters, void* stream, double* us_auto, double* us_direct, double* host_us_auto,
+                          double* host_us_direct) {
+  if (!ctx || !us_auto || !us_direct || iters < 1) return MCR_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // the full entry point once: validates everything and warms the kernel up
+  int rc = mcr_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, stream);
+  if (rc != MCR_OK) return rc;
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  fill_tab(to, out, P, dtype, count > 0, &all16);
+  fill_tab(ti, in, P, dtype, count > 0, &all16);
+  int v;
+  rc = resolve_variant(ctx, MCR_OP_ALLTOALL, dtype, P, count * elem_bytes(dtype),
+                       all16 && ((count / P) % per_vec(dtype) == 0), MCR_AUTO, &v);
+  if (rc != MCR_OK) return rc;
+  if (hipStreamSynchronize(st) != hipSuccess) return MCR_EHIP;
+  typedef std::chrono::steady_clock clk;
+  auto us = [](clk::time_point a, clk::time_point b, int n) {
+    return std::chrono::duration<double, std::micro>(b - a).count() / n;
+  };
+  double best_auto = 1e30, best_direct = 1e30, host_auto = 1e30, host_direct = 1e30;
+  for (int round = 0; round < 3; ++round) {
+    auto t0 = clk::now();
+    for (int i = 0; i < iters; ++i) {
+      rc = mcr_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, stream);
+      if (rc != MCR_OK) return rc;
+    }
+    auto t0e = clk::now();                                       // everything enqueued
+    if (hipStreamSynchronize(st) != hipSuccess) return MCR_EHIP;
+    auto t1 = clk::now();
+    for (int i = 0; i < iters; ++i) {
+      rc = launch_alltoall(ctx, to, ti, count, dtype, P, v, st);
+      if (rc != MCR_OK) return rc;
+    }
+    auto t1e = clk::now();
+    if (hipStreamSynchronize(st) != hipSuccess) return MCR_EHIP;
+    auto t2 = clk::now();
+    best_auto = std::min(best_auto, us(t0, t1, iters));
+    best_direct = std::min(best_direct, us(t1, t2, iters));
+    host_auto = std::min(host_auto, us(t0, t0e, iters));
+    host_direct = std::min(host_direct, us(t1, t1e, iters));
+  }
+  *us_auto = best_auto;
+  *us_direct = best_direct;
+  if (host_us_auto) *host_us_auto = host_auto;
+  if (host_us_direct) *host_us_direct = host_direct;
   return MCR_OK;
 }
 

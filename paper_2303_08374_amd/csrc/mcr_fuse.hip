@@ -60,7 +60,7 @@ fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
 }
 
 // All-reduce of one chunk of one tensor across the bound ranks, in place.
-template <int DT, int P, bool NTL, bool NTS, bool FORCE_SCALAR>
+template <int DT, int P, bool NTL, bool NTS, bool FORCE_SCALAR, bool GENERIC>
 __global__ void __launch_bounds__(kBlock)
 allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
   using E = Elem<DT>;
@@ -102,7 +102,7 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
           float x[W];
           E::widen(v[u][p], x);
 #pragma unroll
-          for (int k = 0; k < W; ++k) acc[k] = combine(acc[k], x[k], op);
+          for (int k = 0; k < W; ++k) acc[k] = GENERIC ? combine(acc[k], x[k], op) : acc[k] + x[k];
         }
         if (op == MCR_AVG) {
 #pragma unroll
@@ -124,7 +124,7 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
   for (uint64_t e = done + threadIdx.x; e < ne; e += kBlock) {
     float acc = E::load1(base[0], e);
 #pragma unroll
-    for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(base[p], e), op);
+    for (int p = 1; p < P; ++p) acc = GENERIC ? combine(acc, E::load1(base[p], e), op) : acc + E::load1(base[p], e);
     if (op == MCR_AVG) acc = acc * scale;
 #pragma unroll
     for (int p = 0; p < P; ++p) E::store1(base[p], e, acc);
@@ -176,12 +176,19 @@ int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, 
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int DT = decltype(dt)::value;
       constexpr int kP = decltype(pp)::value;
+      if (op > MCR_AVG) {      // the other ReduceOps: one nontemporal shape, or the element path
+        if (variant == SV_SCALAR)
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+        else
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, true, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+        return launch_status();
+      }
       if (variant == SV_SCALAR) {
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
         return launch_status();
       }
       return dispatch_hint(variant, [&](auto ntl, auto nts) {
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false>), dim3(c1 - c0),
+        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false, false>), dim3(c1 - c0),
                            dim3(kBlock), 0, stream, d, c0, scale, op);
         return launch_status();
       });

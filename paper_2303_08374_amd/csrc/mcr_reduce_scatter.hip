@@ -8,7 +8,7 @@ namespace mcr {
 namespace {
 
 // blockIdx.y = destination rank r; slice r of every input is bvec vectors long.
-template <int DT, int P, int U, bool NTL, bool NTS>
+template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
 __global__ void __launch_bounds__(kBlock)
 reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
@@ -19,8 +19,8 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   if (tile >= bvec) return;
   u32x4 res[U];
   const bool full = tile + kTile <= bvec;
-  if (full) reduce_tile<DT, P, U, NTL, true>(in, off, tile, bvec, scale, op, res);
-  else reduce_tile<DT, P, U, NTL, false>(in, off, tile, bvec, scale, op, res);
+  if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, off, tile, bvec, scale, op, res);
+  else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, off, tile, bvec, scale, op, res);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
@@ -60,11 +60,18 @@ int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t
   const unsigned gx = grid_x(bvec, variant);
   return dispatch_dtype(dtype, [&](auto dt) {
     return dispatch_ranks(P, [&](auto pp) {
+      constexpr int DT = decltype(dt)::value;
+      constexpr int kP = decltype(pp)::value;
+      if (op > MCR_AVG) {
+        return dispatch_unroll(variant, [&](auto uu) {
+          hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx, P), dim3(kBlock), 0,
+                             stream, out, in, bvec, scale, op);
+          return launch_status();
+        });
+      }
       return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
-        constexpr int DT = decltype(dt)::value;
-        constexpr int kP = decltype(pp)::value;
         constexpr int U = decltype(uu)::value;
-        hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value>),
+        hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
                            dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, op);
         return launch_status();
       });

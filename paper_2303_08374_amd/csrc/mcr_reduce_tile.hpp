@@ -10,7 +10,9 @@ namespace mcr {
 // All U*P loads are issued before the first add, stream by stream (rank-major):
 // a wavefront then asks each rank buffer for U pieces in a row, which the memory
 // system serves better than a round-robin over the P buffers.
-template <int DT, int P, int U, bool NTL, bool FULL>
+// GENERIC = false is the sum (SUM / AVG), the hot path; GENERIC = true switches on the run-time
+// ReduceOp (MAX / MIN / PROD) and is compiled for fewer launch shapes.
+template <int DT, int P, int U, bool NTL, bool FULL, bool GENERIC>
 __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off, size_t tile,
                                             size_t nvec, float scale, int op,
                                             u32x4 (&out)[U]) {
@@ -36,7 +38,7 @@ __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off
         float x[W];
         E::widen(v[u][p], x);
 #pragma unroll
-        for (int k = 0; k < W; ++k) acc[k] = combine(acc[k], x[k], op);
+        for (int k = 0; k < W; ++k) acc[k] = GENERIC ? combine(acc[k], x[k], op) : acc[k] + x[k];
       }
       if (op == MCR_AVG) {
 #pragma unroll
@@ -55,6 +57,17 @@ __device__ __forceinline__ float reduce_scalar(const CPtrTab& in, size_t i, int 
   for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(in.p[p], i), op);
   if (op == MCR_AVG) acc = acc * scale;
   return acc;
+}
+
+// The launch shapes the generic-op kernels are compiled for: the variant's unroll, nontemporal
+// loads and stores.  f(Int<U>)
+template <class F>
+inline int dispatch_unroll(int variant, F&& f) {
+  switch (shape_unroll(variant)) {
+    case 2: return f(Int<2>{});
+    case 4: return f(Int<4>{});
+  }
+  return f(Int<1>{});
 }
 
 inline unsigned scalar_grid(size_t n) {

@@ -279,6 +279,18 @@ def mcr_fuse_plan_destroy(plan) -> None:
     _check(lib().mcr_fuse_plan_destroy(plan), "mcr_fuse_plan_destroy")
 
 
+# ---- diagnostic ----------------------------------------------------------------------------
+def mcr_dispatch_overhead(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, P: int, iters: int,
+                          stream=None):
+    """Microseconds per op: (through MCR_AUTO, as bare kernel launches, host cost per MCR_AUTO call,
+    host cost per bare launch)."""
+    a, d, ha, hd = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().mcr_dispatch_overhead(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, iters,
+                                       _stream(stream), ctypes.byref(a), ctypes.byref(d), ctypes.byref(ha),
+                                       ctypes.byref(hd)), "mcr_dispatch_overhead")
+    return a.value, d.value, ha.value, hd.value
+
+
 # ---- tuning table --------------------------------------------------------------------------
 def mcr_tune_set(ctx, op_id: int, dtype: int, P: int, nbytes: int, variant: int) -> None:
     _check(lib().mcr_tune_set(ctx, op_id, dtype, P, _sz(nbytes), variant), "mcr_tune_set")

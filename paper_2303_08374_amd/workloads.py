@@ -314,6 +314,21 @@ def small_tensor_path(ctx, reps: int = 5, w: inputs.GradBucketWorkload = inputs.
         mcr.mcr_fuse_plan_destroy(plan)
 
 
+def dispatch_overhead(ctx, P: int = inputs.SWEEP_P) -> Dict:
+    """Cost of the dispatch layer per all_to_all_single operation against bare launches of the same
+    kernel, over message sizes (the paper's overhead-over-OMB figure, Sec. V-B)."""
+    out = {}
+    for M, iters in ((4 << 10, 500), (64 << 10, 500), (1 << 20, 500), (16 << 20, 200), (128 << 20, 30)):
+        src = [torch.empty(M // 4, dtype=torch.float32, device="cuda").uniform_(-1, 1) for _ in range(P)]
+        dst = [torch.empty(M // 4, dtype=torch.float32, device="cuda") for _ in range(P)]
+        a, d, ha, hd = mcr.mcr_dispatch_overhead(ctx, dst, src, M // 4, mcr.F32, P, iters)
+        out[str(M)] = {"auto_us": round(a, 3), "direct_us": round(d, 3), "overhead_pct": round(100.0 * (a - d) / d, 2),
+                       "host_auto_us": round(ha, 3), "host_direct_us": round(hd, 3),
+                       "host_dispatch_cost_us": round(ha - hd, 3)}
+        del src, dst
+    return out
+
+
 def run_all(ctx) -> Dict:
     out = {"allreduce_small": allreduce_small(ctx)}
     torch.cuda.empty_cache()
@@ -324,5 +339,7 @@ def run_all(ctx) -> Dict:
     out["grad_buckets"] = grad_buckets(ctx)
     torch.cuda.empty_cache()
     out["small_tensor_path"] = small_tensor_path(ctx)
+    torch.cuda.empty_cache()
+    out["dispatch_overhead_alltoall"] = dispatch_overhead(ctx)
     torch.cuda.empty_cache()
     return out
