@@ -1,0 +1,155 @@
+"""Parity at the benchmark's full sizes and in the launch configuration bench.py times (MCR_AUTO
+with the shipped tuning table): the op sweep at 64 and 256 MiB per rank and the 1.3 B-parameter
+gradient list.  Whole outputs are too large for the CPU oracle, so windows of the output are
+checked: the inputs of each window are downloaded, the oracle runs on them, and the result must
+match the downloaded output bit for bit.  Windows include the first and last elements, tile and
+super-chunk boundaries, and random places."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2303_08374_amd import inputs, mcr
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+TABLE = os.path.join(ROOT, "paper_2303_08374_amd", "tuning", "mi355x.tbl")
+P = inputs.SWEEP_P
+W = 2048                      # elements per window
+
+
+@pytest.fixture(scope="module")
+def tuned_ctx():
+    c = mcr.mcr_init(0)
+    if os.path.exists(TABLE):
+        mcr.mcr_tune_load(c, TABLE)
+    yield c
+    mcr.mcr_finalize(c)
+
+
+def _fill(n, dtype, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    td = torch.float32 if dtype == mcr.F32 else torch.bfloat16
+    return torch.empty(n, dtype=td, device="cuda").uniform_(-1.0, 1.0, generator=g)
+
+
+def _host(t, s, w, dtype):
+    a = t[s:s + w]
+    if dtype == mcr.BF16:
+        return a.view(torch.int16).cpu().numpy().view(np.uint16).copy()
+    return a.cpu().numpy().copy()
+
+
+def _starts(n, rng, extra=()):
+    """Window starts in [0, n - W]: both ends, boundaries of 4 KiB tiles and of 4/8/16 MiB super-chunks
+    (in elements of either dtype), and random places."""
+    cand = [0, n - W, 1024 - 7, (1 << 20) - W // 2, (2 << 20) - 3, (4 << 20) - 1000, (8 << 20) - 5] + list(extra)
+    cand += [int(x) for x in rng.integers(0, max(n - W, 1), size=12)]
+    return sorted({min(max(c, 0), n - W) for c in cand})
+
+
+@pytest.mark.parametrize("M", [64 << 20, 256 << 20])
+@pytest.mark.parametrize("dtype", [mcr.F32, mcr.BF16])
+def test_sweep_ops_sampled(tuned_ctx, dtype, M):
+    s = gu.EB[dtype]
+    n = M // s
+    b = n // P
+    rng = np.random.Generator(np.random.Philox(key=M + dtype))
+    ins = [_fill(n, dtype, 2000 + p) for p in range(P)]
+
+    # reduce_scatter: out[r][j] = sum_p in[p][r*b + j]
+    outs = [torch.zeros(b, dtype=ins[0].dtype, device="cuda") for _ in range(P)]
+    mcr.mcr_reduce_scatter(tuned_ctx, outs, ins, n, dtype, mcr.SUM, P)
+    gu.sync()
+    for r in (0, 3, P - 1):
+        for st in _starts(b, rng):
+            win = [_host(ins[p], r * b + st, W, dtype) for p in range(P)]
+            oracle.allreduce(win, dtype, oracle.SUM)
+            gu.assert_bits_equal(_host(outs[r], st, W, dtype), win[0], f"reduce_scatter M={M} r={r} at {st}")
+    del outs
+
+    # all_to_all: out[r][p*b + k] = in[p][r*b + k]
+    outs = [torch.zeros(n, dtype=ins[0].dtype, device="cuda") for _ in range(P)]
+    mcr.mcr_alltoall(tuned_ctx, outs, ins, n, dtype, P)
+    gu.sync()
+    for r in (0, 5):
+        for p in (0, 2, P - 1):
+            for st in _starts(b, rng)[::3]:
+                gu.assert_bits_equal(_host(outs[r], p * b + st, W, dtype), _host(ins[p], r * b + st, W, dtype),
+                                     f"alltoall M={M} r={r} p={p} at {st}")
+    del outs
+
+    # all_gather: out[r][p*n + j] = in[p][j]  (P*M per output: 2 GiB each at the top size)
+    outs = [torch.zeros(P * n, dtype=ins[0].dtype, device="cuda") for _ in range(P)]
+    mcr.mcr_allgather(tuned_ctx, outs, ins, n, dtype, P)
+    gu.sync()
+    for r in (0, 6):
+        for p in (0, 3, P - 1):
+            for st in _starts(n, rng)[::2]:
+                gu.assert_bits_equal(_host(outs[r], p * n + st, W, dtype), _host(ins[p], st, W, dtype),
+                                     f"allgather M={M} r={r} p={p} at {st}")
+    del outs
+
+    # all_reduce, in place: download the windows first
+    starts = _starts(n, rng)
+    before = {st: [_host(ins[p], st, W, dtype) for p in range(P)] for st in starts}
+    mcr.mcr_allreduce(tuned_ctx, ins, n, dtype, mcr.SUM, P)
+    gu.sync()
+    for st in starts:
+        exp = before[st]
+        oracle.allreduce(exp, dtype, oracle.SUM)
+        for r in (0, P - 1):
+            gu.assert_bits_equal(_host(ins[r], st, W, dtype), exp[r], f"allreduce M={M} r={r} at {st}")
+    # every rank holds the same bits everywhere (a property that needs no oracle)
+    for r in range(1, P):
+        assert torch.equal(ins[r].view(torch.int16 if dtype == mcr.BF16 else torch.int32),
+                           ins[0].view(torch.int16 if dtype == mcr.BF16 else torch.int32))
+
+
+def test_gradient_buckets_full_size_sampled(tuned_ctx):
+    """292 bf16 tensors, 1,315,819,520 elements per rank, 8 ranks: the fused multi-tensor average,
+    and fuse -> allreduce -> unfuse of the largest and of a mixed bucket."""
+    w = inputs.GradBucketWorkload()
+    numel = w.numel()
+    total = sum(numel)
+    n_t = len(numel)
+    offs = np.concatenate([[0], np.cumsum(numel)[:-1]]).astype(np.int64)
+    arenas = [torch.empty(total, dtype=torch.bfloat16, device="cuda").normal_(0.0, w.std) for _ in range(w.P)]
+    plan = mcr.mcr_fuse_plan_create(tuned_ctx, numel, w.bucket_elems, mcr.BF16)
+    try:
+        bn, tb, to = mcr.mcr_fuse_plan_info(plan, n_t)
+        assert len(bn) == 73
+        mcr.mcr_fuse_plan_bind(tuned_ctx, plan, [arenas[p].data_ptr() + int(offs[i]) * 2 for p in range(w.P) for i in range(n_t)], w.P)
+        rng = np.random.Generator(np.random.Philox(key=77))
+        # windows: every small tensor near its start, and places inside the big ones
+        wins = []
+        for i in list(range(0, n_t, 7)) + [numel.index(max(numel))]:
+            n = numel[i]
+            ww = min(W, n)
+            for st in {0, n - ww, int(rng.integers(0, n - ww + 1))}:
+                wins.append((i, st, ww))
+        before = {k: [_host(arenas[p], int(offs[k[0]]) + k[1], k[2], mcr.BF16) for p in range(w.P)] for k in wins}
+        # fuse of two buckets (checked before anything is reduced)
+        flats = [torch.zeros(max(bn), dtype=torch.bfloat16, device="cuda") for _ in range(w.P)]
+        for k in (tb[numel.index(max(numel))], 5):
+            mcr.mcr_fuse(tuned_ctx, plan, k, flats, w.P)
+            gu.sync()
+            for i in [j for j in range(n_t) if tb[j] == k][:4]:
+                ww = min(W, numel[i])
+                gu.assert_bits_equal(_host(flats[3], to[i], ww, mcr.BF16), _host(arenas[3], int(offs[i]), ww, mcr.BF16), f"fuse t={i}")
+        mcr.mcr_allreduce_multi(tuned_ctx, plan, -1, mcr.AVG)
+        gu.sync()
+        for k in wins:
+            exp = before[k]
+            oracle.allreduce(exp, oracle.BF16, oracle.AVG)
+            for p in (0, w.P - 1):
+                gu.assert_bits_equal(_host(arenas[p], int(offs[k[0]]) + k[1], k[2], mcr.BF16), exp[p], f"allreduce_multi t={k[0]} at {k[1]}")
+        for p in range(1, w.P):
+            assert torch.equal(arenas[p].view(torch.int16), arenas[0].view(torch.int16))
+    finally:
+        mcr.mcr_fuse_plan_destroy(plan)
