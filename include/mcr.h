@@ -326,7 +326,9 @@ int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in,
  * One table per (op, dtype, P): rows (message bytes -> variant), kept sorted by
  * size.  Lookup takes the row with the largest size not above the message; a
  * message below the first row takes the first, above the last the last; no rows
- * gives MCR_EVARIANT from mcr_tune_get (MCR_AUTO then uses its default).
+ * gives MCR_EVARIANT from mcr_tune_get.  MCR_AUTO, finding no table for its rank count,
+ * takes the table of the closest rank count of the same op and dtype, and its built-in
+ * default (one vector per thread below 1 MiB, four above) when there is none at all.
  * "Message bytes" is one rank's send-buffer size: count*elem for allreduce,
  * reduce_scatter, allgather, alltoall; in_rows*row bytes for alltoallv;
  * T*row bytes for pack/unpack; bucket bytes for fuse/unfuse/allreduce_multi. */

@@ -50,10 +50,21 @@ bool fill_tab(Tab& tab, Ptr const* arr, int P, int dtype_for_align, bool need, b
   return true;
 }
 
-// Table lookup: floor-to-row rule.  Returns -1 when there is no table for the key.
-int table_lookup(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes) {
+// Table lookup: floor-to-row rule.  Returns -1 when there is no table for the key.  With
+// nearest_scale, a missing table for this rank count is replaced by the one for the closest rank
+// count of the same op and dtype (the paper notes that trends carry over between similar scales);
+// MCR_AUTO uses that, mcr_tune_get reports the table as it is.
+int table_lookup(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes, bool nearest_scale) {
   std::lock_guard<std::mutex> lock(ctx->mu);
   auto it = ctx->tables.find(TuneKey{op, dtype, P});
+  if ((it == ctx->tables.end() || it->second.empty()) && nearest_scale) {
+    int best_gap = 1 << 30;
+    for (auto jt = ctx->tables.begin(); jt != ctx->tables.end(); ++jt) {
+      if (jt->first.op != op || jt->first.dtype != dtype || jt->second.empty()) continue;
+      const int gap = jt->first.P > P ? jt->first.P - P : P - jt->first.P;
+      if (gap < best_gap) { best_gap = gap; it = jt; }
+    }
+  }
   if (it == ctx->tables.end() || it->second.empty()) return -1;
   const auto& rows = it->second;
   int pick = rows.front().second;
@@ -72,7 +83,7 @@ int default_variant(size_t bytes) { return bytes >= (size_t(1) << 20) ? SV_V4 : 
 int resolve_variant(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes, bool vec_ok, int variant, int* out) {
   if (variant == MCR_AUTO) {
     if (!vec_ok) { *out = SV_SCALAR; return MCR_OK; }
-    int v = table_lookup(ctx, op, dtype, P, bytes);
+    int v = table_lookup(ctx, op, dtype, P, bytes, true);
     if (v < 0 || v >= n_variants(op)) v = default_variant(bytes);
     *out = v;
     return MCR_OK;
@@ -152,10 +163,6 @@ int mcr_init(mcr_ctx** out, int device) {
   mcr_ctx* ctx = new (std::nothrow) mcr_ctx;
   if (!ctx) return MCR_ENOMEM;
   ctx->device = device;
-  int cus = 0;
-  if (device != MCR_NO_DEVICE &&
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
-    ctx->num_cus = cus;
   const char* path = std::getenv("MCR_TUNING_TABLE");
   if (path && *path) (void)mcr_tune_load(ctx, path);   // an unreadable file leaves the table empty
   *out = ctx;
@@ -681,7 +688,6 @@ int mcr_fuse_plan_bind(mcr_ctx* ctx, mcr_fuse_plan* plan, void* const* tensors, 
   }
   if (n > 0 && hipMemcpy(plan->d_ptrs, tensors, n * P * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)
     return MCR_EHIP;
-  plan->h_ptrs.assign(tensors, tensors + n * P);
   plan->bound_P = P;
   return MCR_OK;
 }
@@ -808,7 +814,7 @@ int mcr_tune_get(mcr_ctx* ctx, int op_id, mcr_dtype dtype, int P, size_t bytes, 
   if (!ctx || !variant || !valid_P(P)) return MCR_EINVAL;
   if (op_id < 0 || op_id >= MCR_OP_COUNT) return MCR_EOP;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  const int v = table_lookup(ctx, op_id, dtype, P, bytes);
+  const int v = table_lookup(ctx, op_id, dtype, P, bytes, false);
   if (v < 0) return MCR_EVARIANT;
   *variant = v;
   return MCR_OK;

@@ -45,7 +45,6 @@ struct TuneKey {
 
 struct mcr_ctx {
   int device = 0;
-  int num_cus = 256;
   std::mutex mu;                                                      // guards `tables`
   std::map<mcr::TuneKey, std::vector<std::pair<size_t, int>>> tables; // sorted by bytes
 };
@@ -69,7 +68,6 @@ struct mcr_fuse_plan {
   void** d_ptrs = nullptr;                  // bound_P * n_tensors, rank-major
   int bound_P = 0;
   int alloc_P = 0;
-  std::vector<void*> h_ptrs;                // host copy of the bound table (alignment checks)
 };
 
 namespace mcr {

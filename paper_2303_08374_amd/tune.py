@@ -3,7 +3,7 @@ op over the message-size sweep, picks the variant with the least time per (op, d
 size) and writes the static tuning table that MCR_AUTO consults.
 
     python -m paper_2303_08374_amd.tune [--out paper_2303_08374_amd/tuning/mi355x.tbl]
-                                        [--report gpurun_out/tune_report.json]
+                                        [--report tune_report.json] [--ranks 4,8,16]
 
 One table cell = one batch of identical launches on one stream over cold buffers, mean time
 per launch.  Ties go to the lower variant id.  Besides the per-size ("fine", the paper's
@@ -82,15 +82,33 @@ def tune_workload_ops(ctx, verbose: bool = True):
     return report
 
 
-def run(out_path: str, report_path: str | None, P: int, max_bytes: int, arena_gib: float, verbose: bool = True):
+def run(out_path: str, report_path: str | None, scales, max_bytes: int, arena_gib: float, verbose: bool = True):
+    """`scales`: the rank counts (world sizes) to tune the swept collectives for; the table is keyed by
+    scale first, then by message size."""
     ctx = mcr.mcr_init(0)
     mcr.mcr_tune_clear(ctx)
     sizes = [m for m in inputs.SWEEP_BYTES if m <= max_bytes]
+    names = mcr.mcr_get_variants(ctx, mcr.OP_ALLGATHER)                  # the longest list; a prefix serves the others
+    report = {"scales": list(scales), "variants": names, "cells": {}, "coarse_vs_fine": {}}
+    for P in scales:
+        _tune_sweep(ctx, P, sizes, arena_gib, names, report, verbose)
+    report["workload_ops"] = tune_workload_ops(ctx, verbose)
+    os.makedirs(os.path.dirname(out_path) or ".", exist_ok=True)
+    mcr.mcr_tune_save(ctx, out_path)
+    if report_path:
+        os.makedirs(os.path.dirname(report_path) or ".", exist_ok=True)
+        with open(report_path, "w") as f:
+            json.dump(report, f, indent=1)
+    n = mcr.mcr_tune_count(ctx)
+    mcr.mcr_finalize(ctx)
+    return n, report
+
+
+def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbose: bool):
     cells = sweep.make_cells(P, inputs.SWEEP_OPS, inputs.SWEEP_DTYPES, sizes)
     need = max(c.footprint for c in cells)
     arena = sweep.Arena(max(int(arena_gib * (1 << 30)), need + (1 << 20)))
-    names = mcr.mcr_get_variants(ctx, mcr.OP_ALLGATHER)                  # the longest list; a prefix serves the others
-    report = {"P": P, "variants": names, "cells": {}}
+    report = {"cells": {}}
     for cell in cells:
         n_var = len(mcr.mcr_get_variants(ctx, sweep.OPS[cell.op]))
         variants = list(range(1, n_var))             # the 128-bit variants; scalar is only the fallback
@@ -111,7 +129,7 @@ def run(out_path: str, report_path: str | None, P: int, max_bytes: int, arena_gi
             "GBps": {names[v]: round(cell.alg_bytes / (times[v] * 1e-3) / 1e9, 1) for v in variants},
         }
         if verbose:
-            print(f"{cell.key:34s} best={names[best]:6s} {times[best]*1e3:10.2f} us "
+            print(f"P={P:2d} {cell.key:34s} best={names[best]:6s} {times[best]*1e3:10.2f} us "
                   f"{cell.alg_bytes / (times[best] * 1e-3) / 1e9:8.1f} GB/s", flush=True)
     # coarse (one variant per op and dtype) versus fine (one per size)
     coarse = {}
@@ -124,31 +142,26 @@ def run(out_path: str, report_path: str | None, P: int, max_bytes: int, arena_gi
             bv = min(variants, key=lambda v: (tot[v], v))
             coarse[f"{op}/{dt}"] = {"variant": names[bv], "sum_us": round(tot[bv], 2), "fine_sum_us": round(fine, 2),
                                     "fine_gain": round(tot[bv] / fine, 4)}
-    report["coarse_vs_fine"] = coarse
-    report["workload_ops"] = tune_workload_ops(ctx, verbose)
-    os.makedirs(os.path.dirname(out_path), exist_ok=True)
-    mcr.mcr_tune_save(ctx, out_path)
-    if report_path:
-        os.makedirs(os.path.dirname(report_path) or ".", exist_ok=True)
-        with open(report_path, "w") as f:
-            json.dump(report, f, indent=1)
-    n = mcr.mcr_tune_count(ctx)
-    mcr.mcr_finalize(ctx)
-    return n, report
+    for k, v in report["cells"].items():
+        full_report["cells"][f"P{P}/{k}"] = v
+    for k, v in coarse.items():
+        full_report["coarse_vs_fine"][f"P{P}/{k}"] = v
+    del arena
+    torch.cuda.empty_cache()
 
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=DEFAULT_TABLE)
     ap.add_argument("--report", default=None)
-    ap.add_argument("--ranks", type=int, default=inputs.SWEEP_P)
+    ap.add_argument("--ranks", default="4,8,16", help="rank counts to tune the swept collectives for")
     ap.add_argument("--max-bytes", type=int, default=inputs.SWEEP_BYTES[-1])
     ap.add_argument("--arena-gib", type=float, default=4.0)
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("the tuning suite needs a GPU", file=sys.stderr)
         return 2
-    n, _ = run(a.out, a.report, a.ranks, a.max_bytes, a.arena_gib)
+    n, _ = run(a.out, a.report, [int(x) for x in a.ranks.split(",")], a.max_bytes, a.arena_gib)
     print(f"wrote {n} rows to {a.out}")
     return 0
 

@@ -172,6 +172,25 @@ def test_tuning_table_reproduces_table2(ctx, tmp_path):
     assert mcr.mcr_tune_count(ctx) == 0
 
 
+def test_auto_falls_back_to_the_nearest_scale(ctx):
+    """A table exists for P=8 only: mcr_tune_get reports nothing for other rank counts, MCR_AUTO borrows
+    the closest scale's table, and with no table at all takes the built-in default."""
+    mcr.mcr_tune_clear(ctx)
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 4, 64 << 20) == 3            # default: v4 above 1 MiB
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 4, 4096) == 1                # default: v1 below
+    mcr.mcr_tune_set(ctx, mcr.OP_ALLTOALL, mcr.F32, 8, 4096, 2)
+    mcr.mcr_tune_set(ctx, mcr.OP_ALLTOALL, mcr.F32, 8, 1 << 20, 4)
+    mcr.mcr_tune_set(ctx, mcr.OP_ALLTOALL, mcr.F32, 2, 4096, 7)
+    assert _status(mcr.mcr_tune_get, ctx, mcr.OP_ALLTOALL, mcr.F32, 4, 4096) == mcr.EVARIANT
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 8, 64 << 20) == 4
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 16, 64 << 20) == 4           # nearest scale is 8
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 6, 8192) == 2                # 6 is closer to 8 than to 2
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 3, 8192) == 7                # 3 is closer to 2
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.BF16, 8, 8192) == 1               # other dtype: no table, default
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 8, 8192, False) == 0         # shape rules the vectors out
+    mcr.mcr_tune_clear(ctx)
+
+
 def test_shipped_tuning_table_is_well_formed(ctx):
     """The table measured on MI355X that ships with the package loads, and holds a row for
     every (op, dtype, size) cell of the sweep at P=8."""
