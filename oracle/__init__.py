@@ -201,6 +201,50 @@ def moe_route(ids: np.ndarray, E: int, P: int, C: int):
     return slot, counts, srow
 
 
+def moe_expert_layout(counts: np.ndarray):
+    """counts [P, E] int32 -> (block_first [P, E], expert_first [E], expert_rows [E]) int64."""
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    P, E = counts.shape
+    bf = np.zeros((P, E), dtype=np.int64)
+    ef = np.zeros(E, dtype=np.int64)
+    er = np.zeros(E, dtype=np.int64)
+    _check(lib().orc_moe_expert_layout(_p(counts), E, P, _p(bf), _p(ef), _p(er)), "moe_expert_layout")
+    return bf, ef, er
+
+
+def _i32_ptrs(arrs):
+    keep = [np.ascontiguousarray(a, dtype=np.int32) for a in arrs]
+    return keep, _ptrs(keep)
+
+
+def moe_dispatch_by_expert(recv: List[np.ndarray], toks: List[np.ndarray], ids, slots, counts: np.ndarray, row_elems: int,
+                           dtype: int) -> None:
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    P, E = counts.shape
+    k1, pi = _i32_ptrs(ids)
+    k2, ps = _i32_ptrs(slots)
+    _check(lib().orc_moe_dispatch_by_expert(_ptrs(recv), _ptrs(toks), pi, ps, _p(counts), ctypes.c_int64(k1[0].size), E, P,
+                                            ctypes.c_size_t(row_elems), dtype), "moe_dispatch_by_expert")
+
+
+def moe_combine_by_expert(expert_out: List[np.ndarray], ids, slots, gates, counts: np.ndarray, row_elems: int,
+                          dtype: int) -> List[np.ndarray]:
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    P, E = counts.shape
+    k1, pi = _i32_ptrs(ids)
+    k2, ps = _i32_ptrs(slots)
+    T = k1[0].size
+    outs = [np.empty(T * row_elems, dtype=np_dtype(dtype)) for _ in range(P)]
+    if gates is None:
+        pg = None
+    else:
+        kg = [np.ascontiguousarray(g, dtype=np.float32) for g in gates]
+        pg = _ptrs(kg)
+    _check(lib().orc_moe_combine_by_expert(_ptrs(outs), _ptrs(expert_out), pi, ps, pg, _p(counts), ctypes.c_int64(T), E, P,
+                                           ctypes.c_size_t(row_elems), dtype), "moe_combine_by_expert")
+    return outs
+
+
 def pack(tok: np.ndarray, slot: np.ndarray, row_elems: int, dtype: int, out: np.ndarray) -> np.ndarray:
     slot = np.ascontiguousarray(slot, dtype=np.int32)
     _check(lib().orc_pack(_p(out), _p(tok), _p(slot), ctypes.c_int64(slot.size),

@@ -343,6 +343,94 @@ int orc_moe_route(const int32_t* ids, int T, int E, int P, int C, int32_t* slot,
   return 0;
 }
 
+// ---- expert-major receive layout (the other half of MoE dispatch: the expert FFN wants all
+// the tokens of one expert in one block) ------------------------------------------------------
+// counts[p*E + e] = kept tokens of source rank p for expert e (as orc_moe_route gives them).
+// At the rank that owns expert e (rank e / (E/P)) the receive buffer is ordered by
+// (local expert, source rank, token order within the source):
+//   expert_rows[e]  = sum_p counts[p][e]
+//   expert_first[e] = sum of expert_rows over the experts of the same rank before e
+//   block_first[p*E + e] = expert_first[e] + sum_{q<p} counts[q][e]     (first row of (p, e))
+int orc_moe_expert_layout(const int32_t* counts, int E, int P, int64_t* block_first, int64_t* expert_first,
+                          int64_t* expert_rows) {
+  if (!counts || !block_first || !expert_first || !expert_rows || E < 1 || P < 1 || E % P != 0) return -1;
+  const int per_rank = E / P;
+  for (int e = 0; e < E; ++e) {
+    int64_t rows = 0;
+    for (int p = 0; p < P; ++p) rows += counts[p * E + e];
+    expert_rows[e] = rows;
+  }
+  for (int e = 0; e < E; ++e) {
+    int64_t first = 0;
+    for (int e2 = (e / per_rank) * per_rank; e2 < e; ++e2) first += expert_rows[e2];
+    expert_first[e] = first;
+    int64_t above = 0;
+    for (int p = 0; p < P; ++p) {
+      block_first[p * E + e] = first + above;
+      above += counts[p * E + e];
+    }
+  }
+  return 0;
+}
+
+// Dispatch into that layout: the k-th kept token (in token order) of source p for expert e goes
+// to row block_first[p][e] + k of the receive buffer of rank e / (E/P).  A token is kept when its
+// slot is >= 0.  Rows of recv that receive nothing are left untouched.
+int orc_moe_dispatch_by_expert(void* const* recv, const void* const* tok, const int32_t* const* ids,
+                               const int32_t* const* slot, const int32_t* counts, int64_t T, int E, int P,
+                               size_t row_elems, int dtype) {
+  if (!recv || !tok || !ids || !slot || !counts || T < 0 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype)) return -1;
+  std::vector<int64_t> block_first(static_cast<size_t>(P) * E), ef(E), er(E);
+  if (orc_moe_expert_layout(counts, E, P, block_first.data(), ef.data(), er.data()) != 0) return -1;
+  const size_t rb = row_elems * elem_bytes(dtype);
+  const int per_rank = E / P;
+  for (int p = 0; p < P; ++p) {
+    std::vector<int64_t> seen(static_cast<size_t>(E), 0);
+    for (int64_t t = 0; t < T; ++t) {
+      if (slot[p][t] < 0) continue;
+      const int e = ids[p][t];
+      const int64_t row = block_first[static_cast<size_t>(p) * E + e] + seen[e];
+      seen[e] += 1;
+      std::memcpy(static_cast<char*>(recv[e / per_rank]) + static_cast<size_t>(row) * rb,
+                  static_cast<const char*>(tok[p]) + static_cast<size_t>(t) * rb, rb);
+    }
+  }
+  return 0;
+}
+
+// Combine out of that layout: out[p][t] = round(gate[p][t] * f32(expert_out row of token t)), +0 for
+// a dropped token; gate == nullptr copies.
+int orc_moe_combine_by_expert(void* const* out, const void* const* expert_out, const int32_t* const* ids,
+                              const int32_t* const* slot, const float* const* gate, const int32_t* counts, int64_t T,
+                              int E, int P, size_t row_elems, int dtype) {
+  if (!out || !expert_out || !ids || !slot || !counts || T < 0 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype)) return -1;
+  std::vector<int64_t> block_first(static_cast<size_t>(P) * E), ef(E), er(E);
+  if (orc_moe_expert_layout(counts, E, P, block_first.data(), ef.data(), er.data()) != 0) return -1;
+  const size_t rb = row_elems * elem_bytes(dtype);
+  const int per_rank = E / P;
+  for (int p = 0; p < P; ++p) {
+    std::vector<int64_t> seen(static_cast<size_t>(E), 0);
+    for (int64_t t = 0; t < T; ++t) {
+      char* dst = static_cast<char*>(out[p]) + static_cast<size_t>(t) * rb;
+      if (slot[p][t] < 0) {
+        std::memset(dst, 0, rb);
+        continue;
+      }
+      const int e = ids[p][t];
+      const int64_t row = block_first[static_cast<size_t>(p) * E + e] + seen[e];
+      seen[e] += 1;
+      const char* src = static_cast<const char*>(expert_out[e / per_rank]) + static_cast<size_t>(row) * rb;
+      if (!gate) {
+        std::memcpy(dst, src, rb);
+      } else {
+        const float g = gate[p][t];
+        for (size_t c = 0; c < row_elems; ++c) store_elem(dst, c, dtype, g * load_elem(src, c, dtype));
+      }
+    }
+  }
+  return 0;
+}
+
 // ---- pack / unpack / gate-weighted combine ------------------------------------
 // pack:   Packed[slot[t]][:] = Tok[t][:] for kept t (slot >= 0).
 int orc_pack(void* out, const void* in, const int32_t* slot, int64_t T, size_t row_elems,

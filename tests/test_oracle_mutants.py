@@ -44,6 +44,9 @@ MUTANTS = [
     ("route_base_inclusive", "base[static_cast<size_t>(e)] = run;\n    run += c;", "run += c;\n    base[static_cast<size_t>(e)] = run;"),
     ("route_counts_unclamped", "const int64_t c = seen[static_cast<size_t>(e)] < C ? seen[static_cast<size_t>(e)] : C;", "const int64_t c = seen[static_cast<size_t>(e)];"),
     ("route_rank_map_strided", "for (int e = r * per_rank; e < (r + 1) * per_rank; ++e) s += counts[e];", "for (int e = r; e < E; e += P) s += counts[e];"),
+    ("layout_first_not_reset_per_rank", "for (int e2 = (e / per_rank) * per_rank; e2 < e; ++e2) first += expert_rows[e2];", "for (int e2 = 0; e2 < e; ++e2) first += expert_rows[e2];"),
+    ("layout_sources_not_stacked", "      block_first[p * E + e] = first + above;\n      above += counts[p * E + e];", "      block_first[p * E + e] = first + above;"),
+    ("by_expert_wrong_rank", "      std::memcpy(static_cast<char*>(recv[e / per_rank]) + static_cast<size_t>(row) * rb,", "      std::memcpy(static_cast<char*>(recv[e % P]) + static_cast<size_t>(row) * rb,"),
     ("unpack_dropped_not_zeroed", "std::memset(dst, 0, rb);\n      continue;", "continue;"),
     ("unpack_gate_of_slot", "const float g = gate[t];", "const float g = gate[slot[t]];"),
     ("pack_gathers_instead", "std::memcpy(static_cast<char*>(out) + static_cast<size_t>(slot[t]) * rb,\n                static_cast<const char*>(in) + static_cast<size_t>(t) * rb, rb);",

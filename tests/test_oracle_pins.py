@@ -410,6 +410,62 @@ def check_route_out_of_range_ids():
     assert slot.tolist() == [0, -1, 2, -1, 1, 3] and cnt.tolist() == [2, 2] and srow.tolist() == [2, 2]
 
 
+# ============================ expert-major receive layout =======================
+def check_expert_layout_golden():
+    g = gio.keyed_ints("moe_expert_layout_case.txt")
+    E, P = g["E"][0], g["P"][0]
+    bf, ef, er = oracle.moe_expert_layout(np.array(g["counts"], dtype=np.int32).reshape(P, E))
+    assert er.tolist() == g["expert_rows"] and ef.tolist() == g["expert_first"] and bf.reshape(-1).tolist() == g["block_first"]
+
+
+def check_dispatch_by_expert_is_a_stable_regroup():
+    """The expert-major receive buffer holds the rows of the source-major one (pack + all_to_allv),
+    stably re-sorted by local expert; every expert's rows form one block of expert_rows[e] rows."""
+    for w, permute in ((inputs.MoEWorkload(P=4, T=300, H=4, E=8), False), (inputs.MoEWorkload(P=2, T=77, H=3, E=6, capacity_factor=0.6), True),
+                       (inputs.MoEWorkload(P=1, T=40, H=2, E=3), False)):
+        P, T, H, E = w.P, w.T, w.H, w.E
+        ids = [w.ids(p, permute) for p in range(P)]
+        routes = [oracle.moe_route(ids[p], E, P, w.C) for p in range(P)]
+        slots = [r[0] for r in routes]
+        counts = np.stack([r[1] for r in routes])
+        S = np.stack([r[2] for r in routes])
+        # payload: float(p * 2^16 + t) in column 0, the expert id in column 1
+        toks = []
+        for p in range(P):
+            v = np.zeros((T, H), dtype=np.float32)
+            v[:, 0] = p * 65536 + np.arange(T)
+            v[:, 1] = ids[p]
+            toks.append(v.reshape(-1))
+        # source-major reference through the already pinned chain
+        packed = []
+        for p in range(P):
+            buf = np.zeros(int(S[p].sum()) * H, dtype=np.float32)
+            oracle.pack(toks[p], slots[p], H, F32, buf)
+            packed.append(buf)
+        src_major = oracle.alltoallv(packed, S, H, F32)
+        bf, ef, er = oracle.moe_expert_layout(counts)
+        assert np.array_equal(er, counts.sum(axis=0))
+        recv = [np.full(int(S[:, r].sum()) * H, -1.0, dtype=np.float32) for r in range(P)]
+        oracle.moe_dispatch_by_expert(recv, toks, ids, slots, counts, H, F32)
+        per = E // P
+        for r in range(P):
+            a = src_major[r].reshape(-1, H)
+            b = recv[r].reshape(-1, H)
+            order = np.argsort(a[:, 1], kind="stable")            # numpy's stable sort by expert id
+            assert np.array_equal(b, a[order])
+            for e in range(r * per, (r + 1) * per):
+                blk = b[ef[e]: ef[e] + er[e]]
+                assert (blk[:, 1] == e).all()
+        # combine with gate 1 returns the kept tokens, zeros elsewhere; gate 2^-1 halves them exactly
+        back = oracle.moe_combine_by_expert(recv, ids, slots, None, counts, H, F32)
+        half = oracle.moe_combine_by_expert(recv, ids, slots, [np.full(T, 0.5, dtype=np.float32)] * P, counts, H, F32)
+        for p in range(P):
+            kept = slots[p] >= 0
+            exp = np.where(kept[:, None], toks[p].reshape(T, H), 0)
+            assert np.array_equal(back[p].reshape(T, H), exp)
+            assert np.array_equal(half[p].reshape(T, H), exp * np.float32(0.5))
+
+
 # ============================ pack / unpack / combine ==========================
 def check_pack_unpack_identity():
     for dtype, w in ((F32, 5), (BF16, 8)):
