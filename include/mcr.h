@@ -254,6 +254,43 @@ int mcr_moe_combine(mcr_ctx* ctx, void* const* out, const void* const* expert_ou
                     size_t T, size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant,
                     void* stream);
 
+/* ---- expert-major receive layout ---------------------------------------------------
+ * The expert FFN that follows the dispatch Alltoall of paper Sec. II-C works on the tokens of
+ * one expert at a time.  The calls below deliver every expert's tokens as one block:
+ * the receive buffer of rank r is ordered by (local expert, source rank, token order).
+ *
+ * mcr_moe_expert_layout: from counts[p][e] (kept tokens per source rank and expert, as
+ * mcr_moe_route leaves them; negative entries count as 0), with per = E/P:
+ *   expert_rows[e]  = sum_p counts[p][e]
+ *   expert_first[e] = sum of expert_rows[e'] for per*(e/per) <= e' < e
+ *   row_table[p*E + e] = expert_first[e] + sum_{q<p} counts[q][e] - sum_{e'<e} counts[p][e']
+ * so that token t of rank p (kept, expert id) lands in row row_table[p*E + id] + slot[p][t]
+ * of rank id/per.  counts: host array of P device pointers (E int32 each); row_table,
+ * expert_first, expert_rows: DEVICE memory, 8-byte aligned, P*E, E and E int64, overwritten.
+ * One small launch; nothing is synchronised. */
+int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int P,
+                          int64_t* row_table, int64_t* expert_first, int64_t* expert_rows,
+                          void* stream);
+
+/* mcr_moe_dispatch_by_expert: for every rank p and token t with slot[p][t] >= 0 and
+ * 0 <= expert_ids[p][t] < E, the token row is written to row
+ * row_table[p*E + id] + slot[p][t] of recv[id / (E/P)]; a row outside [0, recv_rows) is
+ * skipped, other rows of recv are left untouched.  expert_ids, slot: as for
+ * mcr_moe_route; row_table: DEVICE memory as mcr_moe_expert_layout writes it. */
+int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* const* tokens,
+                               const int32_t* const* expert_ids, const int32_t* const* slot,
+                               const int64_t* row_table, size_t T, int E, size_t recv_rows,
+                               size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream);
+
+/* mcr_moe_combine_by_expert: the way back.  out[p] row t = round_to_dtype(gate[p][t] *
+ * f32(expert_out[id/(E/P)] row row_table[p*E + id] + slot[p][t])), all-zero bits for a token
+ * that was not dispatched.  gate may be NULL (rows are copied). */
+int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const* expert_out,
+                              const int32_t* const* expert_ids, const int32_t* const* slot,
+                              const float* const* gate, const int64_t* row_table, size_t T, int E,
+                              size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P,
+                              int variant, void* stream);
+
 /* mcr_dlrm_shuffle: the embedding shuffle of paper Sec. II-D as one row permutation.
  * n_tables tables, table t on rank t mod P as its local table t div P.
  *   backward == 0: in[p] is [T_p][batch][dim] (table-major pooled rows), out[r] is

@@ -532,6 +532,69 @@ int mcr_moe_combine(mcr_ctx* ctx, void* const* out, const void* const* expert_ou
                             static_cast<hipStream_t>(stream));
 }
 
+int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int P, int64_t* row_table,
+                          int64_t* expert_first, int64_t* expert_rows, void* stream) {
+  if (!ctx || !counts || !row_table || !expert_first || !expert_rows || !valid_P(P)) return MCR_EINVAL;
+  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0) return MCR_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(row_table) | reinterpret_cast<uintptr_t>(expert_first) |
+       reinterpret_cast<uintptr_t>(expert_rows)) & 7u)
+    return MCR_EINVAL;
+  CPtrTab tc;
+  if (!fill_tab(tc, counts, P, MCR_F32, true, nullptr)) return MCR_EINVAL;
+  int rc;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_moe_expert_layout(ctx, tc, E, P, row_table, expert_first, expert_rows, static_cast<hipStream_t>(stream));
+}
+
+int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* const* tokens, const int32_t* const* expert_ids,
+                               const int32_t* const* slot, const int64_t* row_table, size_t T, int E, size_t recv_rows,
+                               size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !recv || !tokens || !expert_ids || !slot || !row_table || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0) return MCR_EINVAL;
+  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull || (reinterpret_cast<uintptr_t>(row_table) & 7u)) return MCR_EINVAL;
+  const bool any = T > 0 && row_elems > 0 && recv_rows > 0;
+  PtrTab to;
+  CPtrTab ti, tid, tsl;
+  bool all16 = true;
+  if (!fill_tab(to, recv, P, dtype, any, &all16) || !fill_tab(ti, tokens, P, dtype, any, &all16) ||
+      !fill_tab(tid, expert_ids, P, MCR_F32, any, nullptr) || !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
+    return MCR_EINVAL;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_MOE_DISPATCH, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_moe_dispatch_by_expert(ctx, to, ti, tid, tsl, row_table, E, T, recv_rows, row_bytes,
+                                       static_cast<int>(elem_bytes(dtype)), P, v, static_cast<hipStream_t>(stream));
+}
+
+int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const* expert_out, const int32_t* const* expert_ids,
+                              const int32_t* const* slot, const float* const* gate, const int64_t* row_table, size_t T, int E,
+                              size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !out || !expert_out || !expert_ids || !slot || !row_table || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0) return MCR_EINVAL;
+  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull || (reinterpret_cast<uintptr_t>(row_table) & 7u)) return MCR_EINVAL;
+  const bool any = T > 0 && row_elems > 0;
+  PtrTab to;
+  CPtrTab ti, tid, tsl, tg;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, expert_out, P, dtype, any && recv_rows > 0, &all16) ||
+      !fill_tab(tid, expert_ids, P, MCR_F32, any, nullptr) || !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
+    return MCR_EINVAL;
+  if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
+  const size_t row_bytes = row_elems * elem_bytes(dtype);
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_MOE_COMBINE, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (!any) return MCR_OK;
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_moe_combine_by_expert(ctx, to, ti, tid, tsl, gate ? &tg : nullptr, row_table, E, T, recv_rows, row_elems, dtype,
+                                      P, v, static_cast<hipStream_t>(stream));
+}
+
 int mcr_dlrm_shuffle(mcr_ctx* ctx, void* const* out, const void* const* in, int n_tables, size_t batch, size_t dim,
                      mcr_dtype dtype, int P, int backward, int variant, void* stream) {
   if (!ctx || !out || !in || !valid_P(P) || n_tables < 0) return MCR_EINVAL;

@@ -211,6 +211,210 @@ moe_combine_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gat
   }
 }
 
+// ---- expert-major receive layout -------------------------------------------------------
+// The expert FFN wants the tokens of one expert in one block.  The receive buffer of a rank is
+// then ordered by (local expert, source rank, token order), and since the packed order of a
+// sender is ordered by expert, row(p, t) = row_table[p][id] + slot[p][t] with
+//   row_table[p][e] = first row of block (p, e) - (rows sender p packs before expert e).
+
+// Exclusive prefix sum of one value per thread over a workgroup of kLayoutBlock threads.
+constexpr int kLayoutBlock = 512;   // >= MCR_MAX_EXPERTS: thread e owns expert e
+__device__ __forceinline__ long long block_exclusive_scan(long long v, long long* wave_total) {
+  const unsigned lane = __lane_id();
+  const unsigned w = threadIdx.x / kWave;
+  long long incl = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const long long up = __shfl_up(incl, d);
+    if (lane >= static_cast<unsigned>(d)) incl += up;
+  }
+  if (lane == kWave - 1) wave_total[w] = incl;
+  __syncthreads();
+  long long before = 0;
+  for (unsigned i = 0; i < w; ++i) before += wave_total[i];
+  __syncthreads();
+  return before + incl - v;
+}
+
+__global__ void __launch_bounds__(kLayoutBlock)
+moe_expert_layout_kernel(CPtrTab counts, int E, int P, int64_t* row_table, int64_t* expert_first, int64_t* expert_rows) {
+  __shared__ long long wave_total[kLayoutBlock / kWave];
+  __shared__ long long before_expert[kLayoutBlock];
+  const int e = threadIdx.x;
+  const bool live = e < E;
+  const int per_rank = E / P;
+  int32_t c[MCR_MAX_RANKS];
+  long long rows = 0;
+#pragma unroll
+  for (int p = 0; p < MCR_MAX_RANKS; ++p) {
+    c[p] = 0;
+    if (live && p < P) {
+      const int32_t x = static_cast<const int32_t*>(counts.p[p])[e];
+      c[p] = x > 0 ? x : 0;
+    }
+    rows += c[p];
+  }
+  const long long excl = block_exclusive_scan(rows, wave_total);
+  before_expert[threadIdx.x] = excl;
+  __syncthreads();
+  const long long first = live ? excl - before_expert[(e / per_rank) * per_rank] : 0;
+  if (live) {
+    expert_first[e] = first;
+    expert_rows[e] = rows;
+  }
+  long long above = 0;
+#pragma unroll
+  for (int p = 0; p < MCR_MAX_RANKS; ++p) {
+    if (p < P) {                                                       // uniform
+      const long long packed_before = block_exclusive_scan(c[p], wave_total);
+      if (live) row_table[static_cast<size_t>(p) * E + e] = first + above - packed_before;
+      above += c[p];
+    }
+  }
+}
+
+// Where token t of this sender goes: rank (negative: nowhere) and row in that rank's buffer.
+struct RowDest {
+  int32_t r;
+  int64_t row;
+};
+__device__ __forceinline__ RowDest dest_of(const int64_t* table, const int32_t* ids, const int32_t* slot, size_t t, size_t T,
+                                           int E, int per_rank, uint64_t recv_rows) {
+  RowDest d{-1, 0};
+  if (t >= T) return d;
+  const int32_t sl = slot[t];
+  const int32_t e = ids[t];
+  if (sl < 0 || e < 0 || e >= E) return d;
+  const int64_t row = table[e] + sl;
+  if (row < 0 || static_cast<uint64_t>(row) >= recv_rows) return d;
+  d.r = e / per_rank;
+  d.row = row;
+  return d;
+}
+// WAVE (a row is at least a wavefront wide): lane k resolves the wave's k-th row once, before the
+// row loop, and the loop fetches the answer by shuffle.
+template <bool WAVE>
+__device__ __forceinline__ RowDest prefetch_dest(const int64_t* table, const int32_t* ids, const int32_t* slot, size_t t0,
+                                                 uint32_t rows_per_pass, uint32_t tpr_shift, size_t T, int E, int per_rank,
+                                                 uint64_t recv_rows) {
+  if constexpr (!WAVE) return RowDest{-1, 0};
+  const unsigned lane = __lane_id();
+  const size_t t = t0 + static_cast<size_t>(lane) * rows_per_pass + (threadIdx.x >> tpr_shift);
+  return dest_of(table, ids, slot, lane < kRowsPerBlock ? t : T, T, E, per_rank, recv_rows);
+}
+template <bool WAVE>
+__device__ __forceinline__ RowDest row_dest(const RowDest& mine, int k, const int64_t* table, const int32_t* ids,
+                                            const int32_t* slot, size_t t, size_t T, int E, int per_rank, uint64_t recv_rows) {
+  if constexpr (WAVE) {
+    RowDest d;
+    d.r = __shfl(mine.r, k);
+    const uint32_t lo = __shfl(static_cast<uint32_t>(mine.row), k);
+    const uint32_t hi = __shfl(static_cast<uint32_t>(static_cast<uint64_t>(mine.row) >> 32), k);
+    d.row = static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+    return d;
+  } else {
+    return dest_of(table, ids, slot, t, T, E, per_rank, recv_rows);
+  }
+}
+
+__device__ __forceinline__ void stage_row_table(int64_t* lds, const int64_t* row_table, int p, int E) {
+  for (int e = threadIdx.x; e < E; e += kBlock) lds[e] = row_table[static_cast<size_t>(p) * E + e];
+  __syncthreads();
+}
+
+template <int UB, bool NTL, bool NTS, bool WAVE>
+__global__ void __launch_bounds__(kBlock)
+moe_dispatch_by_expert_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab slot_tab, const int64_t* row_table, int E,
+                              int P, size_t T, uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  __shared__ int64_t table[MCR_MAX_EXPERTS];
+  const int p = blockIdx.y;
+  stage_row_table(table, row_table, p, E);
+  const int per_rank = E / P;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
+  const U* src = static_cast<const U*>(tok.p[p]);
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  const RowDest mine = prefetch_dest<WAVE>(table, ids, slot, t0, rows_per_pass, tpr_shift, T, E, per_rank, recv_rows);
+  for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
+    const U* srow[kRowsInFlight];
+    U* drow[kRowsInFlight];
+    bool ok[kRowsInFlight];
+#pragma unroll
+    for (int j = 0; j < kRowsInFlight; ++j) {
+      const size_t t = t0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
+      const RowDest d = row_dest<WAVE>(mine, k0 + j, table, ids, slot, t, T, E, per_rank, recv_rows);
+      ok[j] = d.r >= 0 && d.r < P;
+      srow[j] = src + t * upr;
+      drow[j] = ok[j] ? static_cast<U*>(recv.p[d.r]) + static_cast<uint64_t>(d.row) * upr : nullptr;
+    }
+    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+      U v[kRowsInFlight];
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j)
+        if (ok[j]) v[j] = ldu<NTL, U>(srow[j] + c);
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j)
+        if (ok[j]) stu<NTS, U>(drow[j] + c, v[j]);
+    }
+  }
+}
+
+template <int DT, int UB, bool NTL, bool NTS, bool GATE, bool WAVE>
+__global__ void __launch_bounds__(kBlock)
+moe_combine_by_expert_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab slot_tab, CPtrTab gate_tab,
+                             const int64_t* row_table, int E, int P, size_t T, uint64_t recv_rows, uint32_t upr,
+                             uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  __shared__ int64_t table[MCR_MAX_EXPERTS];
+  const int p = blockIdx.y;
+  stage_row_table(table, row_table, p, E);
+  const int per_rank = E / P;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
+  U* dst = static_cast<U*>(out.p[p]);
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  const RowDest mine = prefetch_dest<WAVE>(table, ids, slot, t0, rows_per_pass, tpr_shift, T, E, per_rank, recv_rows);
+  for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
+    const U* srow[kRowsInFlight];
+    U* drow[kRowsInFlight];
+    bool live[kRowsInFlight], kept[kRowsInFlight];
+    float g[kRowsInFlight];
+#pragma unroll
+    for (int j = 0; j < kRowsInFlight; ++j) {
+      const size_t t = t0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
+      const RowDest d = row_dest<WAVE>(mine, k0 + j, table, ids, slot, t, T, E, per_rank, recv_rows);
+      live[j] = t < T;
+      kept[j] = d.r >= 0 && d.r < P;
+      srow[j] = kept[j] ? static_cast<const U*>(expert_out.p[d.r]) + static_cast<uint64_t>(d.row) * upr : nullptr;
+      drow[j] = dst + t * upr;
+      g[j] = 1.0f;
+      if constexpr (GATE) {
+        if (kept[j]) g[j] = static_cast<const float*>(gate_tab.p[p])[t];
+      }
+    }
+    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+      U v[kRowsInFlight];
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j) {
+        v[j] = U{};
+        if (kept[j]) v[j] = ldu<NTL, U>(srow[j] + c);
+      }
+#pragma unroll
+      for (int j = 0; j < kRowsInFlight; ++j) {
+        if (!live[j]) continue;
+        U y = v[j];
+        if constexpr (GATE) {
+          if (kept[j]) y = scale_unit<DT, UB, U>(y, g[j]);
+        }
+        stu<NTS, U>(drow[j] + c, y);
+      }
+    }
+  }
+}
+
 // DLRM shuffle.  Table t lives on rank t mod P as local table t div P; the table-major side is
 // [T_p][batch][dim], the batch-major side [batch/P][n_tables][dim].  blockIdx.y = rank r of the
 // batch-major side; rows j = b*n_tables + t of that side are walked in order.
@@ -302,6 +506,68 @@ int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, c
         hipLaunchKernelGGL((moe_combine_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value, false>),
                            dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, slot, g, splits, P, T,
                            static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+      return launch_status();
+    };
+    if (variant == SV_SCALAR)
+      return gate ? go(Int<EB>{}, Bool<false>{}, Bool<false>{}, Bool<true>{}) : go(Int<EB>{}, Bool<false>{}, Bool<false>{}, Bool<false>{});
+    return dispatch_hint(variant, [&](auto ntl, auto nts) {
+      return gate ? go(Int<16>{}, ntl, nts, Bool<true>{}) : go(Int<16>{}, ntl, nts, Bool<false>{});
+    });
+  });
+}
+
+int launch_moe_expert_layout(mcr_ctx*, const CPtrTab& counts, int E, int P, int64_t* row_table, int64_t* expert_first,
+                             int64_t* expert_rows, hipStream_t stream) {
+  hipLaunchKernelGGL(moe_expert_layout_kernel, dim3(1), dim3(kLayoutBlock), 0, stream, counts, E, P, row_table, expert_first,
+                     expert_rows);
+  return launch_status();
+}
+
+int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& ids, const CPtrTab& slot,
+                                  const int64_t* row_table, int E, size_t T, size_t recv_rows, size_t row_bytes, int elem_b,
+                                  int P, int variant, hipStream_t stream) {
+  if (T == 0 || row_bytes == 0) return MCR_OK;
+  auto go = [&](auto ub, auto ntl, auto nts) {
+    constexpr int UB = decltype(ub)::value;
+    const RowShape s = row_shape(row_bytes / UB);
+    const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
+    if (s.tpr >= kWave)
+      hipLaunchKernelGGL((moe_dispatch_by_expert_kernel<UB, decltype(ntl)::value, decltype(nts)::value, true>), dim3(gx, P),
+                         dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E, P, T, static_cast<uint64_t>(recv_rows),
+                         s.upr, s.tpr, s.shift);
+    else
+      hipLaunchKernelGGL((moe_dispatch_by_expert_kernel<UB, decltype(ntl)::value, decltype(nts)::value, false>), dim3(gx, P),
+                         dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E, P, T, static_cast<uint64_t>(recv_rows),
+                         s.upr, s.tpr, s.shift);
+    return launch_status();
+  };
+  if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
+  return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(Int<16>{}, ntl, nts); });
+}
+
+int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& ids,
+                                 const CPtrTab& slot, const CPtrTab* gate, const int64_t* row_table, int E, size_t T,
+                                 size_t recv_rows, size_t row_elems, int dtype, int P, int variant, hipStream_t stream) {
+  if (T == 0 || row_elems == 0) return MCR_OK;
+  CPtrTab g;
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
+  return dispatch_dtype(dtype, [&](auto dt) {
+    constexpr int DT = decltype(dt)::value;
+    constexpr int EB = Elem<DT>::kBytes;
+    auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
+      constexpr int UB = decltype(ub)::value;
+      const RowShape s = row_shape(row_elems * EB / UB);
+      const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
+      if (s.tpr >= kWave)
+        hipLaunchKernelGGL(
+            (moe_combine_by_expert_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value, true>),
+            dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, ids, slot, g, row_table, E, P, T,
+            static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+      else
+        hipLaunchKernelGGL(
+            (moe_combine_by_expert_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value, false>),
+            dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, ids, slot, g, row_table, E, P, T,
+            static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
       return launch_status();
     };
     if (variant == SV_SCALAR)

@@ -232,6 +232,30 @@ def mcr_moe_combine(ctx, out: Sequence[Ptr], expert_out: Sequence[Ptr], slot: Se
                                  variant, _stream(stream)), "mcr_moe_combine")
 
 
+def mcr_moe_expert_layout(ctx, counts: Sequence[Ptr], E: int, P: int, row_table: Ptr, expert_first: Ptr, expert_rows: Ptr,
+                          stream=None) -> None:
+    _check(lib().mcr_moe_expert_layout(ctx, _ptr_array(counts), E, P, ctypes.c_void_p(_addr(row_table)),
+                                       ctypes.c_void_p(_addr(expert_first)), ctypes.c_void_p(_addr(expert_rows)),
+                                       _stream(stream)), "mcr_moe_expert_layout")
+
+
+def mcr_moe_dispatch_by_expert(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], expert_ids: Sequence[Ptr], slot: Sequence[Ptr],
+                               row_table: Ptr, T: int, E: int, recv_rows: int, row_elems: int, dtype: int, P: int,
+                               variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_moe_dispatch_by_expert(ctx, _ptr_array(recv), _ptr_array(tokens), _ptr_array(expert_ids), _ptr_array(slot),
+                                            ctypes.c_void_p(_addr(row_table)), _sz(T), E, _sz(recv_rows), _sz(row_elems), dtype,
+                                            P, variant, _stream(stream)), "mcr_moe_dispatch_by_expert")
+
+
+def mcr_moe_combine_by_expert(ctx, out: Sequence[Ptr], expert_out: Sequence[Ptr], expert_ids: Sequence[Ptr],
+                              slot: Sequence[Ptr], gate: Optional[Sequence[Ptr]], row_table: Ptr, T: int, E: int,
+                              recv_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_moe_combine_by_expert(ctx, _ptr_array(out), _ptr_array(expert_out), _ptr_array(expert_ids),
+                                           _ptr_array(slot), _ptr_array(gate), ctypes.c_void_p(_addr(row_table)), _sz(T), E,
+                                           _sz(recv_rows), _sz(row_elems), dtype, P, variant, _stream(stream)),
+           "mcr_moe_combine_by_expert")
+
+
 def mcr_dlrm_shuffle(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], n_tables: int, batch: int, dim: int, dtype: int,
                      P: int, backward: bool = False, variant: int = AUTO, stream=None) -> None:
     _check(lib().mcr_dlrm_shuffle(ctx, _ptr_array(out), _ptr_array(inp), n_tables, _sz(batch), _sz(dim), dtype, P,

@@ -126,6 +126,29 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     falg = [0, 2 * kept * row + P * T * 4, kept * row + P * T * row + P * T * 8]
     rep["fused"] = _stage_report(["route", "moe_dispatch", "moe_combine"], falg, rows)
     rep["fused"]["speedup_vs_chain"] = round(rep["end_to_end"]["us"] / rep["fused"]["end_to_end"]["us"], 2)
+    # the expert-major receive layout (every expert's tokens in one block), same row traffic
+    d_tab = torch.empty(P * E, dtype=torch.int64, device="cuda")
+    d_first = torch.empty(E, dtype=torch.int64, device="cuda")
+    d_rows = torch.empty(E, dtype=torch.int64, device="cuda")
+    rows = []
+    for it in range(reps + 2):
+        e = _events(5)
+        e[0].record()
+        mcr.mcr_moe_route(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+        e[1].record()
+        mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
+        e[2].record()
+        mcr.mcr_moe_dispatch_by_expert(ctx, d_recv, d_tok, d_ids, d_slot, d_tab, T, E, w.recv_rows, H, mcr.BF16, P,
+                                       _v(variants, "moe_dispatch"))
+        e[3].record()
+        mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, E, w.recv_rows, H, mcr.BF16, P,
+                                      _v(variants, "moe_combine"))
+        e[4].record()
+        if it >= 2:
+            rows.append(e)
+    torch.cuda.synchronize()
+    ealg = [0, 0, 2 * kept * row + P * T * 8, kept * row + P * T * row + P * T * 12]
+    rep["by_expert"] = _stage_report(["route", "expert_layout", "moe_dispatch_by_expert", "moe_combine_by_expert"], ealg, rows)
     return rep
 
 

@@ -21,9 +21,9 @@ MUTANTS = [
     ("bf16_tie_always_down", "round_up = (kept & 1u) != 0u;", "round_up = false;"),
     ("bf16_nan_to_inf", "return static_cast<uint16_t>((u >> 16) | 0x0040u);", "return static_cast<uint16_t>(u >> 16);"),
     ("reduce_starts_from_zero", "float acc = load_elem(bufs[0], i, dtype);\n  for (int p = 1;", "float acc = 0.0f;\n  for (int p = 0;"),
-    ("reduce_drops_last_rank", "for (int p = 1; p < P; ++p) {\n    acc = acc + load_elem", "for (int p = 1; p < P - 1; ++p) {\n    acc = acc + load_elem"),
-    ("reduce_reverse_order", "float acc = load_elem(bufs[0], i, dtype);\n  for (int p = 1; p < P; ++p) {\n    acc = acc + load_elem(bufs[p], i, dtype);",
-     "float acc = load_elem(bufs[P - 1], i, dtype);\n  for (int p = 1; p < P; ++p) {\n    acc = acc + load_elem(bufs[P - 1 - p], i, dtype);"),
+    ("reduce_drops_last_rank", "for (int p = 1; p < P; ++p) {\n    acc = combine(acc, load_elem", "for (int p = 1; p < P - 1; ++p) {\n    acc = combine(acc, load_elem"),
+    ("reduce_reverse_order", "float acc = load_elem(bufs[0], i, dtype);\n  for (int p = 1; p < P; ++p) {\n    acc = combine(acc, load_elem(bufs[p], i, dtype), op);",
+     "float acc = load_elem(bufs[P - 1], i, dtype);\n  for (int p = 1; p < P; ++p) {\n    acc = combine(acc, load_elem(bufs[P - 1 - p], i, dtype), op);"),
     ("avg_divides", "acc = acc * scale;", "acc = acc / static_cast<float>(P);"),
     ("allreduce_writes_rank0_only", "for (int r = 0; r < P; ++r) store_elem(bufs[r], i, dtype, y);", "store_elem(bufs[0], i, dtype, y);"),
     ("reduce_writes_everyone", "    store_elem(bufs[root], i, dtype, y);\n  }\n  return 0;\n}\n\n// ---- bcast", "    for (int r = 0; r < P; ++r) store_elem(bufs[r], i, dtype, y);\n  }\n  return 0;\n}\n\n// ---- bcast"),
