@@ -350,14 +350,20 @@ int mcr_fuse_plan_destroy(mcr_fuse_plan* plan);
  * large messages).  Runs `iters` back-to-back all_to_all_single operations on `stream` twice:
  * through mcr_alltoall with MCR_AUTO (validation, table lookup, pointer-table marshalling,
  * launch) and as bare launches of the kernel that call resolves to, each followed by one
- * stream synchronisation; reports the best of three rounds as microseconds per operation:
+ * stream synchronisation, the two loops swapping places from round to round; reports the best
+ * of four rounds as microseconds per operation:
  * us_auto / us_direct from the first call to the end of the synchronisation (what an
  * application sees), host_us_auto / host_us_direct (either may be NULL) up to the return of
- * the last enqueueing call (the CPU cost per call, exact while the hardware queue has room).
+ * the last enqueueing call (the CPU cost per call while the hardware queue has room; it moves
+ * by a microsecond with the state of the runtime's queue), and dispatch_only_us (may be NULL):
+ * the CPU time per call of everything mcr_alltoall does before its launch (checks, pointer
+ * tables, table lookup), timed in a loop of 20 * iters calls that launches nothing, which is
+ * the dispatch layer's cost with no noise from the GPU in it.
  * Arguments as for mcr_alltoall; the buffers are overwritten. */
 int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
                           mcr_dtype dtype, int P, int iters, void* stream, double* us_auto,
-                          double* us_direct, double* host_us_auto, double* host_us_direct);
+                          double* us_direct, double* host_us_auto, double* host_us_direct,
+                          double* dispatch_only_us);
 
 /* ---- static tuning table (paper Sec. IV-E, Table II) ---------------------------
  * One table per (op, dtype, P): rows (message bytes -> variant), kept sorted by

@@ -100,6 +100,19 @@ int set_device(mcr_ctx* ctx) {
   return hip_status(hipSetDevice(ctx->device));
 }
 
+// Everything mcr_alltoall does before it launches: argument checks, the rank pointer tables,
+// the launch-shape choice.
+int prepare_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype, int P,
+                     int variant, PtrTab* to, CPtrTab* ti, int* v) {
+  if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (count % static_cast<size_t>(P) != 0) return MCR_EINVAL;
+  bool all16 = true;
+  if (!fill_tab(*to, out, P, dtype, count > 0, &all16) || !fill_tab(*ti, in, P, dtype, count > 0, &all16)) return MCR_EINVAL;
+  const bool vec_ok = all16 && ((count / P) % per_vec(dtype) == 0);
+  return resolve_variant(ctx, MCR_OP_ALLTOALL, dtype, P, count * elem_bytes(dtype), vec_ok, variant, v);
+}
+
 // Common tail of the vector collectives: counts[i] elements per block; the split matrix is built by
 // `fill(S, rows)` from counts expressed in rows of `row_elems` elements (one 128-bit vector when
 // every count and pointer allows it, else one element).
@@ -245,16 +258,10 @@ int mcr_allgather(mcr_ctx* ctx, void* const* out, const void* const* in, size_t 
 
 int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype, int P,
                  int variant, void* stream) {
-  if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
-  if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  if (count % static_cast<size_t>(P) != 0) return MCR_EINVAL;
   PtrTab to;
   CPtrTab ti;
-  bool all16 = true;
-  if (!fill_tab(to, out, P, dtype, count > 0, &all16) || !fill_tab(ti, in, P, dtype, count > 0, &all16)) return MCR_EINVAL;
-  const bool vec_ok = all16 && ((count / P) % per_vec(dtype) == 0);
   int v;
-  int rc = resolve_variant(ctx, MCR_OP_ALLTOALL, dtype, P, count * elem_bytes(dtype), vec_ok, variant, &v);
+  int rc = prepare_alltoall(ctx, out, in, count, dtype, P, variant, &to, &ti, &v);
   if (rc != MCR_OK) return rc;
   if ((rc = set_device(ctx)) != MCR_OK) return rc;
   return launch_alltoall(ctx, to, ti, count, dtype, P, v, static_cast<hipStream_t>(stream));
@@ -809,7 +816,7 @@ int mcr_fuse_plan_destroy(mcr_fuse_plan* plan) {
 // ---- dispatch overhead (paper Sec. V-B: the runtime's overhead over a C-level benchmark) ------
 int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype, int P,
                           int iters, void* stream, double* us_auto, double* us_direct, double* host_us_auto,
-                          double* host_us_direct) {
+                          double* host_us_direct, double* dispatch_only_us) {
   if (!ctx || !us_auto || !us_direct || iters < 1) return MCR_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the full entry point once: validates everything and warms the kernel up
@@ -817,12 +824,8 @@ int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in,
   if (rc != MCR_OK) return rc;
   PtrTab to;
   CPtrTab ti;
-  bool all16 = true;
-  fill_tab(to, out, P, dtype, count > 0, &all16);
-  fill_tab(ti, in, P, dtype, count > 0, &all16);
   int v;
-  rc = resolve_variant(ctx, MCR_OP_ALLTOALL, dtype, P, count * elem_bytes(dtype),
-                       all16 && ((count / P) % per_vec(dtype) == 0), MCR_AUTO, &v);
+  rc = prepare_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, &to, &ti, &v);
   if (rc != MCR_OK) return rc;
   if (hipStreamSynchronize(st) != hipSuccess) return MCR_EHIP;
   typedef std::chrono::steady_clock clk;
@@ -830,26 +833,48 @@ int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in,
     return std::chrono::duration<double, std::micro>(b - a).count() / n;
   };
   double best_auto = 1e30, best_direct = 1e30, host_auto = 1e30, host_direct = 1e30;
-  for (int round = 0; round < 3; ++round) {
-    auto t0 = clk::now();
+  // one timed loop of `iters` calls: through the entry point (table lookup and checks) or bare launches
+  auto timed_loop = [&](bool through_entry, double* total_us, double* enqueue_us) -> int {
+    auto a = clk::now();
     for (int i = 0; i < iters; ++i) {
-      rc = mcr_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, stream);
-      if (rc != MCR_OK) return rc;
+      const int r = through_entry ? mcr_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, stream)
+                                  : launch_alltoall(ctx, to, ti, count, dtype, P, v, st);
+      if (r != MCR_OK) return r;
     }
-    auto t0e = clk::now();                                       // everything enqueued
+    auto b = clk::now();                                         // everything enqueued
     if (hipStreamSynchronize(st) != hipSuccess) return MCR_EHIP;
-    auto t1 = clk::now();
-    for (int i = 0; i < iters; ++i) {
-      rc = launch_alltoall(ctx, to, ti, count, dtype, P, v, st);
-      if (rc != MCR_OK) return rc;
+    auto c = clk::now();
+    *total_us = std::min(*total_us, us(a, c, iters));
+    *enqueue_us = std::min(*enqueue_us, us(a, b, iters));
+    return MCR_OK;
+  };
+  // the two loops swap places every round, so that neither always runs in the other's wake
+  for (int round = 0; round < 4; ++round) {
+    const bool entry_first = (round % 2) == 0;
+    if ((rc = timed_loop(entry_first, entry_first ? &best_auto : &best_direct, entry_first ? &host_auto : &host_direct)) != MCR_OK)
+      return rc;
+    if ((rc = timed_loop(!entry_first, entry_first ? &best_direct : &best_auto, entry_first ? &host_direct : &host_auto)) != MCR_OK)
+      return rc;
+  }
+  if (dispatch_only_us) {
+    // the dispatch layer by itself: no launch, no GPU, so nothing but the CPU work is in it
+    const int n = iters * 20;
+    double best = 1e30;
+    int sink = 0;
+    for (int round = 0; round < 4; ++round) {
+      auto a = clk::now();
+      for (int i = 0; i < n; ++i) {
+        PtrTab t2;
+        CPtrTab s2;
+        int v2 = 0;
+        sink += prepare_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, &t2, &s2, &v2) + v2 +
+                static_cast<int>(reinterpret_cast<uintptr_t>(t2.p[0]) & 1u);
+      }
+      auto b = clk::now();
+      best = std::min(best, us(a, b, n));
     }
-    auto t1e = clk::now();
-    if (hipStreamSynchronize(st) != hipSuccess) return MCR_EHIP;
-    auto t2 = clk::now();
-    best_auto = std::min(best_auto, us(t0, t1, iters));
-    best_direct = std::min(best_direct, us(t1, t2, iters));
-    host_auto = std::min(host_auto, us(t0, t0e, iters));
-    host_direct = std::min(host_direct, us(t1, t1e, iters));
+    if (sink == -12345) return MCR_ESTATE;          // keeps the loop's results alive
+    *dispatch_only_us = best;
   }
   *us_auto = best_auto;
   *us_direct = best_direct;

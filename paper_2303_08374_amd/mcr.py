@@ -307,12 +307,12 @@ def mcr_fuse_plan_destroy(plan) -> None:
 def mcr_dispatch_overhead(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, P: int, iters: int,
                           stream=None):
     """Microseconds per op: (through MCR_AUTO, as bare kernel launches, host cost per MCR_AUTO call,
-    host cost per bare launch)."""
-    a, d, ha, hd = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+    host cost per bare launch, CPU cost of the dispatch layer alone)."""
+    a, d, ha, hd, do = (ctypes.c_double(0) for _ in range(5))
     _check(lib().mcr_dispatch_overhead(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, iters,
                                        _stream(stream), ctypes.byref(a), ctypes.byref(d), ctypes.byref(ha),
-                                       ctypes.byref(hd)), "mcr_dispatch_overhead")
-    return a.value, d.value, ha.value, hd.value
+                                       ctypes.byref(hd), ctypes.byref(do)), "mcr_dispatch_overhead")
+    return a.value, d.value, ha.value, hd.value, do.value
 
 
 # ---- tuning table --------------------------------------------------------------------------
