@@ -218,29 +218,32 @@ def _i32_ptrs(arrs):
 
 
 def moe_dispatch_by_expert(recv: List[np.ndarray], toks: List[np.ndarray], ids, slots, counts: np.ndarray, row_elems: int,
-                           dtype: int) -> None:
+                           dtype: int, K: int = 1) -> None:
+    """ids, slots: per rank K*T entries, choice-major (entry k*T + t = choice k of token t)."""
     counts = np.ascontiguousarray(counts, dtype=np.int32)
     P, E = counts.shape
     k1, pi = _i32_ptrs(ids)
     k2, ps = _i32_ptrs(slots)
-    _check(lib().orc_moe_dispatch_by_expert(_ptrs(recv), _ptrs(toks), pi, ps, _p(counts), ctypes.c_int64(k1[0].size), E, P,
-                                            ctypes.c_size_t(row_elems), dtype), "moe_dispatch_by_expert")
+    assert k1[0].size % K == 0
+    _check(lib().orc_moe_dispatch_by_expert(_ptrs(recv), _ptrs(toks), pi, ps, _p(counts), ctypes.c_int64(k1[0].size // K), K,
+                                            E, P, ctypes.c_size_t(row_elems), dtype), "moe_dispatch_by_expert")
 
 
 def moe_combine_by_expert(expert_out: List[np.ndarray], ids, slots, gates, counts: np.ndarray, row_elems: int,
-                          dtype: int) -> List[np.ndarray]:
+                          dtype: int, K: int = 1) -> List[np.ndarray]:
     counts = np.ascontiguousarray(counts, dtype=np.int32)
     P, E = counts.shape
     k1, pi = _i32_ptrs(ids)
     k2, ps = _i32_ptrs(slots)
-    T = k1[0].size
+    assert k1[0].size % K == 0
+    T = k1[0].size // K
     outs = [np.empty(T * row_elems, dtype=np_dtype(dtype)) for _ in range(P)]
     if gates is None:
         pg = None
     else:
         kg = [np.ascontiguousarray(g, dtype=np.float32) for g in gates]
         pg = _ptrs(kg)
-    _check(lib().orc_moe_combine_by_expert(_ptrs(outs), _ptrs(expert_out), pi, ps, pg, _p(counts), ctypes.c_int64(T), E, P,
+    _check(lib().orc_moe_combine_by_expert(_ptrs(outs), _ptrs(expert_out), pi, ps, pg, _p(counts), ctypes.c_int64(T), K, E, P,
                                            ctypes.c_size_t(row_elems), dtype), "moe_combine_by_expert")
     return outs
 

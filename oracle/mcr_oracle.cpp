@@ -373,58 +373,88 @@ int orc_moe_expert_layout(const int32_t* counts, int E, int P, int64_t* block_fi
   return 0;
 }
 
-// Dispatch into that layout: the k-th kept token (in token order) of source p for expert e goes
-// to row block_first[p][e] + k of the receive buffer of rank e / (E/P).  A token is kept when its
-// slot is >= 0.  Rows of recv that receive nothing are left untouched.
+// Dispatch into that layout with top-K gating.  Every token has K assignments; ids[p], slot[p]
+// (and gate[p] below) are K blocks of T entries, choice-major: entry a = k*T + t is choice k of
+// token t, which is also the order the routing walked them in (all first choices before any second
+// choice, so first choices fill an expert's capacity first).  An assignment is kept when its slot is
+// >= 0.  The j-th kept assignment (in that order) of source p for expert e puts a copy of its token
+// row in row block_first[p][e] + j of the receive buffer of rank e / (E/P).  Rows of recv that
+// receive nothing are left untouched.  K = 1 is plain top-1 dispatch.
 int orc_moe_dispatch_by_expert(void* const* recv, const void* const* tok, const int32_t* const* ids,
-                               const int32_t* const* slot, const int32_t* counts, int64_t T, int E, int P,
+                               const int32_t* const* slot, const int32_t* counts, int64_t T, int K, int E, int P,
                                size_t row_elems, int dtype) {
-  if (!recv || !tok || !ids || !slot || !counts || T < 0 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype)) return -1;
+  if (!recv || !tok || !ids || !slot || !counts || T < 0 || K < 1 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype))
+    return -1;
   std::vector<int64_t> block_first(static_cast<size_t>(P) * E), ef(E), er(E);
   if (orc_moe_expert_layout(counts, E, P, block_first.data(), ef.data(), er.data()) != 0) return -1;
   const size_t rb = row_elems * elem_bytes(dtype);
   const int per_rank = E / P;
   for (int p = 0; p < P; ++p) {
     std::vector<int64_t> seen(static_cast<size_t>(E), 0);
-    for (int64_t t = 0; t < T; ++t) {
-      if (slot[p][t] < 0) continue;
-      const int e = ids[p][t];
-      const int64_t row = block_first[static_cast<size_t>(p) * E + e] + seen[e];
-      seen[e] += 1;
-      std::memcpy(static_cast<char*>(recv[e / per_rank]) + static_cast<size_t>(row) * rb,
-                  static_cast<const char*>(tok[p]) + static_cast<size_t>(t) * rb, rb);
+    for (int k = 0; k < K; ++k) {
+      for (int64_t t = 0; t < T; ++t) {
+        const int64_t a = static_cast<int64_t>(k) * T + t;
+        if (slot[p][a] < 0) continue;
+        const int e = ids[p][a];
+        const int64_t row = block_first[static_cast<size_t>(p) * E + e] + seen[e];
+        seen[e] += 1;
+        std::memcpy(static_cast<char*>(recv[e / per_rank]) + static_cast<size_t>(row) * rb,
+                    static_cast<const char*>(tok[p]) + static_cast<size_t>(t) * rb, rb);
+      }
     }
   }
   return 0;
 }
 
-// Combine out of that layout: out[p][t] = round(gate[p][t] * f32(expert_out row of token t)), +0 for
-// a dropped token; gate == nullptr copies.
+// Combine out of that layout.  For token t of rank p, over its kept assignments in choice order
+// k = 0..K-1:  acc = gate_k * f32(row_k) for the first kept one, acc = acc + gate_k * f32(row_k)
+// for each later one (binary32 multiply and add, each rounded once), then one rounding to the
+// element type.  No kept assignment: all-zero bits.  gate == nullptr stands for gates of 1
+// (with K = 1 the row is then copied bit for bit).
 int orc_moe_combine_by_expert(void* const* out, const void* const* expert_out, const int32_t* const* ids,
                               const int32_t* const* slot, const float* const* gate, const int32_t* counts, int64_t T,
-                              int E, int P, size_t row_elems, int dtype) {
-  if (!out || !expert_out || !ids || !slot || !counts || T < 0 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype)) return -1;
+                              int K, int E, int P, size_t row_elems, int dtype) {
+  if (!out || !expert_out || !ids || !slot || !counts || T < 0 || K < 1 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype))
+    return -1;
   std::vector<int64_t> block_first(static_cast<size_t>(P) * E), ef(E), er(E);
   if (orc_moe_expert_layout(counts, E, P, block_first.data(), ef.data(), er.data()) != 0) return -1;
   const size_t rb = row_elems * elem_bytes(dtype);
   const int per_rank = E / P;
   for (int p = 0; p < P; ++p) {
+    // first pass, in routing order: where every kept assignment's row is
     std::vector<int64_t> seen(static_cast<size_t>(E), 0);
+    std::vector<const char*> src(static_cast<size_t>(K) * static_cast<size_t>(T), nullptr);
+    for (int64_t a = 0; a < static_cast<int64_t>(K) * T; ++a) {
+      if (slot[p][a] < 0) continue;
+      const int e = ids[p][a];
+      const int64_t row = block_first[static_cast<size_t>(p) * E + e] + seen[e];
+      seen[e] += 1;
+      src[static_cast<size_t>(a)] = static_cast<const char*>(expert_out[e / per_rank]) + static_cast<size_t>(row) * rb;
+    }
     for (int64_t t = 0; t < T; ++t) {
       char* dst = static_cast<char*>(out[p]) + static_cast<size_t>(t) * rb;
-      if (slot[p][t] < 0) {
+      int kept = 0;
+      for (int k = 0; k < K; ++k) kept += src[static_cast<size_t>(k) * T + t] ? 1 : 0;
+      if (kept == 0) {
         std::memset(dst, 0, rb);
         continue;
       }
-      const int e = ids[p][t];
-      const int64_t row = block_first[static_cast<size_t>(p) * E + e] + seen[e];
-      seen[e] += 1;
-      const char* src = static_cast<const char*>(expert_out[e / per_rank]) + static_cast<size_t>(row) * rb;
-      if (!gate) {
-        std::memcpy(dst, src, rb);
-      } else {
-        const float g = gate[p][t];
-        for (size_t c = 0; c < row_elems; ++c) store_elem(dst, c, dtype, g * load_elem(src, c, dtype));
+      if (K == 1 && !gate) {
+        std::memcpy(dst, src[static_cast<size_t>(t)], rb);
+        continue;
+      }
+      for (size_t c = 0; c < row_elems; ++c) {
+        float acc = 0.0f;
+        bool first = true;
+        for (int k = 0; k < K; ++k) {
+          const size_t a = static_cast<size_t>(k) * T + t;
+          if (!src[a]) continue;
+          const float g = gate ? gate[p][a] : 1.0f;
+          const float term = g * load_elem(src[a], c, dtype);
+          acc = first ? term : acc + term;
+          first = false;
+        }
+        store_elem(dst, c, dtype, acc);
       }
     }
   }

@@ -47,6 +47,10 @@ MUTANTS = [
     ("layout_first_not_reset_per_rank", "for (int e2 = (e / per_rank) * per_rank; e2 < e; ++e2) first += expert_rows[e2];", "for (int e2 = 0; e2 < e; ++e2) first += expert_rows[e2];"),
     ("layout_sources_not_stacked", "      block_first[p * E + e] = first + above;\n      above += counts[p * E + e];", "      block_first[p * E + e] = first + above;"),
     ("by_expert_wrong_rank", "      std::memcpy(static_cast<char*>(recv[e / per_rank]) + static_cast<size_t>(row) * rb,", "      std::memcpy(static_cast<char*>(recv[e % P]) + static_cast<size_t>(row) * rb,"),
+    ("topk_second_choice_reads_first_token", "static_cast<const char*>(tok[p]) + static_cast<size_t>(t) * rb, rb);\n      }\n    }", "static_cast<const char*>(tok[p]) + static_cast<size_t>(a % (K * T)) * 0 + static_cast<size_t>(k == 0 ? t : 0) * rb, rb);\n      }\n    }"),
+    ("topk_sum_reversed", "for (int k = 0; k < K; ++k) {\n          const size_t a = static_cast<size_t>(k) * T + t;\n          if (!src[a]) continue;", "for (int k = K - 1; k >= 0; --k) {\n          const size_t a = static_cast<size_t>(k) * T + t;\n          if (!src[a]) continue;"),
+    ("topk_gate_of_first_choice", "const float g = gate ? gate[p][a] : 1.0f;", "const float g = gate ? gate[p][t] : 1.0f;"),
+    ("topk_sum_starts_from_zero", "acc = first ? term : acc + term;", "acc = acc + term;"),
     ("unpack_dropped_not_zeroed", "std::memset(dst, 0, rb);\n      continue;", "continue;"),
     ("unpack_gate_of_slot", "const float g = gate[t];", "const float g = gate[slot[t]];"),
     ("pack_gathers_instead", "std::memcpy(static_cast<char*>(out) + static_cast<size_t>(slot[t]) * rb,\n                static_cast<const char*>(in) + static_cast<size_t>(t) * rb, rb);",

@@ -466,6 +466,68 @@ def check_dispatch_by_expert_is_a_stable_regroup():
             assert np.array_equal(half[p].reshape(T, H), exp * np.float32(0.5))
 
 
+def check_top2_golden():
+    g = gio.keyed_ints("moe_top2_case.txt")
+    E, P, T, K, C = (g[k][0] for k in "EPTKC")
+    ids = np.array(g["ids"], dtype=np.int32)
+    slot, counts, _ = oracle.moe_route(ids, E, P, C)                # routing walks the K*T assignments in order
+    assert slot.tolist() == g["slot"] and counts.tolist() == g["counts"]
+    tok = np.array(g["tokens"], dtype=np.float32)
+    recv = [np.full(len(g["recv"]), -1, dtype=np.float32)]
+    oracle.moe_dispatch_by_expert(recv, [tok], [ids], [slot], counts[None, :], 2, F32, K=K)
+    assert recv[0].tolist() == g["recv"]
+    gate = np.array(g["gate_x16"], dtype=np.float32) / 16
+    out = oracle.moe_combine_by_expert(recv, [ids], [slot], [gate], counts[None, :], 2, F32, K=K)
+    assert (out[0] * 16).tolist() == g["out_x16"]
+
+
+def check_topk_combine_against_numpy_binary32():
+    """K = 3: the weighted sum is binary32 multiply, binary32 add in choice order, one rounding
+    (numpy float32 arithmetic as the library routine); dropped assignments add nothing; the order
+    matters for K = 3, so a sum taken in another order fails here."""
+    for dtype, K, w in ((F32, 3, inputs.MoEWorkload(P=2, T=200, H=5, E=4, capacity_factor=2.2)),
+                        (BF16, 3, inputs.MoEWorkload(P=2, T=200, H=5, E=4, capacity_factor=2.2)),
+                        (BF16, 2, inputs.MoEWorkload(P=4, T=150, H=3, E=8, capacity_factor=1.6))):
+        P, T, H, E = w.P, w.T, w.H, w.E
+        C = int(np.ceil(w.capacity_factor * T / E))
+        rng = np.random.default_rng(7 + K)
+        ids = [np.concatenate([np.roll(w.ids(p, True), 17 * k) for k in range(K)]).astype(np.int32) for p in range(P)]
+        gates = [rng.random(K * T, dtype=np.float32) for p in range(P)]
+        routes = [oracle.moe_route(ids[p], E, P, C) for p in range(P)]
+        slots = [r[0] for r in routes]
+        counts = np.stack([r[1] for r in routes])
+        assert any((s < 0).any() for s in slots) and any((s >= 0).all(axis=0).any() for s in [x.reshape(K, T) for x in slots])
+        if dtype == F32:
+            toks = [rng.standard_normal(T * H).astype(np.float32) for p in range(P)]
+            for x in toks:
+                x[::7] = np.float32(-0.0)                         # a sum that starts from +0 would lose the sign
+            as_f32 = lambda x: x
+            to_dt = lambda x: x.astype(np.float32)
+        else:
+            toks = [w.tokens(p) for p in range(P)]
+            as_f32 = inputs.bf16_bits_to_f32
+            to_dt = lambda x: torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        bf, ef, er = oracle.moe_expert_layout(counts)
+        rows = int(er.reshape(P, -1).sum(axis=1).max())
+        recv = [np.zeros(rows * H, dtype=toks[0].dtype) for _ in range(P)]
+        oracle.moe_dispatch_by_expert(recv, toks, ids, slots, counts, H, dtype, K=K)
+        got = oracle.moe_combine_by_expert(recv, ids, slots, gates, counts, H, dtype, K=K)
+        for p in range(P):
+            x = as_f32(toks[p]).reshape(T, H)                     # identity experts: the row that comes back is the token
+            kept = (slots[p] >= 0).reshape(K, T)
+            g = gates[p].reshape(K, T)
+            acc = np.zeros((T, H), dtype=np.float32)
+            started = np.zeros(T, dtype=bool)
+            for k in range(K):
+                term = (g[k][:, None] * x).astype(np.float32)
+                summed = (acc + term).astype(np.float32)
+                nxt = np.where(started[:, None], summed, term)
+                acc = np.where(kept[k][:, None], nxt, acc)
+                started |= kept[k]
+            exp = to_dt(np.where(started[:, None], acc, np.float32(0)))
+            assert np.array_equal(got[p].view(np.uint8), np.ascontiguousarray(exp).reshape(-1).view(np.uint8)), (dtype, K, p)
+
+
 # ============================ pack / unpack / combine ==========================
 def check_pack_unpack_identity():
     for dtype, w in ((F32, 5), (BF16, 8)):
