@@ -91,6 +91,7 @@ typedef enum {
 #define MCR_NO_DEVICE (-1)
 #define MCR_MAX_RANKS 16
 #define MCR_MAX_EXPERTS 512
+#define MCR_MAX_TOPK 4
 
 /* ---- lifecycle (API listing: init, finalize, synchronize, get_backends) ---- */
 
@@ -272,23 +273,32 @@ int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int
                           int64_t* row_table, int64_t* expert_first, int64_t* expert_rows,
                           void* stream);
 
-/* mcr_moe_dispatch_by_expert: for every rank p and token t with slot[p][t] >= 0 and
- * 0 <= expert_ids[p][t] < E, the token row is written to row
- * row_table[p*E + id] + slot[p][t] of recv[id / (E/P)]; a row outside [0, recv_rows) is
+/* Top-K gating: every token has K choices (1 <= K <= MCR_MAX_TOPK).  expert_ids[p], slot[p] and
+ * gate[p] then hold K*T entries, choice-major: entry a = k*T + t is choice k of token t.  Routing
+ * is mcr_moe_route over those K*T entries (its T argument = K*T), which walks them in that order,
+ * so first choices fill an expert's capacity before any second choice; mcr_moe_expert_layout is
+ * unchanged.  K*T < 2^31.
+ *
+ * mcr_moe_dispatch_by_expert: for every rank p and assignment a < K*T with slot[p][a] >= 0 and
+ * 0 <= id = expert_ids[p][a] < E, row (a mod T) of tokens[p] is written to row
+ * row_table[p*E + id] + slot[p][a] of recv[id / (E/P)]; a row outside [0, recv_rows) is
  * skipped, other rows of recv are left untouched.  expert_ids, slot: as for
  * mcr_moe_route; row_table: DEVICE memory as mcr_moe_expert_layout writes it. */
 int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* const* tokens,
                                const int32_t* const* expert_ids, const int32_t* const* slot,
-                               const int64_t* row_table, size_t T, int E, size_t recv_rows,
+                               const int64_t* row_table, size_t T, int K, int E, size_t recv_rows,
                                size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream);
 
-/* mcr_moe_combine_by_expert: the way back.  out[p] row t = round_to_dtype(gate[p][t] *
- * f32(expert_out[id/(E/P)] row row_table[p*E + id] + slot[p][t])), all-zero bits for a token
- * that was not dispatched.  gate may be NULL (rows are copied). */
+/* mcr_moe_combine_by_expert: the way back.  With x_k = f32(row row_table[p*E + id_k] + slot_k of
+ * expert_out[id_k/(E/P)]) for the dispatched choices k of token t, in choice order:
+ * out[p] row t = round_to_dtype(g_0*x_0 + g_1*x_1 + ...), binary32 products and sums, the sum
+ * starting from the first dispatched product, one rounding; all-zero bits when no choice of the
+ * token was dispatched.  gate: host array of P device pointers to K*T binary32 weights, or NULL
+ * (weights of 1; with K = 1 the row is then copied bit for bit). */
 int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const* expert_out,
                               const int32_t* const* expert_ids, const int32_t* const* slot,
-                              const float* const* gate, const int64_t* row_table, size_t T, int E,
-                              size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P,
+                              const float* const* gate, const int64_t* row_table, size_t T, int K,
+                              int E, size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P,
                               int variant, void* stream);
 
 /* mcr_dlrm_shuffle: the embedding shuffle of paper Sec. II-D as one row permutation.

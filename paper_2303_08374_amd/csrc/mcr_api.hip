@@ -554,12 +554,14 @@ int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int
 }
 
 int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* const* tokens, const int32_t* const* expert_ids,
-                               const int32_t* const* slot, const int64_t* row_table, size_t T, int E, size_t recv_rows,
-                               size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
+                               const int32_t* const* slot, const int64_t* row_table, size_t T, int K, int E,
+                               size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
   if (!ctx || !recv || !tokens || !expert_ids || !slot || !row_table || !valid_P(P)) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0) return MCR_EINVAL;
-  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull || (reinterpret_cast<uintptr_t>(row_table) & 7u)) return MCR_EINVAL;
+  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0 || K < 1 || K > MCR_MAX_TOPK) return MCR_EINVAL;
+  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull / static_cast<size_t>(K) ||
+      (reinterpret_cast<uintptr_t>(row_table) & 7u))
+    return MCR_EINVAL;
   const bool any = T > 0 && row_elems > 0 && recv_rows > 0;
   PtrTab to;
   CPtrTab ti, tid, tsl;
@@ -573,17 +575,19 @@ int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* cons
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
   if ((rc = set_device(ctx)) != MCR_OK) return rc;
-  return launch_moe_dispatch_by_expert(ctx, to, ti, tid, tsl, row_table, E, T, recv_rows, row_bytes,
+  return launch_moe_dispatch_by_expert(ctx, to, ti, tid, tsl, row_table, E, T, K, recv_rows, row_bytes,
                                        static_cast<int>(elem_bytes(dtype)), P, v, static_cast<hipStream_t>(stream));
 }
 
 int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const* expert_out, const int32_t* const* expert_ids,
-                              const int32_t* const* slot, const float* const* gate, const int64_t* row_table, size_t T, int E,
-                              size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
+                              const int32_t* const* slot, const float* const* gate, const int64_t* row_table, size_t T, int K,
+                              int E, size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
   if (!ctx || !out || !expert_out || !expert_ids || !slot || !row_table || !valid_P(P)) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0) return MCR_EINVAL;
-  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull || (reinterpret_cast<uintptr_t>(row_table) & 7u)) return MCR_EINVAL;
+  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0 || K < 1 || K > MCR_MAX_TOPK) return MCR_EINVAL;
+  if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull / static_cast<size_t>(K) ||
+      (reinterpret_cast<uintptr_t>(row_table) & 7u))
+    return MCR_EINVAL;
   const bool any = T > 0 && row_elems > 0;
   PtrTab to;
   CPtrTab ti, tid, tsl, tg;
@@ -598,7 +602,7 @@ int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const*
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
   if ((rc = set_device(ctx)) != MCR_OK) return rc;
-  return launch_moe_combine_by_expert(ctx, to, ti, tid, tsl, gate ? &tg : nullptr, row_table, E, T, recv_rows, row_elems, dtype,
+  return launch_moe_combine_by_expert(ctx, to, ti, tid, tsl, gate ? &tg : nullptr, row_table, E, T, K, recv_rows, row_elems, dtype,
                                       P, v, static_cast<hipStream_t>(stream));
 }
 

@@ -322,10 +322,12 @@ __device__ __forceinline__ void stage_row_table(int64_t* lds, const int64_t* row
   __syncthreads();
 }
 
+// A = K*T assignments per sender, choice-major (assignment a is choice a / T of token a mod T);
+// the rows walked are assignments, the row read is the token's.
 template <int UB, bool NTL, bool NTS, bool WAVE>
 __global__ void __launch_bounds__(kBlock)
 moe_dispatch_by_expert_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab slot_tab, const int64_t* row_table, int E,
-                              int P, size_t T, uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
+                              int P, size_t A, size_t T, uint64_t recv_rows, uint32_t upr, uint32_t tpr, uint32_t tpr_shift) {
   typedef typename RowUnit<UB>::type U;
   __shared__ int64_t table[MCR_MAX_EXPERTS];
   const int p = blockIdx.y;
@@ -335,17 +337,18 @@ moe_dispatch_by_expert_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab
   const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
   const U* src = static_cast<const U*>(tok.p[p]);
   const uint32_t rows_per_pass = kBlock >> tpr_shift;
-  const size_t t0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
-  const RowDest mine = prefetch_dest<WAVE>(table, ids, slot, t0, rows_per_pass, tpr_shift, T, E, per_rank, recv_rows);
+  const size_t a0 = static_cast<size_t>(blockIdx.x) * kRowsPerBlock * rows_per_pass;
+  const RowDest mine = prefetch_dest<WAVE>(table, ids, slot, a0, rows_per_pass, tpr_shift, A, E, per_rank, recv_rows);
   for (int k0 = 0; k0 < kRowsPerBlock; k0 += kRowsInFlight) {
     const U* srow[kRowsInFlight];
     U* drow[kRowsInFlight];
     bool ok[kRowsInFlight];
 #pragma unroll
     for (int j = 0; j < kRowsInFlight; ++j) {
-      const size_t t = t0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
-      const RowDest d = row_dest<WAVE>(mine, k0 + j, table, ids, slot, t, T, E, per_rank, recv_rows);
+      const size_t a = a0 + static_cast<size_t>(k0 + j) * rows_per_pass + (threadIdx.x >> tpr_shift);
+      const RowDest d = row_dest<WAVE>(mine, k0 + j, table, ids, slot, a, A, E, per_rank, recv_rows);
       ok[j] = d.r >= 0 && d.r < P;
+      const size_t t = a < T ? a : a % T;
       srow[j] = src + t * upr;
       drow[j] = ok[j] ? static_cast<U*>(recv.p[d.r]) + static_cast<uint64_t>(d.row) * upr : nullptr;
     }
@@ -411,6 +414,94 @@ moe_combine_by_expert_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CP
         }
         stu<NTS, U>(drow[j] + c, y);
       }
+    }
+  }
+}
+
+// Top-K combine: out[p] row t = round(sum over the kept choices k, in order, of gate[k*T + t] *
+// f32(row of assignment k*T + t)): binary32 products and sums, the sum starting from the first kept
+// product, one rounding at the end; all-zero bits when nothing was kept.  KU = compile-time bound
+// on K.  One group of tpr threads per token row, kTopkRows rows per group and workgroup.
+constexpr int kTopkRows = 8;
+template <int DT, int UB> struct UnitF32 {
+  static constexpr int kN = UB / Elem<DT>::kBytes;
+  typedef typename RowUnit<UB>::type U;
+  __device__ static __forceinline__ void widen(U v, float (&f)[kN]) {
+    if constexpr (UB == 16) Elem<DT>::widen(v, f);
+    else if constexpr (DT == MCR_F32) f[0] = __uint_as_float(static_cast<uint32_t>(v));
+    else f[0] = __uint_as_float(static_cast<uint32_t>(v) << 16);
+  }
+  __device__ static __forceinline__ U narrow(const float (&f)[kN]) {
+    if constexpr (UB == 16) return Elem<DT>::narrow(f);
+    else if constexpr (DT == MCR_F32) return static_cast<U>(__float_as_uint(f[0]));
+    else return static_cast<U>(f32_to_bf16_rne(f[0]));
+  }
+};
+
+template <int DT, int UB, int KU, bool NTL, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+moe_combine_topk_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab slot_tab, CPtrTab gate_tab,
+                        const int64_t* row_table, int E, int P, size_t T, int K, uint64_t recv_rows, uint32_t upr,
+                        uint32_t tpr, uint32_t tpr_shift) {
+  typedef typename RowUnit<UB>::type U;
+  typedef UnitF32<DT, UB> F;
+  __shared__ int64_t table[MCR_MAX_EXPERTS];
+  const int p = blockIdx.y;
+  stage_row_table(table, row_table, p, E);
+  const int per_rank = E / P;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
+  const float* gate = static_cast<const float*>(gate_tab.p[p]);
+  U* dst = static_cast<U*>(out.p[p]);
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const size_t A = T * static_cast<size_t>(K);
+  const size_t t0 = static_cast<size_t>(blockIdx.x) * kTopkRows * rows_per_pass;
+  for (int i = 0; i < kTopkRows; ++i) {
+    const size_t t = t0 + static_cast<size_t>(i) * rows_per_pass + (threadIdx.x >> tpr_shift);
+    if (t >= T) continue;
+    const U* srow[KU];
+    float g[KU];
+    bool kept[KU];
+#pragma unroll
+    for (int k = 0; k < KU; ++k) {
+      kept[k] = false;
+      srow[k] = nullptr;
+      g[k] = 1.0f;
+      if (k < K) {
+        const size_t a = static_cast<size_t>(k) * T + t;
+        const RowDest d = dest_of(table, ids, slot, a, A, E, per_rank, recv_rows);
+        kept[k] = d.r >= 0 && d.r < P;
+        if (kept[k]) {
+          srow[k] = static_cast<const U*>(expert_out.p[d.r]) + static_cast<uint64_t>(d.row) * upr;
+          if (gate) g[k] = gate[a];
+        }
+      }
+    }
+    U* drow = dst + t * upr;
+    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+      U v[KU];
+#pragma unroll
+      for (int k = 0; k < KU; ++k) {
+        v[k] = U{};
+        if (kept[k]) v[k] = ldu<NTL, U>(srow[k] + c);
+      }
+      float acc[F::kN];
+      bool started = false;
+#pragma unroll
+      for (int k = 0; k < KU; ++k) {
+        if (!kept[k]) continue;
+        float f[F::kN];
+        F::widen(v[k], f);
+#pragma unroll
+        for (int e = 0; e < F::kN; ++e) {
+          const float term = g[k] * f[e];
+          acc[e] = started ? acc[e] + term : term;
+        }
+        started = true;
+      }
+      U y = U{};
+      if (started) y = F::narrow(acc);
+      stu<NTS, U>(drow + c, y);
     }
   }
 }
@@ -524,21 +615,22 @@ int launch_moe_expert_layout(mcr_ctx*, const CPtrTab& counts, int E, int P, int6
 }
 
 int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& ids, const CPtrTab& slot,
-                                  const int64_t* row_table, int E, size_t T, size_t recv_rows, size_t row_bytes, int elem_b,
-                                  int P, int variant, hipStream_t stream) {
+                                  const int64_t* row_table, int E, size_t T, int K, size_t recv_rows, size_t row_bytes,
+                                  int elem_b, int P, int variant, hipStream_t stream) {
   if (T == 0 || row_bytes == 0) return MCR_OK;
+  const size_t A = T * static_cast<size_t>(K);
   auto go = [&](auto ub, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     const RowShape s = row_shape(row_bytes / UB);
-    const unsigned gx = blocks_for(T, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
+    const unsigned gx = blocks_for(A, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
     if (s.tpr >= kWave)
       hipLaunchKernelGGL((moe_dispatch_by_expert_kernel<UB, decltype(ntl)::value, decltype(nts)::value, true>), dim3(gx, P),
-                         dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E, P, T, static_cast<uint64_t>(recv_rows),
-                         s.upr, s.tpr, s.shift);
+                         dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E, P, A, T,
+                         static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
     else
       hipLaunchKernelGGL((moe_dispatch_by_expert_kernel<UB, decltype(ntl)::value, decltype(nts)::value, false>), dim3(gx, P),
-                         dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E, P, T, static_cast<uint64_t>(recv_rows),
-                         s.upr, s.tpr, s.shift);
+                         dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E, P, A, T,
+                         static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
     return launch_status();
   };
   if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
@@ -546,7 +638,7 @@ int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& t
 }
 
 int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& ids,
-                                 const CPtrTab& slot, const CPtrTab* gate, const int64_t* row_table, int E, size_t T,
+                                 const CPtrTab& slot, const CPtrTab* gate, const int64_t* row_table, int E, size_t T, int K,
                                  size_t recv_rows, size_t row_elems, int dtype, int P, int variant, hipStream_t stream) {
   if (T == 0 || row_elems == 0) return MCR_OK;
   CPtrTab g;
@@ -554,6 +646,24 @@ int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& exp
   return dispatch_dtype(dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
+    if (K > 1) {
+      auto topk = [&](auto ub, auto ntl, auto nts) {
+        constexpr int UB = decltype(ub)::value;
+        const RowShape s = row_shape(row_elems * EB / UB);
+        const unsigned gx = blocks_for(T, static_cast<size_t>(kTopkRows) * s.rows_per_pass);
+        if (K <= 2)
+          hipLaunchKernelGGL((moe_combine_topk_kernel<DT, UB, 2, decltype(ntl)::value, decltype(nts)::value>), dim3(gx, P),
+                             dim3(kBlock), 0, stream, out, expert_out, ids, slot, g, row_table, E, P, T, K,
+                             static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+        else
+          hipLaunchKernelGGL((moe_combine_topk_kernel<DT, UB, MCR_MAX_TOPK, decltype(ntl)::value, decltype(nts)::value>),
+                             dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, ids, slot, g, row_table, E, P, T, K,
+                             static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+        return launch_status();
+      };
+      if (variant == SV_SCALAR) return topk(Int<EB>{}, Bool<false>{}, Bool<false>{});
+      return dispatch_hint(variant, [&](auto ntl, auto nts) { return topk(Int<16>{}, ntl, nts); });
+    }
     auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
       constexpr int UB = decltype(ub)::value;
       const RowShape s = row_shape(row_elems * EB / UB);

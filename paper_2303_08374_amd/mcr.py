@@ -16,6 +16,7 @@ SUM, AVG, MAX, MIN, PROD = 0, 1, 2, 3, 4
 AUTO = -1
 MAX_RANKS = 16
 MAX_EXPERTS = 512
+MAX_TOPK = 4
 
 OP_ALLREDUCE, OP_REDUCE_SCATTER, OP_ALLGATHER, OP_ALLTOALL, OP_ALLTOALLV = 0, 1, 2, 3, 4
 OP_PACK, OP_UNPACK, OP_FUSE, OP_UNFUSE, OP_ALLREDUCE_MULTI, OP_MOE_ROUTE = 5, 6, 7, 8, 9, 10
@@ -240,18 +241,18 @@ def mcr_moe_expert_layout(ctx, counts: Sequence[Ptr], E: int, P: int, row_table:
 
 
 def mcr_moe_dispatch_by_expert(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], expert_ids: Sequence[Ptr], slot: Sequence[Ptr],
-                               row_table: Ptr, T: int, E: int, recv_rows: int, row_elems: int, dtype: int, P: int,
+                               row_table: Ptr, T: int, K: int, E: int, recv_rows: int, row_elems: int, dtype: int, P: int,
                                variant: int = AUTO, stream=None) -> None:
     _check(lib().mcr_moe_dispatch_by_expert(ctx, _ptr_array(recv), _ptr_array(tokens), _ptr_array(expert_ids), _ptr_array(slot),
-                                            ctypes.c_void_p(_addr(row_table)), _sz(T), E, _sz(recv_rows), _sz(row_elems), dtype,
-                                            P, variant, _stream(stream)), "mcr_moe_dispatch_by_expert")
+                                            ctypes.c_void_p(_addr(row_table)), _sz(T), K, E, _sz(recv_rows), _sz(row_elems),
+                                            dtype, P, variant, _stream(stream)), "mcr_moe_dispatch_by_expert")
 
 
 def mcr_moe_combine_by_expert(ctx, out: Sequence[Ptr], expert_out: Sequence[Ptr], expert_ids: Sequence[Ptr],
-                              slot: Sequence[Ptr], gate: Optional[Sequence[Ptr]], row_table: Ptr, T: int, E: int,
+                              slot: Sequence[Ptr], gate: Optional[Sequence[Ptr]], row_table: Ptr, T: int, K: int, E: int,
                               recv_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
     _check(lib().mcr_moe_combine_by_expert(ctx, _ptr_array(out), _ptr_array(expert_out), _ptr_array(expert_ids),
-                                           _ptr_array(slot), _ptr_array(gate), ctypes.c_void_p(_addr(row_table)), _sz(T), E,
+                                           _ptr_array(slot), _ptr_array(gate), ctypes.c_void_p(_addr(row_table)), _sz(T), K, E,
                                            _sz(recv_rows), _sz(row_elems), dtype, P, variant, _stream(stream)),
            "mcr_moe_combine_by_expert")
 

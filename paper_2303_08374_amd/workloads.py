@@ -11,6 +11,8 @@ from __future__ import annotations
 
 from typing import Dict, List, Optional
 
+import math
+
 import numpy as np
 import torch
 
@@ -138,10 +140,10 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
         e[1].record()
         mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
         e[2].record()
-        mcr.mcr_moe_dispatch_by_expert(ctx, d_recv, d_tok, d_ids, d_slot, d_tab, T, E, w.recv_rows, H, mcr.BF16, P,
+        mcr.mcr_moe_dispatch_by_expert(ctx, d_recv, d_tok, d_ids, d_slot, d_tab, T, 1, E, w.recv_rows, H, mcr.BF16, P,
                                        _v(variants, "moe_dispatch"))
         e[3].record()
-        mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, E, w.recv_rows, H, mcr.BF16, P,
+        mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, 1, E, w.recv_rows, H, mcr.BF16, P,
                                       _v(variants, "moe_combine"))
         e[4].record()
         if it >= 2:
@@ -149,6 +151,36 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     torch.cuda.synchronize()
     ealg = [0, 0, 2 * kept * row + P * T * 8, kept * row + P * T * row + P * T * 12]
     rep["by_expert"] = _stage_report(["route", "expert_layout", "moe_dispatch_by_expert", "moe_combine_by_expert"], ealg, rows)
+    # top-2 gating on the same tokens: second choice = the id stream rotated by 17 tokens, capacity doubled
+    K = 2
+    A, C2 = K * T, int(math.ceil(w.capacity_factor * K * T / E))
+    rows2 = P * min(A, (E // P) * C2)
+    d_ids2 = [torch.cat([x, torch.roll(x, 17)]) for x in d_ids]
+    d_gate2 = [torch.rand(A, dtype=torch.float32, device="cuda") for _ in range(P)]
+    d_slot2 = [torch.empty(A, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_recv2 = mk(rows2)
+    rows = []
+    for it in range(reps + 2):
+        e = _events(5)
+        e[0].record()
+        mcr.mcr_moe_route(ctx, d_ids2, A, E, P, C2, d_slot2, d_cnt, d_S)
+        e[1].record()
+        mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
+        e[2].record()
+        mcr.mcr_moe_dispatch_by_expert(ctx, d_recv2, d_tok, d_ids2, d_slot2, d_tab, T, K, E, rows2, H, mcr.BF16, P,
+                                       _v(variants, "moe_dispatch"))
+        e[3].record()
+        mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv2, d_ids2, d_slot2, d_gate2, d_tab, T, K, E, rows2, H, mcr.BF16, P,
+                                      _v(variants, "moe_combine"))
+        e[4].record()
+        if it >= 2:
+            rows.append(e)
+    torch.cuda.synchronize()
+    kept2 = int(d_S.sum().item())
+    talg = [0, 0, 2 * kept2 * row + P * A * 8, kept2 * row + P * T * row + P * A * 12]
+    rep["top2"] = _stage_report(["route", "expert_layout", "moe_dispatch_by_expert", "moe_combine_by_expert"], talg, rows)
+    rep["top2"]["kept_assignments"] = kept2
+    rep["top2"]["kept_fraction"] = round(kept2 / (P * A), 4)
     return rep
 
 

@@ -182,21 +182,25 @@ def test_moe_pipeline_config3_full_size():
     _moe_pipeline(inputs.MoEWorkload())
 
 
-def _moe_by_expert(w: inputs.MoEWorkload, permute=False, variant=mcr.AUTO, dtype=mcr.BF16):
-    """route -> expert layout -> dispatch by expert -> [identity experts] -> combine by expert."""
-    P, T, H, E, C = w.P, w.T, w.H, w.E, w.C
+def _moe_by_expert(w: inputs.MoEWorkload, permute=False, variant=mcr.AUTO, dtype=mcr.BF16, K=1):
+    """route -> expert layout -> dispatch by expert -> [identity experts] -> combine by expert, with
+    K choices per token (choice-major ids / slots / gates of K*T entries per rank)."""
+    P, T, H, E = w.P, w.T, w.H, w.E
+    A = K * T
+    C = int(np.ceil(w.capacity_factor * A / E))
     npdt = gu.NPDT[dtype]
-    ids = [w.ids(p, permute) for p in range(P)]
+    # choice k of token t: the workload's id stream rotated by 17*k tokens (distinct experts are not required)
+    ids = [np.concatenate([np.roll(w.ids(p, permute), 17 * k) for k in range(K)]).astype(np.int32) for p in range(P)]
     if dtype == mcr.BF16:
         toks = [w.tokens(p) for p in range(P)]
     else:
         toks = [inputs.bf16_bits_to_f32(w.tokens(p)) * np.float32(1.0009765625) for p in range(P)]
-    gates = [w.gate(p) for p in range(P)]
-    recv_rows = w.recv_rows
+    gates = [inputs.uniform01(A, w.seed, p, 4) for p in range(P)]
+    recv_rows = P * min(A, (E // P) * C)
     d_ids = [_i32(x) for x in ids]
     d_tok = [gu.to_dev(t) for t in toks]
     d_gate = [torch.from_numpy(x).cuda() for x in gates]
-    d_slot = [torch.empty(max(T, 1), dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_slot = [torch.empty(max(A, 1), dtype=torch.int32, device="cuda") for _ in range(P)]
     d_cnt = [torch.empty(E, dtype=torch.int32, device="cuda") for _ in range(P)]
     d_S = torch.empty(P * P, dtype=torch.int64, device="cuda")
     d_tab = torch.full((P * E,), -77, dtype=torch.int64, device="cuda")
@@ -206,11 +210,11 @@ def _moe_by_expert(w: inputs.MoEWorkload, permute=False, variant=mcr.AUTO, dtype
     d_out = [gu.dev_empty(max(T * H, 1), dtype, 1) for _ in range(P)]
     d_plain = [gu.dev_empty(max(T * H, 1), dtype, 1) for _ in range(P)]
     c = gu.ctx()
-    mcr.mcr_moe_route(c, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+    mcr.mcr_moe_route(c, d_ids, A, E, P, C, d_slot, d_cnt, d_S)
     mcr.mcr_moe_expert_layout(c, d_cnt, E, P, d_tab, d_first, d_rows)
-    mcr.mcr_moe_dispatch_by_expert(c, d_recv, d_tok, d_ids, d_slot, d_tab, T, E, recv_rows, H, dtype, P, variant)
-    mcr.mcr_moe_combine_by_expert(c, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, E, recv_rows, H, dtype, P, variant)
-    mcr.mcr_moe_combine_by_expert(c, d_plain, d_recv, d_ids, d_slot, None, d_tab, T, E, recv_rows, H, dtype, P, variant)
+    mcr.mcr_moe_dispatch_by_expert(c, d_recv, d_tok, d_ids, d_slot, d_tab, T, K, E, recv_rows, H, dtype, P, variant)
+    mcr.mcr_moe_combine_by_expert(c, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, K, E, recv_rows, H, dtype, P, variant)
+    mcr.mcr_moe_combine_by_expert(c, d_plain, d_recv, d_ids, d_slot, None, d_tab, T, K, E, recv_rows, H, dtype, P, variant)
     gu.sync()
     routes = [oracle.moe_route(ids[p], E, P, C) for p in range(P)]
     slots = [r[0] for r in routes]
@@ -221,9 +225,9 @@ def _moe_by_expert(w: inputs.MoEWorkload, permute=False, variant=mcr.AUTO, dtype
     packed_before = np.cumsum(counts, axis=1) - counts
     assert np.array_equal(d_tab.cpu().numpy().reshape(P, E), bf - packed_before)
     recv = [np.zeros(max(recv_rows * H, 1), dtype=npdt) for _ in range(P)]
-    oracle.moe_dispatch_by_expert(recv, toks, ids, slots, counts, H, dtype)
-    exp_g = oracle.moe_combine_by_expert(recv, ids, slots, gates, counts, H, dtype)
-    exp_p = oracle.moe_combine_by_expert(recv, ids, slots, None, counts, H, dtype)
+    oracle.moe_dispatch_by_expert(recv, toks, ids, slots, counts, H, dtype, K=K)
+    exp_g = oracle.moe_combine_by_expert(recv, ids, slots, gates, counts, H, dtype, K=K)
+    exp_p = oracle.moe_combine_by_expert(recv, ids, slots, None, counts, H, dtype, K=K)
     for p in range(P):
         gu.assert_bits_equal(gu.to_host(d_recv[p], npdt), recv[p], f"dispatch by expert r={p}")
         gu.assert_bits_equal(gu.to_host(d_out[p], npdt)[:T * H], exp_g[p], f"combine by expert r={p}")
@@ -243,9 +247,26 @@ def test_moe_by_expert_small():
     _moe_by_expert(inputs.MoEWorkload(P=2, T=0, H=16, E=4))
 
 
+@pytest.mark.parametrize("K", [2, 3, 4])
+def test_moe_by_expert_top_k(K):
+    _moe_by_expert(inputs.MoEWorkload(P=4, T=1000, H=72, E=8), K=K)
+    _moe_by_expert(inputs.MoEWorkload(P=4, T=1000, H=72, E=8, capacity_factor=0.7), K=K, dtype=mcr.F32)   # many dropped choices
+    _moe_by_expert(inputs.MoEWorkload(P=2, T=333, H=7, E=6), K=K, permute=True)                       # element path
+    _moe_by_expert(inputs.MoEWorkload(P=2, T=333, H=7, E=6), K=K, dtype=mcr.F32, variant=0)
+    for v in (1, 4, 7, 10):
+        _moe_by_expert(inputs.MoEWorkload(P=3, T=500, H=256, E=48), variant=v, K=K)
+    _moe_by_expert(inputs.MoEWorkload(P=2, T=0, H=16, E=4), K=K)
+    _moe_by_expert(inputs.MoEWorkload(P=1, T=65, H=16, E=3), K=K)
+
+
 def test_moe_by_expert_config3_full_size():
     """P=16, T=16384, H=2048 bf16, E=64, Zipf(1.2), capacity 320: every rank, every row."""
     _moe_by_expert(inputs.MoEWorkload())
+
+
+def test_moe_top2_config3_full_size():
+    """The same workload with two choices per token (capacity 640)."""
+    _moe_by_expert(inputs.MoEWorkload(), K=2)
 
 
 # ---------------------------------------------------------------------------- DLRM
