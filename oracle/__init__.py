@@ -142,6 +142,46 @@ def allgatherv(ins: List[np.ndarray], counts: Sequence[int], dtype: int) -> List
     return outs
 
 
+def gatherv_displs(out: np.ndarray, ins: List[np.ndarray], counts: Sequence[int], displs: Sequence[int], dtype: int) -> None:
+    """Writes into ``out`` (kept elsewhere): out[displs[p] + j] = ins[p][j]."""
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    d = np.ascontiguousarray(displs, dtype=np.uint64)
+    assert all(int(d[p] + c[p]) <= out.size and ins[p].size >= int(c[p]) for p in range(len(ins)))
+    _check(lib().orc_gatherv_displs(_p(out), _ptrs(ins), _p(c), _p(d), dtype, len(ins)), "gatherv_displs")
+
+
+def scatterv_displs(root_in: np.ndarray, counts: Sequence[int], displs: Sequence[int], dtype: int) -> List[np.ndarray]:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    d = np.ascontiguousarray(displs, dtype=np.uint64)
+    assert all(int(d[r] + c[r]) <= root_in.size for r in range(c.size))
+    outs = [np.zeros(int(n), dtype=np_dtype(dtype)) for n in c]
+    _check(lib().orc_scatterv_displs(_ptrs(outs), _p(root_in), _p(c), _p(d), dtype, len(outs)), "scatterv_displs")
+    return outs
+
+
+def allgatherv_displs(outs: List[np.ndarray], ins: List[np.ndarray], counts: Sequence[int], displs: Sequence[int],
+                      dtype: int) -> None:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    d = np.ascontiguousarray(displs, dtype=np.uint64)
+    assert all(int(d[p] + c[p]) <= o.size for o in outs for p in range(len(ins)))
+    _check(lib().orc_allgatherv_displs(_ptrs(outs), _ptrs(ins), _p(c), _p(d), dtype, len(ins)), "allgatherv_displs")
+
+
+def alltoallv_displs(outs: List[np.ndarray], ins: List[np.ndarray], counts: np.ndarray, sdispls: np.ndarray,
+                     rdispls: np.ndarray, row_elems: int, dtype: int) -> None:
+    """counts[p, r] rows from row sdispls[p, r] of ins[p] to row rdispls[r, p] of outs[r]."""
+    P = len(ins)
+    C = np.ascontiguousarray(counts, dtype=np.int64)
+    SD = np.ascontiguousarray(sdispls, dtype=np.int64)
+    RD = np.ascontiguousarray(rdispls, dtype=np.int64)
+    assert C.shape == SD.shape == RD.shape == (P, P)
+    for p in range(P):
+        for r in range(P):
+            assert (SD[p, r] + C[p, r]) * row_elems <= ins[p].size and (RD[r, p] + C[p, r]) * row_elems <= outs[r].size
+    _check(lib().orc_alltoallv_displs(_ptrs(outs), _ptrs(ins), _p(C), _p(SD), _p(RD), ctypes.c_size_t(row_elems), dtype, P),
+           "alltoallv_displs")
+
+
 def reduce_scatter(ins: List[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
     P = len(ins)
     n = ins[0].size

@@ -220,6 +220,63 @@ int orc_allgatherv(void* const* out, const void* const* in, const uint64_t* coun
   return 0;
 }
 
+// ---- the same with displacements chosen by the caller (the displs / sdispls / rdispls
+// arguments of the API listing), in elements (rows for all_to_allv) from the buffer start.
+// Gaps between blocks are left untouched; blocks of one destination must not overlap.
+//   gatherv   : root_out[displs[p] + j] = in[p][j]                       j < counts[p]
+//   scatterv  : out[r][j] = root_in[displs[r] + j]                       j < counts[r]
+//   allgatherv: out[r][displs[p] + j] = in[p][j] for every r
+//   alltoallv : out[r][rdispls[r*P + p] + k] = in[p][sdispls[p*P + r] + k]   k < counts[p*P + r] rows
+int orc_gatherv_displs(void* root_out, const void* const* in, const uint64_t* counts, const uint64_t* displs, int dtype,
+                       int P) {
+  if (!in || !counts || !displs || P < 1 || bad_dtype(dtype)) return -1;
+  const size_t s = elem_bytes(dtype);
+  for (int p = 0; p < P; ++p)
+    for (uint64_t j = 0; j < counts[p]; ++j)
+      std::memcpy(static_cast<char*>(root_out) + (displs[p] + j) * s, static_cast<const char*>(in[p]) + j * s, s);
+  return 0;
+}
+
+int orc_scatterv_displs(void* const* out, const void* root_in, const uint64_t* counts, const uint64_t* displs, int dtype,
+                        int P) {
+  if (!out || !counts || !displs || P < 1 || bad_dtype(dtype)) return -1;
+  const size_t s = elem_bytes(dtype);
+  for (int r = 0; r < P; ++r)
+    for (uint64_t j = 0; j < counts[r]; ++j)
+      std::memcpy(static_cast<char*>(out[r]) + j * s, static_cast<const char*>(root_in) + (displs[r] + j) * s, s);
+  return 0;
+}
+
+int orc_allgatherv_displs(void* const* out, const void* const* in, const uint64_t* counts, const uint64_t* displs,
+                          int dtype, int P) {
+  if (!out || !in || !counts || !displs || P < 1 || bad_dtype(dtype)) return -1;
+  for (int r = 0; r < P; ++r) {
+    const int rc = orc_gatherv_displs(out[r], in, counts, displs, dtype, P);
+    if (rc != 0) return rc;
+  }
+  return 0;
+}
+
+int orc_alltoallv_displs(void* const* out, const void* const* in, const int64_t* counts, const int64_t* sdispls,
+                         const int64_t* rdispls, size_t row_elems, int dtype, int P) {
+  if (!out || !in || !counts || !sdispls || !rdispls || P < 1 || bad_dtype(dtype)) return -1;
+  for (int i = 0; i < P * P; ++i)
+    if (counts[i] < 0 || sdispls[i] < 0 || rdispls[i] < 0) return -2;
+  const size_t rb = row_elems * elem_bytes(dtype);
+  for (int r = 0; r < P; ++r) {
+    for (int p = 0; p < P; ++p) {
+      const int64_t cnt = counts[p * P + r];
+      const int64_t from = sdispls[p * P + r];
+      const int64_t to = rdispls[r * P + p];
+      for (int64_t k = 0; k < cnt; ++k) {
+        std::memcpy(static_cast<char*>(out[r]) + static_cast<size_t>(to + k) * rb,
+                    static_cast<const char*>(in[p]) + static_cast<size_t>(from + k) * rb, rb);
+      }
+    }
+  }
+  return 0;
+}
+
 // ---- reduce_scatter (API listing, reduce_scatter; the root it prints is ------
 // a slip, there is none) : rank r receives slice r of the reduction.
 int orc_reduce_scatter(void* const* out, const void* const* in, size_t n, int dtype,

@@ -33,6 +33,10 @@ MUTANTS = [
     ("max_is_min", "case OP_MAX: return (x > acc || x != x) ? x : acc;", "case OP_MAX: return (x < acc || x != x) ? x : acc;"),
     ("min_drops_nan", "case OP_MIN: return (x < acc || x != x) ? x : acc;", "case OP_MIN: return (x < acc) ? x : acc;"),
     ("prod_adds", "case OP_PROD: return acc * x;", "case OP_PROD: return acc + x;"),
+    ("displs_alltoallv_tables_swapped", "const int64_t from = sdispls[p * P + r];\n      const int64_t to = rdispls[r * P + p];", "const int64_t from = rdispls[r * P + p];\n      const int64_t to = sdispls[p * P + r];"),
+    ("displs_rdispls_indexed_by_sender", "const int64_t to = rdispls[r * P + p];", "const int64_t to = rdispls[p * P + r];"),
+    ("displs_gatherv_ignored", "static_cast<char*>(root_out) + (displs[p] + j) * s, static_cast<const char*>(in[p]) + j * s, s);", "static_cast<char*>(root_out) + (displs[0] + j) * s, static_cast<const char*>(in[p]) + j * s, s);"),
+    ("displs_scatterv_on_the_wrong_side", "std::memcpy(static_cast<char*>(out[r]) + j * s, static_cast<const char*>(root_in) + (displs[r] + j) * s, s);", "std::memcpy(static_cast<char*>(out[r]) + (displs[r] + j) * 0 + j * s, static_cast<const char*>(root_in) + j * s, s);"),
     ("rs_wrong_slice", "reduce_at(in, static_cast<size_t>(r) * b + j, dtype, op, P);", "reduce_at(in, j, dtype, op, P);"),
     ("allgather_transposed", "static_cast<char*>(out[r]) + (static_cast<size_t>(p) * m + j) * s,\n                    static_cast<const char*>(in[p]) + j * s, s);",
      "static_cast<char*>(out[r]) + (static_cast<size_t>(r) * m + j) * s,\n                    static_cast<const char*>(in[p]) + j * s, s);"),

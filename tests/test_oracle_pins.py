@@ -410,6 +410,66 @@ def check_route_out_of_range_ids():
     assert slot.tolist() == [0, -1, 2, -1, 1, 3] and cnt.tolist() == [2, 2] and srow.tolist() == [2, 2]
 
 
+# ============================ displacements chosen by the caller ================
+def check_alltoallv_displs_golden():
+    g = gio.keyed_ints("alltoallv_displs_case.txt")
+    P = g["P"][0]
+    ins = [np.array(g[f"send{p}"], dtype=np.float32) for p in range(P)]
+    outs = [np.full(len(g[f"recv{r}"]), -1, dtype=np.float32) for r in range(P)]
+    sq = lambda k: np.array(g[k], dtype=np.int64).reshape(P, P)
+    oracle.alltoallv_displs(outs, ins, sq("counts"), sq("sdispls"), sq("rdispls"), 1, F32)
+    for r in range(P):
+        assert outs[r].tolist() == g[f"recv{r}"]
+
+
+def check_displs_reduce_to_the_packed_forms_and_to_numpy_slicing():
+    rng = np.random.default_rng(11)
+    for P, dtype, re in ((3, F32, 1), (4, BF16, 5), (1, F32, 2)):
+        npdt = oracle.np_dtype(dtype)
+        mk = lambda n: rng.integers(0, 60000, size=n).astype(npdt)
+        # packed displacements give what the packed functions (pinned elsewhere) give
+        S = rng.integers(0, 6, size=(P, P)).astype(np.int64)
+        S[0, P - 1] = 0
+        ins = [mk(int(S[p].sum()) * re) for p in range(P)]
+        SD = np.cumsum(S, axis=1) - S
+        RD = (np.cumsum(S, axis=0) - S).T.copy()                 # RD[r, p] = rows of senders before p at receiver r
+        outs = [np.full(int(S[:, r].sum()) * re, 7, dtype=npdt) for r in range(P)]
+        oracle.alltoallv_displs(outs, ins, S, SD, RD, re, dtype)
+        for a, b in zip(outs, oracle.alltoallv(ins, S, re, dtype)):
+            assert np.array_equal(a, b)
+        counts = rng.integers(0, 9, size=P)
+        counts[P // 2] = 0
+        packed = np.cumsum(counts) - counts
+        gin = [mk(int(c)) for c in counts]
+        out = np.full(int(counts.sum()), 7, dtype=npdt)
+        oracle.gatherv_displs(out, gin, counts, packed, dtype)
+        assert np.array_equal(out, oracle.gatherv(gin, counts, dtype))
+        root = mk(int(counts.sum()))
+        for a, b in zip(oracle.scatterv_displs(root, counts, packed, dtype), oracle.scatterv(root, counts, dtype)):
+            assert np.array_equal(a, b)
+        # blocks in reverse order with a gap of 2 between them: numpy slicing says where everything is
+        displs = np.zeros(P, dtype=np.int64)
+        at = 1
+        for p in reversed(range(P)):
+            displs[p] = at
+            at += int(counts[p]) + 2
+        out = np.full(at, 7, dtype=npdt)
+        oracle.gatherv_displs(out, gin, counts, displs, dtype)
+        exp = np.full(at, 7, dtype=npdt)
+        for p in range(P):
+            exp[displs[p]: displs[p] + counts[p]] = gin[p]
+        assert np.array_equal(out, exp)
+        outs = [np.full(at, 9, dtype=npdt) for _ in range(P)]
+        oracle.allgatherv_displs(outs, gin, counts, displs, dtype)
+        exp9 = np.full(at, 9, dtype=npdt)
+        for p in range(P):
+            exp9[displs[p]: displs[p] + counts[p]] = gin[p]
+        assert all(np.array_equal(o, exp9) for o in outs)
+        src = mk(at)
+        for r, o in enumerate(oracle.scatterv_displs(src, counts, displs, dtype)):
+            assert np.array_equal(o, src[displs[r]: displs[r] + counts[r]])
+
+
 # ============================ expert-major receive layout =======================
 def check_expert_layout_golden():
     g = gio.keyed_ints("moe_expert_layout_case.txt")
