@@ -199,6 +199,37 @@ int mcr_scatterv(mcr_ctx* ctx, void* const* out, const void* in, const size_t* c
 int mcr_allgatherv(mcr_ctx* ctx, void* const* out, const void* const* in, const size_t* counts,
                    mcr_dtype dtype, int P, int variant, void* stream);
 
+/* ---- the vector collectives with displacements chosen by the caller (API listing: the
+ * displs of gatherv / scatterv / all_gatherv, the sdispls and rdispls of all_to_allv) ------
+ * Offsets count from the start of the buffer, in elements (rows of row_elems elements for
+ * all_to_allv); gaps between blocks are left untouched.  The caller states the extent of the
+ * buffers that displacements point into (out_elems, in_elems, in_rows, out_rows); a block that
+ * leaves it gives MCR_ESPLIT and two blocks that overlap in one destination MCR_EINVAL, before
+ * anything is launched.  counts, displs, sdispls, rdispls: HOST arrays.  Counts and offsets that
+ * are not all multiples of 16 bytes take the element path (variant "scalar").
+ *
+ * mcr_alltoallv_displs: out[r] rows rdispls[r*P + p] + k = in[p] rows sdispls[p*P + r] + k for
+ * k < counts[p*P + r]. */
+int mcr_alltoallv_displs(mcr_ctx* ctx, void* const* out, const void* const* in,
+                         const int64_t* counts, const int64_t* sdispls, const int64_t* rdispls,
+                         size_t in_rows, size_t out_rows, size_t row_elems, mcr_dtype dtype, int P,
+                         int variant, void* stream);
+
+/* out[displs[p] + j] = in[p][j], j < counts[p]; out holds out_elems elements. */
+int mcr_gatherv_displs(mcr_ctx* ctx, void* out, size_t out_elems, const void* const* in,
+                       const size_t* counts, const size_t* displs, mcr_dtype dtype, int P,
+                       int variant, void* stream);
+
+/* out[r][j] = in[displs[r] + j], j < counts[r]; in holds in_elems elements. */
+int mcr_scatterv_displs(mcr_ctx* ctx, void* const* out, const void* in, size_t in_elems,
+                        const size_t* counts, const size_t* displs, mcr_dtype dtype, int P,
+                        int variant, void* stream);
+
+/* out[r][displs[p] + j] = in[p][j] for every r; every out[r] holds out_elems elements. */
+int mcr_allgatherv_displs(mcr_ctx* ctx, void* const* out, size_t out_elems, const void* const* in,
+                          const size_t* counts, const size_t* displs, mcr_dtype dtype, int P,
+                          int variant, void* stream);
+
 /* ---- MoE dispatch / combine (paper Sec. II-C: routing of tokens to experts and
  * the combination of the expert outputs each need an Alltoall) -------------------
  *

@@ -142,6 +142,50 @@ int vector_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool al
                           static_cast<int>(elem_bytes(dtype)), P, same_src, v, static_cast<hipStream_t>(stream));
 }
 
+// Pairs with caller-chosen offsets, in elements: pair i = p*P + r copies cnt[i] elements from
+// offset sd[i] of in[p] to offset rd[i] of out[r].  src_elems[p] / dst_elems[r] are the extents the
+// caller vouches for; a pair outside them, or two pairs that overlap in one destination, is an
+// error (the result would depend on the order of the copies).
+int pair_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool all16, const uint64_t* cnt, const uint64_t* sd,
+                    const uint64_t* rd, const uint64_t* src_elems, const uint64_t* dst_elems, mcr_dtype dtype, int P,
+                    int variant, void* stream) {
+  const uint64_t W = per_vec(dtype);
+  bool vec_ok = all16;
+  uint64_t total = 0, biggest = 0;
+  for (int p = 0; p < P; ++p) {
+    for (int r = 0; r < P; ++r) {
+      const int i = p * P + r;
+      if (cnt[i] == 0) continue;
+      if (sd[i] > src_elems[p] || cnt[i] > src_elems[p] - sd[i]) return MCR_ESPLIT;
+      if (rd[i] > dst_elems[r] || cnt[i] > dst_elems[r] - rd[i]) return MCR_ESPLIT;
+      if (!to.p[r] || !ti.p[p]) return MCR_EINVAL;
+      if (cnt[i] % W || sd[i] % W || rd[i] % W) vec_ok = false;
+      total += cnt[i];
+      if (cnt[i] > biggest) biggest = cnt[i];
+      for (int q = 0; q < p; ++q) {                                   // overlap with an earlier sender's block at r
+        const int k = q * P + r;
+        if (cnt[k] && rd[i] < rd[k] + cnt[k] && rd[k] < rd[i] + cnt[i]) return MCR_EINVAL;
+      }
+    }
+  }
+  int v;
+  int rc = resolve_variant(ctx, MCR_OP_ALLTOALLV, dtype, P, biggest * elem_bytes(dtype), vec_ok, variant, &v);
+  if (rc != MCR_OK) return rc;
+  if (total == 0) return MCR_OK;
+  const uint64_t unit = (v == SV_SCALAR) ? 1 : W;
+  uint32_t c32[MCR_MAX_RANKS * MCR_MAX_RANKS], s32[MCR_MAX_RANKS * MCR_MAX_RANKS], r32[MCR_MAX_RANKS * MCR_MAX_RANKS];
+  for (int i = 0; i < P * P; ++i) {
+    const uint64_t c = cnt[i] / unit, s = cnt[i] ? sd[i] / unit : 0, d = cnt[i] ? rd[i] / unit : 0;
+    if (c > 0xffffffffull || s > 0xffffffffull || d > 0xffffffffull) return MCR_EINVAL;
+    c32[i] = static_cast<uint32_t>(c);
+    s32[i] = static_cast<uint32_t>(s);
+    r32[i] = static_cast<uint32_t>(d);
+  }
+  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  return launch_alltoallv_pairs(ctx, to, ti, c32, s32, r32, static_cast<int>(elem_bytes(dtype)), P, v,
+                                static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 }  // namespace mcr
 
@@ -424,6 +468,113 @@ int mcr_allgatherv(mcr_ctx* ctx, void* const* out, const void* const* in, const 
     for (int p = 0; p < P; ++p)
       for (int r = 0; r < P; ++r) S[p * P + r] = static_cast<int64_t>(counts[p] / re);
   });
+}
+
+// ---- the vector collectives with displacements chosen by the caller ---------------------
+int mcr_alltoallv_displs(mcr_ctx* ctx, void* const* out, const void* const* in, const int64_t* counts,
+                         const int64_t* sdispls, const int64_t* rdispls, size_t in_rows, size_t out_rows, size_t row_elems,
+                         mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !out || !in || !counts || !sdispls || !rdispls || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (row_elems > (size_t(1) << 28) || in_rows > (size_t(1) << 40) || out_rows > (size_t(1) << 40)) return MCR_EINVAL;
+  uint64_t cnt[MCR_MAX_RANKS * MCR_MAX_RANKS], sd[MCR_MAX_RANKS * MCR_MAX_RANKS], rd[MCR_MAX_RANKS * MCR_MAX_RANKS];
+  uint64_t src_e[MCR_MAX_RANKS], dst_e[MCR_MAX_RANKS];
+  bool any = false;
+  for (int p = 0; p < P; ++p) {
+    for (int r = 0; r < P; ++r) {
+      const int i = p * P + r;
+      if (counts[i] < 0 || sdispls[i] < 0 || rdispls[r * P + p] < 0) return MCR_EINVAL;
+      if (static_cast<uint64_t>(counts[i]) > in_rows || static_cast<uint64_t>(sdispls[i]) > in_rows ||
+          static_cast<uint64_t>(rdispls[r * P + p]) > out_rows)
+        return MCR_ESPLIT;
+      cnt[i] = static_cast<uint64_t>(counts[i]) * row_elems;
+      sd[i] = static_cast<uint64_t>(sdispls[i]) * row_elems;
+      rd[i] = static_cast<uint64_t>(rdispls[r * P + p]) * row_elems;
+      any = any || cnt[i] > 0;
+    }
+    src_e[p] = static_cast<uint64_t>(in_rows) * row_elems;
+    dst_e[p] = static_cast<uint64_t>(out_rows) * row_elems;
+  }
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, in, P, dtype, any, &all16)) return MCR_EINVAL;
+  return pair_collective(ctx, to, ti, all16, cnt, sd, rd, src_e, dst_e, dtype, P, variant, stream);
+}
+
+int mcr_gatherv_displs(mcr_ctx* ctx, void* out, size_t out_elems, const void* const* in, const size_t* counts,
+                       const size_t* displs, mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !in || !counts || !displs || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  uint64_t cnt[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0}, sd[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0}, rd[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0};
+  uint64_t src_e[MCR_MAX_RANKS], dst_e[MCR_MAX_RANKS];
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = aligned16(out);
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) { to.p[i] = nullptr; ti.p[i] = nullptr; }
+  if (out && !elem_aligned(out, dtype)) return MCR_EINVAL;
+  to.p[0] = out;                                        // the root is "receiver 0"
+  for (int p = 0; p < P; ++p) {
+    if (counts[p] > 0 && (!in[p] || !elem_aligned(in[p], dtype))) return MCR_EINVAL;
+    if (counts[p] > 0 && !aligned16(in[p])) all16 = false;
+    ti.p[p] = in[p];
+    cnt[p * P + 0] = counts[p];
+    rd[p * P + 0] = displs[p];
+    src_e[p] = counts[p];
+    dst_e[p] = p == 0 ? out_elems : 0;
+  }
+  return pair_collective(ctx, to, ti, all16, cnt, sd, rd, src_e, dst_e, dtype, P, variant, stream);
+}
+
+int mcr_scatterv_displs(mcr_ctx* ctx, void* const* out, const void* in, size_t in_elems, const size_t* counts,
+                        const size_t* displs, mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !out || !counts || !displs || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  uint64_t cnt[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0}, sd[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0}, rd[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0};
+  uint64_t src_e[MCR_MAX_RANKS], dst_e[MCR_MAX_RANKS];
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = aligned16(in);
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) { to.p[i] = nullptr; ti.p[i] = nullptr; }
+  if (in && !elem_aligned(in, dtype)) return MCR_EINVAL;
+  ti.p[0] = in;                                         // the root is "sender 0"
+  for (int r = 0; r < P; ++r) {
+    if (counts[r] > 0 && (!out[r] || !elem_aligned(out[r], dtype))) return MCR_EINVAL;
+    if (counts[r] > 0 && !aligned16(out[r])) all16 = false;
+    to.p[r] = out[r];
+    cnt[0 * P + r] = counts[r];
+    sd[0 * P + r] = displs[r];
+    dst_e[r] = counts[r];
+    src_e[r] = r == 0 ? in_elems : 0;
+  }
+  return pair_collective(ctx, to, ti, all16, cnt, sd, rd, src_e, dst_e, dtype, P, variant, stream);
+}
+
+int mcr_allgatherv_displs(mcr_ctx* ctx, void* const* out, size_t out_elems, const void* const* in, const size_t* counts,
+                          const size_t* displs, mcr_dtype dtype, int P, int variant, void* stream) {
+  if (!ctx || !out || !in || !counts || !displs || !valid_P(P)) return MCR_EINVAL;
+  if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  uint64_t cnt[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0}, sd[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0}, rd[MCR_MAX_RANKS * MCR_MAX_RANKS] = {0};
+  uint64_t src_e[MCR_MAX_RANKS], dst_e[MCR_MAX_RANKS];
+  size_t total = 0;
+  for (int p = 0; p < P; ++p) total += counts[p];
+  PtrTab to;
+  CPtrTab ti;
+  bool all16 = true;
+  if (!fill_tab(to, out, P, dtype, total > 0, &all16)) return MCR_EINVAL;
+  for (int i = 0; i < MCR_MAX_RANKS; ++i) ti.p[i] = nullptr;
+  for (int p = 0; p < P; ++p) {
+    if (counts[p] > 0 && (!in[p] || !elem_aligned(in[p], dtype))) return MCR_EINVAL;
+    if (counts[p] > 0 && !aligned16(in[p])) all16 = false;
+    ti.p[p] = in[p];
+    src_e[p] = counts[p];
+    dst_e[p] = out_elems;
+    for (int r = 0; r < P; ++r) {
+      cnt[p * P + r] = counts[p];
+      rd[p * P + r] = displs[p];
+    }
+  }
+  return pair_collective(ctx, to, ti, all16, cnt, sd, rd, src_e, dst_e, dtype, P, variant, stream);
 }
 
 // ---- MoE ------------------------------------------------------------------------

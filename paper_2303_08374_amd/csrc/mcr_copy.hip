@@ -168,6 +168,42 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
   }
 }
 
+// all_to_allv with displacements chosen by the caller: the host has checked every pair against
+// the buffer extents and passes, per (sender p, receiver r), the pair's length and its two
+// offsets in units of UB bytes.  Same grid and copy loop as above.
+struct PairArg {
+  uint32_t cnt[MCR_MAX_RANKS * MCR_MAX_RANKS];
+  uint32_t sd[MCR_MAX_RANKS * MCR_MAX_RANKS];   // offset in in[p]
+  uint32_t rd[MCR_MAX_RANKS * MCR_MAX_RANKS];   // offset in out[r], also indexed [p*P + r]
+};
+
+template <int UB, int U, bool NTL, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+alltoallv_pairs_kernel(PtrTab out, CPtrTab in, PairArg a, int P) {
+  typedef typename Unit<UB>::type T;
+  constexpr uint64_t kTile = static_cast<uint64_t>(U) * kBlock;
+  const int p = blockIdx.y, r = blockIdx.z;
+  const int i = p * P + r;
+  const uint64_t n = a.cnt[i];
+  if (static_cast<uint64_t>(blockIdx.x) * kTile >= n) return;
+  const T* src = static_cast<const T*>(in.p[p]) + a.sd[i];
+  T* dst = static_cast<T*>(out.p[r]) + a.rd[i];
+  const uint64_t step = static_cast<uint64_t>(gridDim.x) * kTile;
+  for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < n; tile += step) {
+    T v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+      if (idx < n) v[u] = load_unit<NTL, T>(src, idx);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+      if (idx < n) store_unit<NTS, T>(dst, idx, v[u]);
+    }
+  }
+}
+
 inline unsigned capped_blocks(size_t units, size_t per_block, size_t cap) {
   size_t blocks = (units + per_block - 1) / per_block;
   if (blocks == 0) blocks = 1;
@@ -270,6 +306,35 @@ int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64
     else
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
                          hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src);
+    return launch_status();
+  };
+  if (variant == SV_SCALAR) {
+    if (elem_b == 4) return go(Int<4>{}, Int<4>{}, Bool<false>{}, Bool<false>{});
+    return go(Int<2>{}, Int<4>{}, Bool<false>{}, Bool<false>{});
+  }
+  return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) { return go(Int<16>{}, uu, ntl, nts); });
+}
+
+// cnt / sd / rd: P*P entries each, [p*P + r], in units of 16 bytes (vector variants) or of one
+// element (SV_SCALAR); the caller has checked them against the buffers.
+int launch_alltoallv_pairs(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const uint32_t* cnt, const uint32_t* sd,
+                           const uint32_t* rd, int elem_b, int P, int variant, hipStream_t stream) {
+  PairArg a;
+  uint32_t longest = 0;
+  for (int i = 0; i < MCR_MAX_RANKS * MCR_MAX_RANKS; ++i) {
+    const bool live = i < P * P;
+    a.cnt[i] = live ? cnt[i] : 0;
+    a.sd[i] = live ? sd[i] : 0;
+    a.rd[i] = live ? rd[i] : 0;
+    if (a.cnt[i] > longest) longest = a.cnt[i];
+  }
+  if (longest == 0) return MCR_OK;
+  auto go = [&](auto ub, auto uu, auto ntl, auto nts) {
+    constexpr int UB = decltype(ub)::value;
+    constexpr int U = decltype(uu)::value;
+    const unsigned gx = capped_blocks(longest, static_cast<size_t>(U) * kBlock, 65535 * 16);
+    hipLaunchKernelGGL((alltoallv_pairs_kernel<UB, U, decltype(ntl)::value, decltype(nts)::value>), dim3(gx, P, P),
+                       dim3(kBlock), 0, stream, out, in, a, P);
     return launch_status();
   };
   if (variant == SV_SCALAR) {

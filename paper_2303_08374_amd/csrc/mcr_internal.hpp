@@ -87,6 +87,8 @@ int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t coun
 int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
 int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits, const int64_t* dev_splits,
                      size_t in_rows, size_t out_rows, size_t row_bytes, int elem_b, int P, int same_src, int variant, hipStream_t);
+int launch_alltoallv_pairs(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const uint32_t* cnt, const uint32_t* sd,
+                           const uint32_t* rd, int elem_b, int P, int variant, hipStream_t);
 int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot, const PtrTab& counts,
                      int64_t* splits, hipStream_t);
 int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows, size_t row_bytes,

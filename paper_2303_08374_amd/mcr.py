@@ -217,6 +217,37 @@ def mcr_unpack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr],
                             _sz(in_rows), _sz(row_elems), dtype, P, variant, _stream(stream)), "mcr_unpack")
 
 
+def _i64_array(xs):
+    flat = [int(x) for x in xs]
+    return (ctypes.c_int64 * max(len(flat), 1))(*flat)
+
+
+def mcr_alltoallv_displs(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], counts, sdispls, rdispls, in_rows: int, out_rows: int,
+                         row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    """counts, sdispls, rdispls: P*P integers each, row-major ([p][r], [p][r], [r][p])."""
+    _check(lib().mcr_alltoallv_displs(ctx, _ptr_array(out), _ptr_array(inp), _i64_array(counts), _i64_array(sdispls),
+                                      _i64_array(rdispls), _sz(in_rows), _sz(out_rows), _sz(row_elems), dtype, P, variant,
+                                      _stream(stream)), "mcr_alltoallv_displs")
+
+
+def mcr_gatherv_displs(ctx, out: Ptr, out_elems: int, inp: Sequence[Ptr], counts: Sequence[int], displs: Sequence[int],
+                       dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_gatherv_displs(ctx, ctypes.c_void_p(_addr(out)), _sz(out_elems), _ptr_array(inp), _counts(counts),
+                                    _counts(displs), dtype, P, variant, _stream(stream)), "mcr_gatherv_displs")
+
+
+def mcr_scatterv_displs(ctx, out: Sequence[Ptr], inp: Ptr, in_elems: int, counts: Sequence[int], displs: Sequence[int],
+                        dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_scatterv_displs(ctx, _ptr_array(out), ctypes.c_void_p(_addr(inp)), _sz(in_elems), _counts(counts),
+                                     _counts(displs), dtype, P, variant, _stream(stream)), "mcr_scatterv_displs")
+
+
+def mcr_allgatherv_displs(ctx, out: Sequence[Ptr], out_elems: int, inp: Sequence[Ptr], counts: Sequence[int],
+                          displs: Sequence[int], dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
+    _check(lib().mcr_allgatherv_displs(ctx, _ptr_array(out), _sz(out_elems), _ptr_array(inp), _counts(counts),
+                                       _counts(displs), dtype, P, variant, _stream(stream)), "mcr_allgatherv_displs")
+
+
 # ---- fused pipelines -----------------------------------------------------------------------
 def mcr_moe_dispatch(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], slot: Sequence[Ptr], splits: Ptr, T: int,
                      recv_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:

@@ -105,6 +105,24 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_scatterv, ctx, A16[1:3], 0, [8, 8], S.F32, 2, S.AUTO, 0) == S.EINVAL
     assert _status(S.mcr_allgatherv, ctx, A16[:2], A16[2:4], [3, 8], S.F32, 2, 2, 0) == S.EVARIANT
     assert _status(S.mcr_allgatherv, ctx, A16[:2], A16[2:4], [0, 0], S.F32, 2, S.AUTO, 0) == 0                   # nothing to move
+    # displacements chosen by the caller: extents, overlaps, alignment of the vector path
+    C, SD, RD = [1, 2, 2, 1], [4, 1, 3, 0], [3, 0, 2, 5]
+    assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, SD, RD, 6, 6, 4, S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, SD, RD, 4, 6, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT     # 4+1 > 4 send rows
+    assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, SD, RD, 6, 5, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT     # 5+1 > 5 receive rows
+    assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, SD, [1, 0, 2, 5], 6, 6, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL   # blocks overlap at rank 0
+    assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, [4, -1, 3, 0], RD, 6, 6, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL
+    assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, SD, RD, 6, 6, 3, S.F32, 2, 1, 0) == S.EVARIANT         # 12-byte rows, vector variant
+    assert _status(S.mcr_gatherv_displs, ctx, A16[0], 20, A16[1:3], [8, 8], [12, 0], S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_gatherv_displs, ctx, A16[0], 19, A16[1:3], [8, 8], [12, 0], S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_gatherv_displs, ctx, A16[0], 20, A16[1:3], [8, 8], [7, 0], S.F32, 2, S.AUTO, 0) == S.EINVAL          # overlap
+    assert _status(S.mcr_gatherv_displs, ctx, A16[0], 20, A16[1:3], [8, 8], [10, 0], S.F32, 2, 1, 0) == S.EVARIANT             # offset 10 floats is not 16-byte aligned
+    assert _status(S.mcr_scatterv_displs, ctx, A16[1:3], A16[0], 16, [8, 8], [8, 0], S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_scatterv_displs, ctx, A16[1:3], A16[0], 16, [8, 8], [4, 0], S.F32, 2, S.AUTO, 0) == S.ESTATE          # source blocks may overlap
+    assert _status(S.mcr_scatterv_displs, ctx, A16[1:3], A16[0], 15, [8, 8], [8, 0], S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_allgatherv_displs, ctx, A16[:2], 32, A16[2:4], [8, 4], [20, 0], S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_allgatherv_displs, ctx, A16[:2], 27, A16[2:4], [8, 4], [20, 0], S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_allgatherv_displs, ctx, A16[:2], 32, A16[2:4], [0, 0], [20, 0], S.F32, 2, S.AUTO, 0) == 0
     # MoE routing
     assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 6, 4, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL      # P does not divide E
     assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 1024, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL  # too many experts

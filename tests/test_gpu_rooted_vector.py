@@ -106,3 +106,95 @@ def test_gather_scatter_equal_counts():
     sc_exp = oracle.scatterv(np.concatenate(ins), [n] * P, dtype)
     for r in range(P):
         gu.assert_bits_equal(gu.to_host(d_back[r], np.float32), sc_exp[r], "scatter")
+
+
+# ------------------------------------------------- displacements chosen by the caller
+def _scattered_displs(counts, W, rng, vec):
+    """Blocks in a shuffled order with gaps; offsets multiples of W when `vec`."""
+    order = rng.permutation(len(counts))
+    displs = [0] * len(counts)
+    at = int(rng.integers(0, 3)) * (W if vec else 1)
+    for p in order:
+        displs[p] = at
+        gap = int(rng.integers(0, 5))
+        at += counts[p] + (gap * W if vec else gap)
+    return displs, at + 8
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("P", [1, 2, 5, 16])
+def test_vector_collectives_with_displacements(dtype, P):
+    W = 4 if dtype == mcr.F32 else 8
+    npdt = gu.NPDT[dtype]
+    rng = np.random.Generator(np.random.Philox(key=1800 + P))
+    bf = dtype == mcr.BF16
+    for vec in (True, False):
+        counts = [int(c) * (W if vec else 1) for c in rng.integers(0, 40 if vec else 50, size=P)]
+        counts[P // 2] = 0
+        if P == 16 and vec:
+            counts[3] = 70000 * W                                                   # several tiles and a tail in one pair
+        displs, extent = _scattered_displs(counts, W, rng, vec)
+        ins = [inputs.uniform_pm1(c, 1801, p, bf16=bf) for p, c in enumerate(counts)]
+        d_ins = [gu.to_dev(x) if x.size else gu.dev_empty(8, dtype, 0) for x in ins]
+        g_exp = np.full(extent, 0, dtype=npdt)
+        oracle.gatherv_displs(g_exp, ins, counts, displs, dtype)
+        ag_exp = [np.full(extent, 0, dtype=npdt) for _ in range(P)]
+        oracle.allgatherv_displs(ag_exp, ins, counts, displs, dtype)
+        root = inputs.uniform_pm1(extent, 1802, 0, bf16=bf)
+        sc_exp = oracle.scatterv_displs(root, counts, displs, dtype)
+        d_root = gu.to_dev(root)
+        for variant in [mcr.AUTO, 0] + ([1, 5, 9] if vec else []):
+            d_g = gu.dev_empty(extent, dtype, 0)
+            mcr.mcr_gatherv_displs(gu.ctx(), d_g, extent, d_ins, counts, displs, dtype, P, variant)
+            d_ag = [gu.dev_empty(extent, dtype, 0) for _ in range(P)]
+            mcr.mcr_allgatherv_displs(gu.ctx(), d_ag, extent, d_ins, counts, displs, dtype, P, variant)
+            d_sc = [gu.dev_empty(c + 8, dtype, 0) for c in counts]
+            mcr.mcr_scatterv_displs(gu.ctx(), d_sc, d_root, extent, counts, displs, dtype, P, variant)
+            gu.sync()
+            gu.assert_bits_equal(gu.to_host(d_g, npdt), g_exp, f"gatherv_displs P={P} v={variant}")     # gaps stay 0
+            for r in range(P):
+                gu.assert_bits_equal(gu.to_host(d_ag[r], npdt), ag_exp[r], f"allgatherv_displs P={P} v={variant} r={r}")
+                s = gu.to_host(d_sc[r], npdt)
+                gu.assert_bits_equal(s[:counts[r]], sc_exp[r], f"scatterv_displs P={P} v={variant} r={r}")
+                assert (s[counts[r]:] == 0).all()
+
+
+@pytest.mark.parametrize("dtype,row_elems", [(mcr.F32, 4), (mcr.BF16, 8), (mcr.F32, 3), (mcr.BF16, 5), (mcr.BF16, 2048)])
+@pytest.mark.parametrize("P", [1, 3, 8, 16])
+def test_alltoallv_with_displacements(dtype, row_elems, P):
+    npdt = gu.NPDT[dtype]
+    rng = np.random.Generator(np.random.Philox(key=1900 + P + row_elems))
+    bf = dtype == mcr.BF16
+    C = rng.integers(0, 9, size=(P, P)).astype(np.int64)
+    C[0, P - 1] = 0
+    if row_elems == 2048:
+        C[P - 1, 0] = 300                                                          # 1.2 MB in one pair
+    # send side: blocks of a sender in shuffled order with gaps; receive side likewise
+    SD = np.zeros((P, P), dtype=np.int64)
+    RD = np.zeros((P, P), dtype=np.int64)
+    in_rows = out_rows = 0
+    for p in range(P):
+        at = int(rng.integers(0, 3))
+        for r in rng.permutation(P):
+            SD[p, r] = at
+            at += int(C[p, r]) + int(rng.integers(0, 3))
+        in_rows = max(in_rows, at)
+    for r in range(P):
+        at = int(rng.integers(0, 3))
+        for p in rng.permutation(P):
+            RD[r, p] = at
+            at += int(C[p, r]) + int(rng.integers(0, 3))
+        out_rows = max(out_rows, at)
+    in_rows, out_rows = in_rows + 1, out_rows + 1
+    ins = [inputs.uniform_pm1(in_rows * row_elems, 1901, p, bf16=bf) for p in range(P)]
+    exp = [np.zeros(out_rows * row_elems, dtype=npdt) for _ in range(P)]
+    oracle.alltoallv_displs(exp, ins, C, SD, RD, row_elems, dtype)
+    d_ins = [gu.to_dev(x) for x in ins]
+    vec_ok = (row_elems * gu.EB[dtype]) % 16 == 0
+    for variant in [mcr.AUTO, 0] + ([1, 6, 11] if vec_ok else []):
+        d_out = [gu.dev_empty(out_rows * row_elems, dtype, 0) for _ in range(P)]
+        mcr.mcr_alltoallv_displs(gu.ctx(), d_out, d_ins, C.reshape(-1), SD.reshape(-1), RD.reshape(-1), in_rows, out_rows,
+                                 row_elems, dtype, P, variant)
+        gu.sync()
+        for r in range(P):
+            gu.assert_bits_equal(gu.to_host(d_out[r], npdt), exp[r], f"alltoallv_displs P={P} v={variant} r={r}")
