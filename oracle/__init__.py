@@ -19,6 +19,8 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+F16 = 2          # IEEE binary16, carried as numpy float16
+I32 = 3
 SUM = 0
 AVG = 1
 MAX = 2
@@ -56,7 +58,7 @@ def lib() -> ctypes.CDLL:
 
 
 def np_dtype(dtype: int):
-    return np.float32 if dtype == F32 else np.uint16
+    return {F32: np.float32, BF16: np.uint16, F16: np.float16, I32: np.int32}[dtype]
 
 
 def _check(rc: int, what: str) -> None:
@@ -89,6 +91,21 @@ def bf16_to_f32(h: np.ndarray) -> np.ndarray:
     h = np.ascontiguousarray(h, dtype=np.uint16)
     out = np.empty(h.shape, dtype=np.float32)
     lib().orc_bf16_to_f32_array(_p(h), _p(out), ctypes.c_size_t(h.size))
+    return out
+
+
+# ---- fp16 (bit patterns in, bit patterns out, so that NaN payloads can be looked at) ----
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().orc_f32_to_f16_array(_p(x), _p(out), ctypes.c_size_t(x.size))
+    return out
+
+
+def f16_bits_to_f32(h: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape, dtype=np.float32)
+    lib().orc_f16_to_f32_array(_p(h), _p(out), ctypes.c_size_t(h.size))
     return out
 
 

@@ -10,7 +10,10 @@
 // the obvious loop nest, single-threaded, one element at a time.  Sums are
 // taken in IEEE binary32 in rank order 0,1,...,P-1 starting from rank 0's
 // value (not from 0.0f), and compiled with -ffp-contract=off so that no
-// multiply-add is fused.  bf16 is carried as uint16_t.
+// multiply-add is fused.  bf16 and fp16 are carried as uint16_t.  fp16 (IEEE binary16) is
+// reduced like bf16: widened exactly, combined in binary32, rounded once.  int32 is reduced in
+// two's-complement arithmetic that wraps (sums and products modulo 2^32), which does not depend
+// on the order; AVG of integers and gate-scaling of integers are not defined and are refused.
 //
 // The paper delegates the semantics of each collective to MPI/NCCL
 // (Sec. II-B "Communication Backends"); the definitions below are the MPI
@@ -20,6 +23,7 @@
 // produce their own expectation (closed forms, involutions, brute force,
 // library routines); none is "parity unpinned".
 
+#include <cmath>
 #include <cstddef>
 #include <cstdint>
 #include <cstring>
@@ -27,7 +31,7 @@
 
 namespace {
 
-enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_I32 = 3 };
 enum { OP_SUM = 0, OP_AVG = 1, OP_MAX = 2, OP_MIN = 3, OP_PROD = 4 };
 
 // bf16 is the upper half of a binary32 pattern.
@@ -67,22 +71,74 @@ inline uint16_t float_to_bf16_bits(float f) {
   return static_cast<uint16_t>(kept);
 }
 
+// IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.
+inline float half_bits_to_float(uint16_t h) {
+  const uint32_t sign = static_cast<uint32_t>(h & 0x8000u) << 16;
+  const int exp = (h >> 10) & 0x1f;
+  const uint32_t frac = h & 0x3ffu;
+  if (exp == 31) {                                   // infinity or NaN (payload kept)
+    const uint32_t u = sign | 0x7f800000u | (frac << 13);
+    float f;
+    std::memcpy(&f, &u, sizeof f);
+    return f;
+  }
+  // value = frac * 2^-24 (subnormal) or (1024 + frac) * 2^(exp-25): exact in binary32
+  const float mag = exp == 0 ? std::ldexp(static_cast<float>(frac), -24)
+                             : std::ldexp(static_cast<float>(1024u + frac), exp - 25);
+  return sign ? -mag : mag;
+}
+
+// Round to nearest, ties to even, from binary32 to binary16, by definition: in the binade
+// 2^E <= |f| < 2^(E+1) the representable values are multiples of the quantum 2^(E-10); below
+// 2^-14 (subnormal results) the quantum stays 2^-24.  |f| / quantum is exact in binary64, its
+// fractional part decides, a tie goes to the even multiple; 2048 quanta are 1024 of the next
+// binade; past the largest exponent the result is infinity.
+inline uint16_t float_to_half_bits(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, sizeof u);
+  const uint16_t sign = static_cast<uint16_t>((u >> 16) & 0x8000u);
+  const uint32_t mag = u & 0x7fffffffu;
+  if (mag > 0x7f800000u) return static_cast<uint16_t>(sign | 0x7e00u | ((mag >> 13) & 0x3ffu));   // NaN, quiet bit forced
+  if (mag == 0x7f800000u) return static_cast<uint16_t>(sign | 0x7c00u);
+  const double a = std::fabs(static_cast<double>(f));
+  if (a == 0.0) return sign;
+  int e2;
+  std::frexp(a, &e2);                                // a = m * 2^e2, 0.5 <= m < 1
+  int E = e2 - 1;
+  if (E < -14) E = -14;
+  const double scaled = a / std::ldexp(1.0, E - 10);
+  double n = std::floor(scaled);
+  const double rem = scaled - n;
+  if (rem > 0.5 || (rem == 0.5 && std::fmod(n, 2.0) == 1.0)) n += 1.0;
+  if (n == 2048.0) {
+    E += 1;
+    n = 1024.0;
+  }
+  if (E > 15) return static_cast<uint16_t>(sign | 0x7c00u);
+  const uint32_t q = static_cast<uint32_t>(n);
+  if (q < 1024u) return static_cast<uint16_t>(sign | q);                     // subnormal (E == -14)
+  return static_cast<uint16_t>(sign | (static_cast<uint32_t>(E + 15) << 10) | (q - 1024u));
+}
+
 inline float load_elem(const void* base, size_t i, int dtype) {
   if (dtype == DT_F32) return static_cast<const float*>(base)[i];
+  if (dtype == DT_F16) return half_bits_to_float(static_cast<const uint16_t*>(base)[i]);
   return bf16_bits_to_float(static_cast<const uint16_t*>(base)[i]);
 }
 
 inline void store_elem(void* base, size_t i, int dtype, float v) {
   if (dtype == DT_F32) {
     static_cast<float*>(base)[i] = v;
+  } else if (dtype == DT_F16) {
+    static_cast<uint16_t*>(base)[i] = float_to_half_bits(v);
   } else {
     static_cast<uint16_t*>(base)[i] = float_to_bf16_bits(v);
   }
 }
 
-inline size_t elem_bytes(int dtype) { return dtype == DT_F32 ? 4u : 2u; }
+inline size_t elem_bytes(int dtype) { return (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u; }
 
-inline bool bad_dtype(int dtype) { return dtype != DT_F32 && dtype != DT_BF16; }
+inline bool bad_dtype(int dtype) { return dtype < DT_F32 || dtype > DT_I32; }
 inline bool bad_op(int op) { return op < OP_SUM || op > OP_PROD; }
 
 // One step of the ReduceOp chain (API listing: all_reduce / reduce / reduce_scatter take a
@@ -110,6 +166,28 @@ inline float reduce_at(const void* const* bufs, size_t i, int dtype, int op, int
   return acc;
 }
 
+// The same for int32: sums and products wrap modulo 2^32 (computed on the unsigned patterns),
+// MAX and MIN compare as signed integers.
+inline int32_t combine_i32(int32_t acc, int32_t x, int op) {
+  switch (op) {
+    case OP_MAX: return x > acc ? x : acc;
+    case OP_MIN: return x < acc ? x : acc;
+    case OP_PROD: return static_cast<int32_t>(static_cast<uint32_t>(acc) * static_cast<uint32_t>(x));
+    default: return static_cast<int32_t>(static_cast<uint32_t>(acc) + static_cast<uint32_t>(x));
+  }
+}
+
+inline int32_t reduce_at_i32(const void* const* bufs, size_t i, int op, int P) {
+  int32_t acc = static_cast<const int32_t*>(bufs[0])[i];
+  for (int p = 1; p < P; ++p) {
+    acc = combine_i32(acc, static_cast<const int32_t*>(bufs[p])[i], op);
+  }
+  return acc;
+}
+
+// int32 has no average and no gate-scaling.
+inline bool int_refused(int dtype, int op) { return dtype == DT_I32 && op == OP_AVG; }
+
 }  // namespace
 
 extern "C" {
@@ -125,11 +203,26 @@ void orc_bf16_to_f32_array(const uint16_t* in, float* out, size_t n) {
   for (size_t i = 0; i < n; ++i) out[i] = bf16_bits_to_float(in[i]);
 }
 
+uint16_t orc_f32_to_f16(float f) { return float_to_half_bits(f); }
+float orc_f16_to_f32(uint16_t h) { return half_bits_to_float(h); }
+void orc_f32_to_f16_array(const float* in, uint16_t* out, size_t n) {
+  for (size_t i = 0; i < n; ++i) out[i] = float_to_half_bits(in[i]);
+}
+void orc_f16_to_f32_array(const uint16_t* in, float* out, size_t n) {
+  for (size_t i = 0; i < n; ++i) out[i] = half_bits_to_float(in[i]);
+}
+
 // ---- all_reduce (API listing, all_reduce) ------------------------------------
 // In place: every rank's buffer ends up holding the reduction.
 int orc_allreduce(void* const* bufs, size_t n, int dtype, int op, int P) {
   if (!bufs || P < 1 || bad_dtype(dtype) || bad_op(op)) return -1;
+  if (int_refused(dtype, op)) return -3;
   for (size_t i = 0; i < n; ++i) {
+    if (dtype == DT_I32) {
+      const int32_t y = reduce_at_i32(bufs, i, op, P);
+      for (int r = 0; r < P; ++r) static_cast<int32_t*>(bufs[r])[i] = y;
+      continue;
+    }
     const float y = reduce_at(bufs, i, dtype, op, P);
     for (int r = 0; r < P; ++r) store_elem(bufs[r], i, dtype, y);
   }
@@ -141,7 +234,7 @@ int orc_allreduce(void* const* bufs, size_t n, int dtype, int op, int P) {
 // binary64, mag[i] = sum_p |x_p[i]| (the error-bound denominator).
 int orc_allreduce_ref64(const void* const* bufs, size_t n, int dtype, int op, int P,
                         double* out, double* mag) {
-  if (!bufs || P < 1 || bad_dtype(dtype) || bad_op(op)) return -1;
+  if (!bufs || P < 1 || bad_dtype(dtype) || dtype == DT_I32 || bad_op(op)) return -1;
   for (size_t i = 0; i < n; ++i) {
     double acc = 0.0, m = 0.0;
     for (int p = 0; p < P; ++p) {
@@ -162,7 +255,12 @@ int orc_allreduce_ref64(const void* const* bufs, size_t n, int dtype, int op, in
 // ---- reduce (API listing, reduce) : only the root's buffer receives the result --
 int orc_reduce(void* const* bufs, size_t n, int dtype, int op, int P, int root) {
   if (!bufs || P < 1 || root < 0 || root >= P || bad_dtype(dtype) || bad_op(op)) return -1;
+  if (int_refused(dtype, op)) return -3;
   for (size_t i = 0; i < n; ++i) {
+    if (dtype == DT_I32) {
+      static_cast<int32_t*>(bufs[root])[i] = reduce_at_i32(bufs, i, op, P);
+      continue;
+    }
     const float y = reduce_at(bufs, i, dtype, op, P);
     store_elem(bufs[root], i, dtype, y);
   }
@@ -283,9 +381,14 @@ int orc_reduce_scatter(void* const* out, const void* const* in, size_t n, int dt
                        int op, int P) {
   if (!out || !in || P < 1 || bad_dtype(dtype) || bad_op(op)) return -1;
   if (n % static_cast<size_t>(P) != 0) return -2;
+  if (int_refused(dtype, op)) return -3;
   const size_t b = n / static_cast<size_t>(P);
   for (int r = 0; r < P; ++r) {
     for (size_t j = 0; j < b; ++j) {
+      if (dtype == DT_I32) {
+        static_cast<int32_t*>(out[r])[j] = reduce_at_i32(in, static_cast<size_t>(r) * b + j, op, P);
+        continue;
+      }
       const float y = reduce_at(in, static_cast<size_t>(r) * b + j, dtype, op, P);
       store_elem(out[r], j, dtype, y);
     }
@@ -473,6 +576,7 @@ int orc_moe_combine_by_expert(void* const* out, const void* const* expert_out, c
                               int K, int E, int P, size_t row_elems, int dtype) {
   if (!out || !expert_out || !ids || !slot || !counts || T < 0 || K < 1 || E < 1 || P < 1 || E % P != 0 || bad_dtype(dtype))
     return -1;
+  if (dtype == DT_I32 && (gate || K > 1)) return -4;
   std::vector<int64_t> block_first(static_cast<size_t>(P) * E), ef(E), er(E);
   if (orc_moe_expert_layout(counts, E, P, block_first.data(), ef.data(), er.data()) != 0) return -1;
   const size_t rb = row_elems * elem_bytes(dtype);
@@ -538,6 +642,7 @@ int orc_pack(void* out, const void* in, const int32_t* slot, int64_t T, size_t r
 int orc_unpack(void* out, const void* in, const int32_t* slot, const float* gate, int64_t T,
                size_t row_elems, int dtype) {
   if (!out || !in || !slot || T < 0 || bad_dtype(dtype)) return -1;
+  if (gate && dtype == DT_I32) return -4;
   const size_t s = elem_bytes(dtype);
   const size_t rb = row_elems * s;
   for (int64_t t = 0; t < T; ++t) {

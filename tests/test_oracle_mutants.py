@@ -20,6 +20,13 @@ MUTANTS = [
     ("bf16_tie_always_up", "round_up = (kept & 1u) != 0u;", "round_up = true;"),
     ("bf16_tie_always_down", "round_up = (kept & 1u) != 0u;", "round_up = false;"),
     ("bf16_nan_to_inf", "return static_cast<uint16_t>((u >> 16) | 0x0040u);", "return static_cast<uint16_t>(u >> 16);"),
+    ("f16_tie_rounds_up", "if (rem > 0.5 || (rem == 0.5 && std::fmod(n, 2.0) == 1.0)) n += 1.0;", "if (rem >= 0.5) n += 1.0;"),
+    ("f16_truncates", "if (rem > 0.5 || (rem == 0.5 && std::fmod(n, 2.0) == 1.0)) n += 1.0;", "if (rem > 2.0) n += 1.0;"),
+    ("f16_subnormal_quantum_shrinks", "  if (E < -14) E = -14;\n", ""),
+    ("f16_no_carry_into_next_binade", "  if (n == 2048.0) {\n    E += 1;\n    n = 1024.0;\n  }", "  if (n == 2048.0) {\n    n = 2047.0;\n  }"),
+    ("f16_widen_subnormal_scale", "std::ldexp(static_cast<float>(frac), -24)", "std::ldexp(static_cast<float>(frac), -25)"),
+    ("i32_sum_saturates", "default: return static_cast<int32_t>(static_cast<uint32_t>(acc) + static_cast<uint32_t>(x));", "default: { const int64_t w = static_cast<int64_t>(acc) + x; return static_cast<int32_t>(w > 2147483647 ? 2147483647 : (w < -2147483647 - 1 ? -2147483647 - 1 : w)); }"),
+    ("i32_max_unsigned", "case OP_MAX: return x > acc ? x : acc;\n    case OP_MIN: return x < acc ? x : acc;\n    case OP_PROD: return static_cast<int32_t>(static_cast<uint32_t>(acc)", "case OP_MAX: return static_cast<uint32_t>(x) > static_cast<uint32_t>(acc) ? x : acc;\n    case OP_MIN: return x < acc ? x : acc;\n    case OP_PROD: return static_cast<int32_t>(static_cast<uint32_t>(acc)"),
     ("reduce_starts_from_zero", "float acc = load_elem(bufs[0], i, dtype);\n  for (int p = 1;", "float acc = 0.0f;\n  for (int p = 0;"),
     ("reduce_drops_last_rank", "for (int p = 1; p < P; ++p) {\n    acc = combine(acc, load_elem", "for (int p = 1; p < P - 1; ++p) {\n    acc = combine(acc, load_elem"),
     ("reduce_reverse_order", "float acc = load_elem(bufs[0], i, dtype);\n  for (int p = 1; p < P; ++p) {\n    acc = combine(acc, load_elem(bufs[p], i, dtype), op);",

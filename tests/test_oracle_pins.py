@@ -410,6 +410,93 @@ def check_route_out_of_range_ids():
     assert slot.tolist() == [0, -1, 2, -1, 1, 3] and cnt.tolist() == [2, 2] and srow.tolist() == [2, 2]
 
 
+# ============================ fp16 and int32 =====================================
+def check_f16_widening_is_numpy_float16_for_every_pattern():
+    h = np.arange(65536, dtype=np.uint16)
+    got = oracle.f16_bits_to_f32(h)
+    exp = h.view(np.float16).astype(np.float32)
+    nan = np.isnan(exp)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), exp[~nan].view(np.uint32))
+    # NaN payloads keep their place (fraction << 13)
+    assert np.array_equal(got[nan].view(np.uint32) & 0x7fffff, (h[nan].astype(np.uint32) & 0x3ff) << 13)
+
+
+def check_f16_rounding_against_numpy_and_by_hand():
+    F16 = np.float16
+    rng = np.random.default_rng(5)
+    # random binary32 patterns over the whole range, and dense samples around every fp16 value and midpoint
+    pats = rng.integers(0, 2**32, size=400000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    halves = np.arange(0x7c00, dtype=np.uint16).view(F16).astype(np.float64)          # all finite non-negative
+    mids = (halves[:-1] + halves[1:]) / 2
+    around = np.concatenate([halves, mids, np.nextafter(mids.astype(np.float32), np.float32(np.inf)).astype(np.float64),
+                             np.nextafter(mids.astype(np.float32), np.float32(-np.inf)).astype(np.float64),
+                             [65504.0, 65519.99, 65520.0, 65536.0, 1e30, 2.0**-24, 2.0**-25, 2.0**-25 * 1.0000001, 2.0**-26, 0.0]])
+    xs = np.concatenate([pats, around.astype(np.float32), -around.astype(np.float32), [np.float32(np.inf), -np.float32(np.inf)]]).astype(np.float32)
+    finite_or_inf = ~np.isnan(xs)
+    with np.errstate(over="ignore"):
+        exp = xs.astype(F16).view(np.uint16)
+    got = oracle.f32_to_f16_bits(xs)
+    assert np.array_equal(got[finite_or_inf], exp[finite_or_inf])
+    nan_in = np.isnan(xs)
+    assert ((got[nan_in] & 0x7c00) == 0x7c00).all() and ((got[nan_in] & 0x3ff) != 0).all()
+    # by hand: ties to even at 1 + 2^-11 (down to 1.0) and 1 + 3*2^-11 (up to 1 + 2^-9); 65520 overflows; 2^-25 is a tie to 0
+    by_hand = {1.0 + 2.0**-11: 0x3c00, 1.0 + 3 * 2.0**-11: 0x3c02, 65520.0: 0x7c00, 65519.0: 0x7bff, 2.0**-25: 0x0000,
+               3 * 2.0**-25: 0x0002, 2.0**-14 - 2.0**-25: 0x0400, -2.0: 0xc000}
+    for x, bits in by_hand.items():
+        assert int(oracle.f32_to_f16_bits(np.array([x], dtype=np.float32))[0]) == bits, x
+
+
+def check_f16_allreduce_brute_force():
+    """P=2 and 3: numpy's own float16 -> float32, binary32 add in rank order, -> float16."""
+    rng = np.random.default_rng(6)
+    special = np.array([0.0, -0.0, 1.0, -1.0, 65504.0, -65504.0, 6.1e-5, 6e-8, np.inf, -np.inf, 1000.0, 0.333], dtype=np.float16)
+    for P in (2, 3):
+        bufs = [np.concatenate([rng.standard_normal(500).astype(np.float16) * np.float16(100), rng.permutation(np.tile(special, 4))]) for _ in range(P)]
+        for op, f in ((SUM, None), (AVG, None), (oracle.MAX, None), (oracle.PROD, None)):
+            acc = bufs[0].astype(np.float32)
+            with np.errstate(all="ignore"):
+                for b in bufs[1:]:
+                    x = b.astype(np.float32)
+                    if op in (SUM, AVG):
+                        acc = (acc + x).astype(np.float32)
+                    elif op == oracle.PROD:
+                        acc = (acc * x).astype(np.float32)
+                    else:
+                        acc = np.where((x > acc) | np.isnan(x), x, acc)
+                if op == AVG:
+                    acc = (acc * (np.float32(1.0) / np.float32(P))).astype(np.float32)
+                exp = acc.astype(np.float16)
+            work = [b.copy() for b in bufs]
+            oracle.allreduce(work, oracle.F16, op)
+            nan = np.isnan(exp)
+            for wbuf in work:
+                assert np.array_equal(np.isnan(wbuf), nan)
+                assert np.array_equal(wbuf[~nan].view(np.uint16), exp[~nan].view(np.uint16)), (P, op)
+
+
+def check_i32_reductions_wrap_like_numpy():
+    rng = np.random.default_rng(8)
+    for P in (1, 2, 5):
+        bufs = [rng.integers(-2**31, 2**31, size=300, dtype=np.int64).astype(np.int32) for _ in range(P)]
+        for b in bufs:
+            b[:4] = [2**31 - 1, -2**31, -1, 0]
+        with np.errstate(over="ignore"):
+            exp = {SUM: np.sum(np.stack(bufs).astype(np.int64), axis=0).astype(np.int32),            # mod 2^32 of the exact sum
+                   oracle.MAX: np.max(np.stack(bufs), axis=0), oracle.MIN: np.min(np.stack(bufs), axis=0),
+                   oracle.PROD: np.array([int(np.prod([int(b[i]) for b in bufs], dtype=object)) & 0xffffffff for i in range(300)],
+                                         dtype=np.uint32).view(np.int32)}
+        for op, e in exp.items():
+            work = [b.copy() for b in bufs]
+            oracle.allreduce(work, oracle.I32, op)
+            assert all(np.array_equal(wb, e) for wb in work), (P, op)
+            if 300 % P == 0:
+                rs = oracle.reduce_scatter(bufs, oracle.I32, op)
+                assert np.array_equal(np.concatenate(rs), e)
+        with pytest.raises(ValueError):
+            oracle.allreduce([b.copy() for b in bufs], oracle.I32, AVG)
+
+
 # ============================ displacements chosen by the caller ================
 def check_alltoallv_displs_golden():
     g = gio.keyed_ints("alltoallv_displs_case.txt")
