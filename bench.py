@@ -41,8 +41,8 @@ def parse_args():
     return ap.parse_args()
 
 
-SWEEP_KERNEL_SOURCES = ("csrc/mcr_allreduce.hip", "csrc/mcr_reduce_scatter.hip", "csrc/mcr_copy.hip", "csrc/mcr_device.hpp",
-                        "csrc/mcr_dispatch.hpp", "csrc/mcr_reduce_tile.hpp", "tuning/mi355x.tbl")
+SWEEP_KERNEL_SOURCES = ("csrc/mcr_allreduce_impl.hpp", "csrc/mcr_reduce_scatter_impl.hpp", "csrc/mcr_copy.hip",
+                        "csrc/mcr_device.hpp", "csrc/mcr_dispatch.hpp", "csrc/mcr_reduce_tile.hpp", "tuning/mi355x.tbl")
 
 
 def kernel_sources_digest():

@@ -48,7 +48,14 @@ extern "C" {
 typedef struct mcr_ctx mcr_ctx;             /* library-owned: variant registry + tuning table */
 typedef struct mcr_fuse_plan mcr_fuse_plan; /* library-owned: bucket plan + device descriptors */
 
-typedef enum { MCR_F32 = 0, MCR_BF16 = 1 } mcr_dtype;
+/* Element types.  bf16 and fp16 (IEEE binary16) are widened exactly to binary32, combined in
+ * binary32 and rounded once (to nearest even) when stored.  int32 is combined in two's-complement
+ * arithmetic that wraps (sums and products modulo 2^32; MAX and MIN compare as signed), which
+ * does not depend on the order; MCR_AVG of int32 gives MCR_EOP, and the calls that scale rows by
+ * a gate weight (mcr_unpack, mcr_moe_combine, mcr_moe_combine_by_expert with a gate or K > 1)
+ * give MCR_EDTYPE for it.  The reductions on MCR_F32 and MCR_BF16 are compiled for every launch
+ * shape; on MCR_F16 and MCR_I32 the vector variants all run the nontemporal shape of their unroll. */
+typedef enum { MCR_F32 = 0, MCR_BF16 = 1, MCR_F16 = 2, MCR_I32 = 3 } mcr_dtype;
 
 /* ReduceOp of the API listing; every op runs as a left-to-right chain in rank order in
  * binary32 with one final rounding.  MCR_AVG is the sum multiplied (before that rounding) by

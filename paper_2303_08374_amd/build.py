@@ -14,7 +14,11 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmcr.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["mcr_api.hip", "mcr_allreduce.hip", "mcr_reduce_scatter.hip", "mcr_copy.hip", "mcr_moe.hip", "mcr_fuse.hip", "mcr_fused.hip"]
+# the reductions' kernels are instantiated per element type, the slowest units first
+SOURCES = ["mcr_allreduce_f32.hip", "mcr_allreduce_bf16.hip", "mcr_reduce_scatter_f32.hip", "mcr_reduce_scatter_bf16.hip",
+           "mcr_fuse.hip", "mcr_allreduce_f16.hip", "mcr_allreduce_i32.hip", "mcr_reduce_scatter_f16.hip",
+           "mcr_reduce_scatter_i32.hip", "mcr_copy.hip", "mcr_fused.hip", "mcr_moe.hip", "mcr_allreduce.hip",
+           "mcr_reduce_scatter.hip", "mcr_api.hip"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler otherwise forms packed
 # binary32 instructions from ordinary float code.
@@ -38,7 +42,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 7) -> str:
+def build(jobs: int = 8) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(_compile, SOURCES))

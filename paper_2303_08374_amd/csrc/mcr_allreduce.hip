@@ -1,99 +1,22 @@
-// all_reduce over P rank buffers in one GPU's memory (API listing of the paper).
-//
-// A streaming sum: every element index is read from all P buffers with 128-bit
-// loads, summed in rank order in binary32, optionally scaled by 1/P, rounded
-// once, and written back to all P buffers with 128-bit stores.  The thread that
-// reads an index is the only one that writes it, so in place has no race.
-// reduce (rooted) is the same kernel with the stores to all but the root's
-// buffer switched off (root >= 0).
-// Bound by HBM bandwidth: (P-1) adds per 2*P*s bytes.
-#include "mcr_reduce_tile.hpp"
+// all_reduce over P rank buffers in one GPU's memory (API listing of the paper): the dispatch
+// over the element type.  The kernels are in mcr_allreduce_impl.hpp, instantiated per element
+// type in mcr_allreduce_<type>.hip.
+#include "mcr_dispatch.hpp"
 
 namespace mcr {
-namespace {
-
-template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
-__global__ void __launch_bounds__(kBlock)
-allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root) {
-  using E = Elem<DT>;
-  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
-  CPtrTab in;
-#pragma unroll
-  for (int p = 0; p < P; ++p) in.p[p] = bufs.p[p];
-  const size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
-  if (tile < nvec) {
-    u32x4 out[U];
-    const bool full = tile + kTile <= nvec;
-    if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, 0, tile, nvec, scale, op, out);
-    else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, 0, tile, nvec, scale, op, out);
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-        if ((full || idx < nvec) && (root < 0 || root == p)) store16<NTS>(bufs.p[p], idx, out[u]);
-      }
-    }
-  }
-  // elements past the last whole vector
-  const size_t done = nvec * E::kPerVec;
-  if (blockIdx.x == 0 && done + threadIdx.x < count) {
-    const size_t i = done + threadIdx.x;
-    const float y = reduce_scalar<DT>(in, i, P, scale, op);
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
-  }
-}
 
 template <int DT>
-__global__ void __launch_bounds__(kBlock)
-allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int op, int root) {
-  using E = Elem<DT>;
-  CPtrTab in;
-  for (int p = 0; p < MCR_MAX_RANKS; ++p) in.p[p] = bufs.p[p];
-  const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += step) {
-    const float y = reduce_scalar<DT>(in, i, P, scale, op);
-    for (int p = 0; p < P; ++p)
-      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
-  }
-}
-
-}  // namespace
+int launch_allreduce_dt(const PtrTab& bufs, size_t count, int op, int P, int root, int variant, hipStream_t stream);
+extern template int launch_allreduce_dt<MCR_F32>(const PtrTab&, size_t, int, int, int, int, hipStream_t);
+extern template int launch_allreduce_dt<MCR_BF16>(const PtrTab&, size_t, int, int, int, int, hipStream_t);
+extern template int launch_allreduce_dt<MCR_F16>(const PtrTab&, size_t, int, int, int, int, hipStream_t);
+extern template int launch_allreduce_dt<MCR_I32>(const PtrTab&, size_t, int, int, int, int, hipStream_t);
 
 int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int root,
                      int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
-  const float scale = 1.0f / static_cast<float>(P);
-  if (variant == SV_SCALAR) {
-    return dispatch_dtype(dtype, [&](auto dt) {
-      constexpr int DT = decltype(dt)::value;
-      hipLaunchKernelGGL((allreduce_scalar<DT>), dim3(scalar_grid(count)), dim3(kBlock), 0, stream,
-                         bufs, count, P, scale, op, root);
-      return launch_status();
-    });
-  }
-  const size_t nvec = count / per_vec(dtype);
-  const unsigned gx = grid_x(nvec, variant);
   return dispatch_dtype(dtype, [&](auto dt) {
-    return dispatch_ranks(P, [&](auto pp) {
-      constexpr int DT = decltype(dt)::value;
-      constexpr int kP = decltype(pp)::value;
-      if (op > MCR_AVG) {
-        return dispatch_unroll(variant, [&](auto uu) {
-          hipLaunchKernelGGL((allreduce_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx), dim3(kBlock), 0,
-                             stream, bufs, nvec, count, scale, op, root);
-          return launch_status();
-        });
-      }
-      return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
-        constexpr int U = decltype(uu)::value;
-        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
-                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root);
-        return launch_status();
-      });
-    });
+    return launch_allreduce_dt<decltype(dt)::value>(bufs, count, op, P, root, variant, stream);
   });
 }
 

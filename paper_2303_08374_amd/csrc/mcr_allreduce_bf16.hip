@@ -1,0 +1,6 @@
+// all_reduce kernels for one element type.
+#include "mcr_allreduce_impl.hpp"
+
+namespace mcr {
+template int launch_allreduce_dt<MCR_BF16>(const PtrTab&, size_t, int, int, int, int, hipStream_t);
+}  // namespace mcr

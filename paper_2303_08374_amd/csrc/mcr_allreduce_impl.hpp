@@ -1,0 +1,102 @@
+// Kernels and per-element-type launcher of all_reduce over P rank buffers in one GPU's
+// memory (API listing of the paper).
+//
+// A streaming sum: every element index is read from all P buffers with 128-bit
+// loads, summed in rank order in binary32, optionally scaled by 1/P, rounded
+// once, and written back to all P buffers with 128-bit stores.  The thread that
+// reads an index is the only one that writes it, so in place has no race.
+// reduce (rooted) is the same kernel with the stores to all but the root's
+// buffer switched off (root >= 0).
+// Bound by HBM bandwidth: (P-1) adds per 2*P*s bytes.
+#pragma once
+#include "mcr_reduce_tile.hpp"
+
+namespace mcr {
+namespace {
+
+template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
+__global__ void __launch_bounds__(kBlock)
+allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root) {
+  using E = Elem<DT>;
+  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
+  CPtrTab in;
+#pragma unroll
+  for (int p = 0; p < P; ++p) in.p[p] = bufs.p[p];
+  const size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
+  if (tile < nvec) {
+    u32x4 out[U];
+    const bool full = tile + kTile <= nvec;
+    if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, 0, tile, nvec, scale, op, out);
+    else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, 0, tile, nvec, scale, op, out);
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+        if ((full || idx < nvec) && (root < 0 || root == p)) store16<NTS>(bufs.p[p], idx, out[u]);
+      }
+    }
+  }
+  // elements past the last whole vector
+  const size_t done = nvec * E::kPerVec;
+  if (blockIdx.x == 0 && done + threadIdx.x < count) {
+    const size_t i = done + threadIdx.x;
+    const typename E::acc_t y = reduce_scalar<DT>(in, i, P, scale, op);
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
+  }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kBlock)
+allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int op, int root) {
+  using E = Elem<DT>;
+  CPtrTab in;
+  for (int p = 0; p < MCR_MAX_RANKS; ++p) in.p[p] = bufs.p[p];
+  const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += step) {
+    const typename E::acc_t y = reduce_scalar<DT>(in, i, P, scale, op);
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
+  }
+}
+
+}  // namespace
+
+// One element type's launches.  Each element type is instantiated in a translation unit of its
+// own, which keeps the compile time of the reductions (16 rank counts x launch shapes) spread
+// over the build's workers.
+template <int DT>
+int launch_allreduce_dt(const PtrTab& bufs, size_t count, int op, int P, int root, int variant, hipStream_t stream) {
+  const float scale = 1.0f / static_cast<float>(P);
+  if (variant == SV_SCALAR) {
+    hipLaunchKernelGGL((allreduce_scalar<DT>), dim3(scalar_grid(count)), dim3(kBlock), 0, stream, bufs, count, P, scale, op,
+                       root);
+    return launch_status();
+  }
+  const size_t nvec = count / Elem<DT>::kPerVec;
+  const unsigned gx = grid_x(nvec, variant);
+  return dispatch_ranks(P, [&](auto pp) {
+    constexpr int kP = decltype(pp)::value;
+    if (op > MCR_AVG || !all_shapes(DT)) {
+      return dispatch_unroll(variant, [&](auto uu) {
+        hipLaunchKernelGGL((allreduce_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx), dim3(kBlock), 0,
+                           stream, bufs, nvec, count, scale, op, root);
+        return launch_status();
+      });
+    }
+    if constexpr (all_shapes(DT)) {
+      return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
+        constexpr int U = decltype(uu)::value;
+        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
+                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root);
+        return launch_status();
+      });
+    } else {
+      return static_cast<int>(MCR_EVARIANT);          // not reached: taken by the branch above
+    }
+  });
+}
+
+}  // namespace mcr

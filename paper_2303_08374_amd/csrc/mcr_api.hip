@@ -25,8 +25,10 @@ const char* const kOpNames[MCR_OP_COUNT] = {"allreduce", "reduce_scatter", "allg
 const char* const kDtypeNames[2] = {"f32", "bf16"};
 const char* const kRouteVariantNames[1] = {"wave_ballot"};
 
-bool valid_dtype(int d) { return d == MCR_F32 || d == MCR_BF16; }
+bool valid_dtype(int d) { return d >= MCR_F32 && d <= MCR_I32; }
 bool valid_redop(int o) { return o >= MCR_SUM && o <= MCR_PROD; }
+// integers have no average
+bool redop_fits(int o, int dtype) { return !(dtype == MCR_I32 && o == MCR_AVG); }
 bool valid_P(int P) { return P >= 1 && P <= MCR_MAX_RANKS; }
 int n_variants(int op) { return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : SV_COUNT; }
 
@@ -255,7 +257,7 @@ int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype
                   int variant, void* stream) {
   if (!ctx || !bufs || !valid_P(P)) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  if (!valid_redop(op)) return MCR_EOP;
+  if (!valid_redop(op) || !redop_fits(op, dtype)) return MCR_EOP;
   PtrTab tab;
   bool all16 = true;
   if (!fill_tab(tab, bufs, P, dtype, count > 0, &all16)) return MCR_EINVAL;
@@ -270,7 +272,7 @@ int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, si
                        mcr_redop op, int P, int variant, void* stream) {
   if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  if (!valid_redop(op)) return MCR_EOP;
+  if (!valid_redop(op) || !redop_fits(op, dtype)) return MCR_EOP;
   if (count % static_cast<size_t>(P) != 0) return MCR_EINVAL;
   PtrTab to;
   CPtrTab ti;
@@ -362,7 +364,7 @@ int mcr_reduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, m
                int variant, void* stream) {
   if (!ctx || !bufs || !valid_P(P) || root < 0 || root >= P) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
-  if (!valid_redop(op)) return MCR_EOP;
+  if (!valid_redop(op) || !redop_fits(op, dtype)) return MCR_EOP;
   PtrTab tab;
   bool all16 = true;
   if (!fill_tab(tab, bufs, P, dtype, count > 0, &all16)) return MCR_EINVAL;
@@ -630,6 +632,7 @@ int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int3
   if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, in, P, dtype, any && in_rows > 0, &all16) ||
       !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
     return MCR_EINVAL;
+  if (gate && dtype == MCR_I32) return MCR_EDTYPE;                    // a weight cannot scale integers
   if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
   const size_t row_bytes = row_elems * elem_bytes(dtype);
   const bool vec_ok = all16 && (row_bytes % 16 == 0);
@@ -679,6 +682,7 @@ int mcr_moe_combine(mcr_ctx* ctx, void* const* out, const void* const* expert_ou
   if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, expert_out, P, dtype, any && recv_rows > 0, &all16) ||
       !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
     return MCR_EINVAL;
+  if (gate && dtype == MCR_I32) return MCR_EDTYPE;                    // a weight cannot scale integers
   if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
   const size_t row_bytes = row_elems * elem_bytes(dtype);
   int v;
@@ -735,6 +739,7 @@ int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const*
                               int E, size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
   if (!ctx || !out || !expert_out || !expert_ids || !slot || !row_table || !valid_P(P)) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (dtype == MCR_I32 && K > 1) return MCR_EDTYPE;                   // the weighted sum is a floating-point one
   if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0 || K < 1 || K > MCR_MAX_TOPK) return MCR_EINVAL;
   if (row_elems > (size_t(1) << 28) || T > 0x7fffffffull / static_cast<size_t>(K) ||
       (reinterpret_cast<uintptr_t>(row_table) & 7u))
@@ -746,6 +751,7 @@ int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const*
   if (!fill_tab(to, out, P, dtype, any, &all16) || !fill_tab(ti, expert_out, P, dtype, any && recv_rows > 0, &all16) ||
       !fill_tab(tid, expert_ids, P, MCR_F32, any, nullptr) || !fill_tab(tsl, slot, P, MCR_F32, any, nullptr))
     return MCR_EINVAL;
+  if (gate && dtype == MCR_I32) return MCR_EDTYPE;                    // a weight cannot scale integers
   if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
   const size_t row_bytes = row_elems * elem_bytes(dtype);
   int v;
@@ -946,7 +952,7 @@ int mcr_allreduce_multi(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, mcr
                         void* stream) {
   if (!ctx || !plan || plan->ctx != ctx) return MCR_EINVAL;
   if (bucket < -1 || bucket >= plan->n_buckets) return MCR_EINVAL;
-  if (!valid_redop(op)) return MCR_EOP;
+  if (!valid_redop(op) || !redop_fits(op, plan->dtype)) return MCR_EOP;
   if (plan->bound_P == 0) return MCR_ESTATE;
   const int t0 = bucket < 0 ? 0 : plan->bucket_first[bucket];
   const int t1 = bucket < 0 ? plan->n_tensors : plan->bucket_first[bucket + 1];

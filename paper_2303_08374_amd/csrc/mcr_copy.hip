@@ -220,7 +220,7 @@ int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t coun
     const unsigned gx = capped_blocks(count, kBlock, 1u << 20);
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int kP = decltype(pp)::value;
-      if (dtype == MCR_F32)
+      if (elem_bytes(dtype) == 4)
         hipLaunchKernelGGL((allgather_kernel<4, kP, 1, false, false>), dim3(gx, P), dim3(kBlock), 0, stream, out, in, count);
       else
         hipLaunchKernelGGL((allgather_kernel<2, kP, 1, false, false>), dim3(gx, P), dim3(kBlock), 0, stream, out, in, count);
@@ -258,7 +258,7 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
     const unsigned gx = capped_blocks(b, kBlock, 1u << 16);
-    if (dtype == MCR_F32)
+    if (elem_bytes(dtype) == 4)
       hipLaunchKernelGGL((alltoall_kernel<4, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     else
       hipLaunchKernelGGL((alltoall_kernel<2, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);

@@ -51,13 +51,30 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (f32_to_bf16_rne(lo) & 0xffffu) | (f32_to_bf16_rne(hi) << 16);
 }
 
-// Element traits: how many elements one 128-bit vector holds and how a vector
-// is widened to / narrowed from binary32 lanes.
+// fp16 (IEEE binary16) <-> binary32 through the hardware conversions: widening is exact, narrowing
+// rounds to nearest even, overflows to infinity and keeps NaN a NaN.
+// The binary32 value passes through an empty asm statement on both sides.  Without it the
+// compiler merges a conversion with a neighbouring multiply into one mixed-precision
+// multiply-add whose addend is +0, and (-0) * g + (+0) is +0: the sign of a zero product
+// would be lost.  The statement emits nothing; it only keeps the value in a register of its own.
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
+  float f = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+  asm volatile("" : "+v"(f));
+  return f;
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+  asm volatile("" : "+v"(f));
+  return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+}
+
+// Element traits: how many elements one 128-bit vector holds, the type the reduction is carried
+// in (acc_t: binary32 for the floating types, int32 for int32), and how a vector is widened to /
+// narrowed from lanes of that type.
 template <int DT> struct Elem;
 template <> struct Elem<MCR_F32> {
   static constexpr int kBytes = 4;
   static constexpr int kPerVec = 4;
-  typedef float scalar_t;
+  typedef float acc_t;
   __device__ static __forceinline__ void widen(u32x4 v, float (&f)[4]) {
     f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
     f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
@@ -68,6 +85,9 @@ template <> struct Elem<MCR_F32> {
     v.z = __float_as_uint(f[2]); v.w = __float_as_uint(f[3]);
     return v;
   }
+  // one element as a bit pattern in the low bits of a word
+  __device__ static __forceinline__ float widen1(uint32_t bits) { return __uint_as_float(bits); }
+  __device__ static __forceinline__ uint32_t narrow1(float f) { return __float_as_uint(f); }
   __device__ static __forceinline__ float load1(const void* b, size_t i) {
     return reinterpret_cast<const float*>(b)[i];
   }
@@ -78,7 +98,7 @@ template <> struct Elem<MCR_F32> {
 template <> struct Elem<MCR_BF16> {
   static constexpr int kBytes = 2;
   static constexpr int kPerVec = 8;
-  typedef uint16_t scalar_t;
+  typedef float acc_t;
   __device__ static __forceinline__ void widen(u32x4 v, float (&f)[8]) {
     f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
     f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
@@ -89,11 +109,63 @@ template <> struct Elem<MCR_BF16> {
     v.z = pack_bf16x2(f[4], f[5]); v.w = pack_bf16x2(f[6], f[7]);
     return v;
   }
+  __device__ static __forceinline__ float widen1(uint32_t bits) { return __uint_as_float(bits << 16); }
+  __device__ static __forceinline__ uint32_t narrow1(float f) { return f32_to_bf16_rne(f) & 0xffffu; }
   __device__ static __forceinline__ float load1(const void* b, size_t i) {
-    return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(b)[i]) << 16);
+    return widen1(reinterpret_cast<const uint16_t*>(b)[i]);
   }
   __device__ static __forceinline__ void store1(void* b, size_t i, float f) {
-    reinterpret_cast<uint16_t*>(b)[i] = static_cast<uint16_t>(f32_to_bf16_rne(f));
+    reinterpret_cast<uint16_t*>(b)[i] = static_cast<uint16_t>(narrow1(f));
+  }
+};
+template <> struct Elem<MCR_F16> {
+  static constexpr int kBytes = 2;
+  static constexpr int kPerVec = 8;
+  typedef float acc_t;
+  __device__ static __forceinline__ void widen(u32x4 v, float (&f)[8]) {
+    f[0] = f16_bits_to_f32(v.x & 0xffffu); f[1] = f16_bits_to_f32(v.x >> 16);
+    f[2] = f16_bits_to_f32(v.y & 0xffffu); f[3] = f16_bits_to_f32(v.y >> 16);
+    f[4] = f16_bits_to_f32(v.z & 0xffffu); f[5] = f16_bits_to_f32(v.z >> 16);
+    f[6] = f16_bits_to_f32(v.w & 0xffffu); f[7] = f16_bits_to_f32(v.w >> 16);
+  }
+  __device__ static __forceinline__ u32x4 narrow(const float (&f)[8]) {
+    u32x4 v;
+    v.x = f32_to_f16_bits(f[0]) | (f32_to_f16_bits(f[1]) << 16);
+    v.y = f32_to_f16_bits(f[2]) | (f32_to_f16_bits(f[3]) << 16);
+    v.z = f32_to_f16_bits(f[4]) | (f32_to_f16_bits(f[5]) << 16);
+    v.w = f32_to_f16_bits(f[6]) | (f32_to_f16_bits(f[7]) << 16);
+    return v;
+  }
+  __device__ static __forceinline__ float widen1(uint32_t bits) { return f16_bits_to_f32(bits & 0xffffu); }
+  __device__ static __forceinline__ uint32_t narrow1(float f) { return f32_to_f16_bits(f); }
+  __device__ static __forceinline__ float load1(const void* b, size_t i) {
+    return widen1(reinterpret_cast<const uint16_t*>(b)[i]);
+  }
+  __device__ static __forceinline__ void store1(void* b, size_t i, float f) {
+    reinterpret_cast<uint16_t*>(b)[i] = static_cast<uint16_t>(narrow1(f));
+  }
+};
+template <> struct Elem<MCR_I32> {
+  static constexpr int kBytes = 4;
+  static constexpr int kPerVec = 4;
+  typedef int32_t acc_t;
+  __device__ static __forceinline__ void widen(u32x4 v, int32_t (&f)[4]) {
+    f[0] = static_cast<int32_t>(v.x); f[1] = static_cast<int32_t>(v.y);
+    f[2] = static_cast<int32_t>(v.z); f[3] = static_cast<int32_t>(v.w);
+  }
+  __device__ static __forceinline__ u32x4 narrow(const int32_t (&f)[4]) {
+    u32x4 v;
+    v.x = static_cast<uint32_t>(f[0]); v.y = static_cast<uint32_t>(f[1]);
+    v.z = static_cast<uint32_t>(f[2]); v.w = static_cast<uint32_t>(f[3]);
+    return v;
+  }
+  __device__ static __forceinline__ int32_t widen1(uint32_t bits) { return static_cast<int32_t>(bits); }
+  __device__ static __forceinline__ uint32_t narrow1(int32_t x) { return static_cast<uint32_t>(x); }
+  __device__ static __forceinline__ int32_t load1(const void* b, size_t i) {
+    return reinterpret_cast<const int32_t*>(b)[i];
+  }
+  __device__ static __forceinline__ void store1(void* b, size_t i, int32_t x) {
+    reinterpret_cast<int32_t*>(b)[i] = x;
   }
 };
 
@@ -107,6 +179,22 @@ __device__ __forceinline__ float combine(float acc, float x, int op) {
     default: return acc + x;
   }
 }
+// int32: sums and products wrap modulo 2^32.
+__device__ __forceinline__ int32_t combine(int32_t acc, int32_t x, int op) {
+  switch (op) {
+    case MCR_MAX: return x > acc ? x : acc;
+    case MCR_MIN: return x < acc ? x : acc;
+    case MCR_PROD: return static_cast<int32_t>(static_cast<uint32_t>(acc) * static_cast<uint32_t>(x));
+    default: return static_cast<int32_t>(static_cast<uint32_t>(acc) + static_cast<uint32_t>(x));
+  }
+}
+__device__ __forceinline__ float plain_sum(float a, float b) { return a + b; }
+__device__ __forceinline__ int32_t plain_sum(int32_t a, int32_t b) {
+  return static_cast<int32_t>(static_cast<uint32_t>(a) + static_cast<uint32_t>(b));
+}
+// The AVG step; integers have no average (the entry points refuse it), so theirs is the identity.
+__device__ __forceinline__ float avg_step(float acc, float scale) { return acc * scale; }
+__device__ __forceinline__ int32_t avg_step(int32_t acc, float) { return acc; }
 
 // Lanes of this wavefront with a lower lane id.
 __device__ __forceinline__ uint64_t lanemask_lt() {

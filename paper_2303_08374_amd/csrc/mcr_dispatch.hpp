@@ -27,8 +27,23 @@ template <class F>
 inline int dispatch_dtype(int dtype, F&& f) {
   if (dtype == MCR_F32) return f(Int<MCR_F32>{});
   if (dtype == MCR_BF16) return f(Int<MCR_BF16>{});
+  if (dtype == MCR_F16) return f(Int<MCR_F16>{});
+  if (dtype == MCR_I32) return f(Int<MCR_I32>{});
   return MCR_EDTYPE;
 }
+
+// the element types a gate weight can scale
+template <class F>
+inline int dispatch_float_dtype(int dtype, F&& f) {
+  if (dtype == MCR_F32) return f(Int<MCR_F32>{});
+  if (dtype == MCR_BF16) return f(Int<MCR_BF16>{});
+  if (dtype == MCR_F16) return f(Int<MCR_F16>{});
+  return MCR_EDTYPE;
+}
+
+// The reductions on the hot element types get every launch shape; on fp16 and int32 they are
+// compiled like the generic ReduceOps, for the variant's unroll with nontemporal loads and stores.
+constexpr bool all_shapes(int dtype) { return dtype == MCR_F32 || dtype == MCR_BF16; }
 
 // f(Int<U>, Bool<NT loads>, Bool<NT stores>) for the vector launch shapes
 template <class F>

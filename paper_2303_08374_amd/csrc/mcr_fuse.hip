@@ -95,18 +95,18 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
     for (int u = 0; u < 4; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
       if (idx < nv) {
-        float acc[W];
+        typename E::acc_t acc[W];
         E::widen(v[u][0], acc);
 #pragma unroll
         for (int p = 1; p < P; ++p) {
-          float x[W];
+          typename E::acc_t x[W];
           E::widen(v[u][p], x);
 #pragma unroll
-          for (int k = 0; k < W; ++k) acc[k] = GENERIC ? combine(acc[k], x[k], op) : acc[k] + x[k];
+          for (int k = 0; k < W; ++k) acc[k] = GENERIC ? combine(acc[k], x[k], op) : plain_sum(acc[k], x[k]);
         }
         if (op == MCR_AVG) {
 #pragma unroll
-          for (int k = 0; k < W; ++k) acc[k] = acc[k] * scale;
+          for (int k = 0; k < W; ++k) acc[k] = avg_step(acc[k], scale);
         }
         y[u] = E::narrow(acc);
       }
@@ -122,10 +122,10 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
     done = static_cast<uint64_t>(nv) * W;
   }
   for (uint64_t e = done + threadIdx.x; e < ne; e += kBlock) {
-    float acc = E::load1(base[0], e);
+    typename E::acc_t acc = E::load1(base[0], e);
 #pragma unroll
-    for (int p = 1; p < P; ++p) acc = GENERIC ? combine(acc, E::load1(base[p], e), op) : acc + E::load1(base[p], e);
-    if (op == MCR_AVG) acc = acc * scale;
+    for (int p = 1; p < P; ++p) acc = GENERIC ? combine(acc, E::load1(base[p], e), op) : plain_sum(acc, E::load1(base[p], e));
+    if (op == MCR_AVG) acc = avg_step(acc, scale);
 #pragma unroll
     for (int p = 0; p < P; ++p) E::store1(base[p], e, acc);
   }
@@ -161,7 +161,7 @@ int launch_fuse(mcr_ctx*, const mcr_fuse_plan* plan, int bucket, const PtrTab& f
     if (variant == SV_SCALAR) return go(eb, un, Bool<false>{}, Bool<false>{}, Bool<true>{});
     return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(eb, un, ntl, nts, Bool<false>{}); });
   };
-  if (plan->dtype == MCR_F32) return unfuse ? by_shape(Int<4>{}, Bool<true>{}) : by_shape(Int<4>{}, Bool<false>{});
+  if (elem_bytes(plan->dtype) == 4) return unfuse ? by_shape(Int<4>{}, Bool<true>{}) : by_shape(Int<4>{}, Bool<false>{});
   return unfuse ? by_shape(Int<2>{}, Bool<true>{}) : by_shape(Int<2>{}, Bool<false>{});
 }
 
@@ -176,22 +176,26 @@ int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, 
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int DT = decltype(dt)::value;
       constexpr int kP = decltype(pp)::value;
-      if (op > MCR_AVG) {      // the other ReduceOps: one nontemporal shape, or the element path
+      if (op > MCR_AVG || !all_shapes(DT)) {      // the other ReduceOps and element types: one nontemporal shape, or the element path
         if (variant == SV_SCALAR)
           hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
         else
           hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, true, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
         return launch_status();
       }
-      if (variant == SV_SCALAR) {
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
-        return launch_status();
+      if constexpr (all_shapes(DT)) {
+        if (variant == SV_SCALAR) {
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+          return launch_status();
+        }
+        return dispatch_hint(variant, [&](auto ntl, auto nts) {
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false, false>), dim3(c1 - c0),
+                             dim3(kBlock), 0, stream, d, c0, scale, op);
+          return launch_status();
+        });
+      } else {
+        return static_cast<int>(MCR_EVARIANT);          // not reached: taken by the branch above
       }
-      return dispatch_hint(variant, [&](auto ntl, auto nts) {
-        hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false, false>), dim3(c1 - c0),
-                           dim3(kBlock), 0, stream, d, c0, scale, op);
-        return launch_status();
-      });
     });
   });
 }

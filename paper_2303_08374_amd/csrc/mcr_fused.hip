@@ -148,12 +148,8 @@ template <int DT, int UB, class U> __device__ __forceinline__ U scale_unit(U v, 
     return E::narrow(f);
   } else {
     // one element per unit
-    float x;
-    if constexpr (DT == MCR_F32) x = __uint_as_float(static_cast<uint32_t>(v));
-    else x = __uint_as_float(static_cast<uint32_t>(v) << 16);
-    const float y = g * x;
-    if constexpr (DT == MCR_F32) return static_cast<U>(__float_as_uint(y));
-    else return static_cast<U>(f32_to_bf16_rne(y));
+    const float y = g * Elem<DT>::widen1(static_cast<uint32_t>(v));
+    return static_cast<U>(Elem<DT>::narrow1(y));
   }
 }
 
@@ -428,13 +424,11 @@ template <int DT, int UB> struct UnitF32 {
   typedef typename RowUnit<UB>::type U;
   __device__ static __forceinline__ void widen(U v, float (&f)[kN]) {
     if constexpr (UB == 16) Elem<DT>::widen(v, f);
-    else if constexpr (DT == MCR_F32) f[0] = __uint_as_float(static_cast<uint32_t>(v));
-    else f[0] = __uint_as_float(static_cast<uint32_t>(v) << 16);
+    else f[0] = Elem<DT>::widen1(static_cast<uint32_t>(v));
   }
   __device__ static __forceinline__ U narrow(const float (&f)[kN]) {
     if constexpr (UB == 16) return Elem<DT>::narrow(f);
-    else if constexpr (DT == MCR_F32) return static_cast<U>(__float_as_uint(f[0]));
-    else return static_cast<U>(f32_to_bf16_rne(f[0]));
+    else return static_cast<U>(Elem<DT>::narrow1(f[0]));
   }
 };
 
@@ -580,9 +574,12 @@ int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, c
                        const int64_t* splits, size_t T, size_t recv_rows, size_t row_elems, int dtype, int P, int variant,
                        hipStream_t stream) {
   if (T == 0 || row_elems == 0) return MCR_OK;
+  const int top_k = 1;
   CPtrTab g;
   for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
-  return dispatch_dtype(dtype, [&](auto dt) {
+  // without a gate (and with one choice per token) rows are copied: only the element size matters
+  const int kernel_dtype = (gate || top_k > 1) ? dtype : (elem_bytes(dtype) == 4 ? MCR_F32 : MCR_BF16);
+  return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
     auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
@@ -641,9 +638,12 @@ int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& exp
                                  const CPtrTab& slot, const CPtrTab* gate, const int64_t* row_table, int E, size_t T, int K,
                                  size_t recv_rows, size_t row_elems, int dtype, int P, int variant, hipStream_t stream) {
   if (T == 0 || row_elems == 0) return MCR_OK;
+  const int top_k = K;
   CPtrTab g;
   for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
-  return dispatch_dtype(dtype, [&](auto dt) {
+  // without a gate (and with one choice per token) rows are copied: only the element size matters
+  const int kernel_dtype = (gate || top_k > 1) ? dtype : (elem_bytes(dtype) == 4 ? MCR_F32 : MCR_BF16);
+  return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
     if (K > 1) {

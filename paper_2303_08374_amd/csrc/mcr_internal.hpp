@@ -73,8 +73,8 @@ struct mcr_fuse_plan {
 namespace mcr {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline size_t elem_bytes(int dtype) { return dtype == MCR_F32 ? 4 : 2; }
-inline int per_vec(int dtype) { return dtype == MCR_F32 ? 4 : 8; }
+inline size_t elem_bytes(int dtype) { return (dtype == MCR_F32 || dtype == MCR_I32) ? 4 : 2; }
+inline int per_vec(int dtype) { return (dtype == MCR_F32 || dtype == MCR_I32) ? 4 : 8; }
 
 // Elements one workgroup covers per tensor chunk in the multi-tensor kernels
 // (fuse / unfuse / allreduce_multi): 256 threads x 4 vectors of 16 bytes.

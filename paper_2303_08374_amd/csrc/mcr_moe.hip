@@ -189,12 +189,8 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
         v = scale_vec<DT>(v, g);
       } else {
         // one element per unit
-        float x;
-        if constexpr (DT == MCR_F32) x = __uint_as_float(static_cast<uint32_t>(v));
-        else x = __uint_as_float(static_cast<uint32_t>(v) << 16);
-        const float y = g * x;
-        if constexpr (DT == MCR_F32) v = static_cast<U>(__float_as_uint(y));
-        else v = static_cast<U>(f32_to_bf16_rne(y));
+        const float y = g * Elem<DT>::widen1(static_cast<uint32_t>(v));
+        v = static_cast<U>(Elem<DT>::narrow1(y));
       }
     }
     if constexpr (NTS) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
@@ -252,7 +248,9 @@ int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab&
   if (T == 0 || row_elems == 0) return MCR_OK;
   CPtrTab g;
   for (int i = 0; i < MCR_MAX_RANKS; ++i) g.p[i] = gate ? gate->p[i] : nullptr;
-  return dispatch_dtype(dtype, [&](auto dt) {
+  // without a gate the rows are copied, and only the element size matters
+  const int kernel_dtype = gate ? dtype : (elem_bytes(dtype) == 4 ? MCR_F32 : MCR_BF16);
+  return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
     auto go = [&](auto ub, auto ntl, auto nts, auto gc) {

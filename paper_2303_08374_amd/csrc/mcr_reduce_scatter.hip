@@ -1,81 +1,23 @@
-// reduce_scatter over P rank buffers in one GPU's memory (API listing of the
-// paper; it has no root): rank r receives slice r of the rank-order sum.
-// P reads and one 1/P-size write per element: the most read-heavy of the four
-// collectives.  Bound by HBM bandwidth.
-#include "mcr_reduce_tile.hpp"
+// reduce_scatter over P rank buffers in one GPU's memory (API listing of the paper; it has no
+// root): the dispatch over the element type.  The kernels are in mcr_reduce_scatter_impl.hpp,
+// instantiated per element type in mcr_reduce_scatter_<type>.hip.
+#include "mcr_dispatch.hpp"
 
 namespace mcr {
-namespace {
-
-// blockIdx.y = destination rank r; slice r of every input is bvec vectors long.
-template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
-__global__ void __launch_bounds__(kBlock)
-reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
-  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
-  const unsigned r = blockIdx.y;
-  void* dst = out.p[r];
-  const size_t off = static_cast<size_t>(r) * bvec;
-  const size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
-  if (tile >= bvec) return;
-  u32x4 res[U];
-  const bool full = tile + kTile <= bvec;
-  if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, off, tile, bvec, scale, op, res);
-  else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, off, tile, bvec, scale, op, res);
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-    if (full || idx < bvec) store16<NTS>(dst, idx, res[u]);
-  }
-}
 
 template <int DT>
-__global__ void __launch_bounds__(kBlock)
-reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, int P, float scale, int op) {
-  using E = Elem<DT>;
-  const unsigned r = blockIdx.y;
-  void* dst = out.p[r];
-  const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
-  for (size_t j = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; j < b; j += step) {
-    const float y = reduce_scalar<DT>(in, static_cast<size_t>(r) * b + j, P, scale, op);
-    E::store1(dst, j, y);
-  }
-}
-
-}  // namespace
+int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count, int op, int P, int variant,
+                             hipStream_t stream);
+extern template int launch_reduce_scatter_dt<MCR_F32>(const PtrTab&, const CPtrTab&, size_t, int, int, int, hipStream_t);
+extern template int launch_reduce_scatter_dt<MCR_BF16>(const PtrTab&, const CPtrTab&, size_t, int, int, int, hipStream_t);
+extern template int launch_reduce_scatter_dt<MCR_F16>(const PtrTab&, const CPtrTab&, size_t, int, int, int, hipStream_t);
+extern template int launch_reduce_scatter_dt<MCR_I32>(const PtrTab&, const CPtrTab&, size_t, int, int, int, hipStream_t);
 
 int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype,
                           int op, int P, int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
-  const float scale = 1.0f / static_cast<float>(P);
-  const size_t b = count / static_cast<size_t>(P);
-  if (variant == SV_SCALAR) {
-    return dispatch_dtype(dtype, [&](auto dt) {
-      constexpr int DT = decltype(dt)::value;
-      hipLaunchKernelGGL((reduce_scatter_scalar<DT>), dim3(scalar_grid(b), P), dim3(kBlock), 0, stream,
-                         out, in, b, P, scale, op);
-      return launch_status();
-    });
-  }
-  const size_t bvec = b / per_vec(dtype);
-  const unsigned gx = grid_x(bvec, variant);
   return dispatch_dtype(dtype, [&](auto dt) {
-    return dispatch_ranks(P, [&](auto pp) {
-      constexpr int DT = decltype(dt)::value;
-      constexpr int kP = decltype(pp)::value;
-      if (op > MCR_AVG) {
-        return dispatch_unroll(variant, [&](auto uu) {
-          hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx, P), dim3(kBlock), 0,
-                             stream, out, in, bvec, scale, op);
-          return launch_status();
-        });
-      }
-      return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
-        constexpr int U = decltype(uu)::value;
-        hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
-                           dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, op);
-        return launch_status();
-      });
-    });
+    return launch_reduce_scatter_dt<decltype(dt)::value>(out, in, count, op, P, variant, stream);
   });
 }
 

@@ -31,18 +31,18 @@ __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off
   for (int u = 0; u < U; ++u) {
     const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
     if (FULL || idx < nvec) {
-      float acc[W];
+      typename E::acc_t acc[W];
       E::widen(v[u][0], acc);
 #pragma unroll
       for (int p = 1; p < P; ++p) {
-        float x[W];
+        typename E::acc_t x[W];
         E::widen(v[u][p], x);
 #pragma unroll
-        for (int k = 0; k < W; ++k) acc[k] = GENERIC ? combine(acc[k], x[k], op) : acc[k] + x[k];
+        for (int k = 0; k < W; ++k) acc[k] = GENERIC ? combine(acc[k], x[k], op) : plain_sum(acc[k], x[k]);
       }
       if (op == MCR_AVG) {
 #pragma unroll
-        for (int k = 0; k < W; ++k) acc[k] = acc[k] * scale;
+        for (int k = 0; k < W; ++k) acc[k] = avg_step(acc[k], scale);
       }
       out[u] = E::narrow(acc);
     }
@@ -50,14 +50,15 @@ __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off
 }
 
 template <int DT>
-__device__ __forceinline__ float reduce_scalar(const CPtrTab& in, size_t i, int P, float scale,
-                                               int op) {
+__device__ __forceinline__ typename Elem<DT>::acc_t reduce_scalar(const CPtrTab& in, size_t i, int P, float scale,
+                                                                   int op) {
   using E = Elem<DT>;
-  float acc = E::load1(in.p[0], i);
+  typename E::acc_t acc = E::load1(in.p[0], i);
   for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(in.p[p], i), op);
-  if (op == MCR_AVG) acc = acc * scale;
+  if (op == MCR_AVG) acc = avg_step(acc, scale);
   return acc;
 }
+
 
 // The launch shapes the generic-op kernels are compiled for: the variant's unroll, nontemporal
 // loads and stores.  f(Int<U>)

@@ -11,7 +11,7 @@ import ctypes
 import os
 from typing import List, Optional, Sequence, Union
 
-F32, BF16 = 0, 1
+F32, BF16, F16, I32 = 0, 1, 2, 3
 SUM, AVG, MAX, MIN, PROD = 0, 1, 2, 3, 4
 AUTO = -1
 MAX_RANKS = 16

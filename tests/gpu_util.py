@@ -31,7 +31,7 @@ def to_host(t: torch.Tensor, like: np.dtype) -> np.ndarray:
 
 
 def dev_empty(n: int, dtype: int, fill=None) -> torch.Tensor:
-    td = torch.float32 if dtype == mcr.F32 else torch.int16
+    td = {mcr.F32: torch.float32, mcr.BF16: torch.int16, mcr.F16: torch.float16, mcr.I32: torch.int32}[dtype]
     t = torch.empty(n, dtype=td, device="cuda")
     if fill is not None:
         t.fill_(fill)
@@ -55,7 +55,9 @@ def assert_bits_equal(got: np.ndarray, exp: np.ndarray, what=""):
 
 def assert_reduced_equal(got: np.ndarray, exp: np.ndarray, dtype: int, what=""):
     """Reduced outputs: bit-equal except that a NaN only has to be a NaN."""
-    if dtype == mcr.F32:
+    if dtype == mcr.I32:
+        return assert_bits_equal(got, exp, what)
+    if dtype in (mcr.F32, mcr.F16):
         gn, en = np.isnan(got), np.isnan(exp)
     else:
         isnan = lambda h: ((h & 0x7F80) == 0x7F80) & ((h & 0x7F) != 0)
@@ -67,6 +69,6 @@ def assert_reduced_equal(got: np.ndarray, exp: np.ndarray, dtype: int, what=""):
 VEC_VARIANTS = list(range(1, 13))          # every 128-bit launch shape
 ALL_VARIANTS = [0] + VEC_VARIANTS
 ALLGATHER_EXTRA = [13, 14, 15]             # super-chunk forms of all_gather
-NPDT = {mcr.F32: np.float32, mcr.BF16: np.uint16}
-EB = {mcr.F32: 4, mcr.BF16: 2}
-assert (oracle.F32, oracle.BF16, oracle.SUM, oracle.AVG) == (mcr.F32, mcr.BF16, mcr.SUM, mcr.AVG)
+NPDT = {mcr.F32: np.float32, mcr.BF16: np.uint16, mcr.F16: np.float16, mcr.I32: np.int32}
+EB = {mcr.F32: 4, mcr.BF16: 2, mcr.F16: 2, mcr.I32: 4}
+assert (oracle.F32, oracle.BF16, oracle.F16, oracle.I32, oracle.SUM, oracle.AVG) == (mcr.F32, mcr.BF16, mcr.F16, mcr.I32, mcr.SUM, mcr.AVG)
