@@ -387,6 +387,34 @@ def dispatch_overhead(ctx, P: int = inputs.SWEEP_P) -> Dict:
     return out
 
 
+def graph_replay(ctx, P: int = inputs.SWEEP_P, max_bytes: int = 1 << 20, reps: int = 20) -> Dict:
+    """The launch-bound part of the op sweep (every cell up to `max_bytes` per rank) issued call by
+    call and replayed from one HIP graph: the entry points only enqueue kernels, so the whole batch
+    can be captured once and replayed without the per-call host cost."""
+    from . import sweep
+    cells = [c for c in sweep.make_cells(P, inputs.SWEEP_OPS, inputs.SWEEP_DTYPES, inputs.SWEEP_BYTES) if c.M <= max_bytes]
+    arena = sweep.Arena(max(c.footprint for c in cells) * 2 + (64 << 20), seed=inputs.SWEEP_SEED)
+    bases = [arena.take(c.footprint) for c in cells]
+
+    def batch(stream):
+        for c, b in zip(cells, bases):
+            c.launch(ctx, b, mcr.AUTO, stream)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        batch(None)                                           # warm every kernel up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        batch(torch.cuda.current_stream().cuda_stream)
+    eager_ms = sweep.time_launches(lambda: batch(None), reps)
+    graph_ms = sweep.time_launches(graph.replay, reps)
+    return {"launches": len(cells), "max_bytes_per_rank": max_bytes, "eager_us": round(eager_ms * 1e3, 1),
+            "graph_us": round(graph_ms * 1e3, 1), "eager_us_per_launch": round(eager_ms * 1e3 / len(cells), 2),
+            "graph_us_per_launch": round(graph_ms * 1e3 / len(cells), 2), "speedup": round(eager_ms / graph_ms, 2)}
+
+
 def run_all(ctx) -> Dict:
     out = {"allreduce_small": allreduce_small(ctx)}
     torch.cuda.empty_cache()
@@ -399,5 +427,7 @@ def run_all(ctx) -> Dict:
     out["small_tensor_path"] = small_tensor_path(ctx)
     torch.cuda.empty_cache()
     out["dispatch_overhead_alltoall"] = dispatch_overhead(ctx)
+    torch.cuda.empty_cache()
+    out["small_cells_graph_replay"] = graph_replay(ctx)
     torch.cuda.empty_cache()
     return out
