@@ -213,60 +213,81 @@ moe_combine_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gat
 // sender is ordered by expert, row(p, t) = row_table[p][id] + slot[p][t] with
 //   row_table[p][e] = first row of block (p, e) - (rows sender p packs before expert e).
 
-// Exclusive prefix sum of one value per thread over a workgroup of kLayoutBlock threads.
-constexpr int kLayoutBlock = 512;   // >= MCR_MAX_EXPERTS: thread e owns expert e
-__device__ __forceinline__ long long block_exclusive_scan(long long v, long long* wave_total) {
+// One workgroup of kLayoutBlock threads; thread e owns expert e.
+constexpr int kLayoutBlock = 512;   // >= MCR_MAX_EXPERTS
+constexpr int kLayoutWaves = kLayoutBlock / kWave;
+
+// Inclusive prefix sum over the lanes of a wavefront.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
   const unsigned lane = __lane_id();
-  const unsigned w = threadIdx.x / kWave;
-  long long incl = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int up = __shfl_up(v, d);
+    if (lane >= static_cast<unsigned>(d)) v += up;
+  }
+  return v;
+}
+
+// Steps: (1) counts to LDS; (2) thread e walks its column: rows above each sender's block and the
+// expert's total; (3) one workgroup-wide scan of the totals gives expert_first; (4) wave w turns
+// the rows of senders w and w + 8 into exclusive prefix sums over the experts (what a sender packs
+// before expert e), 64 experts at a time with a carry, no workgroup barrier inside; (5) thread e
+// writes its column of the table.
+__global__ void __launch_bounds__(kLayoutBlock)
+moe_expert_layout_kernel(CPtrTab counts, int E, int P, int64_t* row_table, int64_t* expert_first, int64_t* expert_rows) {
+  __shared__ int32_t cnt[MCR_MAX_RANKS][MCR_MAX_EXPERTS];
+  __shared__ long long wave_total[kLayoutWaves];
+  __shared__ long long before_expert[kLayoutBlock];
+  const int e = threadIdx.x;
+  const unsigned lane = __lane_id();
+  const int wave = threadIdx.x / kWave;
+  const bool live = e < E;
+  const int per_rank = E / P;
+  for (int p = 0; p < P; ++p) {
+    int32_t x = 0;
+    if (live) x = static_cast<const int32_t*>(counts.p[p])[e];
+    cnt[p][e] = x > 0 ? x : 0;
+  }
+  __syncthreads();
+  int32_t above[MCR_MAX_RANKS];
+  long long rows = 0;
+#pragma unroll
+  for (int p = 0; p < MCR_MAX_RANKS; ++p) {
+    above[p] = static_cast<int32_t>(rows);          // < 2^31: at most P * T rows reach one rank's expert
+    if (p < P) rows += cnt[p][e];
+  }
+  // workgroup-wide exclusive scan of the experts' totals
+  long long incl = rows;
 #pragma unroll
   for (int d = 1; d < kWave; d <<= 1) {
     const long long up = __shfl_up(incl, d);
     if (lane >= static_cast<unsigned>(d)) incl += up;
   }
-  if (lane == kWave - 1) wave_total[w] = incl;
+  if (lane == kWave - 1) wave_total[wave] = incl;
   __syncthreads();
   long long before = 0;
-  for (unsigned i = 0; i < w; ++i) before += wave_total[i];
-  __syncthreads();
-  return before + incl - v;
-}
-
-__global__ void __launch_bounds__(kLayoutBlock)
-moe_expert_layout_kernel(CPtrTab counts, int E, int P, int64_t* row_table, int64_t* expert_first, int64_t* expert_rows) {
-  __shared__ long long wave_total[kLayoutBlock / kWave];
-  __shared__ long long before_expert[kLayoutBlock];
-  const int e = threadIdx.x;
-  const bool live = e < E;
-  const int per_rank = E / P;
-  int32_t c[MCR_MAX_RANKS];
-  long long rows = 0;
-#pragma unroll
-  for (int p = 0; p < MCR_MAX_RANKS; ++p) {
-    c[p] = 0;
-    if (live && p < P) {
-      const int32_t x = static_cast<const int32_t*>(counts.p[p])[e];
-      c[p] = x > 0 ? x : 0;
-    }
-    rows += c[p];
-  }
-  const long long excl = block_exclusive_scan(rows, wave_total);
-  before_expert[threadIdx.x] = excl;
-  __syncthreads();
-  const long long first = live ? excl - before_expert[(e / per_rank) * per_rank] : 0;
-  if (live) {
-    expert_first[e] = first;
-    expert_rows[e] = rows;
-  }
-  long long above = 0;
-#pragma unroll
-  for (int p = 0; p < MCR_MAX_RANKS; ++p) {
-    if (p < P) {                                                       // uniform
-      const long long packed_before = block_exclusive_scan(c[p], wave_total);
-      if (live) row_table[static_cast<size_t>(p) * E + e] = first + above - packed_before;
-      above += c[p];
+  for (int w = 0; w < wave; ++w) before += wave_total[w];
+  const long long excl = before + incl - rows;
+  before_expert[e] = excl;
+  // rows of cnt -> what each sender packs before the expert
+  for (int p = wave; p < P; p += kLayoutWaves) {
+    int carry = 0;
+    for (int e0 = 0; e0 < E; e0 += kWave) {
+      const int idx = e0 + static_cast<int>(lane);
+      const int c = idx < E ? cnt[p][idx] : 0;
+      const int inc = wave_inclusive_scan(c);
+      if (idx < E) cnt[p][idx] = carry + inc - c;
+      carry += __shfl(inc, kWave - 1);
     }
   }
+  __syncthreads();
+  if (!live) return;
+  const long long first = excl - before_expert[(e / per_rank) * per_rank];
+  expert_first[e] = first;
+  expert_rows[e] = rows;
+#pragma unroll
+  for (int p = 0; p < MCR_MAX_RANKS; ++p)
+    if (p < P) row_table[static_cast<size_t>(p) * E + e] = first + above[p] - cnt[p][e];
 }
 
 // Where token t of this sender goes: rank (negative: nowhere) and row in that rank's buffer.

@@ -18,6 +18,7 @@ namespace {
 // by latency, not bandwidth.
 constexpr int kRouteWaves = 16;
 constexpr int kRouteBlock = kRouteWaves * kWave;
+constexpr int kRouteBatch = 8;    // 64-token steps whose ids are loaded together
 
 __device__ __forceinline__ uint64_t same_id_mask(int id, bool valid, int nbits) {
   uint64_t mask = __ballot(valid);
@@ -51,12 +52,23 @@ moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* s
   const int s_begin = wave * steps_per_wave;
   const int s_end = min(steps_total, s_begin + steps_per_wave);
 
-  for (int s = s_begin; s < s_end; ++s) {
-    const int t = s * kWave + lane;
-    const int id = (t < T) ? ids[t] : -1;
-    const bool valid = id >= 0 && id < E;
-    const uint64_t mask = same_id_mask(id, valid, nbits);
-    if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);   // lowest lane of the group
+  // kRouteBatch steps at a time: all their ids are requested before the first is used, so the
+  // loop pays the memory latency once per batch, not once per step
+  for (int s0 = s_begin; s0 < s_end; s0 += kRouteBatch) {
+    int idv[kRouteBatch];
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
+      idv[j] = (s0 + j < s_end && t < T) ? ids[t] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      if (s0 + j >= s_end) break;                                  // uniform over the wavefront
+      const int id = idv[j];
+      const bool valid = id >= 0 && id < E;
+      const uint64_t mask = same_id_mask(id, valid, nbits);
+      if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);   // lowest lane of the group
+    }
   }
   __syncthreads();
 
@@ -97,21 +109,31 @@ moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* s
     splits[static_cast<size_t>(rank) * P + tid] = a;
   }
 
-  for (int s = s_begin; s < s_end; ++s) {
-    const int t = s * kWave + lane;
-    const int id = (t < T) ? ids[t] : -1;
-    const bool valid = id >= 0 && id < E;
-    const uint64_t mask = same_id_mask(id, valid, nbits);
-    int out = -1;
-    if (valid) {
-      const int pos = wave_cnt[wave][id] + __popcll(mask & below);
-      if (pos < C) out = ebase[id] + pos;
+  for (int s0 = s_begin; s0 < s_end; s0 += kRouteBatch) {
+    int idv[kRouteBatch];
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
+      idv[j] = (s0 + j < s_end && t < T) ? ids[t] : -1;
     }
-    // every lane has read the running position before the group's first lane moves it on
-    __builtin_amdgcn_wave_barrier();
-    if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);
-    __builtin_amdgcn_wave_barrier();
-    if (t < T) slot[t] = out;
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      if (s0 + j >= s_end) break;                                  // uniform over the wavefront
+      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
+      const int id = idv[j];
+      const bool valid = id >= 0 && id < E;
+      const uint64_t mask = same_id_mask(id, valid, nbits);
+      int out = -1;
+      if (valid) {
+        const int pos = wave_cnt[wave][id] + __popcll(mask & below);
+        if (pos < C) out = ebase[id] + pos;
+      }
+      // every lane has read the running position before the group's first lane moves it on
+      __builtin_amdgcn_wave_barrier();
+      if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);
+      __builtin_amdgcn_wave_barrier();
+      if (t < T) slot[t] = out;
+    }
   }
 }
 
