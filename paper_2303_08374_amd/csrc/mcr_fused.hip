@@ -439,7 +439,8 @@ moe_combine_by_expert_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CP
 // f32(row of assignment k*T + t)): binary32 products and sums, the sum starting from the first kept
 // product, one rounding at the end; all-zero bits when nothing was kept.  KU = compile-time bound
 // on K.  One group of tpr threads per token row, kTopkRows rows per group and workgroup.
-constexpr int kTopkRows = 8;
+constexpr int kTopkRows = 16;   // rows one group of threads walks
+constexpr int kTopkFly = 2;     // rows whose loads are in flight together (4 measured no faster)
 template <int DT, int UB> struct UnitF32 {
   static constexpr int kN = UB / Elem<DT>::kBytes;
   typedef typename RowUnit<UB>::type U;
@@ -453,13 +454,17 @@ template <int DT, int UB> struct UnitF32 {
   }
 };
 
-template <int DT, int UB, int KU, bool NTL, bool NTS>
+// WAVE (a row is at least a wavefront wide): lane i*KU + k resolves choice k of the wave's i-th
+// row (destination and gate) once, before the row loop, which fetches them by shuffle; kTopkFly
+// rows have their K loads each in flight together.
+template <int DT, int UB, int KU, bool NTL, bool NTS, bool WAVE>
 __global__ void __launch_bounds__(kBlock)
 moe_combine_topk_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab slot_tab, CPtrTab gate_tab,
                         const int64_t* row_table, int E, int P, size_t T, int K, uint64_t recv_rows, uint32_t upr,
                         uint32_t tpr, uint32_t tpr_shift) {
   typedef typename RowUnit<UB>::type U;
   typedef UnitF32<DT, UB> F;
+  static_assert(kTopkRows * KU <= kWave, "one lane per (row, choice)");
   __shared__ int64_t table[MCR_MAX_EXPERTS];
   const int p = blockIdx.y;
   stage_row_table(table, row_table, p, E);
@@ -471,52 +476,83 @@ moe_combine_topk_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab
   const uint32_t rows_per_pass = kBlock >> tpr_shift;
   const size_t A = T * static_cast<size_t>(K);
   const size_t t0 = static_cast<size_t>(blockIdx.x) * kTopkRows * rows_per_pass;
-  for (int i = 0; i < kTopkRows; ++i) {
-    const size_t t = t0 + static_cast<size_t>(i) * rows_per_pass + (threadIdx.x >> tpr_shift);
-    if (t >= T) continue;
-    const U* srow[KU];
-    float g[KU];
-    bool kept[KU];
+  const uint32_t group = threadIdx.x >> tpr_shift;
+  RowDest mine{-1, 0};
+  float my_gate = 1.0f;
+  if constexpr (WAVE) {
+    const int lane = static_cast<int>(__lane_id());
+    const int li = lane / KU, lk = lane % KU;
+    const size_t t = t0 + static_cast<size_t>(li) * rows_per_pass + group;
+    if (li < kTopkRows && lk < K && t < T) {
+      const size_t a = static_cast<size_t>(lk) * T + t;
+      mine = dest_of(table, ids, slot, a, A, E, per_rank, recv_rows);
+      if (mine.r >= 0 && mine.r < P && gate) my_gate = gate[a];
+    }
+  }
+  for (int i0 = 0; i0 < kTopkRows; i0 += kTopkFly) {
+    const U* srow[kTopkFly][KU];
+    float g[kTopkFly][KU];
+    bool kept[kTopkFly][KU];
+    bool live[kTopkFly];
+    U* drow[kTopkFly];
 #pragma unroll
-    for (int k = 0; k < KU; ++k) {
-      kept[k] = false;
-      srow[k] = nullptr;
-      g[k] = 1.0f;
-      if (k < K) {
-        const size_t a = static_cast<size_t>(k) * T + t;
-        const RowDest d = dest_of(table, ids, slot, a, A, E, per_rank, recv_rows);
-        kept[k] = d.r >= 0 && d.r < P;
-        if (kept[k]) {
-          srow[k] = static_cast<const U*>(expert_out.p[d.r]) + static_cast<uint64_t>(d.row) * upr;
-          if (gate) g[k] = gate[a];
+    for (int j = 0; j < kTopkFly; ++j) {
+      const size_t t = t0 + static_cast<size_t>(i0 + j) * rows_per_pass + group;
+      live[j] = t < T;
+      drow[j] = dst + t * upr;
+#pragma unroll
+      for (int k = 0; k < KU; ++k) {
+        RowDest d{-1, 0};
+        g[j][k] = 1.0f;
+        if constexpr (WAVE) {
+          const int src_lane = (i0 + j) * KU + k;
+          d.r = __shfl(mine.r, src_lane);
+          const uint32_t lo = __shfl(static_cast<uint32_t>(mine.row), src_lane);
+          const uint32_t hi = __shfl(static_cast<uint32_t>(static_cast<uint64_t>(mine.row) >> 32), src_lane);
+          d.row = static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+          g[j][k] = __shfl(my_gate, src_lane);
+        } else {
+          if (k < K && live[j]) {
+            const size_t a = static_cast<size_t>(k) * T + t;
+            d = dest_of(table, ids, slot, a, A, E, per_rank, recv_rows);
+            if (d.r >= 0 && d.r < P && gate) g[j][k] = gate[a];
+          }
         }
+        kept[j][k] = d.r >= 0 && d.r < P;
+        srow[j][k] = kept[j][k] ? static_cast<const U*>(expert_out.p[d.r]) + static_cast<uint64_t>(d.row) * upr : nullptr;
       }
     }
-    U* drow = dst + t * upr;
     for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
-      U v[KU];
+      U v[kTopkFly][KU];
 #pragma unroll
-      for (int k = 0; k < KU; ++k) {
-        v[k] = U{};
-        if (kept[k]) v[k] = ldu<NTL, U>(srow[k] + c);
-      }
-      float acc[F::kN];
-      bool started = false;
+      for (int j = 0; j < kTopkFly; ++j) {
 #pragma unroll
-      for (int k = 0; k < KU; ++k) {
-        if (!kept[k]) continue;
-        float f[F::kN];
-        F::widen(v[k], f);
-#pragma unroll
-        for (int e = 0; e < F::kN; ++e) {
-          const float term = g[k] * f[e];
-          acc[e] = started ? acc[e] + term : term;
+        for (int k = 0; k < KU; ++k) {
+          v[j][k] = U{};
+          if (kept[j][k]) v[j][k] = ldu<NTL, U>(srow[j][k] + c);
         }
-        started = true;
       }
-      U y = U{};
-      if (started) y = F::narrow(acc);
-      stu<NTS, U>(drow + c, y);
+#pragma unroll
+      for (int j = 0; j < kTopkFly; ++j) {
+        if (!live[j]) continue;
+        float acc[F::kN];
+        bool started = false;
+#pragma unroll
+        for (int k = 0; k < KU; ++k) {
+          if (!kept[j][k]) continue;
+          float f[F::kN];
+          F::widen(v[j][k], f);
+#pragma unroll
+          for (int e = 0; e < F::kN; ++e) {
+            const float term = g[j][k] * f[e];
+            acc[e] = started ? acc[e] + term : term;
+          }
+          started = true;
+        }
+        U y = U{};
+        if (started) y = F::narrow(acc);
+        stu<NTS, U>(drow[j] + c, y);
+      }
     }
   }
 }
@@ -672,14 +708,19 @@ int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& exp
         constexpr int UB = decltype(ub)::value;
         const RowShape s = row_shape(row_elems * EB / UB);
         const unsigned gx = blocks_for(T, static_cast<size_t>(kTopkRows) * s.rows_per_pass);
-        if (K <= 2)
-          hipLaunchKernelGGL((moe_combine_topk_kernel<DT, UB, 2, decltype(ntl)::value, decltype(nts)::value>), dim3(gx, P),
-                             dim3(kBlock), 0, stream, out, expert_out, ids, slot, g, row_table, E, P, T, K,
-                             static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
-        else
-          hipLaunchKernelGGL((moe_combine_topk_kernel<DT, UB, MCR_MAX_TOPK, decltype(ntl)::value, decltype(nts)::value>),
+        auto launch = [&](auto ku, auto wv) {
+          hipLaunchKernelGGL((moe_combine_topk_kernel<DT, UB, decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value,
+                                                      decltype(wv)::value>),
                              dim3(gx, P), dim3(kBlock), 0, stream, out, expert_out, ids, slot, g, row_table, E, P, T, K,
                              static_cast<uint64_t>(recv_rows), s.upr, s.tpr, s.shift);
+        };
+        if (K <= 2) {
+          if (s.tpr >= kWave) launch(Int<2>{}, Bool<true>{});
+          else launch(Int<2>{}, Bool<false>{});
+        } else {
+          if (s.tpr >= kWave) launch(Int<MCR_MAX_TOPK>{}, Bool<true>{});
+          else launch(Int<MCR_MAX_TOPK>{}, Bool<false>{});
+        }
         return launch_status();
       };
       if (variant == SV_SCALAR) return topk(Int<EB>{}, Bool<false>{}, Bool<false>{});
