@@ -86,6 +86,10 @@ int resolve_variant(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes, bool v
   if (variant == MCR_AUTO) {
     if (!vec_ok) { *out = SV_SCALAR; return MCR_OK; }
     int v = table_lookup(ctx, op, dtype, P, bytes, true);
+    // an element type with no table of its own borrows the one of the tuned type of the same size
+    // (the traffic is the same): fp16 from bf16, int32 from fp32
+    if (v < 0 && dtype == MCR_F16) v = table_lookup(ctx, op, MCR_BF16, P, bytes, true);
+    if (v < 0 && dtype == MCR_I32) v = table_lookup(ctx, op, MCR_F32, P, bytes, true);
     if (v < 0 || v >= n_variants(op)) v = default_variant(bytes);
     *out = v;
     return MCR_OK;
@@ -96,11 +100,31 @@ int resolve_variant(mcr_ctx* ctx, int op, int dtype, int P, size_t bytes, bool v
   return MCR_OK;
 }
 
-// A host-only context (device < 0) validates, plans and tunes but never launches.
-int set_device(mcr_ctx* ctx) {
-  if (ctx->device < 0) return MCR_ESTATE;
-  return hip_status(hipSetDevice(ctx->device));
-}
+// Makes the context's device current for the rest of the calling scope and puts the caller's
+// device back when the scope ends, so a call never changes the calling thread's current device.
+// A host-only context (device < 0) validates, plans and tunes but never launches: MCR_ESTATE.
+class DeviceScope {
+ public:
+  explicit DeviceScope(const mcr_ctx* ctx) {
+    if (ctx->device < 0) { status_ = MCR_ESTATE; return; }
+    if (hipGetDevice(&previous_) != hipSuccess) { status_ = MCR_EHIP; return; }
+    if (previous_ != ctx->device) {
+      if (hipSetDevice(ctx->device) != hipSuccess) { status_ = MCR_EHIP; return; }
+      restore_ = true;
+    }
+  }
+  ~DeviceScope() {
+    if (restore_) (void)hipSetDevice(previous_);
+  }
+  DeviceScope(const DeviceScope&) = delete;
+  DeviceScope& operator=(const DeviceScope&) = delete;
+  int status() const { return status_; }
+
+ private:
+  int previous_ = 0;
+  int status_ = MCR_OK;
+  bool restore_ = false;
+};
 
 // Everything mcr_alltoall does before it launches: argument checks, the rank pointer tables,
 // the launch-shape choice.
@@ -137,7 +161,8 @@ int vector_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool al
   int64_t S[MCR_MAX_RANKS * MCR_MAX_RANKS];
   for (int i = 0; i < P * P; ++i) S[i] = 0;
   fill(S, row_elems);
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   // every buffer is bounded by the whole payload: the split matrix is ours, so the bounds never bind
   const size_t rows = total / row_elems;
   return launch_alltoallv(ctx, to, ti, S, nullptr, rows, rows, row_elems * elem_bytes(dtype),
@@ -183,7 +208,8 @@ int pair_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool all1
     s32[i] = static_cast<uint32_t>(s);
     r32[i] = static_cast<uint32_t>(d);
   }
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_alltoallv_pairs(ctx, to, ti, c32, s32, r32, static_cast<int>(elem_bytes(dtype)), P, v,
                                 static_cast<hipStream_t>(stream));
 }
@@ -264,7 +290,8 @@ int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype
   int v;
   int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_allreduce(ctx, tab, count, dtype, op, P, -1, v, static_cast<hipStream_t>(stream));
 }
 
@@ -282,7 +309,8 @@ int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, si
   int v;
   int rc = resolve_variant(ctx, MCR_OP_REDUCE_SCATTER, dtype, P, count * elem_bytes(dtype), vec_ok, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_reduce_scatter(ctx, to, ti, count, dtype, op, P, v, static_cast<hipStream_t>(stream));
 }
 
@@ -298,7 +326,8 @@ int mcr_allgather(mcr_ctx* ctx, void* const* out, const void* const* in, size_t 
   int v;
   int rc = resolve_variant(ctx, MCR_OP_ALLGATHER, dtype, P, count * elem_bytes(dtype), vec_ok, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_allgather(ctx, to, ti, count, dtype, P, v, static_cast<hipStream_t>(stream));
 }
 
@@ -309,7 +338,8 @@ int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t c
   int v;
   int rc = prepare_alltoall(ctx, out, in, count, dtype, P, variant, &to, &ti, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_alltoall(ctx, to, ti, count, dtype, P, v, static_cast<hipStream_t>(stream));
 }
 
@@ -351,7 +381,8 @@ int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const i
   int v;
   int rc = resolve_variant(ctx, MCR_OP_ALLTOALLV, dtype, P, in_rows * row_bytes, vec_ok, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_alltoallv(ctx, to, ti, host, dev, in_rows, out_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P,
                           0, v, static_cast<hipStream_t>(stream));
 }
@@ -371,7 +402,8 @@ int mcr_reduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, m
   int v;
   int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_allreduce(ctx, tab, count, dtype, op, P, root, v, static_cast<hipStream_t>(stream));
 }
 
@@ -592,7 +624,8 @@ int mcr_moe_route(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, 
       !fill_tab(tc, counts, P, MCR_F32, true, nullptr))
     return MCR_EINVAL;
   int rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_route(ctx, ti, T, E, P, capacity, ts, tc, splits, static_cast<hipStream_t>(stream));
 }
 
@@ -614,7 +647,8 @@ int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_
   int rc = resolve_variant(ctx, MCR_OP_PACK, dtype, P, T * row_bytes, vec_ok, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any || out_rows == 0) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_pack(ctx, to, ti, tsl, T, out_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P, v,
                      static_cast<hipStream_t>(stream));
 }
@@ -640,7 +674,8 @@ int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int3
   int rc = resolve_variant(ctx, MCR_OP_UNPACK, dtype, P, T * row_bytes, vec_ok, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_unpack(ctx, to, ti, tsl, gate ? &tg : nullptr, T, in_rows, row_elems, dtype, P, v,
                        static_cast<hipStream_t>(stream));
 }
@@ -664,7 +699,8 @@ int mcr_moe_dispatch(mcr_ctx* ctx, void* const* recv, const void* const* tokens,
   int rc = resolve_variant(ctx, MCR_OP_MOE_DISPATCH, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_dispatch(ctx, to, ti, tsl, splits, T, recv_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P, v,
                              static_cast<hipStream_t>(stream));
 }
@@ -689,7 +725,8 @@ int mcr_moe_combine(mcr_ctx* ctx, void* const* out, const void* const* expert_ou
   int rc = resolve_variant(ctx, MCR_OP_MOE_COMBINE, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_combine(ctx, to, ti, tsl, gate ? &tg : nullptr, splits, T, recv_rows, row_elems, dtype, P, v,
                             static_cast<hipStream_t>(stream));
 }
@@ -704,7 +741,8 @@ int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int
   CPtrTab tc;
   if (!fill_tab(tc, counts, P, MCR_F32, true, nullptr)) return MCR_EINVAL;
   int rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_expert_layout(ctx, tc, E, P, row_table, expert_first, expert_rows, static_cast<hipStream_t>(stream));
 }
 
@@ -729,7 +767,8 @@ int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* cons
   int rc = resolve_variant(ctx, MCR_OP_MOE_DISPATCH, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_dispatch_by_expert(ctx, to, ti, tid, tsl, row_table, E, T, K, recv_rows, row_bytes,
                                        static_cast<int>(elem_bytes(dtype)), P, v, static_cast<hipStream_t>(stream));
 }
@@ -758,7 +797,8 @@ int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const*
   int rc = resolve_variant(ctx, MCR_OP_MOE_COMBINE, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_combine_by_expert(ctx, to, ti, tid, tsl, gate ? &tg : nullptr, row_table, E, T, K, recv_rows, row_elems, dtype,
                                       P, v, static_cast<hipStream_t>(stream));
 }
@@ -790,7 +830,8 @@ int mcr_dlrm_shuffle(mcr_ctx* ctx, void* const* out, const void* const* in, int 
                            all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_dlrm_shuffle(ctx, to, ti, n_tables, batch, row_bytes, static_cast<int>(elem_bytes(dtype)), P, backward != 0,
                              v, static_cast<hipStream_t>(stream));
 }
@@ -867,7 +908,8 @@ int mcr_fuse_plan_create(mcr_ctx* ctx, const size_t* numel, int n_tensors, size_
     *out = plan;
     return MCR_OK;
   }
-  if (set_device(ctx) != MCR_OK) { delete plan; return MCR_EHIP; }
+  DeviceScope on_device(ctx);
+  if (on_device.status() != MCR_OK) { delete plan; return MCR_EHIP; }
   std::vector<uint64_t> h_numel(plan->numel.begin(), plan->numel.end());
   std::vector<uint64_t> h_off(plan->offset.begin(), plan->offset.end());
   bool ok = true;
@@ -908,7 +950,8 @@ int mcr_fuse_plan_bind(mcr_ctx* ctx, mcr_fuse_plan* plan, void* const* tensors, 
     if (plan->numel[i] > 0 && (tensors[k] == nullptr || !elem_aligned(tensors[k], plan->dtype))) return MCR_EINVAL;
   }
   int rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   if (P > plan->alloc_P) {
     if (plan->d_ptrs) (void)hipFree(plan->d_ptrs);
     plan->d_ptrs = nullptr;
@@ -934,7 +977,8 @@ static int fuse_common(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, void
   int rc = resolve_variant(ctx, unfuse ? MCR_OP_UNFUSE : MCR_OP_FUSE, plan->dtype, P,
                            plan->bucket_numel[bucket] * elem_bytes(plan->dtype), true, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_fuse(ctx, plan, bucket, tf, unfuse, v, static_cast<hipStream_t>(stream));
 }
 
@@ -962,7 +1006,8 @@ int mcr_allreduce_multi(mcr_ctx* ctx, const mcr_fuse_plan* plan, int bucket, mcr
   int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE_MULTI, plan->dtype, plan->bound_P, elems * elem_bytes(plan->dtype),
                            true, variant, &v);
   if (rc != MCR_OK) return rc;
-  if ((rc = set_device(ctx)) != MCR_OK) return rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_allreduce_multi(ctx, plan, t0, t1, op, v, static_cast<hipStream_t>(stream));
 }
 
@@ -979,6 +1024,8 @@ int mcr_dispatch_overhead(mcr_ctx* ctx, void* const* out, const void* const* in,
                           int iters, void* stream, double* us_auto, double* us_direct, double* host_us_auto,
                           double* host_us_direct, double* dispatch_only_us) {
   if (!ctx || !us_auto || !us_direct || iters < 1) return MCR_EINVAL;
+  DeviceScope on_device(ctx);                              // the bare launches below need it too
+  if (on_device.status() != MCR_OK) return on_device.status();
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the full entry point once: validates everything and warms the kernel up
   int rc = mcr_alltoall(ctx, out, in, count, dtype, P, MCR_AUTO, stream);

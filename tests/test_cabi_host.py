@@ -206,6 +206,13 @@ def test_auto_falls_back_to_the_nearest_scale(ctx):
     assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 3, 8192) == 7                # 3 is closer to 2
     assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.BF16, 8, 8192) == 1               # other dtype: no table, default
     assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F32, 8, 8192, False) == 0         # shape rules the vectors out
+    # an element type without a table borrows the tuned type of the same size
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.I32, 8, 64 << 20) == 4             # int32 from fp32
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F16, 8, 8192) == 1                # fp16 from bf16, which has none: default
+    mcr.mcr_tune_set(ctx, mcr.OP_ALLTOALL, mcr.BF16, 8, 4096, 9)
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F16, 4, 8192) == 9                # ... now it has, at the nearest scale
+    mcr.mcr_tune_set(ctx, mcr.OP_ALLTOALL, mcr.F16, 8, 4096, 5)
+    assert mcr.mcr_auto_variant(ctx, mcr.OP_ALLTOALL, mcr.F16, 8, 8192) == 5                # its own table wins
     mcr.mcr_tune_clear(ctx)
 
 

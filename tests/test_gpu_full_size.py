@@ -153,3 +153,82 @@ def test_gradient_buckets_full_size_sampled(tuned_ctx):
             assert torch.equal(arenas[p].view(torch.int16), arenas[0].view(torch.int16))
     finally:
         mcr.mcr_fuse_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("dtype", [mcr.F16, mcr.I32])
+def test_f16_i32_reductions_sampled(tuned_ctx, dtype):
+    """64 MiB per rank of fp16 / int32 through MCR_AUTO (their tables are borrowed from bf16 / fp32):
+    reduce_scatter, then all_reduce in place."""
+    M = 64 << 20
+    n = M // gu.EB[dtype]
+    b = n // P
+    rng = np.random.Generator(np.random.Philox(key=M + 10 * dtype))
+    g = torch.Generator(device="cuda")
+    ins = []
+    for p in range(P):
+        g.manual_seed(2900 + p)
+        if dtype == mcr.F16:
+            ins.append(torch.empty(n, dtype=torch.float16, device="cuda").uniform_(-4.0, 4.0, generator=g))
+        else:
+            ins.append(torch.randint(-2**31, 2**31 - 1, (n,), dtype=torch.int32, device="cuda", generator=g))
+    host = lambda t, s: t[s:s + W].cpu().numpy().copy()
+    op = mcr.AVG if dtype == mcr.F16 else mcr.SUM
+    outs = [torch.zeros(b, dtype=ins[0].dtype, device="cuda") for _ in range(P)]
+    mcr.mcr_reduce_scatter(tuned_ctx, outs, ins, n, dtype, op, P)
+    gu.sync()
+    for r in (0, P - 1):
+        for st in _starts(b, rng)[::2]:
+            win = [host(ins[p], r * b + st) for p in range(P)]
+            oracle.allreduce(win, dtype, op)
+            gu.assert_bits_equal(host(outs[r], st), win[0], f"reduce_scatter dt={dtype} r={r} at {st}")
+    starts = _starts(n, rng)
+    before = {st: [host(ins[p], st) for p in range(P)] for st in starts}
+    mcr.mcr_allreduce(tuned_ctx, ins, n, dtype, op, P)
+    gu.sync()
+    for st in starts:
+        exp = before[st]
+        oracle.allreduce(exp, dtype, op)
+        gu.assert_bits_equal(host(ins[P - 1], st), exp[0], f"allreduce dt={dtype} at {st}")
+    view = torch.int16 if dtype == mcr.F16 else torch.int32
+    for r in range(1, P):
+        assert torch.equal(ins[r].view(view), ins[0].view(view))
+
+
+def test_alltoallv_displacements_sampled(tuned_ctx):
+    """P=8, rows of 4 KiB, about 1.5 GiB moved with caller-chosen displacements: every block lands at
+    its own offset (blocks in reverse sender order with gaps), checked on windows of rows."""
+    dtype, re = mcr.BF16, 2048
+    rng = np.random.Generator(np.random.Philox(key=777))
+    C = rng.integers(2000, 9000, size=(P, P)).astype(np.int64)
+    C[1, 2] = 0
+    SD = np.zeros((P, P), dtype=np.int64)
+    RD = np.zeros((P, P), dtype=np.int64)
+    for p in range(P):
+        at = 3
+        for r in rng.permutation(P):
+            SD[p, r] = at
+            at += int(C[p, r]) + 5
+    in_rows = int((SD + C).max()) + 1
+    for r in range(P):
+        at = 1
+        for p in reversed(range(P)):
+            RD[r, p] = at
+            at += int(C[p, r]) + 7
+    out_rows = int(max(RD[r, p] + C[p, r] for r in range(P) for p in range(P))) + 2
+    ins = [_fill(in_rows * re, dtype, 3000 + p) for p in range(P)]
+    outs = [torch.zeros(out_rows * re, dtype=torch.bfloat16, device="cuda") for _ in range(P)]
+    mcr.mcr_alltoallv_displs(tuned_ctx, outs, ins, C.reshape(-1), SD.reshape(-1), RD.reshape(-1), in_rows, out_rows, re, dtype, P)
+    gu.sync()
+    rows_of = lambda t, row, k: t[row * re:(row + k) * re].view(torch.int16).cpu().numpy()
+    for r in (0, 3, P - 1):
+        for p in (0, 2, P - 1):
+            c = int(C[p, r])
+            if c == 0:
+                continue
+            for k0 in sorted({0, c - 2, c // 2, int(rng.integers(0, c - 2))}):
+                got = rows_of(outs[r], int(RD[r, p]) + k0, 2)
+                exp = rows_of(ins[p], int(SD[p, r]) + k0, 2)
+                assert np.array_equal(got, exp), f"alltoallv_displs r={r} p={p} row {k0}"
+            # the gap rows around the block are untouched
+            assert (rows_of(outs[r], int(RD[r, p]) + c, 1) == 0).all()
+            assert (rows_of(outs[r], int(RD[r, p]) - 1, 1) == 0).all()
