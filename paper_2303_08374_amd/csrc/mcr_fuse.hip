@@ -41,14 +41,14 @@ fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
   if (vec_ok) {
     constexpr int W = 16 / EB;
     const uint32_t nv = static_cast<uint32_t>(ne / W);
-    u32x4 v[4];
+    u32x4 v[kChunkVecs];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kChunkVecs; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
       if (idx < nv) v[u] = load16<NTL>(src, idx);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kChunkVecs; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
       if (idx < nv) store16<NTS>(dst, idx, v[u]);
     }
@@ -81,18 +81,18 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
   uint64_t done = 0;
   if (!FORCE_SCALAR && (all & 15u) == 0) {
     const uint32_t nv = static_cast<uint32_t>(ne / W);
-    u32x4 v[4][P];
+    u32x4 v[kChunkVecs][P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {            // rank-major issue order, as in all_reduce
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kChunkVecs; ++u) {
         const uint32_t idx = u * kBlock + threadIdx.x;
         if (idx < nv) v[u][p] = load16<NTL>(base[p], idx);
       }
     }
-    u32x4 y[4];
+    u32x4 y[kChunkVecs];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kChunkVecs; ++u) {
       const uint32_t idx = u * kBlock + threadIdx.x;
       if (idx < nv) {
         typename E::acc_t acc[W];
@@ -114,7 +114,7 @@ allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
 #pragma unroll
     for (int p = 0; p < P; ++p) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kChunkVecs; ++u) {
         const uint32_t idx = u * kBlock + threadIdx.x;
         if (idx < nv) store16<NTS>(base[p], idx, y[u]);
       }

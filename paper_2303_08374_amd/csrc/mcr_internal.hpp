@@ -77,8 +77,9 @@ inline size_t elem_bytes(int dtype) { return (dtype == MCR_F32 || dtype == MCR_I
 inline int per_vec(int dtype) { return (dtype == MCR_F32 || dtype == MCR_I32) ? 4 : 8; }
 
 // Elements one workgroup covers per tensor chunk in the multi-tensor kernels
-// (fuse / unfuse / allreduce_multi): 256 threads x 4 vectors of 16 bytes.
-constexpr uint32_t kChunkBytes = 256 * 4 * 16;
+// (fuse / unfuse / allreduce_multi): 256 threads x kChunkVecs vectors of 16 bytes.
+constexpr int kChunkVecs = 4;    // 2 measured slower for fuse and unfuse, no faster for the multi-tensor all_reduce
+constexpr uint32_t kChunkBytes = 256 * kChunkVecs * 16;
 
 // Every launcher returns MCR_OK or MCR_EHIP and assumes validated arguments.
 int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int root, int variant, hipStream_t);
