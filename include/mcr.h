@@ -255,6 +255,19 @@ int mcr_moe_route(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, 
                   int capacity, int32_t* const* slot, int32_t* const* counts, int64_t* splits,
                   void* stream);
 
+/* mcr_moe_route_ws: the same results as mcr_moe_route, bit for bit, computed by several
+ * workgroups per rank (chunks of at least 2048 tokens, two launches) with a caller-owned
+ * workspace between them: DEVICE memory, 4-byte aligned, at least
+ * mcr_moe_route_workspace_bytes(T, E, P) bytes, contents irrelevant before and after; calls that
+ * may overlap in time need a workspace each.  workspace == NULL, or a T for which the byte count
+ * is 0 (fewer than two chunks), runs mcr_moe_route itself; a workspace that is too small gives
+ * MCR_EINVAL.  For callers who route tens of thousands of tokens per rank: the one-workgroup
+ * kernel is bound by the vector ALU of one compute unit. */
+size_t mcr_moe_route_workspace_bytes(int T, int E, int P);
+int mcr_moe_route_ws(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P,
+                     int capacity, int32_t* const* slot, int32_t* const* counts, int64_t* splits,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* mcr_pack, batched over P ranks: out[p] row slot[p][t] = in[p] row t for every t<T
  * with 0 <= slot[p][t] < out_rows; other rows of out[p] are left untouched. */
 int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot,

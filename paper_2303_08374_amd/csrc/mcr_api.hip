@@ -629,6 +629,35 @@ int mcr_moe_route(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, 
   return launch_moe_route(ctx, ti, T, E, P, capacity, ts, tc, splits, static_cast<hipStream_t>(stream));
 }
 
+size_t mcr_moe_route_workspace_bytes(int T, int E, int P) {
+  if (T < 0 || E < 1 || E > MCR_MAX_EXPERTS || !valid_P(P)) return 0;
+  int chunk_steps;
+  const int chunks = route_chunks(T, &chunk_steps);
+  if (chunks < 2) return 0;
+  return static_cast<size_t>(P) * chunks * E * sizeof(int32_t);
+}
+
+int mcr_moe_route_ws(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P, int capacity,
+                     int32_t* const* slot, int32_t* const* counts, int64_t* splits, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  const size_t need = mcr_moe_route_workspace_bytes(T, E, P);
+  if (need == 0 || !workspace) return mcr_moe_route(ctx, expert_ids, T, E, P, capacity, slot, counts, splits, stream);
+  if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3u)) return MCR_EINVAL;
+  if (!ctx || !expert_ids || !slot || !counts || !splits || !valid_P(P)) return MCR_EINVAL;
+  if (T < 0 || E < 1 || E > MCR_MAX_EXPERTS || capacity < 0 || E % P != 0) return MCR_EINVAL;
+  if (reinterpret_cast<uintptr_t>(splits) & 7u) return MCR_EINVAL;
+  CPtrTab ti;
+  PtrTab ts, tc;
+  if (!fill_tab(ti, expert_ids, P, MCR_F32, T > 0, nullptr) || !fill_tab(ts, slot, P, MCR_F32, T > 0, nullptr) ||
+      !fill_tab(tc, counts, P, MCR_F32, true, nullptr))
+    return MCR_EINVAL;
+  int rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
+  return launch_moe_route_chunked(ctx, ti, T, E, P, capacity, ts, tc, splits, static_cast<int32_t*>(workspace),
+                                  static_cast<hipStream_t>(stream));
+}
+
 int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot, size_t T,
              size_t out_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {
   if (!ctx || !out || !in || !slot || !valid_P(P)) return MCR_EINVAL;

@@ -30,6 +30,81 @@ __device__ __forceinline__ uint64_t same_id_mask(int id, bool valid, int nbits) 
   return mask;
 }
 
+// Pass 1 of one wavefront over its 64-token steps [s_begin, s_end): counts per expert into `cnt`
+// (this wave's row of the LDS table).  kRouteBatch steps at a time: all their ids are requested
+// before the first is used, so the loop pays the memory latency once per batch, not once per step.
+__device__ __forceinline__ void route_count(const int32_t* ids, int s_begin, int s_end, int T, int E, int nbits, int* cnt,
+                                            int lane, uint64_t below) {
+  for (int s0 = s_begin; s0 < s_end; s0 += kRouteBatch) {
+    int idv[kRouteBatch];
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
+      idv[j] = (s0 + j < s_end && t < T) ? ids[t] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      if (s0 + j >= s_end) break;                                  // uniform over the wavefront
+      const int id = idv[j];
+      const bool valid = id >= 0 && id < E;
+      const uint64_t mask = same_id_mask(id, valid, nbits);
+      if (valid && (mask & below) == 0) cnt[id] += __popcll(mask);   // lowest lane of the group
+    }
+  }
+}
+
+// Pass 2: `pos` holds, per expert, the position of this wave's next token; slots go out.
+__device__ __forceinline__ void route_emit(const int32_t* ids, int32_t* slot, int s_begin, int s_end, int T, int E, int C,
+                                           int nbits, int* pos, const int* ebase, int lane, uint64_t below) {
+  for (int s0 = s_begin; s0 < s_end; s0 += kRouteBatch) {
+    int idv[kRouteBatch];
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
+      idv[j] = (s0 + j < s_end && t < T) ? ids[t] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < kRouteBatch; ++j) {
+      if (s0 + j >= s_end) break;                                  // uniform over the wavefront
+      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
+      const int id = idv[j];
+      const bool valid = id >= 0 && id < E;
+      const uint64_t mask = same_id_mask(id, valid, nbits);
+      int out = -1;
+      if (valid) {
+        const int at = pos[id] + __popcll(mask & below);
+        if (at < C) out = ebase[id] + at;
+      }
+      // every lane has read the running position before the group's first lane moves it on
+      __builtin_amdgcn_wave_barrier();
+      if (valid && (mask & below) == 0) pos[id] += __popcll(mask);
+      __builtin_amdgcn_wave_barrier();
+      if (t < T) slot[t] = out;
+    }
+  }
+}
+
+// Exclusive scan of the kept counts over experts by one wavefront (E <= 512: 64 at a time), and
+// the outputs that depend on them only.
+__device__ __forceinline__ void route_expert_bases(const int* ecnt, int* ebase, int32_t* counts, bool write_counts, int E,
+                                                   int lane) {
+  int carry = 0;
+  for (int e0 = 0; e0 < E; e0 += kWave) {
+    const int e = e0 + lane;
+    const int c = (e < E) ? ecnt[e] : 0;
+    int incl = c;
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int up = __shfl_up(incl, d);
+      if (lane >= d) incl += up;
+    }
+    if (e < E) {
+      ebase[e] = carry + incl - c;
+      if (write_counts) counts[e] = c;
+    }
+    carry += __shfl(incl, kWave - 1);
+  }
+}
+
 __global__ void __launch_bounds__(kRouteBlock)
 moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* splits, int T, int E,
                  int P, int C, int nbits) {
@@ -52,24 +127,7 @@ moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* s
   const int s_begin = wave * steps_per_wave;
   const int s_end = min(steps_total, s_begin + steps_per_wave);
 
-  // kRouteBatch steps at a time: all their ids are requested before the first is used, so the
-  // loop pays the memory latency once per batch, not once per step
-  for (int s0 = s_begin; s0 < s_end; s0 += kRouteBatch) {
-    int idv[kRouteBatch];
-#pragma unroll
-    for (int j = 0; j < kRouteBatch; ++j) {
-      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
-      idv[j] = (s0 + j < s_end && t < T) ? ids[t] : -1;
-    }
-#pragma unroll
-    for (int j = 0; j < kRouteBatch; ++j) {
-      if (s0 + j >= s_end) break;                                  // uniform over the wavefront
-      const int id = idv[j];
-      const bool valid = id >= 0 && id < E;
-      const uint64_t mask = same_id_mask(id, valid, nbits);
-      if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);   // lowest lane of the group
-    }
-  }
+  route_count(ids, s_begin, s_end, T, E, nbits, wave_cnt[wave], lane, below);
   __syncthreads();
 
   // per expert: exclusive scan over waves, then clamp the total to the capacity
@@ -83,24 +141,7 @@ moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* s
     ecnt[e] = min(run, C);
   }
   __syncthreads();
-  // exclusive scan of the kept counts over experts (E <= 512: one wave, 64 at a time)
-  if (wave == 0) {
-    int carry = 0;
-    for (int e0 = 0; e0 < E; e0 += kWave) {
-      const int e = e0 + lane;
-      const int c = (e < E) ? ecnt[e] : 0;
-      int incl = c;
-      for (int d = 1; d < kWave; d <<= 1) {
-        const int up = __shfl_up(incl, d);
-        if (lane >= d) incl += up;
-      }
-      if (e < E) {
-        ebase[e] = carry + incl - c;
-        counts[e] = c;
-      }
-      carry += __shfl(incl, kWave - 1);
-    }
-  }
+  if (wave == 0) route_expert_bases(ecnt, ebase, counts, true, E, lane);
   __syncthreads();
   if (tid < P) {
     const int per = E / P;
@@ -108,33 +149,97 @@ moe_route_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* s
     for (int e = tid * per; e < (tid + 1) * per; ++e) a += ecnt[e];
     splits[static_cast<size_t>(rank) * P + tid] = a;
   }
+  route_emit(ids, slot, s_begin, s_end, T, E, C, nbits, wave_cnt[wave], ebase, lane, below);
+}
 
-  for (int s0 = s_begin; s0 < s_end; s0 += kRouteBatch) {
-    int idv[kRouteBatch];
+// ---- routing over several workgroups per rank --------------------------------------------------
+// The one-workgroup kernel above is bound by the vector ALU of the one compute unit it runs on.
+// With a workspace the tokens of a rank are cut into chunks of `chunk_steps` 64-token steps; a
+// first launch counts per (rank, chunk, expert) into the workspace, a second launch gives every
+// chunk its starting positions (the counts of the chunks before it) and emits the slots.  Same
+// results as the kernel above, bit for bit.
+constexpr int kChunkWaves = 4;
+constexpr int kChunkBlock = kChunkWaves * kWave;
+
+__device__ __forceinline__ void chunk_wave_range(int chunk, int chunk_steps, int steps_total, int wave, int* s_begin,
+                                                 int* s_end) {
+  const int c_begin = chunk * chunk_steps;
+  const int c_end = min(steps_total, c_begin + chunk_steps);
+  const int per_wave = (chunk_steps + kChunkWaves - 1) / kChunkWaves;
+  *s_begin = min(c_end, c_begin + wave * per_wave);
+  *s_end = min(c_end, *s_begin + per_wave);
+}
+
+// grid (chunks, P).  workspace[(rank * chunks + chunk) * E + e]
+__global__ void __launch_bounds__(kChunkBlock)
+moe_route_count_kernel(CPtrTab ids_tab, int32_t* workspace, int T, int E, int chunk_steps, int nbits) {
+  __shared__ int wave_cnt[kChunkWaves][MCR_MAX_EXPERTS];
+  const int rank = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[rank]);
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  for (int i = tid; i < kChunkWaves * E; i += kChunkBlock) wave_cnt[i / E][i % E] = 0;
+  __syncthreads();
+  int s_begin, s_end;
+  chunk_wave_range(chunk, chunk_steps, (T + kWave - 1) / kWave, wave, &s_begin, &s_end);
+  route_count(ids, s_begin, s_end, T, E, nbits, wave_cnt[wave], lane, lanemask_lt());
+  __syncthreads();
+  int32_t* out = workspace + (static_cast<size_t>(rank) * chunks + chunk) * E;
+  for (int e = tid; e < E; e += kChunkBlock) {
+    int a = 0;
 #pragma unroll
-    for (int j = 0; j < kRouteBatch; ++j) {
-      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
-      idv[j] = (s0 + j < s_end && t < T) ? ids[t] : -1;
+    for (int w = 0; w < kChunkWaves; ++w) a += wave_cnt[w][e];
+    out[e] = a;
+  }
+}
+
+__global__ void __launch_bounds__(kChunkBlock)
+moe_route_slot_kernel(CPtrTab ids_tab, PtrTab slot_tab, PtrTab counts_tab, int64_t* splits, const int32_t* workspace, int T,
+                      int E, int P, int C, int chunk_steps, int nbits) {
+  __shared__ int wave_cnt[kChunkWaves][MCR_MAX_EXPERTS];
+  __shared__ int ebase[MCR_MAX_EXPERTS];
+  __shared__ int ecnt[MCR_MAX_EXPERTS];
+  __shared__ int before[MCR_MAX_EXPERTS];                  // tokens of the expert in the chunks before this one
+  const int rank = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[rank]);
+  int32_t* slot = static_cast<int32_t*>(slot_tab.p[rank]);
+  int32_t* counts = static_cast<int32_t*>(counts_tab.p[rank]);
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const uint64_t below = lanemask_lt();
+  const int32_t* hist = workspace + static_cast<size_t>(rank) * chunks * E;
+  for (int e = tid; e < E; e += kChunkBlock) {
+    int total = 0, bef = 0;
+    for (int c = 0; c < chunks; ++c) {
+      const int v = hist[static_cast<size_t>(c) * E + e];
+      if (c < chunk) bef += v;
+      total += v;
     }
+    before[e] = bef;
+    ecnt[e] = min(total, C);
+  }
+  for (int i = tid; i < kChunkWaves * E; i += kChunkBlock) wave_cnt[i / E][i % E] = 0;
+  __syncthreads();
+  int s_begin, s_end;
+  chunk_wave_range(chunk, chunk_steps, (T + kWave - 1) / kWave, wave, &s_begin, &s_end);
+  route_count(ids, s_begin, s_end, T, E, nbits, wave_cnt[wave], lane, below);
+  if (wave == 0) route_expert_bases(ecnt, ebase, counts, chunk == 0, E, lane);
+  __syncthreads();
+  for (int e = tid; e < E; e += kChunkBlock) {
+    int run = before[e];
 #pragma unroll
-    for (int j = 0; j < kRouteBatch; ++j) {
-      if (s0 + j >= s_end) break;                                  // uniform over the wavefront
-      const long long t = static_cast<long long>(s0 + j) * kWave + lane;
-      const int id = idv[j];
-      const bool valid = id >= 0 && id < E;
-      const uint64_t mask = same_id_mask(id, valid, nbits);
-      int out = -1;
-      if (valid) {
-        const int pos = wave_cnt[wave][id] + __popcll(mask & below);
-        if (pos < C) out = ebase[id] + pos;
-      }
-      // every lane has read the running position before the group's first lane moves it on
-      __builtin_amdgcn_wave_barrier();
-      if (valid && (mask & below) == 0) wave_cnt[wave][id] += __popcll(mask);
-      __builtin_amdgcn_wave_barrier();
-      if (t < T) slot[t] = out;
+    for (int w = 0; w < kChunkWaves; ++w) {
+      const int c = wave_cnt[w][e];
+      wave_cnt[w][e] = run;
+      run += c;
     }
   }
+  if (chunk == 0 && tid < P) {
+    const int per = E / P;
+    int64_t a = 0;
+    for (int e = tid * per; e < (tid + 1) * per; ++e) a += ecnt[e];
+    splits[static_cast<size_t>(rank) * P + tid] = a;
+  }
+  __syncthreads();
+  route_emit(ids, slot, s_begin, s_end, T, E, C, nbits, wave_cnt[wave], ebase, lane, below);
 }
 
 // ---- pack / unpack -----------------------------------------------------------------
@@ -243,6 +348,32 @@ int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capa
   while ((1 << nbits) < E) ++nbits;
   hipLaunchKernelGGL(moe_route_kernel, dim3(P), dim3(kRouteBlock), 0, stream, ids, slot, counts, splits, T, E,
                      P, capacity, nbits);
+  return launch_status();
+}
+
+// Chunks per rank of the several-workgroup routing: at least 2048 tokens each, at most 64 chunks;
+// 1 means the one-workgroup kernel serves.
+int route_chunks(int T, int* chunk_steps) {
+  const int steps_total = (T + kWave - 1) / kWave;
+  int cs = 32;
+  if ((steps_total + cs - 1) / cs > 64) cs = (steps_total + 63) / 64;
+  *chunk_steps = cs;
+  const int chunks = (steps_total + cs - 1) / cs;
+  return chunks < 1 ? 1 : chunks;
+}
+
+int launch_moe_route_chunked(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot,
+                             const PtrTab& counts, int64_t* splits, int32_t* workspace, hipStream_t stream) {
+  int nbits = 0;
+  while ((1 << nbits) < E) ++nbits;
+  int chunk_steps;
+  const int chunks = route_chunks(T, &chunk_steps);
+  hipLaunchKernelGGL(moe_route_count_kernel, dim3(chunks, P), dim3(kChunkBlock), 0, stream, ids, workspace, T, E, chunk_steps,
+                     nbits);
+  int rc = launch_status();
+  if (rc != MCR_OK) return rc;
+  hipLaunchKernelGGL(moe_route_slot_kernel, dim3(chunks, P), dim3(kChunkBlock), 0, stream, ids, slot, counts, splits,
+                     workspace, T, E, P, capacity, chunk_steps, nbits);
   return launch_status();
 }
 

@@ -205,6 +205,19 @@ def mcr_moe_route(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capaci
                                ctypes.c_void_p(_addr(splits)), _stream(stream)), "mcr_moe_route")
 
 
+def mcr_moe_route_workspace_bytes(T: int, E: int, P: int) -> int:
+    fn = lib().mcr_moe_route_workspace_bytes
+    fn.restype = ctypes.c_size_t
+    return int(fn(T, E, P))
+
+
+def mcr_moe_route_ws(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
+                     counts: Sequence[Ptr], splits: Ptr, workspace: Optional[Ptr], workspace_bytes: int, stream=None) -> None:
+    ws = ctypes.c_void_p(_addr(workspace)) if workspace is not None else ctypes.c_void_p(0)
+    _check(lib().mcr_moe_route_ws(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
+                                  ctypes.c_void_p(_addr(splits)), ws, _sz(workspace_bytes), _stream(stream)), "mcr_moe_route_ws")
+
+
 def mcr_pack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr], T: int, out_rows: int, row_elems: int,
              dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
     _check(lib().mcr_pack(ctx, _ptr_array(out), _ptr_array(inp), _ptr_array(slot), _sz(T), _sz(out_rows),

@@ -128,15 +128,19 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     falg = [0, 2 * kept * row + P * T * 4, kept * row + P * T * row + P * T * 8]
     rep["fused"] = _stage_report(["route", "moe_dispatch", "moe_combine"], falg, rows)
     rep["fused"]["speedup_vs_chain"] = round(rep["end_to_end"]["us"] / rep["fused"]["end_to_end"]["us"], 2)
-    # the expert-major receive layout (every expert's tokens in one block), same row traffic
+    # the expert-major receive layout (every expert's tokens in one block), same row traffic; routing
+    # by several workgroups per rank with a workspace
+    K_MAX = 2
     d_tab = torch.empty(P * E, dtype=torch.int64, device="cuda")
     d_first = torch.empty(E, dtype=torch.int64, device="cuda")
     d_rows = torch.empty(E, dtype=torch.int64, device="cuda")
+    ws_bytes = mcr.mcr_moe_route_workspace_bytes(K_MAX * T, E, P)
+    d_ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.int32, device="cuda")
     rows = []
     for it in range(reps + 2):
         e = _events(5)
         e[0].record()
-        mcr.mcr_moe_route(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
+        mcr.mcr_moe_route_ws(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S, d_ws, ws_bytes)
         e[1].record()
         mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
         e[2].record()
@@ -163,7 +167,7 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     for it in range(reps + 2):
         e = _events(5)
         e[0].record()
-        mcr.mcr_moe_route(ctx, d_ids2, A, E, P, C2, d_slot2, d_cnt, d_S)
+        mcr.mcr_moe_route_ws(ctx, d_ids2, A, E, P, C2, d_slot2, d_cnt, d_S, d_ws, ws_bytes)
         e[1].record()
         mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
         e[2].record()

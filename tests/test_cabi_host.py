@@ -105,6 +105,11 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_scatterv, ctx, A16[1:3], 0, [8, 8], S.F32, 2, S.AUTO, 0) == S.EINVAL
     assert _status(S.mcr_allgatherv, ctx, A16[:2], A16[2:4], [3, 8], S.F32, 2, 2, 0) == S.EVARIANT
     assert _status(S.mcr_allgatherv, ctx, A16[:2], A16[2:4], [0, 0], S.F32, 2, S.AUTO, 0) == 0                   # nothing to move
+    assert S.mcr_moe_route_workspace_bytes(2048, 64, 16) == 0 and S.mcr_moe_route_workspace_bytes(16384, 64, 16) == 16 * 8 * 64 * 4
+    assert S.mcr_moe_route_workspace_bytes(1 << 30, 512, 16) == 16 * 64 * 512 * 4                              # never more than 64 chunks
+    assert _status(S.mcr_moe_route_ws, ctx, A16[:2], 8192, 4, 2, 10, A16[2:4], A16[4:6], A16[6], A16[7], 64, 0) == S.EINVAL   # workspace too small
+    assert _status(S.mcr_moe_route_ws, ctx, A16[:2], 8192, 4, 2, 10, A16[2:4], A16[4:6], A16[6], A16[7], 128, 0) == S.ESTATE
+    assert _status(S.mcr_moe_route_ws, ctx, A16[:2], 8192, 4, 2, 10, A16[2:4], A16[4:6], A16[6], None, 0, 0) == S.ESTATE      # no workspace: the plain call
     # displacements chosen by the caller: extents, overlaps, alignment of the vector path
     C, SD, RD = [1, 2, 2, 1], [4, 1, 3, 0], [3, 0, 2, 5]
     assert _status(S.mcr_alltoallv_displs, ctx, A16[:2], A16[2:4], C, SD, RD, 6, 6, 4, S.F32, 2, S.AUTO, 0) == S.ESTATE

@@ -46,6 +46,47 @@ def test_moe_route_matches_oracle(T, E, P):
             assert np.array_equal(S[p], er), (T, E, P, C, p)
 
 
+@pytest.mark.parametrize("T", [2049, 4096, 16384, 20001, 70000, 150001])
+@pytest.mark.parametrize("E,P", [(4, 2), (64, 16), (512, 8), (48, 3)])
+def test_moe_route_with_workspace_matches_oracle(T, E, P):
+    """Several workgroups per rank: the same slots, counts and splits as the definition."""
+    rng = np.random.Generator(np.random.Philox(key=4000 + T + E))
+    ids = [rng.integers(-1, E + 1, size=T).astype(np.int32) for _ in range(P)]           # a few ids out of range
+    ids[0][: T // 2] = 1                                                              # one expert far over capacity
+    C = int(np.ceil(1.25 * T / E))
+    need = mcr.mcr_moe_route_workspace_bytes(T, E, P)
+    assert need > 0
+    d_ids = [_i32(x) for x in ids]
+    d_slot = [torch.full((T,), -77, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_cnt = [torch.full((E,), -77, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_S = torch.full((P * P,), -77, dtype=torch.int64, device="cuda")
+    ws = torch.full((need // 4 + 3,), -5, dtype=torch.int32, device="cuda")            # stale contents must not matter
+    mcr.mcr_moe_route_ws(gu.ctx(), d_ids, T, E, P, C, d_slot, d_cnt, d_S, ws, need)
+    gu.sync()
+    assert (ws[need // 4:].cpu().numpy() == -5).all()                                # nothing past the stated size is touched
+    for p in range(P):
+        slot, counts, srow = oracle.moe_route(ids[p], E, P, C)
+        assert np.array_equal(d_slot[p].cpu().numpy(), slot), f"slots rank {p}"
+        assert np.array_equal(d_cnt[p].cpu().numpy(), counts)
+        assert np.array_equal(d_S.cpu().numpy().reshape(P, P)[p], srow)
+    with pytest.raises(mcr.McrError) as e:
+        mcr.mcr_moe_route_ws(gu.ctx(), d_ids, T, E, P, C, d_slot, d_cnt, d_S, ws, need - 4)
+    assert e.value.status == mcr.EINVAL
+
+
+def test_moe_route_with_workspace_small_inputs_take_the_one_workgroup_path():
+    T, E, P = 1000, 8, 4
+    assert mcr.mcr_moe_route_workspace_bytes(T, E, P) == 0
+    ids = [inputs.zipf_ids(T, E, 1.2, 11, p) for p in range(P)]
+    d_slot = [torch.empty(T, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_cnt = [torch.empty(E, dtype=torch.int32, device="cuda") for _ in range(P)]
+    d_S = torch.empty(P * P, dtype=torch.int64, device="cuda")
+    mcr.mcr_moe_route_ws(gu.ctx(), [_i32(x) for x in ids], T, E, P, 300, d_slot, d_cnt, d_S, None, 0)
+    gu.sync()
+    for p in range(P):
+        assert np.array_equal(d_slot[p].cpu().numpy(), oracle.moe_route(ids[p], E, P, 300)[0])
+
+
 def test_moe_route_zipf_workload():
     w = inputs.MoEWorkload()
     for permute in (False, True):
