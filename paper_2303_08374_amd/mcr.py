@@ -92,6 +92,9 @@ _sz = ctypes.c_size_t
 
 
 # ---- lifecycle -----------------------------------------------------------------------------
+SHIPPED_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuning", "mi355x.tbl")
+
+
 def mcr_init(device: int = 0) -> ctypes.c_void_p:
     ctx = ctypes.c_void_p()
     _check(lib().mcr_init(ctypes.byref(ctx), device), "mcr_init")
