@@ -78,7 +78,9 @@ typedef enum {
   MCR_OP_MOE_DISPATCH = 11,
   MCR_OP_MOE_COMBINE = 12,
   MCR_OP_DLRM_SHUFFLE = 13,
-  MCR_OP_COUNT = 14
+  MCR_OP_MOE_DISPATCH_BY_EXPERT = 14,
+  MCR_OP_MOE_COMBINE_BY_EXPERT = 15,
+  MCR_OP_COUNT = 16
 } mcr_op;
 
 typedef enum {

@@ -21,8 +21,9 @@ namespace {
 const char* const kOpNames[MCR_OP_COUNT] = {"allreduce", "reduce_scatter", "allgather", "alltoall",
                                             "alltoallv", "pack", "unpack", "fuse",
                                             "unfuse", "allreduce_multi", "moe_route", "moe_dispatch",
-                                            "moe_combine", "dlrm_shuffle"};
-const char* const kDtypeNames[2] = {"f32", "bf16"};
+                                            "moe_combine", "dlrm_shuffle", "moe_dispatch_by_expert",
+                                            "moe_combine_by_expert"};
+const char* const kDtypeNames[4] = {"f32", "bf16", "f16", "i32"};
 const char* const kRouteVariantNames[1] = {"wave_ballot"};
 
 bool valid_dtype(int d) { return d >= MCR_F32 && d <= MCR_I32; }
@@ -793,7 +794,7 @@ int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* cons
     return MCR_EINVAL;
   const size_t row_bytes = row_elems * elem_bytes(dtype);
   int v;
-  int rc = resolve_variant(ctx, MCR_OP_MOE_DISPATCH, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
+  int rc = resolve_variant(ctx, MCR_OP_MOE_DISPATCH_BY_EXPERT, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
   DeviceScope on_device(ctx);
@@ -823,7 +824,7 @@ int mcr_moe_combine_by_expert(mcr_ctx* ctx, void* const* out, const void* const*
   if (gate && !fill_tab(tg, gate, P, MCR_F32, any, nullptr)) return MCR_EINVAL;
   const size_t row_bytes = row_elems * elem_bytes(dtype);
   int v;
-  int rc = resolve_variant(ctx, MCR_OP_MOE_COMBINE, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
+  int rc = resolve_variant(ctx, MCR_OP_MOE_COMBINE_BY_EXPERT, dtype, P, T * row_bytes, all16 && row_bytes % 16 == 0, variant, &v);
   if (rc != MCR_OK) return rc;
   if (!any) return MCR_OK;
   DeviceScope on_device(ctx);
@@ -1205,7 +1206,7 @@ int mcr_tune_load(mcr_ctx* ctx, const char* path) {
     if (std::sscanf(s, "%63s %15s %d %llu %31s", op, dt, &P, &bytes, var) != 5) { ok = false; break; }
     Row r{-1, -1, P, static_cast<size_t>(bytes), -1};
     for (int i = 0; i < MCR_OP_COUNT; ++i) if (!std::strcmp(op, kOpNames[i])) r.op = i;
-    for (int i = 0; i < 2; ++i) if (!std::strcmp(dt, kDtypeNames[i])) r.dtype = i;
+    for (int i = 0; i < 4; ++i) if (!std::strcmp(dt, kDtypeNames[i])) r.dtype = i;
     if (r.op >= 0) {
       for (int i = 0; i < n_variants(r.op); ++i) {
         const char* vname = r.op == MCR_OP_MOE_ROUTE ? kRouteVariantNames[i] : kStreamVariantNames[i];

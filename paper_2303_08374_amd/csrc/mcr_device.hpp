@@ -10,6 +10,10 @@ namespace mcr {
 
 constexpr int kBlock = 256;   // 4 wavefronts of 64 lanes
 constexpr int kWave = 64;
+// Row gathers behind a lookup (unpack, combine) on rows wider than half a workgroup: workgroup size
+// and 16-byte units each thread keeps in flight.
+constexpr int kRowGatherBlock = 128;
+constexpr int kRowGatherVecs = 2;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 

@@ -557,6 +557,134 @@ moe_combine_topk_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab
   }
 }
 
+// ---- the same three operations for rows wider than half a workgroup: one row per workgroup.
+// The row index is uniform over the workgroup, so id, slot, table entry and gate come through
+// scalar loads and nothing is staged in LDS; a one-shot grid of one-row workgroups is also the
+// shape in which 4 KiB rows move fastest on this GPU (6.0 TB/s against 5.0 for 32 rows per
+// workgroup in a plain permutation of rows).
+// Every lookup is written without a branch in front of it (indices are clamped, validity is
+// decided afterwards), so that the loads of one level go out together: kernel arguments, then
+// slot / id / gate of the row, then the table entry and the destination's base pointer, then the
+// row itself.  With early exits between them the compiler strings the scalar loads into eight
+// round trips, which made this shape slower than the one it replaces.
+// `rank_magic` = ceil(2^32 / (E/P)): (e * rank_magic) >> 32 == e / (E/P) for every e < 2^23.
+struct RowLookup {
+  int64_t row;
+  int r;
+  bool ok;
+};
+__device__ __forceinline__ RowLookup lookup_row(const int64_t* table_p, int32_t sl, int32_t e, int E, uint64_t rank_magic,
+                                                uint64_t recv_rows) {
+  const int ec = e < 0 ? 0 : (e >= E ? E - 1 : e);
+  RowLookup out;
+  out.row = table_p[ec] + sl;
+  out.r = static_cast<int>((static_cast<uint64_t>(ec) * rank_magic) >> 32);
+  out.ok = sl >= 0 && e == ec && out.row >= 0 && static_cast<uint64_t>(out.row) < recv_rows;
+  return out;
+}
+
+// blockIdx.x = assignment a (choice a / T of token a mod T), blockIdx.y = sender.
+template <int UB, bool NTL, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+moe_dispatch_row_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab slot_tab, const int64_t* row_table, int E,
+                        uint64_t rank_magic, size_t T, uint64_t recv_rows, uint32_t upr) {
+  typedef typename RowUnit<UB>::type U;
+  const int p = blockIdx.y;
+  const size_t a = blockIdx.x;
+  const int32_t sl = static_cast<const int32_t*>(slot_tab.p[p])[a];
+  const int32_t e = static_cast<const int32_t*>(ids_tab.p[p])[a];
+  const U* src = static_cast<const U*>(tok.p[p]);
+  const RowLookup d = lookup_row(row_table + static_cast<size_t>(p) * E, sl, e, E, rank_magic, recv_rows);
+  U* dbase = static_cast<U*>(recv.p[d.r]);                       // d.r < P whatever the id was
+  if (!d.ok) return;
+  const size_t t = a < T ? a : a % T;
+  const U* srow = src + t * upr;
+  U* drow = dbase + static_cast<uint64_t>(d.row) * upr;
+  for (uint32_t c = threadIdx.x; c < upr; c += kBlock) stu<NTS, U>(drow + c, ldu<NTL, U>(srow + c));
+}
+
+// blockIdx.x = token t.  K choices (KU >= K at compile time).  A gather with a chain of lookups in
+// front of it is bound by how many rows a compute unit has in flight, so the workgroup is half the
+// usual size (kRowGatherBlock threads, twice as many rows per compute unit) and every thread keeps
+// the loads of kRowGatherVecs units of each kept row in flight (6.1 against 5.4 TB/s in a plain
+// gather of 4 KiB rows behind a two-level lookup).
+template <int DT, int UB, int KU, bool NTL, bool NTS, bool GATE>
+__global__ void __launch_bounds__(kRowGatherBlock)
+moe_combine_row_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab slot_tab, CPtrTab gate_tab,
+                       const int64_t* row_table, int E, uint64_t rank_magic, size_t T, int K, uint64_t recv_rows,
+                       uint32_t upr) {
+  typedef typename RowUnit<UB>::type U;
+  typedef UnitF32<DT, UB> F;
+  constexpr int V = kRowGatherVecs;
+  const int p = blockIdx.y;
+  const size_t t = blockIdx.x;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
+  const float* gate = static_cast<const float*>(gate_tab.p[p]);
+  const int64_t* table = row_table + static_cast<size_t>(p) * E;
+  U* drow = static_cast<U*>(out.p[p]) + t * upr;
+  int32_t sl[KU], e[KU];
+  float g[KU];
+#pragma unroll
+  for (int k = 0; k < KU; ++k) {
+    const size_t a = (k < K) ? static_cast<size_t>(k) * T + t : t;          // always a valid index
+    sl[k] = slot[a];
+    e[k] = ids[a];
+    g[k] = 1.0f;
+    if constexpr (GATE) g[k] = gate[a];
+  }
+  const U* srow[KU];
+  bool kept[KU];
+  bool any = false;
+#pragma unroll
+  for (int k = 0; k < KU; ++k) {
+    const RowLookup d = lookup_row(table, sl[k], e[k], E, rank_magic, recv_rows);
+    kept[k] = d.ok && k < K;
+    srow[k] = static_cast<const U*>(expert_out.p[d.r]) + static_cast<uint64_t>(kept[k] ? d.row : 0) * upr;
+    any = any || kept[k];
+  }
+  if (!any) {
+    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) stu<NTS, U>(drow + c, U{});
+    return;
+  }
+  for (uint32_t c0 = threadIdx.x; c0 < upr; c0 += V * kRowGatherBlock) {
+    U v[V][KU];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const uint32_t c = c0 + u * kRowGatherBlock;
+#pragma unroll
+      for (int k = 0; k < KU; ++k) {
+        v[u][k] = U{};
+        if (kept[k] && c < upr) v[u][k] = ldu<NTL, U>(srow[k] + c);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const uint32_t c = c0 + u * kRowGatherBlock;
+      if (c >= upr) continue;
+      if constexpr (KU == 1 && !GATE) {                 // one choice and no weight: the row is copied bit for bit
+        stu<NTS, U>(drow + c, v[u][0]);
+      } else {
+        float acc[F::kN];
+        bool started = false;
+#pragma unroll
+        for (int k = 0; k < KU; ++k) {
+          if (!kept[k]) continue;
+          float f[F::kN];
+          F::widen(v[u][k], f);
+#pragma unroll
+          for (int x = 0; x < F::kN; ++x) {
+            const float term = g[k] * f[x];
+            acc[x] = started ? acc[x] + term : term;
+          }
+          started = true;
+        }
+        stu<NTS, U>(drow + c, F::narrow(acc));
+      }
+    }
+  }
+}
+
 // DLRM shuffle.  Table t lives on rank t mod P as local table t div P; the table-major side is
 // [T_p][batch][dim], the batch-major side [batch/P][n_tables][dim].  blockIdx.y = rank r of the
 // batch-major side; rows j = b*n_tables + t of that side are walked in order.
@@ -600,6 +728,11 @@ inline RowShape row_shape(size_t units_per_row) {
   s.tpr = 1u << s.shift;
   s.rows_per_pass = kBlock >> s.shift;
   return s;
+}
+// ceil(2^32 / (E/P)): the multiplier that turns an expert id into its rank without a division
+inline uint64_t rank_magic(int E, int P) {
+  const uint64_t per_rank = static_cast<uint64_t>(E / P);
+  return ((uint64_t(1) << 32) + per_rank - 1) / per_rank;
 }
 inline unsigned blocks_for(size_t rows, size_t rows_per_block) {
   size_t b = (rows + rows_per_block - 1) / rows_per_block;
@@ -676,6 +809,15 @@ int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& t
   auto go = [&](auto ub, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     const RowShape s = row_shape(row_bytes / UB);
+    // one row per workgroup for single-choice dispatch (193 against 212 us on the MoE workload); with
+    // several choices per token the many-rows-per-workgroup kernel below is the faster one (363
+    // against 398 us for top-2)
+    if (UB == 16 && s.tpr == kBlock && K == 1) {
+      hipLaunchKernelGGL((moe_dispatch_row_kernel<UB, decltype(ntl)::value, decltype(nts)::value>),
+                         dim3(static_cast<unsigned>(A), P), dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E,
+                         rank_magic(E, P), T, static_cast<uint64_t>(recv_rows), s.upr);
+      return launch_status();
+    }
     const unsigned gx = blocks_for(A, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
     if (s.tpr >= kWave)
       hipLaunchKernelGGL((moe_dispatch_by_expert_kernel<UB, decltype(ntl)::value, decltype(nts)::value, true>), dim3(gx, P),
@@ -688,7 +830,12 @@ int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& t
     return launch_status();
   };
   if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
-  return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(Int<16>{}, ntl, nts); });
+  return dispatch_hint(variant, [&](auto ntl, auto nts) {
+    // with several choices per token every token row is read several times: the nontemporal load
+    // hint is dropped (395 -> 363 us for top-2 on the MoE workload)
+    if (K > 1) return go(Int<16>{}, Bool<false>{}, nts);
+    return go(Int<16>{}, ntl, nts);
+  });
 }
 
 int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& ids,
@@ -703,6 +850,25 @@ int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& exp
   return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
+    if (variant != SV_SCALAR && row_shape(row_elems * EB / 16).tpr == kBlock) {     // one row per workgroup
+      const uint32_t upr = static_cast<uint32_t>(row_elems * EB / 16);
+      return dispatch_hint(variant, [&](auto ntl, auto nts) {
+        auto launch = [&](auto ku, auto gc) {
+          hipLaunchKernelGGL((moe_combine_row_kernel<DT, 16, decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value,
+                                                     decltype(gc)::value>),
+                             dim3(static_cast<unsigned>(T), P), dim3(kRowGatherBlock), 0, stream, out, expert_out, ids, slot, g,
+                             row_table, E, rank_magic(E, P), T, K, static_cast<uint64_t>(recv_rows), upr);
+        };
+        auto by_k = [&](auto gc) {
+          if (K == 1) launch(Int<1>{}, gc);
+          else if (K == 2) launch(Int<2>{}, gc);
+          else launch(Int<MCR_MAX_TOPK>{}, gc);
+        };
+        if (gate) by_k(Bool<true>{});
+        else by_k(Bool<false>{});
+        return launch_status();
+      });
+    }
     if (K > 1) {
       auto topk = [&](auto ub, auto ntl, auto nts) {
         constexpr int UB = decltype(ub)::value;

@@ -250,7 +250,24 @@ template <> struct RowUnit<16> { typedef u32x4 type; };
 template <> struct RowUnit<4> { typedef uint32_t type; };
 template <> struct RowUnit<2> { typedef uint16_t type; };
 
-template <int UB, bool NTL, bool NTS>
+// Which row a thread works on and which units of it.  ONE (a row is wider than half a workgroup):
+// the workgroup owns one row, so the row index is uniform and everything looked up by it (slot,
+// gate) comes through scalar loads: a shorter dependent chain in front of the row's own loads,
+// worth 7 % on 4 KiB rows.
+template <bool ONE>
+__device__ __forceinline__ void row_of_thread(uint32_t tpr, uint32_t tpr_shift, size_t* t, uint32_t* c0, uint32_t* step) {
+  if constexpr (ONE) {
+    *t = blockIdx.x;
+    *c0 = threadIdx.x;
+    *step = kBlock;
+  } else {
+    *t = static_cast<size_t>(blockIdx.x) * (kBlock >> tpr_shift) + (threadIdx.x >> tpr_shift);
+    *c0 = threadIdx.x & (tpr - 1);
+    *step = tpr;
+  }
+}
+
+template <int UB, bool NTL, bool NTS, bool ONE>
 __global__ void __launch_bounds__(kBlock)
 pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows, uint32_t upr,
             uint32_t tpr, uint32_t tpr_shift) {
@@ -259,14 +276,15 @@ pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows,
   const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[rank]);
   const U* src = static_cast<const U*>(in.p[rank]);
   U* dst = static_cast<U*>(out.p[rank]);
-  const uint32_t rows_per_block = kBlock >> tpr_shift;
-  const size_t t = static_cast<size_t>(blockIdx.x) * rows_per_block + (threadIdx.x >> tpr_shift);
+  size_t t;
+  uint32_t c0, step;
+  row_of_thread<ONE>(tpr, tpr_shift, &t, &c0, &step);
   if (t >= T) return;
   const int32_t s = slot[t];
   if (s < 0 || static_cast<size_t>(s) >= out_rows) return;
   const U* srow = src + t * upr;
   U* drow = dst + static_cast<size_t>(s) * upr;
-  for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+  for (uint32_t c = c0; c < upr; c += step) {
     U v;
     if constexpr (NTL) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
     if constexpr (NTS) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
@@ -292,15 +310,16 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
   const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[rank]);
   const U* src = static_cast<const U*>(in.p[rank]);
   U* dst = static_cast<U*>(out.p[rank]);
-  const uint32_t rows_per_block = kBlock >> tpr_shift;
-  const size_t t = static_cast<size_t>(blockIdx.x) * rows_per_block + (threadIdx.x >> tpr_shift);
+  size_t t;
+  uint32_t c0, step;
+  row_of_thread<false>(tpr, tpr_shift, &t, &c0, &step);
   if (t >= T) return;
   const int32_t s = slot[t];
   const bool kept = s >= 0 && static_cast<size_t>(s) < in_rows;
   U* drow = dst + t * upr;
   if (!kept) {
     U z = {};
-    for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+    for (uint32_t c = c0; c < upr; c += step) {
       if constexpr (NTS) __builtin_nontemporal_store(z, drow + c); else drow[c] = z;
     }
     return;
@@ -308,7 +327,7 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
   const U* srow = src + static_cast<size_t>(s) * upr;
   float g = 1.0f;
   if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[rank])[t];
-  for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) {
+  for (uint32_t c = c0; c < upr; c += step) {
     U v;
     if constexpr (NTL) v = __builtin_nontemporal_load(srow + c); else v = srow[c];
     if constexpr (GATE) {
@@ -321,6 +340,45 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
       }
     }
     if constexpr (NTS) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
+  }
+}
+
+// unpack for rows wider than half a workgroup: one row per workgroup of kRowGatherBlock threads (the
+// slot and the gate come through scalar loads), kRowGatherVecs units per thread in flight.  A
+// gather behind a lookup is bound by the rows a compute unit has in flight: the smaller workgroup
+// doubles them (6.1 against 5.8 TB/s in a plain gather of 4 KiB rows).
+template <int DT, bool NTL, bool NTS, bool GATE>
+__global__ void __launch_bounds__(kRowGatherBlock)
+unpack_row_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t in_rows, uint32_t upr) {
+  constexpr int V = kRowGatherVecs;
+  const unsigned rank = blockIdx.y;
+  const size_t t = blockIdx.x;
+  const int32_t s = static_cast<const int32_t*>(slot_tab.p[rank])[t];
+  float g = 1.0f;
+  if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[rank])[t];
+  const u32x4* src = static_cast<const u32x4*>(in.p[rank]);
+  u32x4* drow = static_cast<u32x4*>(out.p[rank]) + t * upr;
+  const bool kept = s >= 0 && static_cast<size_t>(s) < in_rows;
+  if (!kept) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) store16<NTS>(drow, c, z);
+    return;
+  }
+  const u32x4* srow = src + static_cast<size_t>(s) * upr;
+  for (uint32_t c0 = threadIdx.x; c0 < upr; c0 += V * kRowGatherBlock) {
+    u32x4 v[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const uint32_t c = c0 + u * kRowGatherBlock;
+      if (c < upr) v[u] = load16<NTL>(srow, c);
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const uint32_t c = c0 + u * kRowGatherBlock;
+      if (c >= upr) continue;
+      if constexpr (GATE) v[u] = scale_vec<DT>(v[u], g);
+      store16<NTS>(drow, c, v[u]);
+    }
   }
 }
 
@@ -383,15 +441,19 @@ int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& s
   if (variant == SV_SCALAR) {
     const RowShape s = row_shape(T, row_bytes / elem_b);
     if (elem_b == 4)
-      hipLaunchKernelGGL((pack_kernel<4, false, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+      hipLaunchKernelGGL((pack_kernel<4, false, false, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
     else
-      hipLaunchKernelGGL((pack_kernel<2, false, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+      hipLaunchKernelGGL((pack_kernel<2, false, false, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
     return launch_status();
   }
   const RowShape s = row_shape(T, row_bytes / 16);
   return dispatch_hint(variant, [&](auto ntl, auto nts) {
-    hipLaunchKernelGGL((pack_kernel<16, decltype(ntl)::value, decltype(nts)::value>), dim3(s.blocks, P), dim3(kBlock), 0,
-                       stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+    if (s.tpr == kBlock)
+      hipLaunchKernelGGL((pack_kernel<16, decltype(ntl)::value, decltype(nts)::value, true>), dim3(s.blocks, P), dim3(kBlock), 0,
+                         stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+    else
+      hipLaunchKernelGGL((pack_kernel<16, decltype(ntl)::value, decltype(nts)::value, false>), dim3(s.blocks, P), dim3(kBlock), 0,
+                         stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
     return launch_status();
   });
 }
@@ -409,8 +471,12 @@ int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab&
     auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
       constexpr int UB = decltype(ub)::value;
       const RowShape s = row_shape(T, row_elems * EB / UB);
-      hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
-                         dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);
+      if (UB == 16 && s.tpr == kBlock)
+        hipLaunchKernelGGL((unpack_row_kernel<DT, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
+                           dim3(static_cast<unsigned>(T), P), dim3(kRowGatherBlock), 0, stream, out, in, slot, g, in_rows, s.upr);
+      else
+        hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
+                           dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);
       return launch_status();
     };
     if (variant == SV_SCALAR)

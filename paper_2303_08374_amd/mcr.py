@@ -21,8 +21,10 @@ MAX_TOPK = 4
 OP_ALLREDUCE, OP_REDUCE_SCATTER, OP_ALLGATHER, OP_ALLTOALL, OP_ALLTOALLV = 0, 1, 2, 3, 4
 OP_PACK, OP_UNPACK, OP_FUSE, OP_UNFUSE, OP_ALLREDUCE_MULTI, OP_MOE_ROUTE = 5, 6, 7, 8, 9, 10
 OP_MOE_DISPATCH, OP_MOE_COMBINE, OP_DLRM_SHUFFLE = 11, 12, 13
+OP_MOE_DISPATCH_BY_EXPERT, OP_MOE_COMBINE_BY_EXPERT = 14, 15
 OP_NAMES = ["allreduce", "reduce_scatter", "allgather", "alltoall", "alltoallv", "pack", "unpack",
-            "fuse", "unfuse", "allreduce_multi", "moe_route", "moe_dispatch", "moe_combine", "dlrm_shuffle"]
+            "fuse", "unfuse", "allreduce_multi", "moe_route", "moe_dispatch", "moe_combine", "dlrm_shuffle",
+            "moe_dispatch_by_expert", "moe_combine_by_expert"]
 
 OK, EINVAL, EDTYPE, EOP, EVARIANT, ESPLIT, EHIP, ENOMEM, EIO, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8, -9
 

@@ -44,7 +44,9 @@ def tune_workload_ops(ctx, verbose: bool = True):
         # (label, runner, {op id: [stage names]}, dtype, P, table bytes)
         ("moe", lambda vv: workloads.moe_dispatch_combine(ctx, reps=5, variants=vv),
          {mcr.OP_PACK: ["pack"], mcr.OP_ALLTOALLV: ["alltoallv_dispatch", "alltoallv_return"], mcr.OP_UNPACK: ["unpack_combine"],
-          mcr.OP_MOE_DISPATCH: ["fused/moe_dispatch"], mcr.OP_MOE_COMBINE: ["fused/moe_combine"]},
+          mcr.OP_MOE_DISPATCH: ["fused/moe_dispatch"], mcr.OP_MOE_COMBINE: ["fused/moe_combine"],
+          mcr.OP_MOE_DISPATCH_BY_EXPERT: ["by_expert/moe_dispatch_by_expert"],
+          mcr.OP_MOE_COMBINE_BY_EXPERT: ["by_expert/moe_combine_by_expert"]},
          mcr.BF16, moe.P, moe.T * moe.H * 2),
         ("dlrm", lambda vv: workloads.dlrm_shuffle(ctx, reps=5, variants=vv),
          {mcr.OP_PACK: ["fwd_pack_send_order", "bwd_pack_permute"], mcr.OP_ALLTOALLV: ["fwd_alltoallv", "bwd_alltoallv"],
@@ -57,7 +59,8 @@ def tune_workload_ops(ctx, verbose: bool = True):
     ]
     key_of = {mcr.OP_PACK: "pack", mcr.OP_ALLTOALLV: "alltoallv", mcr.OP_UNPACK: "unpack", mcr.OP_FUSE: "fuse",
               mcr.OP_UNFUSE: "unfuse", mcr.OP_ALLREDUCE_MULTI: "allreduce_multi", mcr.OP_MOE_DISPATCH: "moe_dispatch",
-              mcr.OP_MOE_COMBINE: "moe_combine", mcr.OP_DLRM_SHUFFLE: "dlrm_shuffle"}
+              mcr.OP_MOE_COMBINE: "moe_combine", mcr.OP_DLRM_SHUFFLE: "dlrm_shuffle",
+              mcr.OP_MOE_DISPATCH_BY_EXPERT: "moe_dispatch_by_expert", mcr.OP_MOE_COMBINE_BY_EXPERT: "moe_combine_by_expert"}
 
     def stage_us(rep, path):
         for part in path.split("/"):

@@ -145,10 +145,10 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
         mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
         e[2].record()
         mcr.mcr_moe_dispatch_by_expert(ctx, d_recv, d_tok, d_ids, d_slot, d_tab, T, 1, E, w.recv_rows, H, mcr.BF16, P,
-                                       _v(variants, "moe_dispatch"))
+                                       _v(variants, "moe_dispatch_by_expert"))
         e[3].record()
         mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, 1, E, w.recv_rows, H, mcr.BF16, P,
-                                      _v(variants, "moe_combine"))
+                                      _v(variants, "moe_combine_by_expert"))
         e[4].record()
         if it >= 2:
             rows.append(e)
@@ -172,10 +172,10 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
         mcr.mcr_moe_expert_layout(ctx, d_cnt, E, P, d_tab, d_first, d_rows)
         e[2].record()
         mcr.mcr_moe_dispatch_by_expert(ctx, d_recv2, d_tok, d_ids2, d_slot2, d_tab, T, K, E, rows2, H, mcr.BF16, P,
-                                       _v(variants, "moe_dispatch"))
+                                       _v(variants, "moe_dispatch_by_expert"))
         e[3].record()
         mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv2, d_ids2, d_slot2, d_gate2, d_tab, T, K, E, rows2, H, mcr.BF16, P,
-                                      _v(variants, "moe_combine"))
+                                      _v(variants, "moe_combine_by_expert"))
         e[4].record()
         if it >= 2:
             rows.append(e)

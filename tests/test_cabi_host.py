@@ -171,13 +171,23 @@ def test_tuning_table_reproduces_table2(ctx, tmp_path):
         for size in sizes:
             mcr.mcr_tune_set(ctx, mcr.OP_ALLREDUCE, mcr.BF16, P, size, 4)
     assert mcr.mcr_tune_count(ctx) == 8 + 1 * 2 * 8
+    # every element type and the last op of the enumeration have a name in the file
+    mcr.mcr_tune_set(ctx, mcr.OP_REDUCE_SCATTER, mcr.F16, 8, 1 << 20, 5)
+    mcr.mcr_tune_set(ctx, mcr.OP_MOE_COMBINE_BY_EXPERT, mcr.I32, 16, 1 << 26, 7)
     # save / load round trip
     path = str(tmp_path / "table.txt")
     mcr.mcr_tune_save(ctx, path)
+    text = open(path).read()
+    assert "reduce_scatter f16 8 1048576 v2nt" in text and "moe_combine_by_expert i32 16 67108864 v1ln" in text
     other = mcr.mcr_init(-1)
     try:
         mcr.mcr_tune_load(other, path)
-        assert mcr.mcr_tune_count(other) == 24
+        assert mcr.mcr_tune_count(other) == 26
+        assert mcr.mcr_tune_get(other, mcr.OP_REDUCE_SCATTER, mcr.F16, 8, 1 << 21) == 5
+        assert mcr.mcr_tune_get(other, mcr.OP_MOE_COMBINE_BY_EXPERT, mcr.I32, 16, 1 << 27) == 7
+        mcr.mcr_tune_clear(ctx)
+        mcr.mcr_tune_load(ctx, path)
+        assert mcr.mcr_tune_count(ctx) == 26
         for probe in [1, 300, 4096, 9000, 1 << 20]:
             assert mcr.mcr_tune_get(other, mcr.OP_ALLGATHER, mcr.F32, 8, probe) == mcr.mcr_tune_get(ctx, mcr.OP_ALLGATHER, mcr.F32, 8, probe)
             assert mcr.mcr_tune_get(other, mcr.OP_ALLREDUCE, mcr.BF16, 4, probe) == 4
@@ -187,7 +197,7 @@ def test_tuning_table_reproduces_table2(ctx, tmp_path):
     bad = tmp_path / "bad.txt"
     bad.write_text("allgather f32 8 4096 v4\nallgather f32 8 oops v4\n")
     assert _status(mcr.mcr_tune_load, ctx, str(bad)) == mcr.EIO
-    assert mcr.mcr_tune_count(ctx) == 24
+    assert mcr.mcr_tune_count(ctx) == 26
     assert _status(mcr.mcr_tune_load, ctx, str(tmp_path / "missing.txt")) == mcr.EIO
     assert _status(mcr.mcr_tune_set, ctx, 0, 0, 8, 4096, 99) == mcr.EVARIANT
     assert _status(mcr.mcr_tune_set, ctx, 99, 0, 8, 4096, 1) == mcr.EOP

@@ -99,7 +99,8 @@ def test_moe_route_zipf_workload():
 
 # ----------------------------------------------------------------- pack / unpack
 @pytest.mark.parametrize("dtype,w", [(mcr.F32, 1), (mcr.F32, 4), (mcr.F32, 128), (mcr.BF16, 5), (mcr.BF16, 8),
-                                      (mcr.BF16, 2048), (mcr.BF16, 24), (mcr.F32, 1028)])
+                                      (mcr.BF16, 2048), (mcr.BF16, 24), (mcr.F32, 1028), (mcr.BF16, 1040), (mcr.F32, 516),
+                                      (mcr.BF16, 8200)])
 def test_pack_unpack_combine(dtype, w):
     P, T, E = 3, 777, 12
     g = np.random.Generator(np.random.Philox(key=w))
@@ -286,6 +287,10 @@ def test_moe_by_expert_small():
     _moe_by_expert(inputs.MoEWorkload(P=8, T=3000, H=16, E=512))                      # the largest expert count
     _moe_by_expert(inputs.MoEWorkload(P=1, T=65, H=16, E=3))
     _moe_by_expert(inputs.MoEWorkload(P=2, T=0, H=16, E=4))
+    # rows wider than half a workgroup take the one-row-per-workgroup kernels: 130, 256, 257 and 1025 vectors per row
+    for H, dt in ((1040, mcr.BF16), (2048, mcr.BF16), (1028, mcr.F32), (8200, mcr.BF16)):
+        for v in (mcr.AUTO, 1, 6, 8, 11):
+            _moe_by_expert(inputs.MoEWorkload(P=4, T=300, H=H, E=8, capacity_factor=0.8), variant=v, dtype=dt, permute=True)
 
 
 @pytest.mark.parametrize("K", [2, 3, 4])
@@ -298,6 +303,9 @@ def test_moe_by_expert_top_k(K):
         _moe_by_expert(inputs.MoEWorkload(P=3, T=500, H=256, E=48), variant=v, K=K)
     _moe_by_expert(inputs.MoEWorkload(P=2, T=0, H=16, E=4), K=K)
     _moe_by_expert(inputs.MoEWorkload(P=1, T=65, H=16, E=3), K=K)
+    for H, dt in ((1040, mcr.BF16), (1028, mcr.F32), (4104, mcr.BF16)):                 # one row per workgroup
+        for v in (mcr.AUTO, 7):
+            _moe_by_expert(inputs.MoEWorkload(P=4, T=300, H=H, E=8, capacity_factor=0.8), variant=v, dtype=dt, K=K, permute=True)
 
 
 def test_moe_by_expert_config3_full_size():
