@@ -217,6 +217,11 @@ def test_moe_pipeline_small():
         _moe_pipeline(inputs.MoEWorkload(P=4, T=1000, H=72, E=8), fused_variant=v)
     _moe_pipeline(inputs.MoEWorkload(P=16, T=100, H=8, E=16, capacity_factor=0.5))   # heavy dropping, one-vector rows
     _moe_pipeline(inputs.MoEWorkload(P=1, T=65, H=16, E=3))
+    # rows wider than half a workgroup: the one-row-per-workgroup forms of the fused pair (130 and 513 vectors per row)
+    for v in (mcr.AUTO, 1, 6, 8, 11):
+        _moe_pipeline(inputs.MoEWorkload(P=4, T=300, H=1040, E=8, capacity_factor=0.8), permute=True, fused_variant=v)
+    _moe_pipeline(inputs.MoEWorkload(P=16, T=90, H=4104, E=16, capacity_factor=0.5))
+    _moe_pipeline(inputs.MoEWorkload(P=1, T=65, H=2048, E=3))
 
 
 def test_moe_pipeline_config3_full_size():
@@ -537,3 +542,73 @@ def test_allreduce_multi_single_bucket():
                 gu.assert_bits_equal(gu.to_host(dev[p][i], np.float32), exp[p], f"bucket-0 only t={i}")
     finally:
         mcr.mcr_fuse_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("H", [24, 2048])
+def test_fused_moe_pair_with_hostile_splits_and_slots(H):
+    """The split matrix and the slots are device data the library cannot check on the host: negative or huge split
+    entries count as 0 / as T, slots outside the packed range and rows outside the receive buffer are skipped.  The
+    result is what that rule says (modelled here in numpy), for the narrow-row and the one-row-per-workgroup kernels."""
+    P, T, recv_rows = 4, 200, 150
+    rng = np.random.Generator(np.random.Philox(key=5200 + H))
+    S = rng.integers(0, 80, size=(P, P)).astype(np.int64)
+    S[1, 2] = -5
+    S[2, 0] = 1 << 40
+    S[3, 3] = T + 7
+    slots = [rng.integers(-3, T + 5, size=T).astype(np.int32) for _ in range(P)]
+    # distinct destinations per sender are not guaranteed any more; make the slots of one sender distinct where valid
+    for p in range(P):
+        perm = rng.permutation(T + 8).astype(np.int32)[:T] - 3
+        slots[p] = perm
+    toks = [inputs.normal(T * H, 5201, p, 3, bf16=True) for p in range(P)]
+    gates = [inputs.uniform01(T, 5202, p) for p in range(P)]
+    Sc = np.clip(S, 0, T)
+    sd = np.concatenate([np.zeros((P, 1), dtype=np.int64), np.cumsum(Sc, axis=1)], axis=1)       # sd[p][r]
+    rd = np.cumsum(Sc, axis=0) - Sc                                                                 # rd[p][r]: rows above p in column r
+    exp_recv = [np.zeros(recv_rows * H, dtype=np.uint16) for _ in range(P)]
+    where = [[None] * T for _ in range(P)]
+    for p in range(P):
+        for t in range(T):
+            s = int(slots[p][t])
+            if s < 0 or s >= sd[p][P] or s >= T:
+                continue
+            r = int(sum(1 for q in range(1, P) if sd[p][q] <= s))
+            row = int(rd[p][r] + (s - sd[p][r]))
+            if row >= recv_rows:
+                continue
+            where[p][t] = (r, row)
+    # two senders may now claim one row; keep the model simple by checking only rows claimed once
+    claims = {}
+    for p in range(P):
+        for t in range(T):
+            if where[p][t]:
+                claims.setdefault(where[p][t], []).append((p, t))
+    d_recv = [gu.dev_empty(recv_rows * H, mcr.BF16, 0) for _ in range(P)]
+    d_slot = [torch.from_numpy(s).cuda() for s in slots]
+    d_S = torch.from_numpy(S.reshape(-1)).cuda()
+    d_tok = [gu.to_dev(x) for x in toks]
+    mcr.mcr_moe_dispatch(gu.ctx(), d_recv, d_tok, d_slot, d_S, T, recv_rows, H, mcr.BF16, P)
+    d_out = [gu.dev_empty(T * H, mcr.BF16, 1) for _ in range(P)]
+    mcr.mcr_moe_combine(gu.ctx(), d_out, d_recv, d_slot, [torch.from_numpy(g).cuda() for g in gates], d_S, T, recv_rows, H,
+                        mcr.BF16, P)
+    gu.sync()
+    got_recv = [gu.to_host(d, np.uint16).reshape(recv_rows, H) for d in d_recv]
+    touched = [np.zeros(recv_rows, dtype=bool) for _ in range(P)]
+    for (r, row), who in claims.items():
+        touched[r][row] = True
+        if len(who) == 1:
+            p, t = who[0]
+            assert np.array_equal(got_recv[r][row], toks[p].reshape(T, H)[t]), f"dispatch ({p},{t}) -> ({r},{row})"
+        else:
+            assert any(np.array_equal(got_recv[r][row], toks[p].reshape(T, H)[t]) for p, t in who)
+    for r in range(P):
+        assert (got_recv[r][~touched[r]] == 0).all(), "a row nobody claimed was written"
+    for p in range(P):
+        got = gu.to_host(d_out[p], np.uint16).reshape(T, H)
+        for t in range(T):
+            if where[p][t] is None:
+                assert (got[t] == 0).all(), f"combine ({p},{t}) should be zeros"
+            else:
+                r, row = where[p][t]
+                exp = oracle.unpack(got_recv[r][row].copy(), np.array([0], dtype=np.int32), gates[p][t:t + 1], H, oracle.BF16)
+                assert np.array_equal(got[t], exp), f"combine ({p},{t})"
