@@ -326,6 +326,16 @@ int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int
                           int64_t* row_table, int64_t* expert_first, int64_t* expert_rows,
                           void* stream);
 
+/* mcr_moe_source_layout: the row table of the OTHER receive layout, the one mcr_pack followed by
+ * mcr_alltoallv (and mcr_moe_dispatch) produces: at rank r the rows are ordered by (source rank,
+ * local expert, token order).  With S[p][r] = sum of counts[p][e] over the experts of rank r:
+ *   row_table[p*E + e] = sum_{q<p} S[q][e/(E/P)] - sum_{r'<e/(E/P)} S[p][r'].
+ * mcr_moe_dispatch_by_expert / mcr_moe_combine_by_expert fed this table move the same rows to the
+ * same places as mcr_moe_dispatch / mcr_moe_combine, bit for bit, with the faster kernels of the
+ * table-driven calls.  Arguments as for mcr_moe_expert_layout. */
+int mcr_moe_source_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int P,
+                          int64_t* row_table, void* stream);
+
 /* Top-K gating: every token has K choices (1 <= K <= MCR_MAX_TOPK).  expert_ids[p], slot[p] and
  * gate[p] then hold K*T entries, choice-major: entry a = k*T + t is choice k of token t.  Routing
  * is mcr_moe_route over those K*T entries (its T argument = K*T), which walks them in that order,

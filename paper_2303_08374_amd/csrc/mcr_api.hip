@@ -776,6 +776,18 @@ int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int
   return launch_moe_expert_layout(ctx, tc, E, P, row_table, expert_first, expert_rows, static_cast<hipStream_t>(stream));
 }
 
+int mcr_moe_source_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int P, int64_t* row_table, void* stream) {
+  if (!ctx || !counts || !row_table || !valid_P(P)) return MCR_EINVAL;
+  if (E < 1 || E > MCR_MAX_EXPERTS || E % P != 0) return MCR_EINVAL;
+  if (reinterpret_cast<uintptr_t>(row_table) & 7u) return MCR_EINVAL;
+  CPtrTab tc;
+  if (!fill_tab(tc, counts, P, MCR_F32, true, nullptr)) return MCR_EINVAL;
+  int rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
+  return launch_moe_source_layout(ctx, tc, E, P, row_table, static_cast<hipStream_t>(stream));
+}
+
 int mcr_moe_dispatch_by_expert(mcr_ctx* ctx, void* const* recv, const void* const* tokens, const int32_t* const* expert_ids,
                                const int32_t* const* slot, const int64_t* row_table, size_t T, int K, int E,
                                size_t recv_rows, size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream) {

@@ -290,6 +290,42 @@ moe_expert_layout_kernel(CPtrTab counts, int E, int P, int64_t* row_table, int64
     if (p < P) row_table[static_cast<size_t>(p) * E + e] = first + above[p] - cnt[p][e];
 }
 
+// The row table of the source-major layout, the one pack + all_to_allv leave behind: at receiver r
+// the rows are ordered by (source rank, local expert, token order), so with S[p][r] = kept tokens
+// of sender p for the experts of rank r,
+//   row_table[p][e] = sum_{q<p} S[q][r(e)] - sum_{r'<r(e)} S[p][r'],
+// and the by-expert dispatch / combine kernels, fed this table, reproduce that layout.
+__global__ void __launch_bounds__(kLayoutBlock)
+moe_source_layout_kernel(CPtrTab counts, int E, int P, int64_t* row_table) {
+  __shared__ int32_t cnt[MCR_MAX_RANKS][MCR_MAX_EXPERTS];
+  __shared__ long long S[MCR_MAX_RANKS][MCR_MAX_RANKS];
+  const int e = threadIdx.x;
+  const bool live = e < E;
+  const int per_rank = E / P;
+  for (int p = 0; p < P; ++p) {
+    int32_t x = 0;
+    if (live) x = static_cast<const int32_t*>(counts.p[p])[e];
+    cnt[p][e] = x > 0 ? x : 0;
+  }
+  __syncthreads();
+  if (threadIdx.x < P * P) {
+    const int p = threadIdx.x / P, r = threadIdx.x % P;
+    long long a = 0;
+    for (int k = r * per_rank; k < (r + 1) * per_rank; ++k) a += cnt[p][k];
+    S[p][r] = a;
+  }
+  __syncthreads();
+  if (!live) return;
+  const int r = e / per_rank;
+  long long above = 0;                                   // rows of the senders before p at receiver r
+  for (int p = 0; p < P; ++p) {
+    long long left = 0;                                  // rows sender p packs for the receivers before r
+    for (int q = 0; q < r; ++q) left += S[p][q];
+    row_table[static_cast<size_t>(p) * E + e] = above - left;
+    above += S[p][r];
+  }
+}
+
 // Where token t of this sender goes: rank (negative: nowhere) and row in that rank's buffer.
 struct RowDest {
   int32_t r;
@@ -798,6 +834,11 @@ int launch_moe_expert_layout(mcr_ctx*, const CPtrTab& counts, int E, int P, int6
                              int64_t* expert_rows, hipStream_t stream) {
   hipLaunchKernelGGL(moe_expert_layout_kernel, dim3(1), dim3(kLayoutBlock), 0, stream, counts, E, P, row_table, expert_first,
                      expert_rows);
+  return launch_status();
+}
+
+int launch_moe_source_layout(mcr_ctx*, const CPtrTab& counts, int E, int P, int64_t* row_table, hipStream_t stream) {
+  hipLaunchKernelGGL(moe_source_layout_kernel, dim3(1), dim3(kLayoutBlock), 0, stream, counts, E, P, row_table);
   return launch_status();
 }
 

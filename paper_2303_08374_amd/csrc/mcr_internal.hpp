@@ -108,6 +108,7 @@ int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, c
                        hipStream_t);
 int launch_moe_expert_layout(mcr_ctx*, const CPtrTab& counts, int E, int P, int64_t* row_table, int64_t* expert_first,
                              int64_t* expert_rows, hipStream_t);
+int launch_moe_source_layout(mcr_ctx*, const CPtrTab& counts, int E, int P, int64_t* row_table, hipStream_t);
 int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& ids, const CPtrTab& slot,
                                   const int64_t* row_table, int E, size_t T, int K, size_t recv_rows, size_t row_bytes,
                                   int elem_b, int P, int variant, hipStream_t);

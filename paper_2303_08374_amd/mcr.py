@@ -289,6 +289,11 @@ def mcr_moe_expert_layout(ctx, counts: Sequence[Ptr], E: int, P: int, row_table:
                                        _stream(stream)), "mcr_moe_expert_layout")
 
 
+def mcr_moe_source_layout(ctx, counts: Sequence[Ptr], E: int, P: int, row_table: Ptr, stream=None) -> None:
+    _check(lib().mcr_moe_source_layout(ctx, _ptr_array(counts), E, P, ctypes.c_void_p(_addr(row_table)), _stream(stream)),
+           "mcr_moe_source_layout")
+
+
 def mcr_moe_dispatch_by_expert(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], expert_ids: Sequence[Ptr], slot: Sequence[Ptr],
                                row_table: Ptr, T: int, K: int, E: int, recv_rows: int, row_elems: int, dtype: int, P: int,
                                variant: int = AUTO, stream=None) -> None:

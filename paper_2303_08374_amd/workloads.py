@@ -155,6 +155,27 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     torch.cuda.synchronize()
     ealg = [0, 0, 2 * kept * row + P * T * 8, kept * row + P * T * row + P * T * 12]
     rep["by_expert"] = _stage_report(["route", "expert_layout", "moe_dispatch_by_expert", "moe_combine_by_expert"], ealg, rows)
+    # the chain's own (source-major) layout through the same table-driven calls
+    rows = []
+    for it in range(reps + 2):
+        e = _events(5)
+        e[0].record()
+        mcr.mcr_moe_route_ws(ctx, d_ids, T, E, P, C, d_slot, d_cnt, d_S, d_ws, ws_bytes)
+        e[1].record()
+        mcr.mcr_moe_source_layout(ctx, d_cnt, E, P, d_tab)
+        e[2].record()
+        mcr.mcr_moe_dispatch_by_expert(ctx, d_recv, d_tok, d_ids, d_slot, d_tab, T, 1, E, w.recv_rows, H, mcr.BF16, P,
+                                       _v(variants, "moe_dispatch_by_expert"))
+        e[3].record()
+        mcr.mcr_moe_combine_by_expert(ctx, d_out, d_recv, d_ids, d_slot, d_gate, d_tab, T, 1, E, w.recv_rows, H, mcr.BF16, P,
+                                      _v(variants, "moe_combine_by_expert"))
+        e[4].record()
+        if it >= 2:
+            rows.append(e)
+    torch.cuda.synchronize()
+    rep["source_major_by_table"] = _stage_report(["route", "source_layout", "moe_dispatch_by_expert", "moe_combine_by_expert"],
+                                                 ealg, rows)
+    rep["source_major_by_table"]["speedup_vs_chain"] = round(rep["end_to_end"]["us"] / rep["source_major_by_table"]["end_to_end"]["us"], 2)
     # top-2 gating on the same tokens: second choice = the id stream rotated by 17 tokens, capacity doubled
     K = 2
     A, C2 = K * T, int(math.ceil(w.capacity_factor * K * T / E))

@@ -196,6 +196,13 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None, fused_
     mcr.mcr_moe_dispatch(c, f_recv, d_tok, d_slot, d_S, T, recv_rows, H, mcr.BF16, P, fused_variant)
     mcr.mcr_moe_combine(c, f_out, f_recv, d_slot, d_gate, d_S, T, recv_rows, H, mcr.BF16, P, fused_variant)
     mcr.mcr_moe_combine(c, f_plain, f_recv, d_slot, None, d_S, T, recv_rows, H, mcr.BF16, P, fused_variant)
+    # the same layout through the table-driven calls: source-major row table
+    d_tab = torch.full((P * E,), -77, dtype=torch.int64, device="cuda")
+    t_recv = [gu.dev_empty(recv_rows * H, mcr.BF16, 0) for _ in range(P)]
+    t_out = [gu.dev_empty(T * H, mcr.BF16, 1) for _ in range(P)]
+    mcr.mcr_moe_source_layout(c, d_cnt, E, P, d_tab)
+    mcr.mcr_moe_dispatch_by_expert(c, t_recv, d_tok, d_ids, d_slot, d_tab, T, 1, E, recv_rows, H, mcr.BF16, P, fused_variant)
+    mcr.mcr_moe_combine_by_expert(c, t_out, t_recv, d_ids, d_slot, d_gate, d_tab, T, 1, E, recv_rows, H, mcr.BF16, P, fused_variant)
     gu.sync()
     for p in (check_ranks if check_ranks is not None else range(P)):
         assert np.array_equal(d_slot[p].cpu().numpy(), routes[p][0])
@@ -206,6 +213,8 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None, fused_
         gu.assert_bits_equal(gu.to_host(d_out[p], np.uint16), exp, f"combine r={p}")
         gu.assert_bits_equal(gu.to_host(f_recv[p], np.uint16), recv[p], f"fused dispatch r={p}")
         gu.assert_bits_equal(gu.to_host(f_out[p], np.uint16), exp, f"fused combine r={p}")
+        gu.assert_bits_equal(gu.to_host(t_recv[p], np.uint16), recv[p], f"table-driven source-major dispatch r={p}")
+        gu.assert_bits_equal(gu.to_host(t_out[p], np.uint16), exp, f"table-driven source-major combine r={p}")
         gu.assert_bits_equal(gu.to_host(f_plain[p], np.uint16), oracle.unpack(back[p], routes[p][0], None, H, oracle.BF16),
                              f"fused combine without gate r={p}")
 
