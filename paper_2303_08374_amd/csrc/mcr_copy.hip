@@ -111,9 +111,10 @@ alltoall_kernel(PtrTab out, CPtrTab in, size_t b) {
 // sides, so a pair is a plain linear copy of S[p][r]*upr units from
 //   in[p]  + sdispl[p][r]*upr    (sdispl = sum of row p of S left of r)
 // to out[r] + rdispl[r][p]*upr   (rdispl = sum of column r of S above p),
-// and every workgroup derives its two displacements itself from at most 2*(P-1)
-// entries of S with uniform loads: no table, no search, no division per thread.
-// S comes by value (host matrix) or is read from device memory (no host sync).
+// A host matrix is turned into a table of pair lengths and displacements on the
+// host (alltoallv_pairs_kernel below).  For a matrix in device memory (no host
+// sync) every workgroup derives its two displacements itself from at most
+// 2*(P-1) entries of S: no table, no search, no division per thread.
 // In dispatch order the chip walks one pair after the other: one read stream
 // and one write stream at a time.  Skew costs nothing but workgroups that find
 // their tile beyond the pair's end and leave at once; pairs longer than the
@@ -141,10 +142,34 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
   uint64_t rows = clamp_split(S[p * P + r], in_rows);
   if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;      // the common early exit
   uint64_t sdispl = 0, rdispl = 0;
-  // same_src: every receiver gets the sender's rows from row 0 on (all_gatherv, bcast)
-  if (!same_src)
-    for (int q = 0; q < r; ++q) sdispl += clamp_split(S[p * P + q], in_rows);
-  for (int q = 0; q < p; ++q) rdispl += clamp_split(S[q * P + r], in_rows);
+  if constexpr (DEV) {
+    // The two displacements: lane q of every wavefront loads the q-th entry of row p (counted when
+    // q < r) and of column r (counted when q < p), both loads go out together, and a butterfly over
+    // the 16 lanes adds them up.  (A loop of uniform loads costs one memory round trip per entry, up
+    // to 2 * (P - 1) of them in a row, before the first byte is copied.)
+    // same_src: every receiver gets the sender's rows from row 0 on (all_gatherv, bcast)
+    const int lane = static_cast<int>(__lane_id());
+    uint64_t a = 0, b = 0;
+    if (lane < P) {
+      if (!same_src && lane < r) a = clamp_split(ds[p * P + lane], in_rows);
+      if (lane < p) b = clamp_split(ds[lane * P + r], in_rows);
+    }
+#pragma unroll
+    for (int d = MCR_MAX_RANKS / 2; d >= 1; d >>= 1) {
+      a += __shfl_xor(static_cast<unsigned long long>(a), d);
+      b += __shfl_xor(static_cast<unsigned long long>(b), d);
+    }
+    sdispl = (static_cast<uint64_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32))) << 32) |
+             __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+    rdispl = (static_cast<uint64_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b >> 32))) << 32) |
+             __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b));
+  } else {
+    // a host matrix normally goes through the pair-table kernel; this is the fallback for pairs too
+    // long for its 32-bit offsets
+    if (!same_src)
+      for (int q = 0; q < r; ++q) sdispl += clamp_split(S[p * P + q], in_rows);
+    for (int q = 0; q < p; ++q) rdispl += clamp_split(S[q * P + r], in_rows);
+  }
   // rows that would leave either buffer are not copied
   if (sdispl >= in_rows || rdispl >= out_rows) return;
   if (rows > in_rows - sdispl) rows = in_rows - sdispl;
@@ -291,6 +316,33 @@ int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64
   }
   if (max_pair == 0 || row_bytes == 0) return MCR_OK;
   const bool dev = host_splits == nullptr;
+  if (!dev) {
+    // a host matrix: the displacements are worked out here and handed to the pair-table kernel,
+    // so that no workgroup computes a prefix sum; rows that would leave either buffer are clipped
+    const uint64_t upr = row_bytes / (variant == SV_SCALAR ? static_cast<size_t>(elem_b) : 16);
+    uint32_t cnt[MCR_MAX_RANKS * MCR_MAX_RANKS], sd[MCR_MAX_RANKS * MCR_MAX_RANKS], rd[MCR_MAX_RANKS * MCR_MAX_RANKS];
+    bool fits = true;
+    uint64_t col[MCR_MAX_RANKS] = {0};
+    for (int p = 0; p < P && fits; ++p) {
+      uint64_t run = 0;
+      for (int r = 0; r < P; ++r) {
+        const int i = p * P + r;
+        uint64_t rows = static_cast<uint64_t>(host_splits[i]);
+        const uint64_t from = same_src ? 0 : run, to = col[r];
+        run += rows;
+        col[r] += rows;
+        if (from >= in_rows || to >= out_rows) rows = 0;
+        if (rows > in_rows - from) rows = in_rows - from;
+        if (rows > out_rows - to) rows = out_rows - to;
+        const uint64_t c = rows * upr, s = rows ? from * upr : 0, d = rows ? to * upr : 0;
+        if (c > 0xffffffffull || s > 0xffffffffull || d > 0xffffffffull) { fits = false; break; }
+        cnt[i] = static_cast<uint32_t>(c);
+        sd[i] = static_cast<uint32_t>(s);
+        rd[i] = static_cast<uint32_t>(d);
+      }
+    }
+    if (fits) return launch_alltoallv_pairs(nullptr, out, in, cnt, sd, rd, elem_b, P, variant, stream);
+  }
 
   auto go = [&](auto ub, auto uu, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
