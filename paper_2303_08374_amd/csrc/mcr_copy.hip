@@ -229,6 +229,30 @@ alltoallv_pairs_kernel(PtrTab out, CPtrTab in, PairArg a, int P) {
   }
 }
 
+// The same table when every sender hands the *same* segment to all of its receivers (bcast,
+// all_gatherv) and the segment is longer than the last-level cache keeps: pair by pair, each
+// receiver's copy would fetch the segment from memory again.  Super-chunk order as in all_gather:
+// workgroups numbered [sender (y)] [super-chunk] [receiver] [tile], plain loads so that the
+// re-reads of a super-chunk hit the cache, nontemporal stores so that they do not push it out.
+// `senders` lists the ranks that send anything, so that the grid holds no idle sender planes.
+struct SenderList {
+  uint8_t p[MCR_MAX_RANKS];
+};
+
+__global__ void __launch_bounds__(kBlock)
+alltoallv_pairs_superchunk_kernel(PtrTab out, CPtrTab in, PairArg a, SenderList senders, unsigned bpc, unsigned P) {
+  const unsigned p = senders.p[blockIdx.y];
+  const unsigned per_sc = P * bpc;
+  const size_t sc = blockIdx.x / per_sc;
+  const unsigned rem = blockIdx.x - static_cast<unsigned>(sc * per_sc);
+  const unsigned r = rem / bpc, j = rem - r * bpc;
+  const unsigned i = p * P + r;
+  const size_t idx = (sc * bpc + j) * static_cast<size_t>(kBlock) + threadIdx.x;
+  if (idx >= a.cnt[i]) return;
+  const u32x4 v = load16<false>(static_cast<const u32x4*>(in.p[p]) + a.sd[i], idx);
+  store16<true>(static_cast<u32x4*>(out.p[r]) + a.rd[i], idx, v);
+}
+
 inline unsigned capped_blocks(size_t units, size_t per_block, size_t cap) {
   size_t blocks = (units + per_block - 1) / per_block;
   if (blocks == 0) blocks = 1;
@@ -381,6 +405,38 @@ int launch_alltoallv_pairs(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const
     if (a.cnt[i] > longest) longest = a.cnt[i];
   }
   if (longest == 0) return MCR_OK;
+  // One segment per sender, sent to two receivers or more, too long to stay cached between two
+  // receivers' copies: super-chunk order (the variant's hints and unroll do not apply to it).
+  constexpr uint32_t kSuperChunkVecs = (16u << 20) / 16;
+  if (variant != SV_SCALAR && longest > kSuperChunkVecs) {
+    SenderList senders;
+    unsigned n_senders = 0;
+    bool shared = true, fanout = false;
+    for (int p = 0; p < P && shared; ++p) {
+      int first = -1, live = 0;
+      for (int r = 0; r < P; ++r) {
+        const int i = p * P + r;
+        if (a.cnt[i] == 0) continue;
+        if (first < 0) first = i;
+        else if (a.cnt[i] != a.cnt[first] || a.sd[i] != a.sd[first]) shared = false;
+        ++live;
+      }
+      if (live > 0) senders.p[n_senders++] = static_cast<uint8_t>(p);
+      if (live > 1) fanout = true;
+    }
+    for (unsigned q = n_senders; q < MCR_MAX_RANKS; ++q) senders.p[q] = 0;
+    if (shared && fanout) {
+      const size_t nblk = (static_cast<size_t>(longest) + kBlock - 1) / kBlock;
+      const size_t bpc = kSuperChunkVecs / kBlock;                      // < nblk here, a multiple of the 8 XCDs
+      const size_t nsc = (nblk + bpc - 1) / bpc;
+      const size_t gx = nsc * bpc * static_cast<size_t>(P);
+      if (gx <= 0x7fffffffull) {
+        hipLaunchKernelGGL(alltoallv_pairs_superchunk_kernel, dim3(static_cast<unsigned>(gx), n_senders), dim3(kBlock), 0,
+                           stream, out, in, a, senders, static_cast<unsigned>(bpc), static_cast<unsigned>(P));
+        return launch_status();
+      }
+    }
+  }
   auto go = [&](auto ub, auto uu, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     constexpr int U = decltype(uu)::value;

@@ -50,6 +50,44 @@ def test_bcast(dtype, P):
                     gu.assert_bits_equal(gu.to_host(dev[r], gu.NPDT[dtype]), exp[r], f"bcast P={P} n={count} root={root} v={variant}")
 
 
+def test_long_shared_segments_take_the_super_chunk_order():
+    """A segment that one sender hands to several receivers and that is longer than 16 MiB is copied
+    super-chunk by super-chunk: bcast and all_gatherv (packed and with displacements), with a ragged
+    last tile, a short sender beside the long ones and an empty one."""
+    P, dtype, W = 4, mcr.F32, 4
+    n = (40 << 20) // 4 + 4 * 77                           # 40 MiB + a ragged tail: three super-chunks
+    host = _bufs(P, n, dtype, 1550)
+    for root in (0, 2):
+        exp = [h.copy() for h in host]
+        oracle.bcast(exp, dtype, root)
+        dev = [gu.to_dev(h) for h in host]
+        mcr.mcr_bcast(gu.ctx(), dev, n, dtype, root, P)
+        gu.sync()
+        for r in range(P):
+            gu.assert_bits_equal(gu.to_host(dev[r], np.float32), exp[r], f"long bcast root={root} r={r}")
+    counts = [(18 << 20) // 4 + W * 3, 0, W * 1001, (33 << 20) // 4 + W * 250]
+    total = sum(counts)
+    ins = [inputs.uniform_pm1(c, 1551, p) for p, c in enumerate(counts)]
+    d_ins = [gu.to_dev(x) if x.size else gu.dev_empty(8, dtype, 0) for x in ins]
+    ag_exp = oracle.allgatherv(ins, counts, dtype)
+    d_ag = [gu.dev_empty(total + 8, dtype, 0) for _ in range(P)]
+    mcr.mcr_allgatherv(gu.ctx(), d_ag, d_ins, counts, dtype, P)
+    gu.sync()
+    for r in range(P):
+        a = gu.to_host(d_ag[r], np.float32)
+        gu.assert_bits_equal(a[:total], ag_exp[r], f"long allgatherv r={r}")
+        assert (a[total:] == 0).all()
+    displs = [W * 5, 0, counts[0] + W * 9, counts[0] + counts[2] + W * 40]
+    extent = displs[3] + counts[3] + W * 2
+    agd_exp = [np.zeros(extent, dtype=np.float32) for _ in range(P)]
+    oracle.allgatherv_displs(agd_exp, ins, counts, displs, dtype)
+    d_agd = [gu.dev_empty(extent, dtype, 0) for _ in range(P)]
+    mcr.mcr_allgatherv_displs(gu.ctx(), d_agd, extent, d_ins, counts, displs, dtype, P)
+    gu.sync()
+    for r in range(P):
+        gu.assert_bits_equal(gu.to_host(d_agd[r], np.float32), agd_exp[r], f"long allgatherv_displs r={r}")
+
+
 def _count_sets(P, W, rng):
     yield [W * int(c) for c in rng.integers(0, 600, size=P)]               # 128-bit friendly, some may be 0
     yield [int(c) for c in rng.integers(0, 50, size=P)]                    # arbitrary: element path
