@@ -186,7 +186,11 @@ int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const i
 int mcr_reduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, mcr_redop op,
                int root, int P, int variant, void* stream);
 
-/* bcast: bufs[r][i] = bufs[root][i] for every r != root.  Bit copy. */
+/* bcast: bufs[r][i] = bufs[root][i] for every r != root.  Bit copy.
+ * In bcast and the all_gatherv calls a message longer than 16 MiB that goes to two receivers or
+ * more is copied 16 MiB at a time to each receiver in turn, so that it is fetched from memory
+ * once; a vector variant then selects the 128-bit path only (its cache hints and unroll apply to
+ * shorter messages). */
 int mcr_bcast(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, int root, int P,
               int variant, void* stream);
 
