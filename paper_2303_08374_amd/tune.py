@@ -25,6 +25,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 DEFAULT_TABLE = os.path.join(HERE, "tuning", "mi355x.tbl")
 
 
+def tie_window(ms: float) -> float:
+    """Times within this factor of the least one count as a tie (the lowest variant id then wins):
+    2 % while a launch is short enough for its time to be mostly launch and ramp-up noise, 0.5 %
+    from 100 us on, where a batch mean repeats to a few tenths of a percent."""
+    return 1.02 if ms < 0.1 else 1.005
+
+
 def reps_for(alg_bytes: int) -> int:
     # about 160 GiB of traffic per batch (tens of milliseconds), between 5 and 50 launches
     return int(max(5, min(50, (160 << 30) // max(alg_bytes, 1))))
@@ -76,7 +83,7 @@ def tune_workload_ops(ctx, verbose: bool = True):
             torch.cuda.empty_cache()
         for op in ops:
             floor = min(times[op].values())
-            best = min(v for v in variants if times[op][v] <= floor * 1.02)
+            best = min(v for v in variants if times[op][v] <= floor * tie_window(floor * 1e-3))
             mcr.mcr_tune_set(ctx, op, dtype, P, nbytes, best)
             report[f"{label}/{mcr.OP_NAMES[op]}"] = {"best": names[best], "us": {names[v]: round(t, 1) for v, t in times[op].items()}}
             if verbose:
@@ -121,10 +128,10 @@ def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbos
             cell.launch(ctx, arena.take(cell.footprint), v)              # first-launch effects out of the way
             ms = sweep.time_launches(lambda: cell.launch(ctx, arena.take(cell.footprint), v), reps)
             times[v] = ms
-        # least time wins; anything within 2 % of it counts as a tie and the lowest id is taken,
-        # so that launch-bound sizes do not pick a variant by noise
+        # least time wins; anything within the tie window of it counts as a tie and the lowest id
+        # is taken, so that launch-bound sizes do not pick a variant by noise
         floor = min(times.values())
-        best = min(v for v in variants if times[v] <= floor * 1.02)
+        best = min(v for v in variants if times[v] <= floor * tie_window(floor))
         mcr.mcr_tune_set(ctx, sweep.OPS[cell.op], sweep.DTYPES[cell.dtype], P, cell.M, best)
         report["cells"][cell.key] = {
             "alg_bytes": cell.alg_bytes, "best": names[best],
