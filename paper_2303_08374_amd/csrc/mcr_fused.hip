@@ -619,24 +619,43 @@ __device__ __forceinline__ RowLookup lookup_row(const int64_t* table_p, int32_t 
   return out;
 }
 
-// blockIdx.x = assignment a (choice a / T of token a mod T), blockIdx.y = sender.
-template <int UB, bool NTL, bool NTS>
+// blockIdx.x = token t, blockIdx.y = sender.  K choices (KU >= K at compile time): the token's row
+// is read once and stored to the place of every kept choice.
+template <int UB, int KU, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 moe_dispatch_row_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab slot_tab, const int64_t* row_table, int E,
-                        uint64_t rank_magic, size_t T, uint64_t recv_rows, uint32_t upr) {
+                        uint64_t rank_magic, size_t T, int K, uint64_t recv_rows, uint32_t upr) {
   typedef typename RowUnit<UB>::type U;
   const int p = blockIdx.y;
-  const size_t a = blockIdx.x;
-  const int32_t sl = static_cast<const int32_t*>(slot_tab.p[p])[a];
-  const int32_t e = static_cast<const int32_t*>(ids_tab.p[p])[a];
-  const U* src = static_cast<const U*>(tok.p[p]);
-  const RowLookup d = lookup_row(row_table + static_cast<size_t>(p) * E, sl, e, E, rank_magic, recv_rows);
-  U* dbase = static_cast<U*>(recv.p[d.r]);                       // d.r < P whatever the id was
-  if (!d.ok) return;
-  const size_t t = a < T ? a : a % T;
-  const U* srow = src + t * upr;
-  U* drow = dbase + static_cast<uint64_t>(d.row) * upr;
-  for (uint32_t c = threadIdx.x; c < upr; c += kBlock) stu<NTS, U>(drow + c, ldu<NTL, U>(srow + c));
+  const size_t t = blockIdx.x;
+  const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
+  const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
+  const int64_t* table = row_table + static_cast<size_t>(p) * E;
+  int32_t sl[KU], e[KU];
+#pragma unroll
+  for (int k = 0; k < KU; ++k) {
+    const size_t a = (k < K) ? static_cast<size_t>(k) * T + t : t;          // always a valid index
+    sl[k] = slot[a];
+    e[k] = ids[a];
+  }
+  U* drow[KU];
+  bool kept[KU];
+  bool any = false;
+#pragma unroll
+  for (int k = 0; k < KU; ++k) {
+    const RowLookup d = lookup_row(table, sl[k], e[k], E, rank_magic, recv_rows);
+    kept[k] = d.ok && k < K;
+    drow[k] = static_cast<U*>(recv.p[d.r]) + static_cast<uint64_t>(kept[k] ? d.row : 0) * upr;   // d.r < P whatever the id was
+    any = any || kept[k];
+  }
+  if (!any) return;
+  const U* srow = static_cast<const U*>(tok.p[p]) + t * upr;
+  for (uint32_t c = threadIdx.x; c < upr; c += kBlock) {
+    const U v = ldu<NTL, U>(srow + c);
+#pragma unroll
+    for (int k = 0; k < KU; ++k)
+      if (kept[k]) stu<NTS, U>(drow[k] + c, v);
+  }
 }
 
 // blockIdx.x = token t.  K choices (KU >= K at compile time).  A gather with a chain of lookups in
@@ -850,13 +869,17 @@ int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& t
   auto go = [&](auto ub, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     const RowShape s = row_shape(row_bytes / UB);
-    // one row per workgroup for single-choice dispatch (193 against 212 us on the MoE workload); with
-    // several choices per token the many-rows-per-workgroup kernel below is the faster one (363
-    // against 398 us for top-2)
-    if (UB == 16 && s.tpr == kBlock && K == 1) {
-      hipLaunchKernelGGL((moe_dispatch_row_kernel<UB, decltype(ntl)::value, decltype(nts)::value>),
-                         dim3(static_cast<unsigned>(A), P), dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E,
-                         rank_magic(E, P), T, static_cast<uint64_t>(recv_rows), s.upr);
+    // one row per workgroup (193 against 212 us on the MoE workload); with several choices per
+    // token the workgroup reads the token's row once and stores it to every kept choice's place
+    if (UB == 16 && s.tpr == kBlock) {
+      auto launch = [&](auto ku) {
+        hipLaunchKernelGGL((moe_dispatch_row_kernel<16, decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value>),
+                           dim3(static_cast<unsigned>(T), P), dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E,
+                           rank_magic(E, P), T, K, static_cast<uint64_t>(recv_rows), s.upr);
+      };
+      if (K == 1) launch(Int<1>{});
+      else if (K == 2) launch(Int<2>{});
+      else launch(Int<MCR_MAX_TOPK>{});
       return launch_status();
     }
     const unsigned gx = blocks_for(A, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
@@ -872,9 +895,9 @@ int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& t
   };
   if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
   return dispatch_hint(variant, [&](auto ntl, auto nts) {
-    // with several choices per token every token row is read several times: the nontemporal load
-    // hint is dropped (395 -> 363 us for top-2 on the MoE workload)
-    if (K > 1) return go(Int<16>{}, Bool<false>{}, nts);
+    // rows narrower than a workgroup with several choices per token: every token row is read once
+    // per choice, so the nontemporal load hint is dropped
+    if (K > 1 && row_shape(row_bytes / 16).tpr != kBlock) return go(Int<16>{}, Bool<false>{}, nts);
     return go(Int<16>{}, ntl, nts);
   });
 }

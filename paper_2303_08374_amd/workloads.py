@@ -202,9 +202,12 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
             rows.append(e)
     torch.cuda.synchronize()
     kept2 = int(d_S.sum().item())
-    talg = [0, 0, 2 * kept2 * row + P * A * 8, kept2 * row + P * T * row + P * A * 12]
+    # dispatch reads a token row once if any of its choices is kept and writes it once per kept choice
+    tokens_sent = sum(int((s.view(K, T) >= 0).any(dim=0).sum().item()) for s in d_slot2)
+    talg = [0, 0, (tokens_sent + kept2) * row + P * A * 8, kept2 * row + P * T * row + P * A * 12]
     rep["top2"] = _stage_report(["route", "expert_layout", "moe_dispatch_by_expert", "moe_combine_by_expert"], talg, rows)
     rep["top2"]["kept_assignments"] = kept2
+    rep["top2"]["tokens_with_a_kept_choice"] = tokens_sent
     rep["top2"]["kept_fraction"] = round(kept2 / (P * A), 4)
     return rep
 
