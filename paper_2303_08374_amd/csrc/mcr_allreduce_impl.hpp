@@ -7,6 +7,10 @@
 // reads an index is the only one that writes it, so in place has no race.
 // reduce (rooted) is the same kernel with the stores to all but the root's
 // buffer switched off (root >= 0).
+// Buffers that are not 16-byte aligned but all misaligned by the same amount (the same view of
+// a tensor on every rank) still take the 128-bit path: the pointers handed to the kernel are
+// advanced to the next 16-byte boundary and the `head` elements in front of them are reduced
+// one by one, like the elements past the last whole vector.
 // Bound by HBM bandwidth: (P-1) adds per 2*P*s bytes.
 #pragma once
 #include "mcr_reduce_tile.hpp"
@@ -16,7 +20,7 @@ namespace {
 
 template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
 __global__ void __launch_bounds__(kBlock)
-allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root) {
+allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root, unsigned head) {
   using E = Elem<DT>;
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
   CPtrTab in;
@@ -46,19 +50,49 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int r
     for (int p = 0; p < P; ++p)
       if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
   }
+  // elements in front of the first whole vector (head < elements per vector)
+  if (blockIdx.x == 0 && threadIdx.x < head) {
+    CPtrTab front;
+#pragma unroll
+    for (int p = 0; p < P; ++p) front.p[p] = static_cast<const char*>(in.p[p]) - static_cast<size_t>(head) * E::kBytes;
+    const typename E::acc_t y = reduce_scalar<DT>(front, threadIdx.x, P, scale, op);
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(const_cast<void*>(front.p[p]), threadIdx.x, y);
+  }
 }
 
-template <int DT>
+// Element path (buffers with different alignments): kScalarUnroll elements per thread, the loads
+// of all P ranks of all of them issued before the first is used.
+
+template <int DT, int P>
 __global__ void __launch_bounds__(kBlock)
-allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int op, int root) {
+allreduce_scalar(PtrTab bufs, size_t count, float scale, int op, int root) {
   using E = Elem<DT>;
-  CPtrTab in;
-  for (int p = 0; p < MCR_MAX_RANKS; ++p) in.p[p] = bufs.p[p];
-  const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < count; i += step) {
-    const typename E::acc_t y = reduce_scalar<DT>(in, i, P, scale, op);
-    for (int p = 0; p < P; ++p)
-      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
+  constexpr int U = kScalarUnroll;
+  const size_t step = static_cast<size_t>(gridDim.x) * kBlock * U;
+  for (size_t i0 = static_cast<size_t>(blockIdx.x) * kBlock * U + threadIdx.x; i0 < count; i0 += step) {
+    typename E::acc_t x[U][P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t i = i0 + static_cast<size_t>(u) * kBlock;
+        if (i < count) x[u][p] = E::load1(bufs.p[p], i);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = i0 + static_cast<size_t>(u) * kBlock;
+      if (i >= count) continue;
+      typename E::acc_t acc = x[u][0];
+#pragma unroll
+      for (int p = 1; p < P; ++p) acc = combine(acc, x[u][p], op);
+      if (op == MCR_AVG) acc = avg_step(acc, scale);
+#pragma unroll
+      for (int p = 0; p < P; ++p)
+        if (root < 0 || root == p) E::store1(bufs.p[p], i, acc);
+    }
   }
 }
 
@@ -68,13 +102,18 @@ allreduce_scalar(PtrTab bufs, size_t count, int P, float scale, int op, int root
 // own, which keeps the compile time of the reductions (16 rank counts x launch shapes) spread
 // over the build's workers.
 template <int DT>
-int launch_allreduce_dt(const PtrTab& bufs, size_t count, int op, int P, int root, int variant, hipStream_t stream) {
+int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op, int P, int root, int variant,
+                        hipStream_t stream) {
   const float scale = 1.0f / static_cast<float>(P);
   if (variant == SV_SCALAR) {
-    hipLaunchKernelGGL((allreduce_scalar<DT>), dim3(scalar_grid(count)), dim3(kBlock), 0, stream, bufs, count, P, scale, op,
-                       root);
-    return launch_status();
+    return dispatch_ranks(P, [&](auto pp) {
+      hipLaunchKernelGGL((allreduce_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(count, kScalarUnroll)), dim3(kBlock), 0,
+                         stream, bufs, count, scale, op, root);
+      return launch_status();
+    });
   }
+  // bufs point at the first whole vector: `head` elements lie in front of it, count - head from it on
+  count -= head;
   const size_t nvec = count / Elem<DT>::kPerVec;
   const unsigned gx = grid_x(nvec, variant);
   return dispatch_ranks(P, [&](auto pp) {
@@ -82,7 +121,7 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, int op, int P, int roo
     if (op > MCR_AVG || !all_shapes(DT)) {
       return dispatch_unroll(variant, [&](auto uu) {
         hipLaunchKernelGGL((allreduce_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx), dim3(kBlock), 0,
-                           stream, bufs, nvec, count, scale, op, root);
+                           stream, bufs, nvec, count, scale, op, root, head);
         return launch_status();
       });
     }
@@ -90,7 +129,7 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, int op, int P, int roo
       return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
         constexpr int U = decltype(uu)::value;
         hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
-                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root);
+                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root, head);
         return launch_status();
       });
     } else {

@@ -215,6 +215,39 @@ int pair_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool all1
                                 static_cast<hipStream_t>(stream));
 }
 
+// Buffers that all miss 16-byte alignment by the same amount (the same view of a tensor on every
+// rank): the number of elements in front of the next 16-byte boundary, and the table advanced to
+// that boundary.  0 and an untouched table when the buffers are aligned, differ from each other,
+// or the message ends before the boundary.
+unsigned peel_common_head(PtrTab& tab, int P, int dtype, size_t count) {
+  const uintptr_t miss = reinterpret_cast<uintptr_t>(tab.p[0]) & 15u;
+  if (miss == 0) return 0;
+  for (int p = 1; p < P; ++p)
+    if ((reinterpret_cast<uintptr_t>(tab.p[p]) & 15u) != miss) return 0;
+  const size_t skip = 16 - miss;                               // a whole number of elements: every pointer is element-aligned
+  const size_t head = skip / elem_bytes(dtype);
+  if (head > count) return 0;
+  for (int p = 0; p < P; ++p) tab.p[p] = static_cast<char*>(tab.p[p]) + skip;
+  return static_cast<unsigned>(head);
+}
+
+// all_reduce and reduce: variant and head for the buffers in `tab` (advanced past the head when
+// the 128-bit path is taken on misaligned buffers).
+int plan_allreduce(mcr_ctx* ctx, PtrTab& tab, bool all16, size_t count, mcr_dtype dtype, int P, int variant, int* v,
+                   unsigned* head) {
+  *head = 0;
+  PtrTab advanced = tab;
+  unsigned h = 0;
+  if (!all16 && count > 0) h = peel_common_head(advanced, P, dtype, count);
+  const int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16 || h > 0, variant, v);
+  if (rc != MCR_OK) return rc;
+  if (*v != SV_SCALAR && h > 0) {
+    tab = advanced;
+    *head = h;
+  }
+  return MCR_OK;
+}
+
 }  // namespace
 }  // namespace mcr
 
@@ -289,11 +322,12 @@ int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype
   bool all16 = true;
   if (!fill_tab(tab, bufs, P, dtype, count > 0, &all16)) return MCR_EINVAL;
   int v;
-  int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
+  unsigned head;
+  int rc = plan_allreduce(ctx, tab, all16, count, dtype, P, variant, &v, &head);
   if (rc != MCR_OK) return rc;
   DeviceScope on_device(ctx);
   if ((rc = on_device.status()) != MCR_OK) return rc;
-  return launch_allreduce(ctx, tab, count, dtype, op, P, -1, v, static_cast<hipStream_t>(stream));
+  return launch_allreduce(ctx, tab, count, head, dtype, op, P, -1, v, static_cast<hipStream_t>(stream));
 }
 
 int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count, mcr_dtype dtype,
@@ -401,11 +435,12 @@ int mcr_reduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, m
   bool all16 = true;
   if (!fill_tab(tab, bufs, P, dtype, count > 0, &all16)) return MCR_EINVAL;
   int v;
-  int rc = resolve_variant(ctx, MCR_OP_ALLREDUCE, dtype, P, count * elem_bytes(dtype), all16, variant, &v);
+  unsigned head;
+  int rc = plan_allreduce(ctx, tab, all16, count, dtype, P, variant, &v, &head);
   if (rc != MCR_OK) return rc;
   DeviceScope on_device(ctx);
   if ((rc = on_device.status()) != MCR_OK) return rc;
-  return launch_allreduce(ctx, tab, count, dtype, op, P, root, v, static_cast<hipStream_t>(stream));
+  return launch_allreduce(ctx, tab, count, head, dtype, op, P, root, v, static_cast<hipStream_t>(stream));
 }
 
 int mcr_bcast(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype, int root, int P, int variant,

@@ -266,6 +266,7 @@ int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t coun
                      int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   if (variant == SV_SCALAR) {
+    // one element per thread: with P stores behind every load, more elements per thread are slower here
     const unsigned gx = capped_blocks(count, kBlock, 1u << 20);
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int kP = decltype(pp)::value;
@@ -306,11 +307,11 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
   if (count == 0) return MCR_OK;
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
-    const unsigned gx = capped_blocks(b, kBlock, 1u << 16);
+    const unsigned gx = capped_blocks(b, 4 * kBlock, 1u << 16);               // four elements per thread in flight
     if (elem_bytes(dtype) == 4)
-      hipLaunchKernelGGL((alltoall_kernel<4, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
+      hipLaunchKernelGGL((alltoall_kernel<4, 4, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     else
-      hipLaunchKernelGGL((alltoall_kernel<2, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
+      hipLaunchKernelGGL((alltoall_kernel<2, 4, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     return launch_status();
   }
   const size_t bvec = b / per_vec(dtype);

@@ -82,7 +82,8 @@ constexpr int kChunkVecs = 4;    // 2 measured slower for fuse and unfuse, no fa
 constexpr uint32_t kChunkBytes = 256 * kChunkVecs * 16;
 
 // Every launcher returns MCR_OK or MCR_EHIP and assumes validated arguments.
-int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, int dtype, int op, int P, int root, int variant, hipStream_t);
+int launch_allreduce(mcr_ctx*, const PtrTab& bufs, size_t count, unsigned head, int dtype, int op, int P, int root,
+                     int variant, hipStream_t);
 int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int op, int P, int variant, hipStream_t);
 int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
 int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);

@@ -30,16 +30,36 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   }
 }
 
-template <int DT>
+// Element path: kScalarUnroll elements per thread, all P x kScalarUnroll loads in flight together.
+template <int DT, int P>
 __global__ void __launch_bounds__(kBlock)
-reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, int P, float scale, int op) {
+reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, float scale, int op) {
   using E = Elem<DT>;
+  constexpr int U = kScalarUnroll;
   const unsigned r = blockIdx.y;
   void* dst = out.p[r];
-  const size_t step = static_cast<size_t>(gridDim.x) * kBlock;
-  for (size_t j = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; j < b; j += step) {
-    const typename E::acc_t y = reduce_scalar<DT>(in, static_cast<size_t>(r) * b + j, P, scale, op);
-    E::store1(dst, j, y);
+  const size_t off = static_cast<size_t>(r) * b;
+  const size_t step = static_cast<size_t>(gridDim.x) * kBlock * U;
+  for (size_t j0 = static_cast<size_t>(blockIdx.x) * kBlock * U + threadIdx.x; j0 < b; j0 += step) {
+    typename E::acc_t x[U][P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t j = j0 + static_cast<size_t>(u) * kBlock;
+        if (j < b) x[u][p] = E::load1(in.p[p], off + j);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t j = j0 + static_cast<size_t>(u) * kBlock;
+      if (j >= b) continue;
+      typename E::acc_t acc = x[u][0];
+#pragma unroll
+      for (int p = 1; p < P; ++p) acc = combine(acc, x[u][p], op);
+      if (op == MCR_AVG) acc = avg_step(acc, scale);
+      E::store1(dst, j, acc);
+    }
   }
 }
 
@@ -52,8 +72,11 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
   const float scale = 1.0f / static_cast<float>(P);
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
-    hipLaunchKernelGGL((reduce_scatter_scalar<DT>), dim3(scalar_grid(b), P), dim3(kBlock), 0, stream, out, in, b, P, scale, op);
-    return launch_status();
+    return dispatch_ranks(P, [&](auto pp) {
+      hipLaunchKernelGGL((reduce_scatter_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(b, kScalarUnroll), P), dim3(kBlock),
+                         0, stream, out, in, b, scale, op);
+      return launch_status();
+    });
   }
   const size_t bvec = b / Elem<DT>::kPerVec;
   const unsigned gx = grid_x(bvec, variant);

@@ -71,8 +71,12 @@ inline int dispatch_unroll(int variant, F&& f) {
   return f(Int<1>{});
 }
 
-inline unsigned scalar_grid(size_t n) {
-  size_t blocks = (n + kBlock - 1) / kBlock;
+// Elements each thread of an element-path reduction kernel works on at a time.
+constexpr int kScalarUnroll = 4;
+
+inline unsigned scalar_grid(size_t n, int per_thread = 1) {
+  const size_t per_block = static_cast<size_t>(kBlock) * per_thread;
+  size_t blocks = (n + per_block - 1) / per_block;
   if (blocks == 0) blocks = 1;
   if (blocks > (1u << 20)) blocks = 1u << 20;   // grid-stride beyond that
   return static_cast<unsigned>(blocks);

@@ -89,24 +89,67 @@ def test_allreduce_closed_form_any_association(dtype):
     assert np.array_equal(got, (36 * (i % mod)).astype(np.float32))
 
 
-def test_allreduce_misaligned_buffers():
-    """Buffers that are only element-aligned: AUTO must fall back to the scalar kernel, an
-    explicit 128-bit variant is refused."""
-    P, n = 4, 4097
-    host = _make(P, n + 1, mcr.F32, seed=7)
-    exp = [h[1:].copy() for h in host]
-    oracle.allreduce(exp, oracle.F32, oracle.SUM)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_allreduce_misaligned_buffers(dtype):
+    """Buffers that are only element-aligned.  Misaligned by the same amount on every rank (the same
+    view of a tensor): the 128-bit variants still apply, with the elements in front of the first
+    16-byte boundary and behind the last whole vector reduced one by one.  Misaligned by different
+    amounts: AUTO falls back to the element kernel and an explicit 128-bit variant is refused.
+    Nothing outside the views is written."""
+    P = 4
+    npdt = gu.NPDT[dtype]
+    W = 4 if dtype == mcr.F32 else 8
+    pad = 16
+    for skip in (1, 3, W - 1):
+        for n in (1, W - 2, 4097, 70001):
+            host = _make(P, pad + n + pad, dtype, seed=7 + skip)
+            for op in (mcr.SUM, mcr.AVG):
+                exp = [h[skip:skip + n].copy() for h in host]
+                oracle.allreduce(exp, dtype, op)
+                for variant in (mcr.AUTO, 0, 3, 5, 12):
+                    dev = [gu.to_dev(h) for h in host]
+                    views = [d[skip:skip + n] for d in dev]
+                    if variant > 0 and n < W - skip:           # the message ends before the first 16-byte boundary
+                        with pytest.raises(mcr.McrError) as e:
+                            mcr.mcr_allreduce(gu.ctx(), views, n, dtype, op, P, variant)
+                        assert e.value.status == mcr.EVARIANT
+                        continue
+                    mcr.mcr_allreduce(gu.ctx(), views, n, dtype, op, P, variant)
+                    gu.sync()
+                    for r in range(P):
+                        got = gu.to_host(dev[r], npdt)
+                        gu.assert_reduced_equal(got[skip:skip + n], exp[r], dtype, f"misaligned skip={skip} n={n} op={op} v={variant}")
+                        gu.assert_bits_equal(got[:skip], host[r][:skip], "in front of the view")
+                        gu.assert_bits_equal(got[skip + n:], host[r][skip + n:], "behind the view")
+            # rooted: only the root's view changes
+            exp = [h[skip:skip + n].copy() for h in host]
+            oracle.reduce(exp, dtype, mcr.SUM, 2)
+            dev = [gu.to_dev(h) for h in host]
+            mcr.mcr_reduce(gu.ctx(), [d[skip:skip + n] for d in dev], n, dtype, mcr.SUM, 2, P, 6 if n >= W - skip else mcr.AUTO)
+            gu.sync()
+            for r in range(P):
+                got = gu.to_host(dev[r], npdt)
+                gu.assert_reduced_equal(got[skip:skip + n], exp[r], dtype, f"misaligned reduce skip={skip} n={n} r={r}")
+                gu.assert_bits_equal(got[:skip], host[r][:skip], "in front of the view")
+                gu.assert_bits_equal(got[skip + n:], host[r][skip + n:], "behind the view")
+    # different misalignments
+    n = 4097
+    host = _make(P, pad + n + pad, dtype, seed=11)
+    skips = [1, 2, 1, 0]
+    exp = [h[k:k + n].copy() for h, k in zip(host, skips)]
+    oracle.allreduce(exp, dtype, mcr.SUM)
     dev = [gu.to_dev(h) for h in host]
-    views = [d[1:] for d in dev]
+    views = [d[k:k + n] for d, k in zip(dev, skips)]
     with pytest.raises(mcr.McrError) as e:
-        mcr.mcr_allreduce(gu.ctx(), views, n, mcr.F32, mcr.SUM, P, 3)
+        mcr.mcr_allreduce(gu.ctx(), views, n, dtype, mcr.SUM, P, 3)
     assert e.value.status == mcr.EVARIANT
-    mcr.mcr_allreduce(gu.ctx(), views, n, mcr.F32, mcr.SUM, P, mcr.AUTO)
+    mcr.mcr_allreduce(gu.ctx(), views, n, dtype, mcr.SUM, P, mcr.AUTO)
     gu.sync()
-    for r in range(P):
-        got = gu.to_host(dev[r], np.float32)
-        gu.assert_bits_equal(got[1:], exp[r], "misaligned")
-        assert got[0] == host[r][0]          # the element before the view is untouched
+    for r, k in enumerate(skips):
+        got = gu.to_host(dev[r], npdt)
+        gu.assert_reduced_equal(got[k:k + n], exp[r], dtype, "different misalignments")
+        gu.assert_bits_equal(got[:k], host[r][:k], "in front of the view")
+        gu.assert_bits_equal(got[k + n:], host[r][k + n:], "behind the view")
 
 
 def test_allreduce_empty_is_a_no_op():
