@@ -134,7 +134,12 @@ const char* mcr_strerror(int status);
  * place: every bufs[r][i] becomes x_0[i] (+) x_1[i] (+) ... (+) x_{P-1}[i], taken left
  * to right in rank order in binary32 (bf16 widened first, rounded once to
  * nearest-even at the end).  Every element index is read (all P) and then
- * written (all P) by one thread, so in-place is race free. */
+ * written (all P) by one thread, so in-place is race free.
+ * Alignment: buffers need only be aligned to the element.  The 128-bit variants apply when all
+ * P buffers are 16-byte aligned, and also when all of them miss that alignment by the same
+ * number of bytes (the same view of a tensor on every rank) and the message reaches the next
+ * 16-byte boundary; otherwise only the element path ("scalar") applies.  `count` may be any
+ * number. */
 int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype,
                   mcr_redop op, int P, int variant, void* stream);
 
