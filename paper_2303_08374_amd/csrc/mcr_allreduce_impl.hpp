@@ -62,37 +62,60 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int r
   }
 }
 
-// Element path (buffers with different alignments): kScalarUnroll elements per thread, the loads
-// of all P ranks of all of them issued before the first is used.
-
+// Element path (buffers with different alignments, any count).  Still 16 bytes per access, at
+// whatever address the elements fall on; kScalarUnroll vectors per thread, the loads of all P
+// ranks of all of them issued before the first is used; the count mod (elements per vector)
+// elements behind the last whole vector are reduced one by one by workgroup 0.
 template <int DT, int P>
 __global__ void __launch_bounds__(kBlock)
 allreduce_scalar(PtrTab bufs, size_t count, float scale, int op, int root) {
   using E = Elem<DT>;
   constexpr int U = kScalarUnroll;
+  constexpr int W = E::kPerVec;
+  const size_t nvec = count / W;
   const size_t step = static_cast<size_t>(gridDim.x) * kBlock * U;
-  for (size_t i0 = static_cast<size_t>(blockIdx.x) * kBlock * U + threadIdx.x; i0 < count; i0 += step) {
-    typename E::acc_t x[U][P];
+  for (size_t i0 = static_cast<size_t>(blockIdx.x) * kBlock * U + threadIdx.x; i0 < nvec; i0 += step) {
+    u32x4 v[U][P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const size_t i = i0 + static_cast<size_t>(u) * kBlock;
-        if (i < count) x[u][p] = E::load1(bufs.p[p], i);
+        if (i < nvec) v[u][p] = load16_unaligned(bufs.p[p], i * 16);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t i = i0 + static_cast<size_t>(u) * kBlock;
-      if (i >= count) continue;
-      typename E::acc_t acc = x[u][0];
+      if (i >= nvec) continue;
+      typename E::acc_t acc[W];
+      E::widen(v[u][0], acc);
 #pragma unroll
-      for (int p = 1; p < P; ++p) acc = combine(acc, x[u][p], op);
-      if (op == MCR_AVG) acc = avg_step(acc, scale);
+      for (int p = 1; p < P; ++p) {
+        typename E::acc_t x[W];
+        E::widen(v[u][p], x);
+#pragma unroll
+        for (int k = 0; k < W; ++k) acc[k] = combine(acc[k], x[k], op);
+      }
+      if (op == MCR_AVG) {
+#pragma unroll
+        for (int k = 0; k < W; ++k) acc[k] = avg_step(acc[k], scale);
+      }
+      const u32x4 y = E::narrow(acc);
 #pragma unroll
       for (int p = 0; p < P; ++p)
-        if (root < 0 || root == p) E::store1(bufs.p[p], i, acc);
+        if (root < 0 || root == p) store16_unaligned(bufs.p[p], i * 16, y);
     }
+  }
+  const size_t i = nvec * W + threadIdx.x;
+  if (blockIdx.x == 0 && i < count) {
+    typename E::acc_t acc = E::load1(bufs.p[0], i);
+#pragma unroll
+    for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(bufs.p[p], i), op);
+    if (op == MCR_AVG) acc = avg_step(acc, scale);
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(bufs.p[p], i, acc);
   }
 }
 
@@ -107,7 +130,7 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
   const float scale = 1.0f / static_cast<float>(P);
   if (variant == SV_SCALAR) {
     return dispatch_ranks(P, [&](auto pp) {
-      hipLaunchKernelGGL((allreduce_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(count, kScalarUnroll)), dim3(kBlock), 0,
+      hipLaunchKernelGGL((allreduce_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(count / Elem<DT>::kPerVec, kScalarUnroll)), dim3(kBlock), 0,
                          stream, bufs, count, scale, op, root);
       return launch_status();
     });

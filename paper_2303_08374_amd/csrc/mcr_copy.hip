@@ -25,6 +25,58 @@ __device__ __forceinline__ void store_unit(void* base, size_t i, T v) {
   else *p = v;
 }
 
+// One linear copy of n units of UB bytes from src to dst, shared by the workgroups along x
+// (blockIdx.x strides over tiles).  UB = 16: aligned 128-bit accesses, U per thread in flight.
+// UB < 16 is the element path (addresses aligned to the element only, any length): still 16 bytes
+// per access, at whatever address the element falls on -- the hardware serves unaligned global
+// accesses, and 64 lanes x 2 bytes per instruction is what made this path 2-3 times slower than
+// the aligned one -- and the n mod (16 / UB) elements behind the last whole 16 bytes one by one.
+template <int UB, int U>
+__device__ constexpr uint64_t run_tile_units() {
+  return static_cast<uint64_t>(U) * kBlock * (16 / UB);
+}
+template <int UB, int U, bool NTL, bool NTS>
+__device__ __forceinline__ void copy_run(const typename Unit<UB>::type* src, typename Unit<UB>::type* dst, uint64_t n) {
+  constexpr uint64_t kTile = static_cast<uint64_t>(U) * kBlock;          // 16-byte pieces per tile
+  if constexpr (UB == 16) {
+    const uint64_t step = static_cast<uint64_t>(gridDim.x) * kTile;
+    for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < n; tile += step) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+        if (idx < n) v[u] = load_unit<NTL, u32x4>(src, idx);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+        if (idx < n) store_unit<NTS, u32x4>(dst, idx, v[u]);
+      }
+    }
+  } else {
+    constexpr uint64_t kPer = 16 / UB;
+    const uint64_t nv = n / kPer;
+    const char* s = reinterpret_cast<const char*>(src);
+    char* d = reinterpret_cast<char*>(dst);
+    const uint64_t step = static_cast<uint64_t>(gridDim.x) * kTile;
+    for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < nv; tile += step) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+        if (idx < nv) __builtin_memcpy(&v[u], s + 16 * idx, 16);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
+        if (idx < nv) __builtin_memcpy(d + 16 * idx, &v[u], 16);
+      }
+    }
+    const uint64_t e = nv * kPer + threadIdx.x;
+    if (blockIdx.x == 0 && e < n) dst[e] = src[e];
+  }
+}
+
 // ---- all_gather -----------------------------------------------------------------
 // Classic form.  blockIdx.y = source rank p; its m units land at offset p*m of every
 // output: one load, P stores per thread.
@@ -37,6 +89,36 @@ allgather_kernel(PtrTab out, CPtrTab in, size_t m) {
   const void* src = in.p[p];
   const size_t off = static_cast<size_t>(p) * m;
   const size_t step = static_cast<size_t>(gridDim.x) * kTile;
+  if constexpr (UB == 2) {
+    // element path on 2-byte elements: 16 bytes per access at element-aligned addresses (see
+    // copy_run), then the m mod 8 elements behind the last whole 16 bytes.  (4-byte elements are
+    // faster one element per lane here: 805 against 899 us for 64 MiB per rank.)
+    constexpr size_t kPer = 16 / UB;
+    const size_t nv = m / kPer;
+    for (size_t tile = static_cast<size_t>(blockIdx.x) * kTile; tile < nv; tile += step) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+        if (idx < nv) v[u] = load16_unaligned(src, idx * 16);
+      }
+#pragma unroll
+      for (int r = 0; r < P; ++r) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+          if (idx < nv) store16_unaligned(out.p[r], off * UB + idx * 16, v[u]);
+        }
+      }
+    }
+    const size_t e = nv * kPer + threadIdx.x;
+    if (blockIdx.x == 0 && e < m) {
+      const T x = static_cast<const T*>(src)[e];
+#pragma unroll
+      for (int r = 0; r < P; ++r) static_cast<T*>(out.p[r])[off + e] = x;
+    }
+    return;
+  }
   for (size_t tile = static_cast<size_t>(blockIdx.x) * kTile; tile < m; tile += step) {
     T v[U];
 #pragma unroll
@@ -84,25 +166,9 @@ template <int UB, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 alltoall_kernel(PtrTab out, CPtrTab in, size_t b) {
   typedef typename Unit<UB>::type T;
-  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
   const unsigned p = blockIdx.y, r = blockIdx.z;
-  const void* src = in.p[p];
-  void* dst = out.p[r];
-  const size_t soff = static_cast<size_t>(r) * b, doff = static_cast<size_t>(p) * b;
-  const size_t step = static_cast<size_t>(gridDim.x) * kTile;
-  for (size_t tile = static_cast<size_t>(blockIdx.x) * kTile; tile < b; tile += step) {
-    T v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-      if (idx < b) v[u] = load_unit<NTL, T>(src, soff + idx);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
-      if (idx < b) store_unit<NTS, T>(dst, doff + idx, v[u]);
-    }
-  }
+  copy_run<UB, U, NTL, NTS>(static_cast<const T*>(in.p[p]) + static_cast<size_t>(r) * b,
+                            static_cast<T*>(out.p[r]) + static_cast<size_t>(p) * b, b);
 }
 
 // ---- all_to_allv -----------------------------------------------------------------
@@ -136,7 +202,7 @@ __global__ void __launch_bounds__(kBlock)
 alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, uint64_t upr,
                  uint64_t in_rows, uint64_t out_rows, int same_src) {
   typedef typename Unit<UB>::type T;
-  constexpr uint64_t kTile = static_cast<uint64_t>(U) * kBlock;
+  constexpr uint64_t kTile = run_tile_units<UB, U>();
   const int p = blockIdx.y, r = blockIdx.z;
   const int64_t* S = DEV ? ds : hs.s;
   uint64_t rows = clamp_split(S[p * P + r], in_rows);
@@ -174,23 +240,8 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
   if (sdispl >= in_rows || rdispl >= out_rows) return;
   if (rows > in_rows - sdispl) rows = in_rows - sdispl;
   if (rows > out_rows - rdispl) rows = out_rows - rdispl;
-  const uint64_t n = rows * upr;
-  const T* src = static_cast<const T*>(in.p[p]) + sdispl * upr;
-  T* dst = static_cast<T*>(out.p[r]) + rdispl * upr;
-  const uint64_t step = static_cast<uint64_t>(gridDim.x) * kTile;
-  for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < n; tile += step) {
-    T v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-      if (idx < n) v[u] = load_unit<NTL, T>(src, idx);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-      if (idx < n) store_unit<NTS, T>(dst, idx, v[u]);
-    }
-  }
+  copy_run<UB, U, NTL, NTS>(static_cast<const T*>(in.p[p]) + sdispl * upr, static_cast<T*>(out.p[r]) + rdispl * upr,
+                            rows * upr);
 }
 
 // all_to_allv with displacements chosen by the caller: the host has checked every pair against
@@ -206,27 +257,12 @@ template <int UB, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 alltoallv_pairs_kernel(PtrTab out, CPtrTab in, PairArg a, int P) {
   typedef typename Unit<UB>::type T;
-  constexpr uint64_t kTile = static_cast<uint64_t>(U) * kBlock;
+  constexpr uint64_t kTile = run_tile_units<UB, U>();
   const int p = blockIdx.y, r = blockIdx.z;
   const int i = p * P + r;
   const uint64_t n = a.cnt[i];
   if (static_cast<uint64_t>(blockIdx.x) * kTile >= n) return;
-  const T* src = static_cast<const T*>(in.p[p]) + a.sd[i];
-  T* dst = static_cast<T*>(out.p[r]) + a.rd[i];
-  const uint64_t step = static_cast<uint64_t>(gridDim.x) * kTile;
-  for (uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kTile; tile < n; tile += step) {
-    T v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-      if (idx < n) v[u] = load_unit<NTL, T>(src, idx);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-      if (idx < n) store_unit<NTS, T>(dst, idx, v[u]);
-    }
-  }
+  copy_run<UB, U, NTL, NTS>(static_cast<const T*>(in.p[p]) + a.sd[i], static_cast<T*>(out.p[r]) + a.rd[i], n);
 }
 
 // The same table when every sender hands the *same* segment to all of its receivers (bcast,
@@ -266,8 +302,9 @@ int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t coun
                      int variant, hipStream_t stream) {
   if (count == 0) return MCR_OK;
   if (variant == SV_SCALAR) {
-    // one element per thread: with P stores behind every load, more elements per thread are slower here
-    const unsigned gx = capped_blocks(count, kBlock, 1u << 20);
+    // one piece (a 4-byte element, or 16 bytes of 2-byte elements) per thread: with P stores behind
+    // every load, more per thread are slower here
+    const unsigned gx = capped_blocks(elem_bytes(dtype) == 4 ? count : count / 8, kBlock, 1u << 20);
     return dispatch_ranks(P, [&](auto pp) {
       constexpr int kP = decltype(pp)::value;
       if (elem_bytes(dtype) == 4)
@@ -307,7 +344,7 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
   if (count == 0) return MCR_OK;
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
-    const unsigned gx = capped_blocks(b, 4 * kBlock, 1u << 16);               // four elements per thread in flight
+    const unsigned gx = capped_blocks(b, 4 * kBlock * (16 / elem_bytes(dtype)), 1u << 16);   // tiles of 4 x 256 16-byte pieces
     if (elem_bytes(dtype) == 4)
       hipLaunchKernelGGL((alltoall_kernel<4, 4, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     else
@@ -376,7 +413,7 @@ int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64
     constexpr bool NTS = decltype(nts)::value;
     const uint64_t upr = row_bytes / UB;
     // a device matrix usually fills a fraction of the bound: cap the tiles per pair, longer pairs stride
-    const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock, dev ? 256 : 65535 * 16);
+    const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock * (16 / UB), dev ? 256 : 65535 * 16);
     if (dev)
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
                          hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src);
@@ -441,7 +478,7 @@ int launch_alltoallv_pairs(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const
   auto go = [&](auto ub, auto uu, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     constexpr int U = decltype(uu)::value;
-    const unsigned gx = capped_blocks(longest, static_cast<size_t>(U) * kBlock, 65535 * 16);
+    const unsigned gx = capped_blocks(longest, static_cast<size_t>(U) * kBlock * (16 / UB), 65535 * 16);
     hipLaunchKernelGGL((alltoallv_pairs_kernel<UB, U, decltype(ntl)::value, decltype(nts)::value>), dim3(gx, P, P),
                        dim3(kBlock), 0, stream, out, in, a, P);
     return launch_status();

@@ -39,6 +39,17 @@ __device__ __forceinline__ void store16(void* base, size_t vec_index, u32x4 v) {
   else *p = v;
 }
 
+// 128-bit global access at an address that is aligned to the element only (the element paths):
+// the hardware serves unaligned global accesses, so this is still one instruction.
+__device__ __forceinline__ u32x4 load16_unaligned(const void* base, size_t byte_offset) {
+  u32x4 v;
+  __builtin_memcpy(&v, static_cast<const char*>(base) + byte_offset, 16);
+  return v;
+}
+__device__ __forceinline__ void store16_unaligned(void* base, size_t byte_offset, u32x4 v) {
+  __builtin_memcpy(static_cast<char*>(base) + byte_offset, &v, 16);
+}
+
 // bf16 <-> binary32.  A bf16 is the upper half of a binary32 pattern.
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

@@ -30,36 +30,58 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   }
 }
 
-// Element path: kScalarUnroll elements per thread, all P x kScalarUnroll loads in flight together.
+// Element path (any alignment, any slice length): 16 bytes per access at element-aligned
+// addresses, kScalarUnroll vectors per thread with all P x kScalarUnroll loads in flight together;
+// the elements behind a slice's last whole vector one by one (see all_reduce's element path).
 template <int DT, int P>
 __global__ void __launch_bounds__(kBlock)
 reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, float scale, int op) {
   using E = Elem<DT>;
   constexpr int U = kScalarUnroll;
+  constexpr int W = E::kPerVec;
   const unsigned r = blockIdx.y;
   void* dst = out.p[r];
-  const size_t off = static_cast<size_t>(r) * b;
+  const size_t off_bytes = static_cast<size_t>(r) * b * E::kBytes;
+  const size_t nvec = b / W;
   const size_t step = static_cast<size_t>(gridDim.x) * kBlock * U;
-  for (size_t j0 = static_cast<size_t>(blockIdx.x) * kBlock * U + threadIdx.x; j0 < b; j0 += step) {
-    typename E::acc_t x[U][P];
+  for (size_t j0 = static_cast<size_t>(blockIdx.x) * kBlock * U + threadIdx.x; j0 < nvec; j0 += step) {
+    u32x4 v[U][P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const size_t j = j0 + static_cast<size_t>(u) * kBlock;
-        if (j < b) x[u][p] = E::load1(in.p[p], off + j);
+        if (j < nvec) v[u][p] = load16_unaligned(in.p[p], off_bytes + j * 16);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t j = j0 + static_cast<size_t>(u) * kBlock;
-      if (j >= b) continue;
-      typename E::acc_t acc = x[u][0];
+      if (j >= nvec) continue;
+      typename E::acc_t acc[W];
+      E::widen(v[u][0], acc);
 #pragma unroll
-      for (int p = 1; p < P; ++p) acc = combine(acc, x[u][p], op);
-      if (op == MCR_AVG) acc = avg_step(acc, scale);
-      E::store1(dst, j, acc);
+      for (int p = 1; p < P; ++p) {
+        typename E::acc_t x[W];
+        E::widen(v[u][p], x);
+#pragma unroll
+        for (int k = 0; k < W; ++k) acc[k] = combine(acc[k], x[k], op);
+      }
+      if (op == MCR_AVG) {
+#pragma unroll
+        for (int k = 0; k < W; ++k) acc[k] = avg_step(acc[k], scale);
+      }
+      store16_unaligned(dst, j * 16, E::narrow(acc));
     }
+  }
+  const size_t j = nvec * W + threadIdx.x;
+  if (blockIdx.x == 0 && j < b) {
+    const size_t i = static_cast<size_t>(r) * b + j;
+    typename E::acc_t acc = E::load1(in.p[0], i);
+#pragma unroll
+    for (int p = 1; p < P; ++p) acc = combine(acc, E::load1(in.p[p], i), op);
+    if (op == MCR_AVG) acc = avg_step(acc, scale);
+    E::store1(dst, j, acc);
   }
 }
 
@@ -73,7 +95,7 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
     return dispatch_ranks(P, [&](auto pp) {
-      hipLaunchKernelGGL((reduce_scatter_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(b, kScalarUnroll), P), dim3(kBlock),
+      hipLaunchKernelGGL((reduce_scatter_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(b / Elem<DT>::kPerVec, kScalarUnroll), P), dim3(kBlock),
                          0, stream, out, in, b, scale, op);
       return launch_status();
     });

@@ -71,8 +71,8 @@ inline int dispatch_unroll(int variant, F&& f) {
   return f(Int<1>{});
 }
 
-// Elements each thread of an element-path reduction kernel works on at a time.
-constexpr int kScalarUnroll = 4;
+// 16-byte pieces each thread of an element-path reduction kernel works on at a time.
+constexpr int kScalarUnroll = 2;
 
 inline unsigned scalar_grid(size_t n, int per_thread = 1) {
   const size_t per_block = static_cast<size_t>(kBlock) * per_thread;
