@@ -344,11 +344,11 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
   if (count == 0) return MCR_OK;
   const size_t b = count / static_cast<size_t>(P);
   if (variant == SV_SCALAR) {
-    const unsigned gx = capped_blocks(b, 4 * kBlock * (16 / elem_bytes(dtype)), 1u << 16);   // tiles of 4 x 256 16-byte pieces
+    const unsigned gx = capped_blocks(b, kBlock * (16 / elem_bytes(dtype)), 1u << 16);   // tiles of 256 16-byte pieces
     if (elem_bytes(dtype) == 4)
-      hipLaunchKernelGGL((alltoall_kernel<4, 4, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
+      hipLaunchKernelGGL((alltoall_kernel<4, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     else
-      hipLaunchKernelGGL((alltoall_kernel<2, 4, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
+      hipLaunchKernelGGL((alltoall_kernel<2, 1, false, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in, b);
     return launch_status();
   }
   const size_t bvec = b / per_vec(dtype);
