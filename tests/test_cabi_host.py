@@ -80,6 +80,13 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_allreduce, ctx, A16[:2], 8, S.F32, S.SUM, 2, 99, 0) == S.EVARIANT
     assert _status(S.mcr_allreduce, ctx, [A16[0], A16[1] + 4], 8, S.F32, S.SUM, 2, 3, 0) == S.EVARIANT    # vector variant, misaligned
     assert _status(S.mcr_allreduce, ctx, [A16[0], A16[1] + 4], 8, S.F32, S.SUM, 2, S.AUTO, 0) == S.ESTATE  # AUTO falls back
+    # misaligned by the same amount on every rank: the 128-bit variants apply once the message reaches the boundary
+    assert _status(S.mcr_allreduce, ctx, [A16[0] + 4, A16[1] + 4], 8, S.F32, S.SUM, 2, 3, 0) == S.ESTATE
+    assert _status(S.mcr_allreduce, ctx, [A16[0] + 4, A16[1] + 4], 3, S.F32, S.SUM, 2, 3, 0) == S.ESTATE   # 3 elements reach it
+    assert _status(S.mcr_allreduce, ctx, [A16[0] + 4, A16[1] + 4], 2, S.F32, S.SUM, 2, 3, 0) == S.EVARIANT  # 2 do not
+    assert _status(S.mcr_allreduce, ctx, [A16[0] + 4, A16[1] + 8], 8, S.F32, S.SUM, 2, 3, 0) == S.EVARIANT  # different amounts
+    assert _status(S.mcr_allreduce, ctx, [A16[0] + 2, A16[1] + 2], 64, S.BF16, S.AVG, 2, 6, 0) == S.ESTATE
+    assert _status(S.mcr_reduce, ctx, [A16[0] + 12, A16[1] + 12], 64, S.F32, S.MAX, 1, 2, 9, 0) == S.ESTATE
     # count must divide by P
     assert _status(S.mcr_reduce_scatter, ctx, A16[:3], A16[3:6], 10, S.F32, S.SUM, 3, S.AUTO, 0) == S.EINVAL
     assert _status(S.mcr_alltoall, ctx, A16[:3], A16[3:6], 10, S.BF16, 3, S.AUTO, 0) == S.EINVAL
