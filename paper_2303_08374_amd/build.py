@@ -1,6 +1,6 @@
 """Builds libmcr.so (the C-ABI library) from csrc/ with hipcc for gfx950.
 
-    python -m paper_2303_08374_amd.build
+    python -m paper_2303_08374_amd.build [--changed]
 """
 from __future__ import annotations
 
@@ -42,13 +42,26 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 8) -> str:
+def _up_to_date(src: str) -> bool:
+    """The object is newer than the source, every header next to it and the public header."""
+    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+    if not os.path.exists(obj):
+        return False
+    deps = [os.path.join(CSRC, src), os.path.join(HERE, "..", "include", "mcr.h")]
+    deps += [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".hpp")]
+    return all(os.path.getmtime(d) < os.path.getmtime(obj) for d in deps)
+
+
+def build(jobs: int = 8, only_changed: bool = False) -> str:
+    """Compiles every source (only_changed: every source whose object is out of date) and links."""
     os.makedirs(OBJ_DIR, exist_ok=True)
+    todo = [s for s in SOURCES if not (only_changed and _up_to_date(s))]
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        objs = list(pool.map(_compile, SOURCES))
+        list(pool.map(_compile, todo))
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build(only_changed="--changed" in sys.argv[1:]))
