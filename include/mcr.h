@@ -93,7 +93,8 @@ typedef enum {
   MCR_EHIP = -6,     /* the HIP runtime reported an error (launch, copy, allocation) */
   MCR_ENOMEM = -7,   /* host allocation failed */
   MCR_EIO = -8,      /* tuning-table file could not be read / written / parsed */
-  MCR_ESTATE = -9    /* call order: plan not bound, wrong P for a bound plan, ... */
+  MCR_ESTATE = -9,   /* call order: plan not bound, wrong P for a bound plan, ... */
+  MCR_ELIMIT = -10   /* the problem needs more than a fixed-size static scratch array holds */
 } mcr_status;
 
 #define MCR_AUTO (-1)
@@ -278,6 +279,22 @@ size_t mcr_moe_route_workspace_bytes(int T, int E, int P);
 int mcr_moe_route_ws(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P,
                      int capacity, int32_t* const* slot, int32_t* const* counts, int64_t* splits,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* mcr_moe_route_static: for callers that cannot allocate device memory or own a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  The same
+ * results as mcr_moe_route_ws, bit for bit, by the same kernels; the chunk counters sit in a
+ * static device array of MCR_ROUTE_SCRATCH_BYTES that each GPU the library runs on holds until
+ * the process ends.  Neither this call nor anything it calls allocates or frees memory.
+ * A routing whose counters need more (mcr_moe_route_workspace_bytes(T, E, P) >
+ * MCR_ROUTE_SCRATCH_BYTES) gives MCR_ELIMIT and launches nothing; a T with fewer than two chunks
+ * runs mcr_moe_route's one-workgroup kernel, which uses no scratch.  All calls on one GPU share
+ * that GPU's array: two calls that may overlap in time there (different streams, or threads)
+ * race; calls on one stream are ordered and safe.  Nothing has to be cleared between calls: the
+ * first launch overwrites every counter the second one reads. */
+#define MCR_ROUTE_SCRATCH_BYTES (1u << 20)
+int mcr_moe_route_static(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P,
+                         int capacity, int32_t* const* slot, int32_t* const* counts,
+                         int64_t* splits, void* stream);
 
 /* mcr_pack, batched over P ranks: out[p] row slot[p][t] = in[p] row t for every t<T
  * with 0 <= slot[p][t] < out_rows; other rows of out[p] are left untouched. */

@@ -267,6 +267,7 @@ const char* mcr_strerror(int status) {
     case MCR_ENOMEM: return "out of host memory";
     case MCR_EIO: return "tuning table file error";
     case MCR_ESTATE: return "call not valid in this state";
+    case MCR_ELIMIT: return "problem exceeds the static scratch array";
   }
   return "unknown status";
 }
@@ -278,6 +279,13 @@ int mcr_init(mcr_ctx** out, int device) {
     if (hipGetDeviceCount(&count) != hipSuccess) return MCR_EHIP;
     if (device >= count) return MCR_EINVAL;
     if (hipSetDevice(device) != hipSuccess) return MCR_EHIP;
+  }
+  if (device != MCR_NO_DEVICE) {
+    // the static scratch array of mcr_moe_route_static: its address on this device, looked up
+    // here so that the entry point itself does nothing but launch
+    int32_t* unused = nullptr;
+    const int rc = route_scratch_address(device, &unused);
+    if (rc != MCR_OK) return rc;
   }
   mcr_ctx* ctx = new (std::nothrow) mcr_ctx;
   if (!ctx) return MCR_ENOMEM;
@@ -692,6 +700,27 @@ int mcr_moe_route_ws(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int 
   if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_moe_route_chunked(ctx, ti, T, E, P, capacity, ts, tc, splits, static_cast<int32_t*>(workspace),
                                   static_cast<hipStream_t>(stream));
+}
+
+int mcr_moe_route_static(mcr_ctx* ctx, const int32_t* const* expert_ids, int T, int E, int P, int capacity,
+                         int32_t* const* slot, int32_t* const* counts, int64_t* splits, void* stream) {
+  if (!ctx || !expert_ids || !slot || !counts || !splits || !valid_P(P)) return MCR_EINVAL;
+  if (T < 0 || E < 1 || E > MCR_MAX_EXPERTS || capacity < 0 || E % P != 0) return MCR_EINVAL;
+  if (reinterpret_cast<uintptr_t>(splits) & 7u) return MCR_EINVAL;
+  const size_t need = mcr_moe_route_workspace_bytes(T, E, P);
+  if (need > MCR_ROUTE_SCRATCH_BYTES) return MCR_ELIMIT;
+  if (need == 0) return mcr_moe_route(ctx, expert_ids, T, E, P, capacity, slot, counts, splits, stream);
+  CPtrTab ti;
+  PtrTab ts, tc;
+  if (!fill_tab(ti, expert_ids, P, MCR_F32, T > 0, nullptr) || !fill_tab(ts, slot, P, MCR_F32, T > 0, nullptr) ||
+      !fill_tab(tc, counts, P, MCR_F32, true, nullptr))
+    return MCR_EINVAL;
+  int rc;
+  DeviceScope on_device(ctx);
+  if ((rc = on_device.status()) != MCR_OK) return rc;
+  int32_t* counters = nullptr;                 // this device's copy of the static array
+  if ((rc = route_scratch_address(ctx->device, &counters)) != MCR_OK) return rc;
+  return launch_moe_route_chunked(ctx, ti, T, E, P, capacity, ts, tc, splits, counters, static_cast<hipStream_t>(stream));
 }
 
 int mcr_pack(mcr_ctx* ctx, void* const* out, const void* const* in, const int32_t* const* slot, size_t T,

@@ -96,6 +96,7 @@ int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capa
 int route_chunks(int T, int* chunk_steps);
 int launch_moe_route_chunked(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot,
                              const PtrTab& counts, int64_t* splits, int32_t* workspace, hipStream_t);
+int route_scratch_address(int device, int32_t** out);
 int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows, size_t row_bytes,
                 int elem_b, int P, int variant, hipStream_t);
 int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, const CPtrTab* gate, size_t T,

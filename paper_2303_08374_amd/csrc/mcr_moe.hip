@@ -2,6 +2,8 @@
 // (histogram + capacity clamp + exclusive scan -> pack slots and the split
 // matrix), pack (row scatter by slot), unpack / gate-weighted combine (row
 // gather by slot).
+#include <mutex>
+
 #include "mcr_dispatch.hpp"
 
 namespace mcr {
@@ -433,6 +435,33 @@ int launch_moe_route_chunked(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, 
   hipLaunchKernelGGL(moe_route_slot_kernel, dim3(chunks, P), dim3(kChunkBlock), 0, stream, ids, slot, counts, splits,
                      workspace, T, E, P, capacity, chunk_steps, nbits);
   return launch_status();
+}
+
+// ---- routing for callers that cannot allocate ---------------------------------------------------
+// The chunk counters of the several-workgroup routing live in a static device array instead of
+// a caller's workspace.  Every GPU the library runs on holds its own copy of the array at its
+// own address until the process ends; the address is looked up once per device, with that device
+// current, and host code uses that address only, never the array's name.
+static __device__ __align__(256) int32_t scratch[MCR_ROUTE_SCRATCH_BYTES / sizeof(int32_t)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+int32_t* scratch_ptr[kMaxDevices] = {nullptr};
+}  // namespace
+
+// Device address of the calling thread's current device's copy of `scratch` (that device must be
+// `device`), looked up on first use.  MCR_EHIP if the runtime cannot resolve the symbol.
+int route_scratch_address(int device, int32_t** out) {
+  if (device < 0 || device >= kMaxDevices) return MCR_EINVAL;
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MCR_EHIP;
+    scratch_ptr[device] = static_cast<int32_t*>(p);
+  }
+  *out = scratch_ptr[device];
+  return MCR_OK;
 }
 
 int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows,

@@ -26,7 +26,8 @@ OP_NAMES = ["allreduce", "reduce_scatter", "allgather", "alltoall", "alltoallv",
             "fuse", "unfuse", "allreduce_multi", "moe_route", "moe_dispatch", "moe_combine", "dlrm_shuffle",
             "moe_dispatch_by_expert", "moe_combine_by_expert"]
 
-OK, EINVAL, EDTYPE, EOP, EVARIANT, ESPLIT, EHIP, ENOMEM, EIO, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8, -9
+OK, EINVAL, EDTYPE, EOP, EVARIANT, ESPLIT, EHIP, ENOMEM, EIO, ESTATE, ELIMIT = 0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10
+ROUTE_SCRATCH_BYTES = 1 << 20
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmcr.so")
 
@@ -221,6 +222,12 @@ def mcr_moe_route_ws(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, cap
     ws = ctypes.c_void_p(_addr(workspace)) if workspace is not None else ctypes.c_void_p(0)
     _check(lib().mcr_moe_route_ws(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
                                   ctypes.c_void_p(_addr(splits)), ws, _sz(workspace_bytes), _stream(stream)), "mcr_moe_route_ws")
+
+
+def mcr_moe_route_static(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
+                         counts: Sequence[Ptr], splits: Ptr, stream=None) -> None:
+    _check(lib().mcr_moe_route_static(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
+                                      ctypes.c_void_p(_addr(splits)), _stream(stream)), "mcr_moe_route_static")
 
 
 def mcr_pack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr], T: int, out_rows: int, row_elems: int,

@@ -44,7 +44,7 @@ def test_binding_has_the_same_names():
 
 def test_strerror_and_variants(ctx):
     assert mcr.strerror(0) == "ok"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert mcr.strerror(code) not in ("ok", "unknown status")
     for op in range(10):
         v = mcr.mcr_get_variants(ctx, op)
@@ -64,6 +64,19 @@ def _status(fn, *a, **k):
 
 
 A16 = [0x10000 * (i + 1) for i in range(16)]       # fake, 16-byte aligned device addresses (never dereferenced)
+
+
+def test_static_scratch_routing_refuses_what_does_not_fit(ctx):
+    """mcr_moe_route_static: a routing whose chunk counters exceed the static array is refused with
+    MCR_ELIMIT before anything else happens; one that fits passes validation (and then stops at the
+    host-only context)."""
+    S = mcr
+    assert S.mcr_moe_route_workspace_bytes(2048 * 40, 512, 16) > S.ROUTE_SCRATCH_BYTES
+    assert _status(S.mcr_moe_route_static, ctx, A16, 2048 * 40, 512, 16, 8, A16, A16, A16[0], 0) == S.ELIMIT
+    assert 0 < S.mcr_moe_route_workspace_bytes(40000, 64, 16) <= S.ROUTE_SCRATCH_BYTES
+    assert _status(S.mcr_moe_route_static, ctx, A16, 40000, 64, 16, 8, A16, A16, A16[0], 0) == S.ESTATE
+    assert _status(S.mcr_moe_route_static, ctx, A16, 40000, 64, 16, 8, A16, A16, A16[0] + 4, 0) == S.EINVAL   # splits not 8-byte aligned
+    assert _status(S.mcr_moe_route_static, ctx, A16, 40000, 60, 16, 8, A16, A16, A16[0], 0) == S.EINVAL       # P does not divide E
 
 
 def test_validation_errors(ctx):
