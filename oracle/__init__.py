@@ -229,20 +229,23 @@ def alltoall(ins: List[np.ndarray], dtype: int) -> List[np.ndarray]:
 
 
 def alltoallv(ins: List[np.ndarray], S: np.ndarray, row_elems: int, dtype: int,
-              outs: Optional[List[np.ndarray]] = None) -> List[np.ndarray]:
-    """``S[p, r]`` rows go from rank p to rank r.  ``outs`` (if given) keeps its
-    rows beyond the received ones; otherwise exact-size outputs are made."""
+              outs: Optional[List[np.ndarray]] = None, transposed: bool = False) -> List[np.ndarray]:
+    """``S[p, r]`` rows go from rank p to rank r (``transposed``: the way back, ``S[p, r]`` rows go
+    from rank r to rank p).  ``outs`` (if given) keeps its rows beyond the received ones; otherwise
+    exact-size outputs are made."""
     P = len(ins)
     S = np.ascontiguousarray(S, dtype=np.int64)
     assert S.shape == (P, P)
+    sent = S.sum(axis=0) if transposed else S.sum(axis=1)
+    received = S.sum(axis=1) if transposed else S.sum(axis=0)
     if outs is None:
-        outs = [np.zeros(int(S[:, r].sum()) * row_elems, dtype=np_dtype(dtype)) for r in range(P)]
+        outs = [np.zeros(int(received[r]) * row_elems, dtype=np_dtype(dtype)) for r in range(P)]
     for p in range(P):
-        assert ins[p].size >= int(S[p].sum()) * row_elems
+        assert ins[p].size >= int(sent[p]) * row_elems
     for r in range(P):
-        assert outs[r].size >= int(S[:, r].sum()) * row_elems
-    _check(lib().orc_alltoallv(_ptrs(outs), _ptrs(ins), _p(S), ctypes.c_size_t(row_elems), dtype, P),
-           "alltoallv")
+        assert outs[r].size >= int(received[r]) * row_elems
+    fn = lib().orc_alltoallv_transposed if transposed else lib().orc_alltoallv
+    _check(fn(_ptrs(outs), _ptrs(ins), _p(S), ctypes.c_size_t(row_elems), dtype, P), "alltoallv")
     return outs
 
 

@@ -455,6 +455,32 @@ int orc_alltoallv(void* const* out, const void* const* in, const int64_t* S,
   return 0;
 }
 
+// The way back (the second Alltoall of Sec. II-C "Mixture-of-Experts", which returns the expert
+// outputs): the same exchange with the roles of the matrix swapped, rank r now sending
+// S[p][r] rows to rank p.  With T[a][b] = S[b][a]: sender a's rows for receiver b start at
+// sum_{q<b} T[a][q] and land at sum_{q<a} T[q][b].
+int orc_alltoallv_transposed(void* const* out, const void* const* in, const int64_t* S,
+                             size_t row_elems, int dtype, int P) {
+  if (!out || !in || !S || P < 1 || bad_dtype(dtype)) return -1;
+  for (int i = 0; i < P * P; ++i)
+    if (S[i] < 0) return -2;
+  const size_t rb = row_elems * elem_bytes(dtype);
+  for (int b = 0; b < P; ++b) {          // receiver
+    int64_t rdispl = 0;
+    for (int a = 0; a < P; ++a) {        // sender
+      int64_t sdispl = 0;
+      for (int q = 0; q < b; ++q) sdispl += S[q * P + a];
+      const int64_t back = S[b * P + a];
+      for (int64_t k = 0; k < back; ++k) {
+        std::memcpy(static_cast<char*>(out[b]) + static_cast<size_t>(rdispl + k) * rb,
+                    static_cast<const char*>(in[a]) + static_cast<size_t>(sdispl + k) * rb, rb);
+      }
+      rdispl += back;
+    }
+  }
+  return 0;
+}
+
 // ---- MoE routing of one rank's tokens (Sec. II-C "Mixture-of-Experts": --------
 // tokens are routed to experts by a gate and exchanged with Alltoall) ----------
 // ids[t] in [0,E) is token t's expert (top-1).  Capacity C per expert per

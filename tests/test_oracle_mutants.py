@@ -51,6 +51,9 @@ MUTANTS = [
      "static_cast<const char*>(in[p]) + (static_cast<size_t>(p) * b + k) * s, s);"),
     ("alltoallv_sdispl_inclusive", "for (int q = 0; q < r; ++q) sdispl += S[p * P + q];", "for (int q = 0; q <= r; ++q) sdispl += S[p * P + q];"),
     ("alltoallv_S_transposed", "const int64_t cnt = S[p * P + r];", "const int64_t cnt = S[r * P + p];"),
+    ("alltoallv_back_counts_not_transposed", "const int64_t back = S[b * P + a];", "const int64_t back = S[a * P + b];"),
+    ("alltoallv_back_sdispl_along_the_row", "for (int q = 0; q < b; ++q) sdispl += S[q * P + a];", "for (int q = 0; q < b; ++q) sdispl += S[a * P + q];"),
+    ("alltoallv_back_sdispl_inclusive", "for (int q = 0; q < b; ++q) sdispl += S[q * P + a];", "for (int q = 0; q <= b; ++q) sdispl += S[q * P + a];"),
     ("route_capacity_off_by_one", "pos[static_cast<size_t>(t)] >= C) {", "pos[static_cast<size_t>(t)] > C) {"),
     ("route_base_inclusive", "base[static_cast<size_t>(e)] = run;\n    run += c;", "run += c;\n    base[static_cast<size_t>(e)] = run;"),
     ("route_counts_unclamped", "const int64_t c = seen[static_cast<size_t>(e)] < C ? seen[static_cast<size_t>(e)] : C;", "const int64_t c = seen[static_cast<size_t>(e)];"),

@@ -335,6 +335,37 @@ def check_alltoallv_properties():
             assert np.array_equal(back[p], ins[p])
 
 
+def check_alltoallv_transposed():
+    """The way back (S[p][r] rows go from rank r to rank p): the hand-worked example returns to its
+    inputs; on random matrices it is the forward exchange with the numpy-transposed matrix, the numpy
+    slicing definition of that, and the inverse of the forward exchange."""
+    g = gio.keyed_ints("alltoallv_case.txt")
+    S = np.array(g["S"], dtype=np.int64).reshape(2, 2)
+    outs = [np.array(g["out0"], dtype=np.float32), np.array(g["out1"], dtype=np.float32)]
+    back = oracle.alltoallv(outs, S, 1, F32, transposed=True)
+    assert back[0].tolist() == g["in0"] and back[1].tolist() == g["in1"]
+    for P, w, seed in ((2, 1, 11), (3, 2, 12), (8, 4, 13), (16, 1, 14)):
+        S = _random_splits(P, 7, seed)
+        T = S.T.copy()
+        ins = []
+        for a in range(P):                      # rank a sends T[a][b] = S[b][a] rows to rank b
+            rows = int(T[a].sum())
+            v = (a << 20) + (np.arange(rows)[:, None] << 6) + np.arange(w)[None, :]
+            ins.append(v.astype(np.float32).reshape(-1))
+        got = oracle.alltoallv(ins, S, w, F32, transposed=True)
+        via_forward = oracle.alltoallv(ins, T, w, F32)
+        sd = np.concatenate([np.zeros((P, 1), dtype=np.int64), np.cumsum(T, axis=1)], axis=1)
+        for b in range(P):
+            ref = np.concatenate([ins[a].reshape(-1, w)[sd[a, b]:sd[a, b + 1]] for a in range(P)]).reshape(-1)
+            assert np.array_equal(got[b], ref) and np.array_equal(got[b], via_forward[b])
+        # forward with S, then the way back with the same S, is the identity
+        fwd_in = [np.arange(int(S[p].sum()) * w, dtype=np.float32) + 1000 * p for p in range(P)]
+        there = oracle.alltoallv(fwd_in, S, w, F32)
+        home = oracle.alltoallv(there, S, w, F32, transposed=True)
+        for p in range(P):
+            assert np.array_equal(home[p], fwd_in[p])
+
+
 def check_alltoallv_equal_is_alltoall():
     P, b, w = 4, 6, 5
     ins = inputs.rank_buffers(P, P * b * w, seed=31, dist="uniform")
