@@ -9,7 +9,9 @@ takes buffers the caches have not seen for gigabytes of traffic.
 
 Prints ONE JSON line: whole-step effective GB/s (algorithmic bytes / time), the roofline of
 the kernel that dominates the step (measured with events on the launch stream inside the
-timed region), and the CPU oracle timed on a bounded sample of the same sweep.
+timed region), the rate of every (op, element type) group on messages of 16 MiB and more
+next to the ceilings that plain library launches reach in the same run, and the CPU oracle
+timed on a bounded sample of the same sweep.
 """
 import argparse
 import hashlib
@@ -31,6 +33,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--cells-out", default=None, help="write the per-cell table (JSON) here")
+    ap.add_argument("--cells-md", default=None, help="write the per-cell table and the workloads as markdown here")
+    ap.add_argument("--trace-passes", type=int, default=0,
+                    help="for a kernel trace: after the warm-up run this many plain passes over the cells and stop")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stages", action="store_true",
                     help="skip the application-shaped workloads (small allreduce, MoE, DLRM, gradient buckets)")
@@ -86,6 +91,40 @@ def kernel_group(op, dtype, variant_name):
     return f"{op}/{variant_name}"
 
 
+def measure_ceilings(ctx, arena, torch, mcr):
+    """What plain library launches reach on this GPU in this run, over cold buffers, median of 5:
+    a copy (all_to_all_single at P=1: one read and one write stream), a read-dominated launch
+    (reduce_scatter at P=16: 16 read streams to 1 write stream) and a write-dominated one (bcast
+    to 7 receivers: 1 read to 7 writes)."""
+    G = 1 << 30
+
+    def timed(launch, footprint, alg_bytes):
+        ms = []
+        for i in range(7):
+            base = arena.take(footprint)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            launch(base)
+            e1.record()
+            e1.synchronize()
+            if i >= 2:
+                ms.append(e0.elapsed_time(e1))
+        t = sorted(ms)[len(ms) // 2]
+        return round(alg_bytes / (t * 1e-3) / 1e9, 1), round(t * 1e3, 1)
+
+    out = {}
+    g, us = timed(lambda b: mcr.mcr_alltoall(ctx, [b + G], [b], G // 4, mcr.F32, 1, 4), 2 * G, 2 * G)
+    out["copy"] = {"GBps": g, "us": us, "what": "mcr_alltoall at P=1, 1 GiB, variant v1nt: 1 GiB read + 1 GiB written"}
+    M = 128 << 20
+    g, us = timed(lambda b: mcr.mcr_reduce_scatter(ctx, [b + 16 * M + r * (M // 16) for r in range(16)], [b + p * M for p in range(16)],
+                                                   M // 4, mcr.F32, mcr.SUM, 16), 17 * M, 17 * M)
+    out["read_dominated"] = {"GBps": g, "us": us, "what": "mcr_reduce_scatter at P=16, 128 MiB per rank, fp32: 2 GiB read + 128 MiB written"}
+    M = 256 << 20
+    g, us = timed(lambda b: mcr.mcr_bcast(ctx, [b + p * M for p in range(8)], M // 4, mcr.F32, 0, 8), 8 * M, 8 * M)
+    out["write_dominated"] = {"GBps": g, "us": us, "what": "mcr_bcast at P=8, 256 MiB, fp32: 256 MiB read + 1.75 GiB written"}
+    return out
+
+
 def cpu_baseline(max_bytes):
     """The oracle as it stands, one thread, on the sweep cells up to `max_bytes` per rank."""
     import numpy as np
@@ -139,7 +178,7 @@ def main():
     cells = sweep.make_cells(P, inputs.SWEEP_OPS, inputs.SWEEP_DTYPES, inputs.SWEEP_BYTES)
     need = max(c.footprint for c in cells)
     arena = sweep.Arena(need + (2 << 30), seed=inputs.SWEEP_SEED)
-    names = mcr.mcr_get_variants(ctx, mcr.OP_ALLGATHER)      # the longest list; a prefix serves the other ops
+    variant_names = {op: mcr.mcr_get_variants(ctx, sweep.OPS[op]) for op in inputs.SWEEP_OPS}
     variant_of = {c.key: c.auto_variant(ctx) for c in cells}
     step_bytes = sum(c.alg_bytes for c in cells)
 
@@ -162,11 +201,18 @@ def main():
     for _ in range(max(args.warmup, 1)):
         run_step()
     torch.cuda.synchronize()
+    if args.trace_passes > 0:
+        for _ in range(args.trace_passes):
+            run_step()
+            torch.cuda.synchronize()
+        mcr.mcr_finalize(ctx)
+        print(json.dumps({"trace_passes": args.trace_passes, "cells_per_pass": len(cells)}))
+        return 0
     # one instrumented pass decides which kernel dominates the step
     evs = run_step(all_keys)
     torch.cuda.synchronize()
     group_ms = {}
-    group_of = {c.key: kernel_group(c.op, c.dtype, names[variant_of[c.key]]) for c in cells}
+    group_of = {c.key: kernel_group(c.op, c.dtype, variant_names[c.op][variant_of[c.key]]) for c in cells}
     for c, e0, e1 in evs:
         g = group_of[c.key]
         group_ms[g] = group_ms.get(g, 0.0) + e0.elapsed_time(e1)
@@ -214,16 +260,26 @@ def main():
         torch.cuda.synchronize()
         for c, e0, e1 in evs:
             per_cell[c.key].append(e0.elapsed_time(e1))
+    ceilings = measure_ceilings(ctx, arena, torch, mcr)
     table_out, large = {}, {}
     for c in cells:
         ms = sorted(per_cell[c.key])[len(per_cell[c.key]) // 2]
         gbps = c.alg_bytes / (ms * 1e-3) / 1e9
-        table_out[c.key] = {"variant": names[variant_of[c.key]], "us": round(ms * 1e3, 2), "GBps": round(gbps, 1),
+        table_out[c.key] = {"variant": variant_names[c.op][variant_of[c.key]], "us": round(ms * 1e3, 2), "GBps": round(gbps, 1),
                             "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
         if c.M >= (16 << 20):
-            k = f"{c.op}/{c.dtype}"
-            large.setdefault(k, []).append(gbps / HBM_PEAK_GBPS)
-    large_summary = {k: {"min_frac": round(min(v), 4), "max_frac": round(max(v), 4)} for k, v in large.items()}
+            g = large.setdefault(f"{c.op}/{c.dtype}", {"bytes": 0, "ms": 0.0, "fracs": []})
+            g["bytes"] += c.alg_bytes
+            g["ms"] += ms
+            g["fracs"].append(gbps / HBM_PEAK_GBPS)
+    # per (op, element type), messages of 16 MiB and more: bytes summed over times summed
+    per_op = {}
+    for k, g in large.items():
+        gbps = g["bytes"] / (g["ms"] * 1e-3) / 1e9
+        per_op[k] = {"GBps": round(gbps, 1), "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                     "frac_of_copy_ceiling": round(gbps / ceilings["copy"]["GBps"], 4),
+                     "min_frac": round(min(g["fracs"]), 4), "max_frac": round(max(g["fracs"]), 4)}
+    worst = min(per_op, key=lambda k: per_op[k]["frac_of_peak"])
     small_us = {f"{c.op}/{c.dtype}": table_out[c.key]["us"] for c in cells if c.M == inputs.SWEEP_BYTES[0]}
     if args.cells_out:
         os.makedirs(os.path.dirname(args.cells_out) or ".", exist_ok=True)
@@ -234,7 +290,7 @@ def main():
         "metric": "effective GB/s and % of HBM peak per op vs message size (4 KB-256 MB)",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32", "element_types": ["f32", "bf16"], "data": "synthetic",
         "config": {"workload": "op sweep: allreduce, reduce_scatter, allgather, alltoall x {fp32, bf16 with fp32 "
                                "accumulate} x 17 per-rank message sizes 4 KiB..256 MiB, P=8 simulated ranks, "
                                "uniform[-1,1), MCR_AUTO dispatch, cold buffers",
@@ -242,7 +298,10 @@ def main():
                    "tuning_table_rows": table_rows},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "roofline": roofline,
-        "messages_ge_16MiB_frac_of_peak": large_summary,
+        "ceilings": ceilings,
+        "roofline_per_op": per_op,
+        "worst_op": f"{worst}: {per_op[worst]['GBps']} GB/s = {100 * per_op[worst]['frac_of_peak']:.1f} % of 8000 GB/s, "
+                    f"{100 * per_op[worst]['frac_of_copy_ceiling']:.1f} % of the copy ceiling",
         "smallest_message_us": small_us,
     }
     if not args.no_stages:
@@ -257,6 +316,11 @@ def main():
         torch.cuda.synchronize()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.cpu_max_bytes)
+    if args.cells_md:
+        from paper_2303_08374_amd import report
+        os.makedirs(os.path.dirname(args.cells_md) or ".", exist_ok=True)
+        with open(args.cells_md, "w") as f:
+            f.write(report.cells_markdown(table_out, out, "python3 bench.py " + " ".join(sys.argv[1:])))
     mcr.mcr_finalize(ctx)
     print(json.dumps(out))
     return 0

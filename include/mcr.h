@@ -53,8 +53,10 @@ typedef struct mcr_fuse_plan mcr_fuse_plan; /* library-owned: bucket plan + devi
  * arithmetic that wraps (sums and products modulo 2^32; MAX and MIN compare as signed), which
  * does not depend on the order; MCR_AVG of int32 gives MCR_EOP, and the calls that scale rows by
  * a gate weight (mcr_unpack, mcr_moe_combine, mcr_moe_combine_by_expert with a gate or K > 1)
- * give MCR_EDTYPE for it.  The reductions on MCR_F32 and MCR_BF16 are compiled for every launch
- * shape; on MCR_F16 and MCR_I32 the vector variants all run the nontemporal shape of their unroll. */
+ * give MCR_EDTYPE for it.  The reductions (SUM / AVG) on MCR_F32 and MCR_BF16 are compiled for the
+ * plain and the nontemporal shape of every unroll (their "ln" / "sn" variants run the nontemporal
+ * one) and for the persistent shape; on MCR_F16 and MCR_I32, and for the other ReduceOps, every
+ * vector variant runs the nontemporal shape of its unroll and the persistent one runs "v4nt". */
 typedef enum { MCR_F32 = 0, MCR_BF16 = 1, MCR_F16 = 2, MCR_I32 = 3 } mcr_dtype;
 
 /* ReduceOp of the API listing; every op runs as a left-to-right chain in rank order in
@@ -140,7 +142,11 @@ const char* mcr_strerror(int status);
  * P buffers are 16-byte aligned, and also when all of them miss that alignment by the same
  * number of bytes (the same view of a tensor on every rank) and the message reaches the next
  * 16-byte boundary; otherwise only the element path ("scalar") applies.  `count` may be any
- * number. */
+ * number.
+ * One variant beyond the common launch shapes (all_reduce, reduce, reduce_scatter): "pk8", a
+ * persistent form with one workgroup of 1024 threads per compute unit, each walking a contiguous
+ * run of the message in rounds (read and reduce 8 steps of one vector per thread, then store
+ * them). */
 int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype,
                   mcr_redop op, int P, int variant, void* stream);
 
@@ -167,18 +173,25 @@ int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t c
  * sum_{q<p} splits[q][r]:
  *     out[r] row (rdispl[r][p] + k) = in[p] row (sdispl[p][r] + k),  k < splits[p][r].
  * Rows of out[r] beyond its received total are left untouched.
- *   splits_on_device == 0: splits is HOST memory, read before return and
- *     validated: a negative entry gives MCR_EINVAL; a row sum above in_rows or
- *     a column sum above out_rows gives MCR_ESPLIT.
- *   splits_on_device != 0: splits is DEVICE memory (e.g. written by
- *     mcr_moe_route earlier on the same stream) and is read by the kernel; no
- *     host synchronisation happens.  The kernel itself skips any row that
- *     would fall outside in_rows / out_rows and treats negative entries as 0.
+ * splits_flags is a sum of:
+ *   MCR_SPLITS_ON_DEVICE: splits is DEVICE memory (e.g. written by mcr_moe_route earlier on the
+ *     same stream) and is read by the kernel; no host synchronisation happens.  The kernel
+ *     itself skips any row that would fall outside in_rows / out_rows and treats negative
+ *     entries as 0.  Without the flag splits is HOST memory, read before return and validated:
+ *     a negative entry gives MCR_EINVAL; a sender's total above in_rows or a receiver's total
+ *     above out_rows gives MCR_ESPLIT.
+ *   MCR_SPLITS_TRANSPOSED: the matrix is read transposed, splits[r*P + p] = rows rank p sends to
+ *     rank r.  This is the way back of an exchange that went out with the same matrix (the
+ *     second Alltoall of paper Sec. II-C, which returns the expert outputs): every rank sends
+ *     back what it received, and nobody has to transpose the matrix in between.
+ * Any other bit gives MCR_EINVAL.
  *   splits == NULL: equal split, every pair exchanges in_rows/P rows (P must
  *     divide in_rows, and out_rows >= in_rows).
  * in_rows / out_rows: capacity, in rows, of every in[p] / out[r]. */
+#define MCR_SPLITS_ON_DEVICE 1
+#define MCR_SPLITS_TRANSPOSED 2
 int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const int64_t* splits,
-                  int splits_on_device, size_t in_rows, size_t out_rows, size_t row_elems,
+                  int splits_flags, size_t in_rows, size_t out_rows, size_t row_elems,
                   mcr_dtype dtype, int P, int variant, void* stream);
 
 /* ---- rooted and vector collectives (API listing: reduce, bcast, gather, scatter, gatherv,

@@ -18,10 +18,34 @@
 namespace mcr {
 namespace {
 
+// The elements that are not part of a whole vector, reduced one by one by workgroup 0: those past
+// the last whole vector, and the `head` (< elements per vector) ones in front of the first.
+template <int DT, int P>
+__device__ __forceinline__ void allreduce_edges(const PtrTab& bufs, const CPtrTab& in, size_t nvec, size_t count, float scale,
+                                                int op, int root, unsigned head) {
+  using E = Elem<DT>;
+  const size_t done = nvec * E::kPerVec;
+  if (blockIdx.x == 0 && done + threadIdx.x < count) {
+    const size_t i = done + threadIdx.x;
+    const typename E::acc_t y = reduce_scalar<DT>(in, i, P, scale, op);
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < head) {
+    CPtrTab front;
+#pragma unroll
+    for (int p = 0; p < P; ++p) front.p[p] = static_cast<const char*>(in.p[p]) - static_cast<size_t>(head) * E::kBytes;
+    const typename E::acc_t y = reduce_scalar<DT>(front, threadIdx.x, P, scale, op);
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      if (root < 0 || root == p) E::store1(const_cast<void*>(front.p[p]), threadIdx.x, y);
+  }
+}
+
 template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
 __global__ void __launch_bounds__(kBlock)
 allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root, unsigned head) {
-  using E = Elem<DT>;
   constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
   CPtrTab in;
 #pragma unroll
@@ -41,25 +65,18 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int r
       }
     }
   }
-  // elements past the last whole vector
-  const size_t done = nvec * E::kPerVec;
-  if (blockIdx.x == 0 && done + threadIdx.x < count) {
-    const size_t i = done + threadIdx.x;
-    const typename E::acc_t y = reduce_scalar<DT>(in, i, P, scale, op);
+  allreduce_edges<DT, P>(bufs, in, nvec, count, scale, op, root, head);
+}
+
+// The persistent form (see reduce_persistent).
+template <int DT, int P, int U, int K>
+__global__ void __launch_bounds__(kPersistBlock)
+allreduce_persist(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root, unsigned head) {
+  CPtrTab in;
 #pragma unroll
-    for (int p = 0; p < P; ++p)
-      if (root < 0 || root == p) E::store1(bufs.p[p], i, y);
-  }
-  // elements in front of the first whole vector (head < elements per vector)
-  if (blockIdx.x == 0 && threadIdx.x < head) {
-    CPtrTab front;
-#pragma unroll
-    for (int p = 0; p < P; ++p) front.p[p] = static_cast<const char*>(in.p[p]) - static_cast<size_t>(head) * E::kBytes;
-    const typename E::acc_t y = reduce_scalar<DT>(front, threadIdx.x, P, scale, op);
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-      if (root < 0 || root == p) E::store1(const_cast<void*>(front.p[p]), threadIdx.x, y);
-  }
+  for (int p = 0; p < P; ++p) in.p[p] = bufs.p[p];
+  reduce_persistent<DT, P, U, K, false, false>(bufs, in, nvec, scale, op, root);
+  allreduce_edges<DT, P>(bufs, in, nvec, count, scale, op, root, head);
 }
 
 // Element path (buffers with different alignments, any count).  Still 16 bytes per access, at
@@ -125,7 +142,7 @@ allreduce_scalar(PtrTab bufs, size_t count, float scale, int op, int root) {
 // own, which keeps the compile time of the reductions (16 rank counts x launch shapes) spread
 // over the build's workers.
 template <int DT>
-int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op, int P, int root, int variant,
+int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op, int P, int root, int variant, int n_cu,
                         hipStream_t stream) {
   const float scale = 1.0f / static_cast<float>(P);
   if (variant == SV_SCALAR) {
@@ -138,6 +155,23 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
   // bufs point at the first whole vector: `head` elements lie in front of it, count - head from it on
   count -= head;
   const size_t nvec = count / Elem<DT>::kPerVec;
+  if (variant == SV_PK8) {
+    if (op > MCR_AVG || !all_shapes(DT)) {
+      variant = SV_V4NT;                                  // the shape that stands in for the persistent one
+    } else {
+      const unsigned g = persistent_grid(n_cu, 1);
+      return dispatch_ranks(P, [&](auto pp) {
+        constexpr int kP = decltype(pp)::value;
+        if constexpr (all_shapes(DT)) {
+          hipLaunchKernelGGL((allreduce_persist<DT, kP, kPersistU, kPersistK>), dim3(g), dim3(kPersistBlock), 0, stream, bufs, nvec,
+                             count, scale, op, root, head);
+          return launch_status();
+        } else {
+          return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above
+        }
+      });
+    }
+  }
   const unsigned gx = grid_x(nvec, variant);
   return dispatch_ranks(P, [&](auto pp) {
     constexpr int kP = decltype(pp)::value;
@@ -149,9 +183,9 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
       });
     }
     if constexpr (all_shapes(DT)) {
-      return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
+      return dispatch_reduce_shape(variant, [&](auto uu, auto nt) {
         constexpr int U = decltype(uu)::value;
-        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
+        hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(nt)::value, decltype(nt)::value, false>),
                            dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root, head);
         return launch_status();
       });

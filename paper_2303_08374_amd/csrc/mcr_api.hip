@@ -16,6 +16,8 @@ namespace mcr {
 const char* const kStreamVariantNames[AG_COUNT] = {"scalar", "v1", "v2", "v4", "v1nt", "v2nt", "v4nt", "v1ln", "v2ln", "v4ln",
                                                    "v1sn", "v2sn", "v4sn", "sc4", "sc8", "sc16"};
 
+const char* const kReduceVariantNames[RV_COUNT - SV_COUNT] = {"pk8"};
+
 namespace {
 
 const char* const kOpNames[MCR_OP_COUNT] = {"allreduce", "reduce_scatter", "allgather", "alltoall",
@@ -31,7 +33,17 @@ bool valid_redop(int o) { return o >= MCR_SUM && o <= MCR_PROD; }
 // integers have no average
 bool redop_fits(int o, int dtype) { return !(dtype == MCR_I32 && o == MCR_AVG); }
 bool valid_P(int P) { return P >= 1 && P <= MCR_MAX_RANKS; }
-int n_variants(int op) { return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : SV_COUNT; }
+bool is_reduction(int op) { return op == MCR_OP_ALLREDUCE || op == MCR_OP_REDUCE_SCATTER; }
+int n_variants(int op) {
+  return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : is_reduction(op) ? RV_COUNT : SV_COUNT;
+}
+// Name of variant `i` of `op`: the ids from SV_COUNT on belong to one op each (super-chunk forms of
+// all_gather, persistent forms of the reductions).
+const char* variant_name(int op, int i) {
+  if (op == MCR_OP_MOE_ROUTE) return kRouteVariantNames[i];
+  if (is_reduction(op) && i >= SV_COUNT) return kReduceVariantNames[i - SV_COUNT];
+  return kStreamVariantNames[i];
+}
 
 bool elem_aligned(const void* p, int dtype) {
   return (reinterpret_cast<uintptr_t>(p) & (elem_bytes(dtype) - 1)) == 0;
@@ -167,7 +179,7 @@ int vector_collective(mcr_ctx* ctx, const PtrTab& to, const CPtrTab& ti, bool al
   // every buffer is bounded by the whole payload: the split matrix is ours, so the bounds never bind
   const size_t rows = total / row_elems;
   return launch_alltoallv(ctx, to, ti, S, nullptr, rows, rows, row_elems * elem_bytes(dtype),
-                          static_cast<int>(elem_bytes(dtype)), P, same_src, v, static_cast<hipStream_t>(stream));
+                          static_cast<int>(elem_bytes(dtype)), P, same_src, false, v, static_cast<hipStream_t>(stream));
 }
 
 // Pairs with caller-chosen offsets, in elements: pair i = p*P + r copies cnt[i] elements from
@@ -290,6 +302,10 @@ int mcr_init(mcr_ctx** out, int device) {
   mcr_ctx* ctx = new (std::nothrow) mcr_ctx;
   if (!ctx) return MCR_ENOMEM;
   ctx->device = device;
+  if (device != MCR_NO_DEVICE) {
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && n_cu > 0) ctx->n_cu = n_cu;
+  }
   const char* path = std::getenv("MCR_TUNING_TABLE");
   if (path && *path) (void)mcr_tune_load(ctx, path);   // an unreadable file leaves the table empty
   *out = ctx;
@@ -314,7 +330,7 @@ int mcr_get_variants(mcr_ctx* ctx, int op_id, const char** names, int* n) {
   const int cap = *n;
   if (names) {
     for (int i = 0; i < have && i < cap; ++i)
-      names[i] = (op_id == MCR_OP_MOE_ROUTE) ? kRouteVariantNames[i] : kStreamVariantNames[i];
+      names[i] = variant_name(op_id, i);
   }
   *n = have;
   return MCR_OK;
@@ -387,22 +403,29 @@ int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t c
 }
 
 int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const int64_t* splits,
-                  int splits_on_device, size_t in_rows, size_t out_rows, size_t row_elems, mcr_dtype dtype, int P,
+                  int splits_flags, size_t in_rows, size_t out_rows, size_t row_elems, mcr_dtype dtype, int P,
                   int variant, void* stream) {
   if (!ctx || !out || !in || !valid_P(P)) return MCR_EINVAL;
   if (!valid_dtype(dtype)) return MCR_EDTYPE;
+  if (splits_flags & ~(MCR_SPLITS_ON_DEVICE | MCR_SPLITS_TRANSPOSED)) return MCR_EINVAL;
+  const bool transposed = splits && (splits_flags & MCR_SPLITS_TRANSPOSED);
   const size_t row_bytes = row_elems * elem_bytes(dtype);
-  int64_t equal[MCR_MAX_RANKS * MCR_MAX_RANKS];
+  int64_t local[MCR_MAX_RANKS * MCR_MAX_RANKS];                       // equal split, or a host matrix transposed
   const int64_t* host = nullptr;
   const int64_t* dev = nullptr;
   if (!splits) {
     if (in_rows % static_cast<size_t>(P) != 0 || out_rows < in_rows) return MCR_EINVAL;
-    for (int i = 0; i < P * P; ++i) equal[i] = static_cast<int64_t>(in_rows / P);
-    host = equal;
-  } else if (splits_on_device) {
+    for (int i = 0; i < P * P; ++i) local[i] = static_cast<int64_t>(in_rows / P);
+    host = local;
+  } else if (splits_flags & MCR_SPLITS_ON_DEVICE) {
     dev = splits;
   } else {
     host = splits;
+    if (transposed) {
+      for (int p = 0; p < P; ++p)
+        for (int r = 0; r < P; ++r) local[p * P + r] = splits[r * P + p];
+      host = local;
+    }
     for (int i = 0; i < P * P; ++i)
       if (host[i] < 0) return MCR_EINVAL;
     for (int p = 0; p < P; ++p) {
@@ -427,7 +450,7 @@ int mcr_alltoallv(mcr_ctx* ctx, void* const* out, const void* const* in, const i
   DeviceScope on_device(ctx);
   if ((rc = on_device.status()) != MCR_OK) return rc;
   return launch_alltoallv(ctx, to, ti, host, dev, in_rows, out_rows, row_bytes, static_cast<int>(elem_bytes(dtype)), P,
-                          0, v, static_cast<hipStream_t>(stream));
+                          0, dev && transposed, v, static_cast<hipStream_t>(stream));
 }
 
 // ---- rooted and vector collectives (API listing: reduce, bcast, gather(v), scatter(v),
@@ -1254,7 +1277,7 @@ int mcr_tune_save(mcr_ctx* ctx, const char* path) {
   std::fprintf(f, "# op dtype P bytes variant\n");
   for (const auto& kv : ctx->tables) {
     for (const auto& row : kv.second) {
-      const char* vname = kv.first.op == MCR_OP_MOE_ROUTE ? kRouteVariantNames[row.second] : kStreamVariantNames[row.second];
+      const char* vname = variant_name(kv.first.op, row.second);
       std::fprintf(f, "%s %s %d %zu %s\n", kOpNames[kv.first.op], kDtypeNames[kv.first.dtype], kv.first.P, row.first, vname);
     }
   }
@@ -1285,7 +1308,7 @@ int mcr_tune_load(mcr_ctx* ctx, const char* path) {
     for (int i = 0; i < 4; ++i) if (!std::strcmp(dt, kDtypeNames[i])) r.dtype = i;
     if (r.op >= 0) {
       for (int i = 0; i < n_variants(r.op); ++i) {
-        const char* vname = r.op == MCR_OP_MOE_ROUTE ? kRouteVariantNames[i] : kStreamVariantNames[i];
+        const char* vname = variant_name(r.op, i);
         if (!std::strcmp(var, vname)) r.variant = i;
       }
     }

@@ -197,15 +197,18 @@ __device__ __forceinline__ uint64_t clamp_split(int64_t s, uint64_t in_rows) {
   return static_cast<uint64_t>(s) > in_rows ? in_rows : static_cast<uint64_t>(s);
 }
 
+// `tr` (device matrix only): the matrix is read transposed, entry (p, r) is ds[r * P + p].
 template <int UB, int U, bool NTL, bool NTS, bool DEV>
 __global__ void __launch_bounds__(kBlock)
 alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, uint64_t upr,
-                 uint64_t in_rows, uint64_t out_rows, int same_src) {
+                 uint64_t in_rows, uint64_t out_rows, int same_src, int tr) {
   typedef typename Unit<UB>::type T;
   constexpr uint64_t kTile = run_tile_units<UB, U>();
   const int p = blockIdx.y, r = blockIdx.z;
   const int64_t* S = DEV ? ds : hs.s;
-  uint64_t rows = clamp_split(S[p * P + r], in_rows);
+  // strides of the sender and the receiver index in the matrix as stored
+  const int sp = (DEV && tr) ? 1 : P, sr = (DEV && tr) ? P : 1;
+  uint64_t rows = clamp_split(S[p * sp + r * sr], in_rows);
   if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;      // the common early exit
   uint64_t sdispl = 0, rdispl = 0;
   if constexpr (DEV) {
@@ -217,8 +220,8 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
     const int lane = static_cast<int>(__lane_id());
     uint64_t a = 0, b = 0;
     if (lane < P) {
-      if (!same_src && lane < r) a = clamp_split(ds[p * P + lane], in_rows);
-      if (lane < p) b = clamp_split(ds[lane * P + r], in_rows);
+      if (!same_src && lane < r) a = clamp_split(ds[p * sp + lane * sr], in_rows);
+      if (lane < p) b = clamp_split(ds[lane * sp + r * sr], in_rows);
     }
 #pragma unroll
     for (int d = MCR_MAX_RANKS / 2; d >= 1; d >>= 1) {
@@ -363,7 +366,8 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
 
 int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits,
                      const int64_t* dev_splits, size_t in_rows, size_t out_rows, size_t row_bytes,
-                     int elem_b, int P, int same_src, int variant, hipStream_t stream) {
+                     int elem_b, int P, int same_src, bool dev_transposed, int variant, hipStream_t stream) {
+  const int tr = dev_transposed ? 1 : 0;
   SplitArg hs;
   for (int i = 0; i < MCR_MAX_RANKS * MCR_MAX_RANKS; ++i) hs.s[i] = 0;
   // rows of the longest pair: exact for a host matrix, the buffer bound for a device one
@@ -416,10 +420,10 @@ int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64
     const unsigned gx = capped_blocks(max_pair * upr, static_cast<size_t>(U) * kBlock * (16 / UB), dev ? 256 : 65535 * 16);
     if (dev)
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, true>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
-                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src);
+                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src, tr);
     else
       hipLaunchKernelGGL((alltoallv_kernel<UB, U, NTL, NTS, false>), dim3(gx, P, P), dim3(kBlock), 0, stream, out, in,
-                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src);
+                         hs, dev_splits, P, upr, static_cast<uint64_t>(in_rows), static_cast<uint64_t>(out_rows), same_src, tr);
     return launch_status();
   };
   if (variant == SV_SCALAR) {

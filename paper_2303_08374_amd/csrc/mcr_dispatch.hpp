@@ -65,6 +65,21 @@ inline int dispatch_shape(int variant, F&& f) {
   return MCR_EVARIANT;
 }
 
+// The reductions are compiled for the plain and the fully nontemporal shape of each unroll; their
+// "ln" and "sn" variants (which won no cell of any tuning run) run the nontemporal one.
+template <class F>
+inline int dispatch_reduce_shape(int variant, F&& f) {
+  switch (variant) {
+    case SV_V1: return f(Int<1>{}, Bool<false>{});
+    case SV_V2: return f(Int<2>{}, Bool<false>{});
+    case SV_V4: return f(Int<4>{}, Bool<false>{});
+    case SV_V1NT: case SV_V1LN: case SV_V1SN: return f(Int<1>{}, Bool<true>{});
+    case SV_V2NT: case SV_V2LN: case SV_V2SN: return f(Int<2>{}, Bool<true>{});
+    case SV_V4NT: case SV_V4LN: case SV_V4SN: return f(Int<4>{}, Bool<true>{});
+  }
+  return MCR_EVARIANT;
+}
+
 // f(Bool<NT loads>, Bool<NT stores>): the cache hint of a shape, for kernels with a fixed unroll
 template <class F>
 inline int dispatch_hint(int variant, F&& f) {

@@ -32,7 +32,13 @@ enum StreamVariant {
 // copies each super-chunk to one destination after the other, so that at any
 // moment the chip streams from one source region into one destination region.
 enum AllgatherVariant { AG_SC4 = 13, AG_SC8 = 14, AG_SC16 = 15, AG_COUNT = 16 };
+// all_reduce, reduce and reduce_scatter only: the persistent form "pk8", one workgroup of 1024
+// threads per compute unit walking a contiguous run of the message in rounds of 8 steps of one
+// vector per thread.  SUM / AVG on fp32 and bf16; other ReduceOps and element types run "v4nt" in
+// its place.
+enum ReduceVariant { SV_PK8 = 13, RV_COUNT = 14 };
 extern const char* const kStreamVariantNames[AG_COUNT];
+extern const char* const kReduceVariantNames[RV_COUNT - SV_COUNT];
 
 struct TuneKey {
   int op, dtype, P;
@@ -45,6 +51,7 @@ struct TuneKey {
 
 struct mcr_ctx {
   int device = 0;
+  int n_cu = 256;                                                     // compute units of the device
   std::mutex mu;                                                      // guards `tables`
   std::map<mcr::TuneKey, std::vector<std::pair<size_t, int>>> tables; // sorted by bytes
 };
@@ -88,7 +95,8 @@ int launch_reduce_scatter(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t
 int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
 int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count, int dtype, int P, int variant, hipStream_t);
 int launch_alltoallv(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const int64_t* host_splits, const int64_t* dev_splits,
-                     size_t in_rows, size_t out_rows, size_t row_bytes, int elem_b, int P, int same_src, int variant, hipStream_t);
+                     size_t in_rows, size_t out_rows, size_t row_bytes, int elem_b, int P, int same_src, bool dev_transposed,
+                     int variant, hipStream_t);
 int launch_alltoallv_pairs(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const uint32_t* cnt, const uint32_t* sd,
                            const uint32_t* rd, int elem_b, int P, int variant, hipStream_t);
 int launch_moe_route(mcr_ctx*, const CPtrTab& ids, int T, int E, int P, int capacity, const PtrTab& slot, const PtrTab& counts,

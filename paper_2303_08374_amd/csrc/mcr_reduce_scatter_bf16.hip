@@ -2,5 +2,5 @@
 #include "mcr_reduce_scatter_impl.hpp"
 
 namespace mcr {
-template int launch_reduce_scatter_dt<MCR_BF16>(const PtrTab&, const CPtrTab&, size_t, int, int, int, hipStream_t);
+template int launch_reduce_scatter_dt<MCR_BF16>(const PtrTab&, const CPtrTab&, size_t, int, int, int, int, hipStream_t);
 }  // namespace mcr

@@ -30,6 +30,13 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   }
 }
 
+// The persistent form (see reduce_persistent): grid (workgroups per slice, P).
+template <int DT, int P, int U, int K>
+__global__ void __launch_bounds__(kPersistBlock)
+reduce_scatter_persist(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
+  reduce_persistent<DT, P, U, K, true, false>(out, in, bvec, scale, op, -1);
+}
+
 // Element path (any alignment, any slice length): 16 bytes per access at element-aligned
 // addresses, kScalarUnroll vectors per thread with all P x kScalarUnroll loads in flight together;
 // the elements behind a slice's last whole vector one by one (see all_reduce's element path).
@@ -89,7 +96,7 @@ reduce_scatter_scalar(PtrTab out, CPtrTab in, size_t b, float scale, int op) {
 
 // One element type's launches (instantiated in a translation unit of its own, as for all_reduce).
 template <int DT>
-int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count, int op, int P, int variant,
+int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count, int op, int P, int variant, int n_cu,
                              hipStream_t stream) {
   const float scale = 1.0f / static_cast<float>(P);
   const size_t b = count / static_cast<size_t>(P);
@@ -101,6 +108,23 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
     });
   }
   const size_t bvec = b / Elem<DT>::kPerVec;
+  if (variant == SV_PK8) {
+    if (op > MCR_AVG || !all_shapes(DT)) {
+      variant = SV_V4NT;                                  // the shape that stands in for the persistent one
+    } else {
+      const dim3 grid(persistent_grid(n_cu, P), P);
+      return dispatch_ranks(P, [&](auto pp) {
+        constexpr int kP = decltype(pp)::value;
+        if constexpr (all_shapes(DT)) {
+          hipLaunchKernelGGL((reduce_scatter_persist<DT, kP, kPersistU, kPersistK>), grid, dim3(kPersistBlock), 0, stream, out, in,
+                             bvec, scale, op);
+          return launch_status();
+        } else {
+          return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above
+        }
+      });
+    }
+  }
   const unsigned gx = grid_x(bvec, variant);
   return dispatch_ranks(P, [&](auto pp) {
     constexpr int kP = decltype(pp)::value;
@@ -112,9 +136,9 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
       });
     }
     if constexpr (all_shapes(DT)) {
-      return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
+      return dispatch_reduce_shape(variant, [&](auto uu, auto nt) {
         constexpr int U = decltype(uu)::value;
-        hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(ntl)::value, decltype(nts)::value, false>),
+        hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(nt)::value, decltype(nt)::value, false>),
                            dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, op);
         return launch_status();
       });

@@ -12,7 +12,8 @@ namespace mcr {
 // system serves better than a round-robin over the P buffers.
 // GENERIC = false is the sum (SUM / AVG), the hot path; GENERIC = true switches on the run-time
 // ReduceOp (MAX / MIN / PROD) and is compiled for fewer launch shapes.
-template <int DT, int P, int U, bool NTL, bool FULL, bool GENERIC>
+// BS = threads of the workgroup (the stride between a thread's U vectors).
+template <int DT, int P, int U, bool NTL, bool FULL, bool GENERIC, int BS = kBlock>
 __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off, size_t tile,
                                             size_t nvec, float scale, int op,
                                             u32x4 (&out)[U]) {
@@ -23,13 +24,13 @@ __device__ __forceinline__ void reduce_tile(const CPtrTab& in, size_t in_vec_off
   for (int p = 0; p < P; ++p) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+      const size_t idx = tile + static_cast<size_t>(u) * BS + threadIdx.x;
       if (FULL || idx < nvec) v[u][p] = load16<NTL>(in.p[p], in_vec_off + idx);
     }
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+    const size_t idx = tile + static_cast<size_t>(u) * BS + threadIdx.x;
     if (FULL || idx < nvec) {
       typename E::acc_t acc[W];
       E::widen(v[u][0], acc);
@@ -59,6 +60,77 @@ __device__ __forceinline__ typename Elem<DT>::acc_t reduce_scalar(const CPtrTab&
   return acc;
 }
 
+
+// ---- the persistent form ------------------------------------------------------------------------
+// One workgroup of kPersistBlock threads per compute unit, each walking a contiguous run of the
+// message in rounds: K steps of U vectors per thread are read from all P buffers and reduced into
+// registers, then the K*U results are stored in one go.  Every compute unit then streams long
+// contiguous runs and alternates between reading and writing them; for long messages this shape
+// is on a par with the one-shot grids of small workgroups and ahead of them for some sizes
+// (reduce_scatter of 32 MiB per rank at 8 ranks: 50 against 51-52 us); which one runs is the
+// tuning table's choice.
+// SLICED (reduce_scatter): blockIdx.y = destination rank, nvec = vectors per slice, the slice's
+// results go to dst.p[blockIdx.y] from vector 0 on.  Otherwise (all_reduce / reduce): nvec = whole
+// message, results go to vector idx of every dst.p[p] (of dst.p[root] when root >= 0).
+constexpr int kPersistBlock = 1024;
+
+template <int DT, int P, int U, int K, bool SLICED, bool GENERIC>
+__device__ __forceinline__ void reduce_persistent(const PtrTab& dst, const CPtrTab& in, size_t nvec, float scale, int op,
+                                                  int root) {
+  constexpr int BS = kPersistBlock;
+  constexpr size_t kStep = static_cast<size_t>(U) * BS;               // vectors per step of the workgroup
+  const unsigned slice = SLICED ? blockIdx.y : 0;
+  const size_t off = SLICED ? static_cast<size_t>(slice) * nvec : 0;
+  const size_t steps = (nvec + kStep - 1) / kStep;
+  const size_t per = (steps + gridDim.x - 1) / gridDim.x;             // steps per workgroup, contiguous
+  const size_t s_begin = static_cast<size_t>(blockIdx.x) * per;
+  const size_t s_end = (s_begin + per < steps) ? s_begin + per : steps;
+  for (size_t s0 = s_begin; s0 < s_end; s0 += K) {
+    u32x4 y[K][U];
+    const bool full = s0 + K <= s_end && (s0 + K) * kStep <= nvec;    // uniform over the workgroup
+    if (full) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) reduce_tile<DT, P, U, true, true, GENERIC, BS>(in, off, (s0 + k) * kStep, nvec, scale, op, y[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < K; ++k)
+        if (s0 + k < s_end) reduce_tile<DT, P, U, true, false, GENERIC, BS>(in, off, (s0 + k) * kStep, nvec, scale, op, y[k]);
+    }
+    if constexpr (SLICED) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const size_t idx = (s0 + k) * kStep + static_cast<size_t>(u) * BS + threadIdx.x;
+          if (full || (s0 + k < s_end && idx < nvec)) store16<true>(dst.p[slice], idx, y[k][u]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < P; ++p) {
+        if (root >= 0 && root != p) continue;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const size_t idx = (s0 + k) * kStep + static_cast<size_t>(u) * BS + threadIdx.x;
+            if (full || (s0 + k < s_end && idx < nvec)) store16<true>(dst.p[p], idx, y[k][u]);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Vectors per thread and step (U) and steps per round (K) of the persistent variant: the registers it
+// needs (4 * U * (P + K) for loads and results) fit, next to the addressing, in the 128 a thread of
+// a 1024-thread workgroup has, for every rank count.
+constexpr int kPersistU = 1;
+constexpr int kPersistK = 8;
+inline unsigned persistent_grid(int n_cu, int slices) {
+  int g = n_cu / slices;
+  return static_cast<unsigned>(g < 1 ? 1 : g);
+}
 
 // The launch shapes the generic-op kernels are compiled for: the variant's unroll, nontemporal
 // loads and stores.  f(Int<U>)

@@ -71,9 +71,13 @@ def _addr(x) -> int:
     return int(x.data_ptr())
 
 
-def _ptr_array(xs: Optional[Sequence[Ptr]]):
+def _ptr_array(xs: Optional[Sequence[Ptr]], need: int = 0):
+    """Host array of device addresses.  The library reads `need` entries (one per rank), so a
+    shorter list is refused here: it would make the library read past the array."""
     if xs is None:
         return None
+    if len(xs) < need:
+        raise ValueError(f"a list of {len(xs)} device pointers was given where the call reads {need}")
     return (ctypes.c_void_p * len(xs))(*[_addr(x) for x in xs])
 
 
@@ -122,42 +126,47 @@ def mcr_get_variants(ctx, op_id: int) -> List[str]:
 # ---- collectives ---------------------------------------------------------------------------
 def mcr_allreduce(ctx, bufs: Sequence[Ptr], count: int, dtype: int, op: int, P: int, variant: int = AUTO,
                   stream=None) -> None:
-    _check(lib().mcr_allreduce(ctx, _ptr_array(bufs), _sz(count), dtype, op, P, variant, _stream(stream)),
+    _check(lib().mcr_allreduce(ctx, _ptr_array(bufs, P), _sz(count), dtype, op, P, variant, _stream(stream)),
            "mcr_allreduce")
 
 
 def mcr_reduce_scatter(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, op: int, P: int,
                        variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_reduce_scatter(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, op, P, variant,
+    _check(lib().mcr_reduce_scatter(ctx, _ptr_array(out, P), _ptr_array(inp, P), _sz(count), dtype, op, P, variant,
                                     _stream(stream)), "mcr_reduce_scatter")
 
 
 def mcr_allgather(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, P: int,
                   variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_allgather(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, variant,
+    _check(lib().mcr_allgather(ctx, _ptr_array(out, P), _ptr_array(inp, P), _sz(count), dtype, P, variant,
                                _stream(stream)), "mcr_allgather")
 
 
 def mcr_alltoall(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: int, dtype: int, P: int,
                  variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_alltoall(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, variant,
+    _check(lib().mcr_alltoall(ctx, _ptr_array(out, P), _ptr_array(inp, P), _sz(count), dtype, P, variant,
                               _stream(stream)), "mcr_alltoall")
 
 
-def mcr_alltoallv(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], splits, splits_on_device: bool, in_rows: int,
+SPLITS_ON_DEVICE, SPLITS_TRANSPOSED = 1, 2
+
+
+def mcr_alltoallv(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], splits, splits_flags: int, in_rows: int,
                   out_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    """``splits``: None (equal split), a device tensor / address (splits_on_device=True), or a host
-    sequence of P*P integers, row-major."""
+    """``splits``: None (equal split), a device tensor / address (SPLITS_ON_DEVICE in splits_flags;
+    True and False still mean "on device" and "on the host"), or a host sequence of P*P integers,
+    row-major.  SPLITS_TRANSPOSED: the matrix is read transposed (the way back)."""
     keep = None
+    splits_flags = int(splits_flags)
     if splits is None:
         sp = ctypes.c_void_p(0)
-    elif splits_on_device:
+    elif splits_flags & SPLITS_ON_DEVICE:
         sp = ctypes.c_void_p(_addr(splits))
     else:
         flat = [int(v) for row in splits for v in (row if hasattr(row, "__len__") else [row])]
         keep = (ctypes.c_int64 * len(flat))(*flat)
         sp = ctypes.cast(keep, ctypes.c_void_p)
-    _check(lib().mcr_alltoallv(ctx, _ptr_array(out), _ptr_array(inp), sp, int(bool(splits_on_device)),
+    _check(lib().mcr_alltoallv(ctx, _ptr_array(out, P), _ptr_array(inp, P), sp, splits_flags,
                                _sz(in_rows), _sz(out_rows), _sz(row_elems), dtype, P, variant, _stream(stream)),
            "mcr_alltoallv")
 
@@ -169,45 +178,45 @@ def _counts(counts: Sequence[int]):
 
 def mcr_reduce(ctx, bufs: Sequence[Ptr], count: int, dtype: int, op: int, root: int, P: int, variant: int = AUTO,
                stream=None) -> None:
-    _check(lib().mcr_reduce(ctx, _ptr_array(bufs), _sz(count), dtype, op, root, P, variant, _stream(stream)), "mcr_reduce")
+    _check(lib().mcr_reduce(ctx, _ptr_array(bufs, P), _sz(count), dtype, op, root, P, variant, _stream(stream)), "mcr_reduce")
 
 
 def mcr_bcast(ctx, bufs: Sequence[Ptr], count: int, dtype: int, root: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_bcast(ctx, _ptr_array(bufs), _sz(count), dtype, root, P, variant, _stream(stream)), "mcr_bcast")
+    _check(lib().mcr_bcast(ctx, _ptr_array(bufs, P), _sz(count), dtype, root, P, variant, _stream(stream)), "mcr_bcast")
 
 
 def mcr_gather(ctx, out: Ptr, inp: Sequence[Ptr], count: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_gather(ctx, ctypes.c_void_p(_addr(out)), _ptr_array(inp), _sz(count), dtype, P, variant,
+    _check(lib().mcr_gather(ctx, ctypes.c_void_p(_addr(out)), _ptr_array(inp, P), _sz(count), dtype, P, variant,
                             _stream(stream)), "mcr_gather")
 
 
 def mcr_gatherv(ctx, out: Ptr, inp: Sequence[Ptr], counts: Sequence[int], dtype: int, P: int, variant: int = AUTO,
                 stream=None) -> None:
-    _check(lib().mcr_gatherv(ctx, ctypes.c_void_p(_addr(out)), _ptr_array(inp), _counts(counts), dtype, P, variant,
+    _check(lib().mcr_gatherv(ctx, ctypes.c_void_p(_addr(out)), _ptr_array(inp, P), _counts(counts), dtype, P, variant,
                              _stream(stream)), "mcr_gatherv")
 
 
 def mcr_scatter(ctx, out: Sequence[Ptr], inp: Ptr, count: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_scatter(ctx, _ptr_array(out), ctypes.c_void_p(_addr(inp)), _sz(count), dtype, P, variant,
+    _check(lib().mcr_scatter(ctx, _ptr_array(out, P), ctypes.c_void_p(_addr(inp)), _sz(count), dtype, P, variant,
                              _stream(stream)), "mcr_scatter")
 
 
 def mcr_scatterv(ctx, out: Sequence[Ptr], inp: Ptr, counts: Sequence[int], dtype: int, P: int, variant: int = AUTO,
                  stream=None) -> None:
-    _check(lib().mcr_scatterv(ctx, _ptr_array(out), ctypes.c_void_p(_addr(inp)), _counts(counts), dtype, P, variant,
+    _check(lib().mcr_scatterv(ctx, _ptr_array(out, P), ctypes.c_void_p(_addr(inp)), _counts(counts), dtype, P, variant,
                               _stream(stream)), "mcr_scatterv")
 
 
 def mcr_allgatherv(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], counts: Sequence[int], dtype: int, P: int,
                    variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_allgatherv(ctx, _ptr_array(out), _ptr_array(inp), _counts(counts), dtype, P, variant,
+    _check(lib().mcr_allgatherv(ctx, _ptr_array(out, P), _ptr_array(inp, P), _counts(counts), dtype, P, variant,
                                 _stream(stream)), "mcr_allgatherv")
 
 
 # ---- MoE -----------------------------------------------------------------------------------
 def mcr_moe_route(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
                   counts: Sequence[Ptr], splits: Ptr, stream=None) -> None:
-    _check(lib().mcr_moe_route(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
+    _check(lib().mcr_moe_route(ctx, _ptr_array(expert_ids, P), T, E, P, capacity, _ptr_array(slot, P), _ptr_array(counts, P),
                                ctypes.c_void_p(_addr(splits)), _stream(stream)), "mcr_moe_route")
 
 
@@ -220,25 +229,25 @@ def mcr_moe_route_workspace_bytes(T: int, E: int, P: int) -> int:
 def mcr_moe_route_ws(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
                      counts: Sequence[Ptr], splits: Ptr, workspace: Optional[Ptr], workspace_bytes: int, stream=None) -> None:
     ws = ctypes.c_void_p(_addr(workspace)) if workspace is not None else ctypes.c_void_p(0)
-    _check(lib().mcr_moe_route_ws(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
+    _check(lib().mcr_moe_route_ws(ctx, _ptr_array(expert_ids, P), T, E, P, capacity, _ptr_array(slot, P), _ptr_array(counts, P),
                                   ctypes.c_void_p(_addr(splits)), ws, _sz(workspace_bytes), _stream(stream)), "mcr_moe_route_ws")
 
 
 def mcr_moe_route_static(ctx, expert_ids: Sequence[Ptr], T: int, E: int, P: int, capacity: int, slot: Sequence[Ptr],
                          counts: Sequence[Ptr], splits: Ptr, stream=None) -> None:
-    _check(lib().mcr_moe_route_static(ctx, _ptr_array(expert_ids), T, E, P, capacity, _ptr_array(slot), _ptr_array(counts),
+    _check(lib().mcr_moe_route_static(ctx, _ptr_array(expert_ids, P), T, E, P, capacity, _ptr_array(slot, P), _ptr_array(counts, P),
                                       ctypes.c_void_p(_addr(splits)), _stream(stream)), "mcr_moe_route_static")
 
 
 def mcr_pack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr], T: int, out_rows: int, row_elems: int,
              dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_pack(ctx, _ptr_array(out), _ptr_array(inp), _ptr_array(slot), _sz(T), _sz(out_rows),
+    _check(lib().mcr_pack(ctx, _ptr_array(out, P), _ptr_array(inp, P), _ptr_array(slot, P), _sz(T), _sz(out_rows),
                           _sz(row_elems), dtype, P, variant, _stream(stream)), "mcr_pack")
 
 
 def mcr_unpack(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], slot: Sequence[Ptr], gate: Optional[Sequence[Ptr]], T: int,
                in_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_unpack(ctx, _ptr_array(out), _ptr_array(inp), _ptr_array(slot), _ptr_array(gate), _sz(T),
+    _check(lib().mcr_unpack(ctx, _ptr_array(out, P), _ptr_array(inp, P), _ptr_array(slot, P), _ptr_array(gate, P), _sz(T),
                             _sz(in_rows), _sz(row_elems), dtype, P, variant, _stream(stream)), "mcr_unpack")
 
 
@@ -250,33 +259,33 @@ def _i64_array(xs):
 def mcr_alltoallv_displs(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], counts, sdispls, rdispls, in_rows: int, out_rows: int,
                          row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
     """counts, sdispls, rdispls: P*P integers each, row-major ([p][r], [p][r], [r][p])."""
-    _check(lib().mcr_alltoallv_displs(ctx, _ptr_array(out), _ptr_array(inp), _i64_array(counts), _i64_array(sdispls),
+    _check(lib().mcr_alltoallv_displs(ctx, _ptr_array(out, P), _ptr_array(inp, P), _i64_array(counts), _i64_array(sdispls),
                                       _i64_array(rdispls), _sz(in_rows), _sz(out_rows), _sz(row_elems), dtype, P, variant,
                                       _stream(stream)), "mcr_alltoallv_displs")
 
 
 def mcr_gatherv_displs(ctx, out: Ptr, out_elems: int, inp: Sequence[Ptr], counts: Sequence[int], displs: Sequence[int],
                        dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_gatherv_displs(ctx, ctypes.c_void_p(_addr(out)), _sz(out_elems), _ptr_array(inp), _counts(counts),
+    _check(lib().mcr_gatherv_displs(ctx, ctypes.c_void_p(_addr(out)), _sz(out_elems), _ptr_array(inp, P), _counts(counts),
                                     _counts(displs), dtype, P, variant, _stream(stream)), "mcr_gatherv_displs")
 
 
 def mcr_scatterv_displs(ctx, out: Sequence[Ptr], inp: Ptr, in_elems: int, counts: Sequence[int], displs: Sequence[int],
                         dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_scatterv_displs(ctx, _ptr_array(out), ctypes.c_void_p(_addr(inp)), _sz(in_elems), _counts(counts),
+    _check(lib().mcr_scatterv_displs(ctx, _ptr_array(out, P), ctypes.c_void_p(_addr(inp)), _sz(in_elems), _counts(counts),
                                      _counts(displs), dtype, P, variant, _stream(stream)), "mcr_scatterv_displs")
 
 
 def mcr_allgatherv_displs(ctx, out: Sequence[Ptr], out_elems: int, inp: Sequence[Ptr], counts: Sequence[int],
                           displs: Sequence[int], dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_allgatherv_displs(ctx, _ptr_array(out), _sz(out_elems), _ptr_array(inp), _counts(counts),
+    _check(lib().mcr_allgatherv_displs(ctx, _ptr_array(out, P), _sz(out_elems), _ptr_array(inp, P), _counts(counts),
                                        _counts(displs), dtype, P, variant, _stream(stream)), "mcr_allgatherv_displs")
 
 
 # ---- fused pipelines -----------------------------------------------------------------------
 def mcr_moe_dispatch(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], slot: Sequence[Ptr], splits: Ptr, T: int,
                      recv_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_moe_dispatch(ctx, _ptr_array(recv), _ptr_array(tokens), _ptr_array(slot),
+    _check(lib().mcr_moe_dispatch(ctx, _ptr_array(recv, P), _ptr_array(tokens, P), _ptr_array(slot, P),
                                   ctypes.c_void_p(_addr(splits)), _sz(T), _sz(recv_rows), _sz(row_elems), dtype, P,
                                   variant, _stream(stream)), "mcr_moe_dispatch")
 
@@ -284,27 +293,27 @@ def mcr_moe_dispatch(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], slot: Sequ
 def mcr_moe_combine(ctx, out: Sequence[Ptr], expert_out: Sequence[Ptr], slot: Sequence[Ptr],
                     gate: Optional[Sequence[Ptr]], splits: Ptr, T: int, recv_rows: int, row_elems: int, dtype: int,
                     P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_moe_combine(ctx, _ptr_array(out), _ptr_array(expert_out), _ptr_array(slot), _ptr_array(gate),
+    _check(lib().mcr_moe_combine(ctx, _ptr_array(out, P), _ptr_array(expert_out, P), _ptr_array(slot, P), _ptr_array(gate, P),
                                  ctypes.c_void_p(_addr(splits)), _sz(T), _sz(recv_rows), _sz(row_elems), dtype, P,
                                  variant, _stream(stream)), "mcr_moe_combine")
 
 
 def mcr_moe_expert_layout(ctx, counts: Sequence[Ptr], E: int, P: int, row_table: Ptr, expert_first: Ptr, expert_rows: Ptr,
                           stream=None) -> None:
-    _check(lib().mcr_moe_expert_layout(ctx, _ptr_array(counts), E, P, ctypes.c_void_p(_addr(row_table)),
+    _check(lib().mcr_moe_expert_layout(ctx, _ptr_array(counts, P), E, P, ctypes.c_void_p(_addr(row_table)),
                                        ctypes.c_void_p(_addr(expert_first)), ctypes.c_void_p(_addr(expert_rows)),
                                        _stream(stream)), "mcr_moe_expert_layout")
 
 
 def mcr_moe_source_layout(ctx, counts: Sequence[Ptr], E: int, P: int, row_table: Ptr, stream=None) -> None:
-    _check(lib().mcr_moe_source_layout(ctx, _ptr_array(counts), E, P, ctypes.c_void_p(_addr(row_table)), _stream(stream)),
+    _check(lib().mcr_moe_source_layout(ctx, _ptr_array(counts, P), E, P, ctypes.c_void_p(_addr(row_table)), _stream(stream)),
            "mcr_moe_source_layout")
 
 
 def mcr_moe_dispatch_by_expert(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], expert_ids: Sequence[Ptr], slot: Sequence[Ptr],
                                row_table: Ptr, T: int, K: int, E: int, recv_rows: int, row_elems: int, dtype: int, P: int,
                                variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_moe_dispatch_by_expert(ctx, _ptr_array(recv), _ptr_array(tokens), _ptr_array(expert_ids), _ptr_array(slot),
+    _check(lib().mcr_moe_dispatch_by_expert(ctx, _ptr_array(recv, P), _ptr_array(tokens, P), _ptr_array(expert_ids, P), _ptr_array(slot, P),
                                             ctypes.c_void_p(_addr(row_table)), _sz(T), K, E, _sz(recv_rows), _sz(row_elems),
                                             dtype, P, variant, _stream(stream)), "mcr_moe_dispatch_by_expert")
 
@@ -312,24 +321,28 @@ def mcr_moe_dispatch_by_expert(ctx, recv: Sequence[Ptr], tokens: Sequence[Ptr], 
 def mcr_moe_combine_by_expert(ctx, out: Sequence[Ptr], expert_out: Sequence[Ptr], expert_ids: Sequence[Ptr],
                               slot: Sequence[Ptr], gate: Optional[Sequence[Ptr]], row_table: Ptr, T: int, K: int, E: int,
                               recv_rows: int, row_elems: int, dtype: int, P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_moe_combine_by_expert(ctx, _ptr_array(out), _ptr_array(expert_out), _ptr_array(expert_ids),
-                                           _ptr_array(slot), _ptr_array(gate), ctypes.c_void_p(_addr(row_table)), _sz(T), K, E,
+    _check(lib().mcr_moe_combine_by_expert(ctx, _ptr_array(out, P), _ptr_array(expert_out, P), _ptr_array(expert_ids, P),
+                                           _ptr_array(slot, P), _ptr_array(gate, P), ctypes.c_void_p(_addr(row_table)), _sz(T), K, E,
                                            _sz(recv_rows), _sz(row_elems), dtype, P, variant, _stream(stream)),
            "mcr_moe_combine_by_expert")
 
 
 def mcr_dlrm_shuffle(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], n_tables: int, batch: int, dim: int, dtype: int,
                      P: int, backward: bool = False, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_dlrm_shuffle(ctx, _ptr_array(out), _ptr_array(inp), n_tables, _sz(batch), _sz(dim), dtype, P,
+    _check(lib().mcr_dlrm_shuffle(ctx, _ptr_array(out, P), _ptr_array(inp, P), n_tables, _sz(batch), _sz(dim), dtype, P,
                                   int(bool(backward)), variant, _stream(stream)), "mcr_dlrm_shuffle")
 
 
 # ---- tensor fusion -------------------------------------------------------------------------
+_plan_tensors = {}          # plan handle -> its number of tensors (what mcr_fuse_plan_bind reads per rank)
+
+
 def mcr_fuse_plan_create(ctx, numel: Sequence[int], bucket_elems: int, dtype: int) -> ctypes.c_void_p:
     arr = (ctypes.c_size_t * max(len(numel), 1))(*[int(n) for n in numel])
     plan = ctypes.c_void_p()
     _check(lib().mcr_fuse_plan_create(ctx, arr, len(numel), _sz(bucket_elems), dtype, ctypes.byref(plan)),
            "mcr_fuse_plan_create")
+    _plan_tensors[plan.value] = len(numel)
     return plan
 
 
@@ -346,15 +359,16 @@ def mcr_fuse_plan_info(plan, n_tensors: int):
 
 def mcr_fuse_plan_bind(ctx, plan, tensors: Sequence[Ptr], P: int) -> None:
     """``tensors``: P*n_tensors entries, rank-major."""
-    _check(lib().mcr_fuse_plan_bind(ctx, plan, _ptr_array(tensors), P), "mcr_fuse_plan_bind")
+    n_tensors = _plan_tensors.get(getattr(plan, "value", plan), 0)
+    _check(lib().mcr_fuse_plan_bind(ctx, plan, _ptr_array(tensors, max(P, 0) * n_tensors), P), "mcr_fuse_plan_bind")
 
 
 def mcr_fuse(ctx, plan, bucket: int, flat: Sequence[Ptr], P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_fuse(ctx, plan, bucket, _ptr_array(flat), P, variant, _stream(stream)), "mcr_fuse")
+    _check(lib().mcr_fuse(ctx, plan, bucket, _ptr_array(flat, P), P, variant, _stream(stream)), "mcr_fuse")
 
 
 def mcr_unfuse(ctx, plan, bucket: int, flat: Sequence[Ptr], P: int, variant: int = AUTO, stream=None) -> None:
-    _check(lib().mcr_unfuse(ctx, plan, bucket, _ptr_array(flat), P, variant, _stream(stream)), "mcr_unfuse")
+    _check(lib().mcr_unfuse(ctx, plan, bucket, _ptr_array(flat, P), P, variant, _stream(stream)), "mcr_unfuse")
 
 
 def mcr_allreduce_multi(ctx, plan, bucket: int, op: int, variant: int = AUTO, stream=None) -> None:
@@ -362,6 +376,7 @@ def mcr_allreduce_multi(ctx, plan, bucket: int, op: int, variant: int = AUTO, st
 
 
 def mcr_fuse_plan_destroy(plan) -> None:
+    _plan_tensors.pop(getattr(plan, "value", plan), None)
     _check(lib().mcr_fuse_plan_destroy(plan), "mcr_fuse_plan_destroy")
 
 
@@ -371,7 +386,7 @@ def mcr_dispatch_overhead(ctx, out: Sequence[Ptr], inp: Sequence[Ptr], count: in
     """Microseconds per op: (through MCR_AUTO, as bare kernel launches, host cost per MCR_AUTO call,
     host cost per bare launch, CPU cost of the dispatch layer alone)."""
     a, d, ha, hd, do = (ctypes.c_double(0) for _ in range(5))
-    _check(lib().mcr_dispatch_overhead(ctx, _ptr_array(out), _ptr_array(inp), _sz(count), dtype, P, iters,
+    _check(lib().mcr_dispatch_overhead(ctx, _ptr_array(out, P), _ptr_array(inp, P), _sz(count), dtype, P, iters,
                                        _stream(stream), ctypes.byref(a), ctypes.byref(d), ctypes.byref(ha),
                                        ctypes.byref(hd), ctypes.byref(do)), "mcr_dispatch_overhead")
     return a.value, d.value, ha.value, hd.value, do.value

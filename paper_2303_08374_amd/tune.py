@@ -25,11 +25,30 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 DEFAULT_TABLE = os.path.join(HERE, "tuning", "mi355x.tbl")
 
 
-def tie_window(ms: float) -> float:
-    """Times within this factor of the least one count as a tie (the lowest variant id then wins):
-    2 % while a launch is short enough for its time to be mostly launch and ramp-up noise, 0.5 %
-    from 100 us on, where a batch mean repeats to a few tenths of a percent."""
-    return 1.02 if ms < 0.1 else 1.005
+def tie_window_us(floor_us: float) -> float:
+    """Times within this many microseconds of the least one count as a tie (the lowest variant id
+    then wins): 2 % of the least time while a launch is shorter than 100 us, 0.5 % from there on
+    (where a batch mean repeats to a few tenths of a percent), and never less than half a
+    microsecond, which is what two batches of the same launch-bound kernel differ by."""
+    return max(0.5, floor_us * (0.02 if floor_us < 100.0 else 0.005))
+
+
+def pick(times_us: dict):
+    """The table's choice among {variant: microseconds per launch}, the figures as they are
+    recorded (two decimals): least time, ties to the variant listed first (the lowest id)."""
+    floor = min(times_us.values())
+    for v, t in times_us.items():
+        if t <= floor + tie_window_us(floor):
+            return v
+
+
+def variants_of(ctx, op_id: int):
+    """The variants worth timing for an op: every 128-bit shape (the element path is only the
+    fallback); for the reductions not the "ln" / "sn" ids, which run the "nt" kernels."""
+    n_var = len(mcr.mcr_get_variants(ctx, op_id))
+    if op_id in (mcr.OP_ALLREDUCE, mcr.OP_REDUCE_SCATTER):
+        return [v for v in range(1, n_var) if not 7 <= v <= 12]
+    return list(range(1, n_var))
 
 
 def reps_for(alg_bytes: int) -> int:
@@ -82,9 +101,11 @@ def tune_workload_ops(ctx, verbose: bool = True):
                 times[op][v] = sum(stage_us(rep, st) for st in stages)
             torch.cuda.empty_cache()
         for op in ops:
-            floor = min(times[op].values())
-            best = min(v for v in variants if times[op][v] <= floor * tie_window(floor * 1e-3))
+            us = {v: round(times[op][v], 2) for v in variants}
+            best = pick(us)
             mcr.mcr_tune_set(ctx, op, dtype, P, nbytes, best)
+            report.setdefault("_rows", []).append((mcr.OP_NAMES[op], dtype, P, nbytes, names[best],
+                                                   {names[v]: t for v, t in us.items()}))
             report[f"{label}/{mcr.OP_NAMES[op]}"] = {"best": names[best], "us": {names[v]: round(t, 1) for v, t in times[op].items()}}
             if verbose:
                 print(f"{label}/{mcr.OP_NAMES[op]:18s} best={names[best]:6s} " +
@@ -92,7 +113,42 @@ def tune_workload_ops(ctx, verbose: bool = True):
     return report
 
 
-def run(out_path: str, report_path: str | None, scales, max_bytes: int, arena_gib: float, verbose: bool = True):
+_NAMES = {}
+
+
+def names_of(ctx, op_id: int):
+    if op_id not in _NAMES:
+        _NAMES[op_id] = mcr.mcr_get_variants(ctx, op_id)
+    return _NAMES[op_id]
+
+
+TIMES_HEADER = ("# every variant's time, in microseconds per launch, behind each row of the tuning table next to it\n"
+                "# (written by python -m paper_2303_08374_amd.tune --times-out): op dtype P bytes chosen | variant=us ...\n")
+
+
+def write_times(path: str, rows) -> None:
+    dt = {mcr.F32: "f32", mcr.BF16: "bf16", mcr.F16: "f16", mcr.I32: "i32"}
+    with open(path, "w") as f:
+        f.write(TIMES_HEADER)
+        for op, dtype, P, nbytes, best, us in rows:
+            f.write(f"{op} {dt[dtype]} {P} {nbytes} {best} | " + " ".join(f"{k}={v}" for k, v in us.items()) + "\n")
+
+
+def read_times(path: str):
+    """[(op, dtype name, P, bytes, chosen, {variant name: us})] of a file written by write_times."""
+    rows = []
+    with open(path) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            head, tail = line.split("|")
+            op, dt, P, nbytes, best = head.split()
+            rows.append((op, dt, int(P), int(nbytes), best, {k: float(v) for k, v in (kv.split("=") for kv in tail.split())}))
+    return rows
+
+
+def run(out_path: str, report_path: str | None, scales, max_bytes: int, arena_gib: float, verbose: bool = True,
+        times_path: str | None = None):
     """`scales`: the rank counts (world sizes) to tune the swept collectives for; the table is keyed by
     scale first, then by message size."""
     ctx = mcr.mcr_init(0)
@@ -103,8 +159,11 @@ def run(out_path: str, report_path: str | None, scales, max_bytes: int, arena_gi
     for P in scales:
         _tune_sweep(ctx, P, sizes, arena_gib, names, report, verbose)
     report["workload_ops"] = tune_workload_ops(ctx, verbose)
+    rows = report.pop("_rows", []) + report["workload_ops"].pop("_rows", [])
     os.makedirs(os.path.dirname(out_path) or ".", exist_ok=True)
     mcr.mcr_tune_save(ctx, out_path)
+    if times_path:
+        write_times(times_path, rows)
     if report_path:
         os.makedirs(os.path.dirname(report_path) or ".", exist_ok=True)
         with open(report_path, "w") as f:
@@ -120,19 +179,25 @@ def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbos
     arena = sweep.Arena(max(int(arena_gib * (1 << 30)), need + (1 << 20)))
     report = {"cells": {}}
     for cell in cells:
-        n_var = len(mcr.mcr_get_variants(ctx, sweep.OPS[cell.op]))
-        variants = list(range(1, n_var))             # the 128-bit variants; scalar is only the fallback
+        variants = variants_of(ctx, sweep.OPS[cell.op])
         reps = reps_for(cell.alg_bytes)
         times = {}
         for v in variants:
             cell.launch(ctx, arena.take(cell.footprint), v)              # first-launch effects out of the way
             ms = sweep.time_launches(lambda: cell.launch(ctx, arena.take(cell.footprint), v), reps)
+            if ms < 0.1:
+                # launch-bound: the least of three batches, which is what the kernel costs when nothing else interferes
+                for _ in range(2):
+                    ms = min(ms, sweep.time_launches(lambda: cell.launch(ctx, arena.take(cell.footprint), v), reps))
             times[v] = ms
         # least time wins; anything within the tie window of it counts as a tie and the lowest id
         # is taken, so that launch-bound sizes do not pick a variant by noise
-        floor = min(times.values())
-        best = min(v for v in variants if times[v] <= floor * tie_window(floor))
+        names = names_of(ctx, sweep.OPS[cell.op])
+        us = {v: round(times[v] * 1e3, 2) for v in variants}              # ascending ids
+        best = pick(us)
         mcr.mcr_tune_set(ctx, sweep.OPS[cell.op], sweep.DTYPES[cell.dtype], P, cell.M, best)
+        full_report.setdefault("_rows", []).append((cell.op, sweep.DTYPES[cell.dtype], P, cell.M, names[best],
+                                                    {names[v]: t for v, t in us.items()}))
         report["cells"][cell.key] = {
             "alg_bytes": cell.alg_bytes, "best": names[best],
             "us": {names[v]: round(times[v] * 1e3, 3) for v in variants},
@@ -144,7 +209,8 @@ def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbos
     # coarse (one variant per op and dtype) versus fine (one per size)
     coarse = {}
     for op in inputs.SWEEP_OPS:
-        variants = list(range(1, len(mcr.mcr_get_variants(ctx, sweep.OPS[op]))))
+        variants = variants_of(ctx, sweep.OPS[op])
+        names = names_of(ctx, sweep.OPS[op])
         for dt in inputs.SWEEP_DTYPES:
             keys = [c.key for c in cells if c.op == op and c.dtype == dt]
             tot = {v: sum(report["cells"][k]["us"][names[v]] for k in keys) for v in variants}
@@ -167,11 +233,12 @@ def main(argv=None) -> int:
     ap.add_argument("--ranks", default="4,8,16", help="rank counts to tune the swept collectives for")
     ap.add_argument("--max-bytes", type=int, default=inputs.SWEEP_BYTES[-1])
     ap.add_argument("--arena-gib", type=float, default=4.0)
+    ap.add_argument("--times-out", default=None, help="write every variant's time behind every table row here")
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("the tuning suite needs a GPU", file=sys.stderr)
         return 2
-    n, _ = run(a.out, a.report, [int(x) for x in a.ranks.split(",")], a.max_bytes, a.arena_gib)
+    n, _ = run(a.out, a.report, [int(x) for x in a.ranks.split(",")], a.max_bytes, a.arena_gib, times_path=a.times_out)
     print(f"wrote {n} rows to {a.out}")
     return 0
 

@@ -91,10 +91,10 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
         e[1].record()
         mcr.mcr_pack(ctx, d_packed, d_tok, d_slot, T, T, H, mcr.BF16, P, _v(variants, "pack"))
         e[2].record()
-        mcr.mcr_alltoallv(ctx, d_recv, d_packed, d_S, True, T, w.recv_rows, H, mcr.BF16, P, _v(variants, "alltoallv"))
-        d_ST = d_S.view(P, P).t().contiguous()
+        mcr.mcr_alltoallv(ctx, d_recv, d_packed, d_S, mcr.SPLITS_ON_DEVICE, T, w.recv_rows, H, mcr.BF16, P, _v(variants, "alltoallv"))
         e[3].record()
-        mcr.mcr_alltoallv(ctx, d_back, d_recv, d_ST, True, w.recv_rows, T, H, mcr.BF16, P, _v(variants, "alltoallv"))
+        mcr.mcr_alltoallv(ctx, d_back, d_recv, d_S, mcr.SPLITS_ON_DEVICE | mcr.SPLITS_TRANSPOSED, w.recv_rows, T, H, mcr.BF16, P,
+                          _v(variants, "alltoallv"))
         e[4].record()
         mcr.mcr_unpack(ctx, d_out, d_back, d_slot, d_gate, T, T, H, mcr.BF16, P, _v(variants, "unpack"))
         e[5].record()
@@ -443,47 +443,6 @@ def graph_replay(ctx, P: int = inputs.SWEEP_P, max_bytes: int = 1 << 20, reps: i
             "graph_us_per_launch": round(graph_ms * 1e3 / len(cells), 2), "speedup": round(eager_ms / graph_ms, 2)}
 
 
-def stream_pool(ctx, P: int = inputs.SWEEP_P, n_ops: int = 64, pool: int = 4, reps: int = 5) -> Dict:
-    """Independent all_reduce operations posted to one stream, and round-robin to a pool of streams
-    that fork from and join the caller's stream through events (the paper's non-blocking model,
-    Sec. IV-C, where overlapping operations on several streams pays for small messages only)."""
-    from . import sweep
-    main = torch.cuda.current_stream()
-    streams = [torch.cuda.Stream() for _ in range(pool)]          # default priority
-    out = {}
-    for M in (64 << 10, 1 << 20, 16 << 20):
-        count = M // 4
-        arena = sweep.Arena(n_ops * P * M + (1 << 20), seed=inputs.SWEEP_SEED + 5)
-        sets = [[arena.base + (k * P + p) * M for p in range(P)] for k in range(n_ops)]
-
-        def single():
-            for k in range(n_ops):
-                mcr.mcr_allreduce(ctx, sets[k], count, mcr.F32, mcr.SUM, P)
-
-        def pooled():
-            fork = torch.cuda.Event()
-            fork.record(main)
-            for s in streams:
-                s.wait_event(fork)
-            for k in range(n_ops):
-                mcr.mcr_allreduce(ctx, sets[k], count, mcr.F32, mcr.SUM, P, mcr.AUTO, streams[k % pool].cuda_stream)
-            for s in streams:
-                join = torch.cuda.Event()
-                join.record(s)
-                main.wait_event(join)
-        single(); pooled()
-        torch.cuda.synchronize()
-        t1 = sweep.time_launches(single, reps)
-        tp = sweep.time_launches(pooled, reps)
-        alg = 2 * P * M * n_ops
-        out[str(M)] = {"ops": n_ops, "pool": pool, "one_stream_us": round(t1 * 1e3, 1), "pool_us": round(tp * 1e3, 1),
-                       "one_stream_GBps": round(alg / (t1 * 1e-3) / 1e9, 1), "pool_GBps": round(alg / (tp * 1e-3) / 1e9, 1),
-                       "speedup": round(t1 / tp, 2)}
-        del arena
-        torch.cuda.empty_cache()
-    return out
-
-
 def run_all(ctx) -> Dict:
     out = {"allreduce_small": allreduce_small(ctx)}
     torch.cuda.empty_cache()
@@ -499,6 +458,5 @@ def run_all(ctx) -> Dict:
     torch.cuda.empty_cache()
     out["small_cells_graph_replay"] = graph_replay(ctx)
     torch.cuda.empty_cache()
-    out["stream_pool_allreduce"] = stream_pool(ctx)
     torch.cuda.empty_cache()
     return out

@@ -48,7 +48,7 @@ def test_strerror_and_variants(ctx):
         assert mcr.strerror(code) not in ("ok", "unknown status")
     for op in range(10):
         v = mcr.mcr_get_variants(ctx, op)
-        assert v[0] == "scalar" and len(v) == len(set(v)) == (16 if op == mcr.OP_ALLGATHER else 13)
+        assert v[0] == "scalar" and len(v) == len(set(v)) == {mcr.OP_ALLGATHER: 16, mcr.OP_ALLREDUCE: 14, mcr.OP_REDUCE_SCATTER: 14}.get(op, 13)
     assert mcr.mcr_get_variants(ctx, mcr.OP_MOE_ROUTE) == ["wave_ballot"]
     with pytest.raises(mcr.McrError) as e:
         mcr.mcr_get_variants(ctx, 99)
@@ -64,6 +64,27 @@ def _status(fn, *a, **k):
 
 
 A16 = [0x10000 * (i + 1) for i in range(16)]       # fake, 16-byte aligned device addresses (never dereferenced)
+
+
+def test_binding_refuses_pointer_lists_shorter_than_the_library_reads(ctx):
+    """The library reads P entries of every per-rank pointer array (P * n_tensors for a plan's
+    tensors); the binding refuses a shorter list instead of letting it read past the end."""
+    S = mcr
+    with pytest.raises(ValueError):
+        S.mcr_allreduce(ctx, A16[:3], 1024, S.F32, S.SUM, 4, S.AUTO, 0)
+    with pytest.raises(ValueError):
+        S.mcr_reduce_scatter(ctx, A16[:8], A16[:7], 1024, S.F32, S.SUM, 8, S.AUTO, 0)
+    with pytest.raises(ValueError):
+        S.mcr_alltoallv(ctx, A16[:2], A16[:1], None, 0, 8, 8, 4, S.F32, 2, S.AUTO, 0)
+    with pytest.raises(ValueError):
+        S.mcr_unpack(ctx, A16[:2], A16[:2], A16[:2], A16[:1], 8, 8, 4, S.F32, 2, S.AUTO, 0)
+    plan = S.mcr_fuse_plan_create(ctx, [10, 20, 30], 100, S.F32)
+    try:
+        with pytest.raises(ValueError):
+            S.mcr_fuse_plan_bind(ctx, plan, A16[:5], 2)               # 2 ranks x 3 tensors = 6 pointers
+        assert _status(S.mcr_fuse_plan_bind, ctx, plan, A16[:6], 2) == S.ESTATE
+    finally:
+        S.mcr_fuse_plan_destroy(plan)
 
 
 def test_static_scratch_routing_refuses_what_does_not_fit(ctx):
@@ -113,6 +134,12 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 0], [4, 0]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 3], [3, 5]], False, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESTATE
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], None, False, 7, 8, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL
+    # the matrix read transposed: rank 0 sends column 0 (9 rows of its 8: refused), receives row 0
+    T = S.SPLITS_TRANSPOSED
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 0], [4, 0]], T, 8, 9, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 0], [4, 0]], T, 9, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESTATE
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[5, 0], [4, 0]], 0, 9, 8, 4, S.F32, 2, S.AUTO, 0) == S.ESPLIT
+    assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[1, 1], [1, 1]], 4, 8, 8, 4, S.F32, 2, S.AUTO, 0) == S.EINVAL    # unknown flag bit
     assert _status(S.mcr_alltoallv, ctx, A16[:2], A16[2:4], [[1, 1], [1, 1]], False, 8, 8, 3, S.BF16, 2, 3, 0) == S.EVARIANT
     # rooted and vector collectives
     assert _status(S.mcr_reduce, ctx, A16[:4], 64, S.F32, S.SUM, 4, 4, S.AUTO, 0) == S.EINVAL                 # root out of range
@@ -149,7 +176,7 @@ def test_validation_errors(ctx):
     assert _status(S.mcr_allgatherv_displs, ctx, A16[:2], 27, A16[2:4], [8, 4], [20, 0], S.F32, 2, S.AUTO, 0) == S.ESPLIT
     assert _status(S.mcr_allgatherv_displs, ctx, A16[:2], 32, A16[2:4], [0, 0], [20, 0], S.F32, 2, S.AUTO, 0) == 0
     # MoE routing
-    assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 6, 4, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL      # P does not divide E
+    assert _status(S.mcr_moe_route, ctx, A16[:4], 64, 6, 4, 10, A16[4:8], A16[8:12], A16[12], 0) == S.EINVAL    # P does not divide E
     assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 1024, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL  # too many experts
     assert _status(S.mcr_moe_route, ctx, A16[:2], -1, 4, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.EINVAL
     assert _status(S.mcr_moe_route, ctx, A16[:2], 64, 4, 2, 10, A16[2:4], A16[4:6], A16[6], 0) == S.ESTATE

@@ -26,7 +26,7 @@ def test_allreduce_all_variants(dtype, P):
         for op in (mcr.SUM, mcr.AVG):
             exp = [h.copy() for h in host]
             oracle.allreduce(exp, dtype, op)
-            for variant in [mcr.AUTO] + gu.ALL_VARIANTS:
+            for variant in [mcr.AUTO] + gu.ALL_VARIANTS + gu.REDUCE_EXTRA:
                 dev = [gu.to_dev(h) for h in host]
                 mcr.mcr_allreduce(gu.ctx(), dev, count, dtype, op, P, variant)
                 gu.sync()
@@ -41,12 +41,41 @@ def test_allreduce_config1_full_size():
     host = w.buffers()
     exp = [h.copy() for h in host]
     oracle.allreduce(exp, oracle.F32, oracle.SUM)
-    for variant in [mcr.AUTO] + gu.ALL_VARIANTS:
+    for variant in [mcr.AUTO] + gu.ALL_VARIANTS + gu.REDUCE_EXTRA:
         dev = [gu.to_dev(h) for h in host]
         mcr.mcr_allreduce(gu.ctx(), dev, w.n, mcr.F32, mcr.SUM, w.P, variant)
         gu.sync()
         for r in range(w.P):
             gu.assert_bits_equal(gu.to_host(dev[r], np.float32), exp[r], f"cfg1 v={variant} r={r}")
+
+
+@pytest.mark.parametrize("dtype,P", [(mcr.F32, 3), (mcr.BF16, 8), (mcr.F32, 16)])
+def test_persistent_reductions_over_several_rounds(dtype, P):
+    """The persistent variants on a message long enough that every workgroup walks more than one
+    round and the last ones end in a ragged tail: all_reduce (AVG), reduce to a root, reduce_scatter."""
+    W = 4 if dtype == mcr.F32 else 8
+    round_vecs = 8 * 1024 * 256                                      # one round of every workgroup of a 256-unit grid
+    b = (round_vecs * W * 5 // 4) // P // W * W + W                  # per-rank slice of reduce_scatter: whole vectors
+    n = P * b
+    host = _make(P, n + 3, dtype, seed=300 + P, dist="uniform")     # all_reduce takes 3 more elements: a ragged end
+    exp_ar = [h.copy() for h in host]
+    oracle.allreduce(exp_ar, dtype, mcr.AVG)
+    exp_red = [h.copy() for h in host]
+    oracle.reduce(exp_red, dtype, mcr.SUM, 1)
+    exp_rs = oracle.reduce_scatter([h[:n] for h in host], dtype, mcr.SUM)
+    for variant in gu.REDUCE_EXTRA:
+        dev = [gu.to_dev(h) for h in host]
+        mcr.mcr_allreduce(gu.ctx(), dev, n + 3, dtype, mcr.AVG, P, variant)
+        d_red = [gu.to_dev(h) for h in host]
+        mcr.mcr_reduce(gu.ctx(), d_red, n + 3, dtype, mcr.SUM, 1, P, variant)
+        d_in = [gu.to_dev(h[:n]) for h in host]
+        d_rs = [gu.dev_empty(b, dtype, 0) for _ in range(P)]
+        mcr.mcr_reduce_scatter(gu.ctx(), d_rs, d_in, n, dtype, mcr.SUM, P, variant)
+        gu.sync()
+        for r in range(P):
+            gu.assert_reduced_equal(gu.to_host(dev[r], gu.NPDT[dtype]), exp_ar[r], dtype, f"persistent allreduce v={variant} r={r}")
+            gu.assert_reduced_equal(gu.to_host(d_red[r], gu.NPDT[dtype]), exp_red[r], dtype, f"persistent reduce v={variant} r={r}")
+            gu.assert_reduced_equal(gu.to_host(d_rs[r], gu.NPDT[dtype]), exp_rs[r], dtype, f"persistent reduce_scatter v={variant} r={r}")
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -182,7 +211,8 @@ def _variants_for(vec_ok, extra=()):
 def test_variant_lists_match_the_library():
     for op in range(10):
         names = mcr.mcr_get_variants(gu.ctx(), op)
-        want = len(gu.ALL_VARIANTS) + (len(gu.ALLGATHER_EXTRA) if op == mcr.OP_ALLGATHER else 0)
+        extra = {mcr.OP_ALLGATHER: gu.ALLGATHER_EXTRA, mcr.OP_ALLREDUCE: gu.REDUCE_EXTRA, mcr.OP_REDUCE_SCATTER: gu.REDUCE_EXTRA}
+        want = len(gu.ALL_VARIANTS) + len(extra.get(op, []))
         assert len(names) == want, (op, names)
 
 
@@ -195,7 +225,7 @@ def test_reduce_scatter(dtype, P):
         host = _make(P, n, dtype, seed=200 + P, dist="uniform")
         for op in (mcr.SUM, mcr.AVG):
             exp = oracle.reduce_scatter(host, dtype, op)
-            for variant in _variants_for(b % W == 0):
+            for variant in _variants_for(b % W == 0, gu.REDUCE_EXTRA):
                 dev_in = [gu.to_dev(h) for h in host]
                 dev_out = [gu.dev_empty(b, dtype, 0) for _ in range(P)]
                 mcr.mcr_reduce_scatter(gu.ctx(), dev_out, dev_in, n, dtype, op, P, variant)
@@ -285,6 +315,46 @@ def test_rs_then_ag_equals_allreduce_on_gpu():
 
 
 # -------------------------------------------------------------------- all_to_allv
+@pytest.mark.parametrize("dtype,w", [(mcr.F32, 1), (mcr.F32, 4), (mcr.BF16, 3), (mcr.BF16, 2048)])
+@pytest.mark.parametrize("P", [1, 3, 16])
+def test_alltoallv_transposed_matrix(dtype, w, P):
+    """MCR_SPLITS_TRANSPOSED: the way back.  Host and device matrices, every variant, against the
+    oracle's own loop nest for the way back; and forward then back through the library returns every
+    sent row to where it was."""
+    S = _splits(P, 40 if w < 1000 else 9, seed=P * 1000 + w)
+    in_rows = int(S.sum(axis=0).max()) + 3                            # a rank sends back what its column says it got
+    out_rows = int(S.sum(axis=1).max()) + 2
+    host = [inputs.uniform_pm1(in_rows * w, 600 + w, p, bf16=(dtype == mcr.BF16)) for p in range(P)]
+    sentinel = np.full(out_rows * w, 0x5A5A if dtype == mcr.BF16 else -123.0, dtype=gu.NPDT[dtype])
+    exp = [sentinel.copy() for _ in range(P)]
+    oracle.alltoallv(host, S, w, dtype, exp, transposed=True)
+    vec_ok = (w * gu.EB[dtype]) % 16 == 0
+    dS = torch.from_numpy(S).cuda()
+    for variant in _variants_for(vec_ok):
+        for flags in (mcr.SPLITS_TRANSPOSED, mcr.SPLITS_TRANSPOSED | mcr.SPLITS_ON_DEVICE):
+            dev_in = [gu.to_dev(h) for h in host]
+            dev_out = [gu.to_dev(sentinel) for _ in range(P)]
+            mcr.mcr_alltoallv(gu.ctx(), dev_out, dev_in, dS if flags & mcr.SPLITS_ON_DEVICE else S, flags, in_rows, out_rows, w,
+                              dtype, P, variant)
+            gu.sync()
+            for r in range(P):
+                gu.assert_bits_equal(gu.to_host(dev_out[r], gu.NPDT[dtype]), exp[r],
+                                     f"alltoallv transposed dt={dtype} w={w} P={P} v={variant} flags={flags} r={r}")
+    # there and back again on the device: rows [0, sum_r S[p][r]) of every rank come home
+    there = [gu.dev_empty(in_rows * w, dtype, 0) for _ in range(P)]
+    src = [inputs.uniform_pm1(out_rows * w, 700 + w, p, bf16=(dtype == mcr.BF16)) for p in range(P)]
+    home = [gu.dev_empty(out_rows * w, dtype, 0) for _ in range(P)]
+    mcr.mcr_alltoallv(gu.ctx(), there, [gu.to_dev(h) for h in src], dS, mcr.SPLITS_ON_DEVICE, out_rows, in_rows, w, dtype, P)
+    mcr.mcr_alltoallv(gu.ctx(), home, there, dS, mcr.SPLITS_ON_DEVICE | mcr.SPLITS_TRANSPOSED, in_rows, out_rows, w, dtype, P)
+    gu.sync()
+    for p in range(P):
+        sent = int(S[p].sum()) * w
+        gu.assert_bits_equal(gu.to_host(home[p], gu.NPDT[dtype])[:sent], src[p][:sent], f"there and back, rank {p}")
+    with pytest.raises(mcr.McrError) as e:
+        mcr.mcr_alltoallv(gu.ctx(), home, there, dS, 4, in_rows, out_rows, w, dtype, P)
+    assert e.value.status == mcr.EINVAL
+
+
 def _splits(P, max_rows, seed, zero_frac=0.2):
     g = np.random.Generator(np.random.Philox(key=seed))
     S = g.integers(0, max_rows + 1, size=(P, P), dtype=np.int64)
@@ -393,7 +463,7 @@ def test_max_min_prod(dtype, op):
         exp_rs = oracle.reduce_scatter(host, dtype, op)
         exp_red = [h.copy() for h in host]
         oracle.reduce(exp_red, dtype, op, 2)
-    for variant in (mcr.AUTO, 0, 2, 6):
+    for variant in (mcr.AUTO, 0, 2, 6, 13):
         dev = [gu.to_dev(h) for h in host]
         mcr.mcr_allreduce(gu.ctx(), dev, n, dtype, op, P, variant)
         d_in = [gu.to_dev(h) for h in host]

@@ -171,9 +171,8 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None, fused_
     c = gu.ctx()
     mcr.mcr_moe_route(c, d_ids, T, E, P, C, d_slot, d_cnt, d_S)
     mcr.mcr_pack(c, d_packed, d_tok, d_slot, T, send_rows, H, mcr.BF16, P)
-    mcr.mcr_alltoallv(c, d_recv, d_packed, d_S, True, send_rows, recv_rows, H, mcr.BF16, P)
-    d_ST = d_S.view(P, P).t().contiguous()            # a 2 KB device-side transpose by torch: plumbing
-    mcr.mcr_alltoallv(c, d_back, d_recv, d_ST, True, recv_rows, send_rows, H, mcr.BF16, P)
+    mcr.mcr_alltoallv(c, d_recv, d_packed, d_S, mcr.SPLITS_ON_DEVICE, send_rows, recv_rows, H, mcr.BF16, P)
+    mcr.mcr_alltoallv(c, d_back, d_recv, d_S, mcr.SPLITS_ON_DEVICE | mcr.SPLITS_TRANSPOSED, recv_rows, send_rows, H, mcr.BF16, P)
     mcr.mcr_unpack(c, d_out, d_back, d_slot, d_gate, T, send_rows, H, mcr.BF16, P)
     gu.sync()
     # oracle side
@@ -188,7 +187,7 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None, fused_
     recv = [np.zeros(recv_rows * H, dtype=np.uint16) for _ in range(P)]
     oracle.alltoallv(packed, S, H, oracle.BF16, recv)
     back = [np.zeros(send_rows * H, dtype=np.uint16) for _ in range(P)]
-    oracle.alltoallv(recv, S.T.copy(), H, oracle.BF16, back)
+    oracle.alltoallv(recv, S, H, oracle.BF16, back, transposed=True)
     # the fused forms: dispatch = pack + alltoallv, combine = alltoallv(S^T) + gate-weighted unpack
     f_recv = [gu.dev_empty(recv_rows * H, mcr.BF16, 0) for _ in range(P)]
     f_out = [gu.dev_empty(T * H, mcr.BF16, 1) for _ in range(P)]
