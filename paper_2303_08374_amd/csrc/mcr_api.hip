@@ -305,6 +305,10 @@ int mcr_init(mcr_ctx** out, int device) {
   if (device != MCR_NO_DEVICE) {
     int n_cu = 0;
     if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && n_cu > 0) ctx->n_cu = n_cu;
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->pair_ring), kPairRingSlots * sizeof(PairSlot)) != hipSuccess) {
+      delete ctx;
+      return MCR_EHIP;
+    }
   }
   const char* path = std::getenv("MCR_TUNING_TABLE");
   if (path && *path) (void)mcr_tune_load(ctx, path);   // an unreadable file leaves the table empty
@@ -314,6 +318,10 @@ int mcr_init(mcr_ctx** out, int device) {
 
 int mcr_finalize(mcr_ctx* ctx) {
   if (!ctx) return MCR_EINVAL;
+  if (ctx->pair_ring) {
+    DeviceScope on_device(ctx);
+    (void)hipFree(ctx->pair_ring);
+  }
   delete ctx;
   return MCR_OK;
 }

@@ -14,6 +14,14 @@ constexpr int kWave = 64;
 // and 16-byte units each thread keeps in flight.
 constexpr int kRowGatherBlock = 128;
 constexpr int kRowGatherVecs = 2;
+// The fused dispatch that finds a row's place from the split matrix, one row per workgroup.  Every
+// wavefront of a workgroup walks the whole lookup chain on the scalar unit, and with a chain as long
+// as this kernel's (and half of the workgroups carrying a dropped token and nothing else) that, not
+// the memory system, is what the rate hangs on: one wavefront per row runs it once per row
+// (187 against 220 us on the MoE workload).  The kernels with a short chain (pack, the table-driven
+// dispatch) are faster with a whole workgroup of 256 threads per row.
+constexpr int kPairScatterBlock = 64;
+constexpr int kPairScatterVecs = 4;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -23,6 +31,19 @@ struct PtrTab {
 };
 struct CPtrTab {
   const void* p[MCR_MAX_RANKS];
+};
+
+// Displacements of an all_to_allv with packed blocks, worked out once per call from a split matrix
+// in device memory for the kernels that place single rows (the fused MoE dispatch / combine).  For
+// sender p, with sd[r] = rows it packs before its block for receiver r and rd[r] = first row of its
+// block in receiver r's buffer:
+//   start[p][r] = min(sd[r], 2^31 - 1) for r < P, the largest int32 for P <= r < 16, and
+//   start[p][16] = min(all the rows p sends, 2^31 - 1): a slot is below 2^31 - 1, so the receiver of
+//                  a slot is found with 32-bit compares and no bound on r;
+//   delta[p][r] = rd[r] - sd[r]: slot s of sender p lands in row s + delta[p][r] of receiver r.
+struct PairSlot {
+  int32_t start[MCR_MAX_RANKS][32];
+  int64_t delta[MCR_MAX_RANKS][MCR_MAX_RANKS];
 };
 
 // 128-bit global access.  NT = nontemporal (streaming) hint.
@@ -48,6 +69,58 @@ __device__ __forceinline__ u32x4 load16_unaligned(const void* base, size_t byte_
 }
 __device__ __forceinline__ void store16_unaligned(void* base, size_t byte_offset, u32x4 v) {
   __builtin_memcpy(static_cast<char*>(base) + byte_offset, &v, 16);
+}
+
+// A row of a row kernel as `pieces` 16-byte pieces followed by a tail shorter than 16 bytes.  AL:
+// the row starts on a 16-byte boundary and has no tail (cache hints apply); otherwise the pieces
+// sit at element-aligned addresses, which the hardware serves as one access all the same, so a
+// row of 4104 bytes moves as fast as one of 4096.
+typedef u32x4 u32x4_elem_aligned __attribute__((aligned(2)));       // 16 bytes at an address aligned to the element only
+template <bool NT, bool AL>
+__device__ __forceinline__ u32x4 load_piece(const void* row, uint32_t c) {
+  if constexpr (AL) return load16<NT>(row, c);
+  const u32x4_elem_aligned* p = reinterpret_cast<const u32x4_elem_aligned*>(static_cast<const char*>(row) + static_cast<size_t>(c) * 16);
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT, bool AL>
+__device__ __forceinline__ void store_piece(void* row, uint32_t c, u32x4 v) {
+  if constexpr (AL) {
+    store16<NT>(row, c, v);
+  } else {
+    u32x4_elem_aligned* p = reinterpret_cast<u32x4_elem_aligned*>(static_cast<char*>(row) + static_cast<size_t>(c) * 16);
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+  }
+}
+// Pieces [0, n) of one row copied by the BS threads of a workgroup, V pieces of a thread in flight.
+template <int BS, int V, bool NTL, bool NTS, bool AL>
+__device__ __forceinline__ void copy_row_pieces(void* drow, const void* srow, uint32_t n) {
+  for (uint32_t c0 = threadIdx.x; c0 < n; c0 += V * BS) {
+    u32x4 v[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u)
+      if (c0 + u * BS < n) v[u] = load_piece<NTL, AL>(srow, c0 + u * BS);
+#pragma unroll
+    for (int u = 0; u < V; ++u)
+      if (c0 + u * BS < n) store_piece<NTS, AL>(drow, c0 + u * BS, v[u]);
+  }
+}
+
+// The tail of a row as 2-byte units (every element type is a multiple of 2 bytes wide): unit `i` of
+// the `tail2` units behind the `pieces` whole pieces.
+__device__ __forceinline__ void copy_tail2(void* drow, const void* srow, uint32_t pieces, uint32_t i) {
+  const size_t at = static_cast<size_t>(pieces) * 8 + i;
+  static_cast<uint16_t*>(drow)[at] = static_cast<const uint16_t*>(srow)[at];
+}
+// Element `i` of a row of EB-byte elements, copied bit for bit.
+template <int EB>
+__device__ __forceinline__ void copy_elem(void* drow, const void* srow, size_t i) {
+  if constexpr (EB == 4) static_cast<uint32_t*>(drow)[i] = static_cast<const uint32_t*>(srow)[i];
+  else static_cast<uint16_t*>(drow)[i] = static_cast<const uint16_t*>(srow)[i];
+}
+__device__ __forceinline__ void zero_tail2(void* drow, uint32_t pieces, uint32_t i) {
+  static_cast<uint16_t*>(drow)[static_cast<size_t>(pieces) * 8 + i] = 0;
 }
 
 // bf16 <-> binary32.  A bf16 is the upper half of a binary32 pattern.

@@ -620,12 +620,13 @@ __device__ __forceinline__ RowLookup lookup_row(const int64_t* table_p, int32_t 
 }
 
 // blockIdx.x = token t, blockIdx.y = sender.  K choices (KU >= K at compile time): the token's row
-// is read once and stored to the place of every kept choice.
-template <int UB, int KU, bool NTL, bool NTS>
+// is read once and stored to the place of every kept choice.  AL = false: rows of any width and
+// alignment, as 16-byte pieces at element-aligned addresses and `tail2` 2-byte units.
+template <int KU, bool NTL, bool NTS, bool AL>
 __global__ void __launch_bounds__(kBlock)
 moe_dispatch_row_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab slot_tab, const int64_t* row_table, int E,
-                        uint64_t rank_magic, size_t T, int K, uint64_t recv_rows, uint32_t upr) {
-  typedef typename RowUnit<UB>::type U;
+                        uint64_t rank_magic, size_t T, int K, uint64_t recv_rows, size_t row_bytes, uint32_t pieces,
+                        uint32_t tail2) {
   const int p = blockIdx.y;
   const size_t t = blockIdx.x;
   const int32_t* slot = static_cast<const int32_t*>(slot_tab.p[p]);
@@ -638,38 +639,70 @@ moe_dispatch_row_kernel(PtrTab recv, CPtrTab tok, CPtrTab ids_tab, CPtrTab slot_
     sl[k] = slot[a];
     e[k] = ids[a];
   }
-  U* drow[KU];
+  char* drow[KU];
   bool kept[KU];
   bool any = false;
 #pragma unroll
   for (int k = 0; k < KU; ++k) {
     const RowLookup d = lookup_row(table, sl[k], e[k], E, rank_magic, recv_rows);
     kept[k] = d.ok && k < K;
-    drow[k] = static_cast<U*>(recv.p[d.r]) + static_cast<uint64_t>(kept[k] ? d.row : 0) * upr;   // d.r < P whatever the id was
+    drow[k] = static_cast<char*>(recv.p[d.r]) + static_cast<uint64_t>(kept[k] ? d.row : 0) * row_bytes;   // d.r < P whatever the id was
     any = any || kept[k];
   }
   if (!any) return;
-  const U* srow = static_cast<const U*>(tok.p[p]) + t * upr;
-  for (uint32_t c = threadIdx.x; c < upr; c += kBlock) {
-    const U v = ldu<NTL, U>(srow + c);
+  const char* srow = static_cast<const char*>(tok.p[p]) + t * row_bytes;
+  constexpr int BS = kBlock, V = 1;
+  for (uint32_t c0 = threadIdx.x; c0 < pieces; c0 += V * BS) {
+    u32x4 v[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u)
+      if (c0 + u * BS < pieces) v[u] = load_piece<NTL, AL>(srow, c0 + u * BS);
+#pragma unroll
+    for (int k = 0; k < KU; ++k) {
+      if (!kept[k]) continue;
+#pragma unroll
+      for (int u = 0; u < V; ++u)
+        if (c0 + u * BS < pieces) store_piece<NTS, AL>(drow[k], c0 + u * BS, v[u]);
+    }
+  }
+  if (!AL && threadIdx.x < tail2) {
 #pragma unroll
     for (int k = 0; k < KU; ++k)
-      if (kept[k]) stu<NTS, U>(drow[k] + c, v);
+      if (kept[k]) copy_tail2(drow[k], srow, pieces, threadIdx.x);
   }
+}
+
+// The weighted sum of the kept choices' values, in choice order, starting from the first kept
+// product; `started` tells whether anything was kept.
+template <int KU, int N>
+__device__ __forceinline__ bool weighted_sum(const float (&f)[KU][N], const float (&g)[KU], const bool (&kept)[KU], float (&acc)[N]) {
+  bool started = false;
+#pragma unroll
+  for (int k = 0; k < KU; ++k) {
+    if (!kept[k]) continue;
+#pragma unroll
+    for (int x = 0; x < N; ++x) {
+      const float term = g[k] * f[k][x];
+      acc[x] = started ? acc[x] + term : term;
+    }
+    started = true;
+  }
+  return started;
 }
 
 // blockIdx.x = token t.  K choices (KU >= K at compile time).  A gather with a chain of lookups in
 // front of it is bound by how many rows a compute unit has in flight, so the workgroup is half the
 // usual size (kRowGatherBlock threads, twice as many rows per compute unit) and every thread keeps
 // the loads of kRowGatherVecs units of each kept row in flight (6.1 against 5.4 TB/s in a plain
-// gather of 4 KiB rows behind a two-level lookup).
-template <int DT, int UB, int KU, bool NTL, bool NTS, bool GATE>
+// gather of 4 KiB rows behind a two-level lookup).  AL = false: rows of any width and alignment
+// (16-byte pieces at element-aligned addresses, then `tail` single elements).
+template <int DT, int KU, bool NTL, bool NTS, bool GATE, bool AL>
 __global__ void __launch_bounds__(kRowGatherBlock)
 moe_combine_row_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab slot_tab, CPtrTab gate_tab,
                        const int64_t* row_table, int E, uint64_t rank_magic, size_t T, int K, uint64_t recv_rows,
-                       uint32_t upr) {
-  typedef typename RowUnit<UB>::type U;
-  typedef UnitF32<DT, UB> F;
+                       size_t row_bytes, uint32_t upr, uint32_t tail) {
+  using EL = Elem<DT>;
+  constexpr int N = EL::kPerVec;
   constexpr int V = kRowGatherVecs;
   const int p = blockIdx.y;
   const size_t t = blockIdx.x;
@@ -677,7 +710,7 @@ moe_combine_row_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab 
   const int32_t* ids = static_cast<const int32_t*>(ids_tab.p[p]);
   const float* gate = static_cast<const float*>(gate_tab.p[p]);
   const int64_t* table = row_table + static_cast<size_t>(p) * E;
-  U* drow = static_cast<U*>(out.p[p]) + t * upr;
+  char* drow = static_cast<char*>(out.p[p]) + t * row_bytes;
   int32_t sl[KU], e[KU];
   float g[KU];
 #pragma unroll
@@ -688,29 +721,32 @@ moe_combine_row_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab 
     g[k] = 1.0f;
     if constexpr (GATE) g[k] = gate[a];
   }
-  const U* srow[KU];
+  const char* srow[KU];
   bool kept[KU];
   bool any = false;
 #pragma unroll
   for (int k = 0; k < KU; ++k) {
     const RowLookup d = lookup_row(table, sl[k], e[k], E, rank_magic, recv_rows);
     kept[k] = d.ok && k < K;
-    srow[k] = static_cast<const U*>(expert_out.p[d.r]) + static_cast<uint64_t>(kept[k] ? d.row : 0) * upr;
+    srow[k] = static_cast<const char*>(expert_out.p[d.r]) + static_cast<uint64_t>(kept[k] ? d.row : 0) * row_bytes;
     any = any || kept[k];
   }
+  const size_t first_tail = static_cast<size_t>(upr) * N;
   if (!any) {
-    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) stu<NTS, U>(drow + c, U{});
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) store_piece<NTS, AL>(drow, c, z);
+    if (!AL && threadIdx.x < tail) EL::store1(drow, first_tail + threadIdx.x, typename EL::acc_t(0));
     return;
   }
   for (uint32_t c0 = threadIdx.x; c0 < upr; c0 += V * kRowGatherBlock) {
-    U v[V][KU];
+    u32x4 v[V][KU];
 #pragma unroll
     for (int u = 0; u < V; ++u) {
       const uint32_t c = c0 + u * kRowGatherBlock;
 #pragma unroll
       for (int k = 0; k < KU; ++k) {
-        v[u][k] = U{};
-        if (kept[k] && c < upr) v[u][k] = ldu<NTL, U>(srow[k] + c);
+        v[u][k] = u32x4{0u, 0u, 0u, 0u};
+        if (kept[k] && c < upr) v[u][k] = load_piece<NTL, AL>(srow[k], c);
       }
     }
 #pragma unroll
@@ -718,25 +754,135 @@ moe_combine_row_kernel(PtrTab out, CPtrTab expert_out, CPtrTab ids_tab, CPtrTab 
       const uint32_t c = c0 + u * kRowGatherBlock;
       if (c >= upr) continue;
       if constexpr (KU == 1 && !GATE) {                 // one choice and no weight: the row is copied bit for bit
-        stu<NTS, U>(drow + c, v[u][0]);
+        store_piece<NTS, AL>(drow, c, v[u][0]);
       } else {
-        float acc[F::kN];
-        bool started = false;
+        float f[KU][N], acc[N];
 #pragma unroll
-        for (int k = 0; k < KU; ++k) {
-          if (!kept[k]) continue;
-          float f[F::kN];
-          F::widen(v[u][k], f);
-#pragma unroll
-          for (int x = 0; x < F::kN; ++x) {
-            const float term = g[k] * f[x];
-            acc[x] = started ? acc[x] + term : term;
-          }
-          started = true;
-        }
-        stu<NTS, U>(drow + c, F::narrow(acc));
+        for (int k = 0; k < KU; ++k) EL::widen(v[u][k], f[k]);
+        weighted_sum<KU, N>(f, g, kept, acc);           // something was kept: `any`
+        store_piece<NTS, AL>(drow, c, EL::narrow(acc));
       }
     }
+  }
+  if (!AL && threadIdx.x < tail) {
+    const size_t i = first_tail + threadIdx.x;
+    if constexpr (KU == 1 && !GATE) {
+      copy_elem<EL::kBytes>(drow, srow[0], i);
+    } else {
+      float f[KU][1], acc[1];
+#pragma unroll
+      for (int k = 0; k < KU; ++k) f[k][0] = kept[k] ? EL::load1(srow[k], i) : 0.0f;
+      weighted_sum<KU, 1>(f, g, kept, acc);
+      EL::store1(drow, i, acc[0]);
+    }
+  }
+}
+
+// ---- the source-major fused pair on wide rows: one row per workgroup -------------------------
+// mcr_moe_dispatch / mcr_moe_combine know a token's place only through its slot and the split
+// matrix.  A first launch of one workgroup turns the matrix into the displacement tables of a
+// PairSlot; the row kernels then find the receiver of a slot among the (at most 16) block starts of
+// their sender and the row from one more entry, all through scalar loads of that table: the same
+// three dependent steps (slot, table entry, row) as the table-driven kernels above.
+__global__ void __launch_bounds__(kBlock)
+moe_pair_tables_kernel(const int64_t* S, int P, int64_t cap, PairSlot* out) {
+  __shared__ int64_t s[MCR_MAX_RANKS][MCR_MAX_RANKS];
+  const int p = threadIdx.x / MCR_MAX_RANKS, r = threadIdx.x % MCR_MAX_RANKS;       // 256 threads: one per (p, r)
+  s[p][r] = (p < P && r < P) ? clamp_rows(S[p * P + r], cap) : 0;                    // one load per thread, all in flight
+  __syncthreads();
+  constexpr int64_t kTop = 0x7fffffff;
+  int64_t sd = 0, rd = 0;
+  for (int q = 0; q < r; ++q) sd += s[p][q];
+  for (int q = 0; q < p; ++q) rd += s[q][r];
+  const bool live = p < P && r < P;
+  out->start[p][r] = live ? static_cast<int32_t>(sd < kTop ? sd : kTop) : static_cast<int32_t>(kTop);
+  out->delta[p][r] = live ? rd - sd : 0;
+  if (r == MCR_MAX_RANKS - 1) {
+    const int64_t all = sd + s[p][r];                                                // rows beyond P count 0
+    out->start[p][MCR_MAX_RANKS] = p < P ? static_cast<int32_t>(all < kTop ? all : kTop) : 0;
+  }
+}
+
+// Receiver and row of packed row `s` of sender p: the receiver is the number of block starts at or
+// below s (the starts are non-decreasing; empty blocks share a start and the last of them, the one
+// that holds the row, wins).  Lane q of the wavefront holds start q (lane 16 the total), one load
+// for all of them, and a ballot counts; half of the workgroups of a dispatch carry a dropped token
+// and do nothing but this, so it is kept to a handful of instructions and has no branch in it.
+struct PairDest {
+  int r;
+  int64_t row;
+  bool ok;
+};
+__device__ __forceinline__ PairDest pair_dest(const PairSlot* tab, int p, int32_t s, int64_t send_rows, uint64_t recv_rows) {
+  const unsigned lane = __lane_id();
+  const int32_t mine_start = tab->start[p][lane & 31u];                  // entries 17..31 of a row are never looked at
+  const uint64_t at_or_below = __ballot(mine_start <= s);
+  const int r = __popcll(at_or_below & 0xfffeull);                       // starts 1..15
+  const bool in_range = ((at_or_below >> MCR_MAX_RANKS) & 1ull) == 0;    // s < all the rows p sends
+  PairDest d;
+  const bool mine = s >= 0 && in_range && s < send_rows;
+  d.r = mine ? r : 0;
+  d.row = s + tab->delta[p][d.r];
+  d.ok = mine && d.row >= 0 && static_cast<uint64_t>(d.row) < recv_rows;
+  return d;
+}
+
+template <bool NTL, bool NTS, bool AL>
+__global__ void __launch_bounds__(kPairScatterBlock)
+moe_dispatch_pairs_row_kernel(PtrTab recv, CPtrTab tok, CPtrTab slot_tab, const PairSlot* tab, size_t T,
+                              uint64_t recv_rows, size_t row_bytes, uint32_t pieces, uint32_t tail2) {
+  const int p = blockIdx.y;
+  const size_t t = blockIdx.x;
+  const int32_t s = static_cast<const int32_t*>(slot_tab.p[p])[t];
+  const PairDest d = pair_dest(tab, p, s, static_cast<int64_t>(T), recv_rows);
+  const char* srow = static_cast<const char*>(tok.p[p]) + t * row_bytes;
+  char* drow = static_cast<char*>(recv.p[d.r]) + static_cast<uint64_t>(d.ok ? d.row : 0) * row_bytes;
+  // a row that goes nowhere has no pieces: the loop bounds are the only branches
+  const uint32_t n = d.ok ? pieces : 0, n_tail = d.ok ? tail2 : 0;
+  copy_row_pieces<kPairScatterBlock, kPairScatterVecs, NTL, NTS, AL>(drow, srow, n);
+  if (!AL && threadIdx.x < n_tail) copy_tail2(drow, srow, pieces, threadIdx.x);
+}
+
+template <int DT, bool NTL, bool NTS, bool GATE, bool AL>
+__global__ void __launch_bounds__(kRowGatherBlock)
+moe_combine_pairs_row_kernel(PtrTab out, CPtrTab expert_out, CPtrTab slot_tab, CPtrTab gate_tab, const PairSlot* tab,
+                             size_t T, uint64_t recv_rows, size_t row_bytes, uint32_t upr, uint32_t tail) {
+  using EL = Elem<DT>;
+  constexpr int V = kRowGatherVecs;
+  const int p = blockIdx.y;
+  const size_t t = blockIdx.x;
+  const int32_t s = static_cast<const int32_t*>(slot_tab.p[p])[t];
+  float g = 1.0f;
+  if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[p])[t];
+  const PairDest d = pair_dest(tab, p, s, static_cast<int64_t>(T), recv_rows);
+  char* drow = static_cast<char*>(out.p[p]) + t * row_bytes;
+  const char* srow = static_cast<const char*>(expert_out.p[d.r]) + static_cast<uint64_t>(d.ok ? d.row : 0) * row_bytes;
+  const size_t first_tail = static_cast<size_t>(upr) * EL::kPerVec;
+  if (!d.ok) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) store_piece<NTS, AL>(drow, c, z);
+    if (!AL && threadIdx.x < tail) EL::store1(drow, first_tail + threadIdx.x, typename EL::acc_t(0));
+    return;
+  }
+  for (uint32_t c0 = threadIdx.x; c0 < upr; c0 += V * kRowGatherBlock) {
+    u32x4 v[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const uint32_t c = c0 + u * kRowGatherBlock;
+      if (c < upr) v[u] = load_piece<NTL, AL>(srow, c);
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const uint32_t c = c0 + u * kRowGatherBlock;
+      if (c >= upr) continue;
+      if constexpr (GATE) v[u] = scale_unit<DT, 16, u32x4>(v[u], g);
+      store_piece<NTS, AL>(drow, c, v[u]);
+    }
+  }
+  if (!AL && threadIdx.x < tail) {
+    const size_t i = first_tail + threadIdx.x;
+    if constexpr (GATE) EL::store1(drow, i, g * EL::load1(srow, i));
+    else copy_elem<EL::kBytes>(drow, srow, i);
   }
 }
 
@@ -796,9 +942,34 @@ inline unsigned blocks_for(size_t rows, size_t rows_per_block) {
 
 }  // namespace
 
-int launch_moe_dispatch(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& slot, const int64_t* splits,
+// The next slot of the context's ring, filled with the displacement tables of `splits` by a launch
+// on `stream` (the row kernels that follow on the same stream read it).
+static int stage_pair_tables(mcr_ctx* ctx, const int64_t* splits, int P, size_t T, hipStream_t stream, const PairSlot** out) {
+  PairSlot* slot = ctx->pair_ring + ctx->pair_next.fetch_add(1u) % kPairRingSlots;
+  hipLaunchKernelGGL(moe_pair_tables_kernel, dim3(1), dim3(kBlock), 0, stream, splits, P, static_cast<int64_t>(T), slot);
+  *out = slot;
+  return launch_status();
+}
+
+int launch_moe_dispatch(mcr_ctx* ctx, const PtrTab& recv, const CPtrTab& tok, const CPtrTab& slot, const int64_t* splits,
                         size_t T, size_t recv_rows, size_t row_bytes, int elem_b, int P, int variant, hipStream_t stream) {
   if (T == 0 || row_bytes == 0) return MCR_OK;
+  if (row_bytes / 16 > kBlock / 2) {
+    // wide rows: one row per workgroup behind a launch that works the displacements out (187 against
+    // 232 us on the MoE workload); the element path takes 16-byte pieces at element-aligned addresses
+    const PairSlot* tab;
+    const int rc = stage_pair_tables(ctx, splits, P, T, stream, &tab);
+    if (rc != MCR_OK) return rc;
+    auto one_row = [&](auto ntl, auto nts, auto al) {
+      hipLaunchKernelGGL((moe_dispatch_pairs_row_kernel<decltype(ntl)::value, decltype(nts)::value, decltype(al)::value>),
+                         dim3(static_cast<unsigned>(T), P), dim3(kPairScatterBlock), 0, stream, recv, tok, slot, tab, T,
+                         static_cast<uint64_t>(recv_rows), row_bytes, static_cast<uint32_t>(row_bytes / 16),
+                         static_cast<uint32_t>((row_bytes % 16) / 2));
+      return launch_status();
+    };
+    if (variant == SV_SCALAR) return one_row(Bool<true>{}, Bool<true>{}, Bool<false>{});   // nontemporal, as tuned for aligned rows
+    return dispatch_hint(variant, [&](auto ntl, auto nts) { return one_row(ntl, nts, Bool<true>{}); });
+  }
   auto go = [&](auto ub, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     const RowShape s = row_shape(row_bytes / UB);
@@ -815,7 +986,7 @@ int launch_moe_dispatch(mcr_ctx*, const PtrTab& recv, const CPtrTab& tok, const 
   return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(Int<16>{}, ntl, nts); });
 }
 
-int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& slot, const CPtrTab* gate,
+int launch_moe_combine(mcr_ctx* ctx, const PtrTab& out, const CPtrTab& expert_out, const CPtrTab& slot, const CPtrTab* gate,
                        const int64_t* splits, size_t T, size_t recv_rows, size_t row_elems, int dtype, int P, int variant,
                        hipStream_t stream) {
   if (T == 0 || row_elems == 0) return MCR_OK;
@@ -827,6 +998,26 @@ int launch_moe_combine(mcr_ctx*, const PtrTab& out, const CPtrTab& expert_out, c
   return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
+    const size_t row_bytes = row_elems * EB;
+    if (row_bytes / 16 > kBlock / 2) {                  // wide rows: one row per workgroup (see launch_moe_dispatch)
+      const PairSlot* tab;
+      const int rc = stage_pair_tables(ctx, splits, P, T, stream, &tab);
+      if (rc != MCR_OK) return rc;
+      auto one_row = [&](auto ntl, auto nts, auto al) {
+        auto launch = [&](auto gc) {
+          hipLaunchKernelGGL((moe_combine_pairs_row_kernel<DT, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value,
+                                                           decltype(al)::value>),
+                             dim3(static_cast<unsigned>(T), P), dim3(kRowGatherBlock), 0, stream, out, expert_out, slot, g, tab, T,
+                             static_cast<uint64_t>(recv_rows), row_bytes, static_cast<uint32_t>(row_bytes / 16),
+                             static_cast<uint32_t>((row_bytes % 16) / EB));
+        };
+        if (gate) launch(Bool<true>{});
+        else launch(Bool<false>{});
+        return launch_status();
+      };
+      if (variant == SV_SCALAR) return one_row(Bool<true>{}, Bool<true>{}, Bool<false>{});   // nontemporal, as tuned for aligned rows
+      return dispatch_hint(variant, [&](auto ntl, auto nts) { return one_row(ntl, nts, Bool<true>{}); });
+    }
     auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
       constexpr int UB = decltype(ub)::value;
       const RowShape s = row_shape(row_elems * EB / UB);
@@ -866,22 +1057,27 @@ int launch_moe_dispatch_by_expert(mcr_ctx*, const PtrTab& recv, const CPtrTab& t
                                   int elem_b, int P, int variant, hipStream_t stream) {
   if (T == 0 || row_bytes == 0) return MCR_OK;
   const size_t A = T * static_cast<size_t>(K);
+  // one row per workgroup (193 against 212 us on the MoE workload); with several choices per
+  // token the workgroup reads the token's row once and stores it to every kept choice's place.
+  // al = false: the element path on wide rows, 16-byte pieces at element-aligned addresses and a tail
+  auto one_row = [&](auto ntl, auto nts, auto al) {
+    auto launch = [&](auto ku) {
+      hipLaunchKernelGGL((moe_dispatch_row_kernel<decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value, decltype(al)::value>),
+                         dim3(static_cast<unsigned>(T), P), dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E,
+                         rank_magic(E, P), T, K, static_cast<uint64_t>(recv_rows), row_bytes, static_cast<uint32_t>(row_bytes / 16),
+                         static_cast<uint32_t>((row_bytes % 16) / 2));
+    };
+    if (K == 1) launch(Int<1>{});
+    else if (K == 2) launch(Int<2>{});
+    else launch(Int<MCR_MAX_TOPK>{});
+    return launch_status();
+  };
+  const bool wide = row_bytes / 16 > kBlock / 2;
+  if (variant == SV_SCALAR && wide) return one_row(Bool<true>{}, Bool<true>{}, Bool<false>{});   // nontemporal, as tuned for aligned rows
   auto go = [&](auto ub, auto ntl, auto nts) {
     constexpr int UB = decltype(ub)::value;
     const RowShape s = row_shape(row_bytes / UB);
-    // one row per workgroup (193 against 212 us on the MoE workload); with several choices per
-    // token the workgroup reads the token's row once and stores it to every kept choice's place
-    if (UB == 16 && s.tpr == kBlock) {
-      auto launch = [&](auto ku) {
-        hipLaunchKernelGGL((moe_dispatch_row_kernel<16, decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value>),
-                           dim3(static_cast<unsigned>(T), P), dim3(kBlock), 0, stream, recv, tok, ids, slot, row_table, E,
-                           rank_magic(E, P), T, K, static_cast<uint64_t>(recv_rows), s.upr);
-      };
-      if (K == 1) launch(Int<1>{});
-      else if (K == 2) launch(Int<2>{});
-      else launch(Int<MCR_MAX_TOPK>{});
-      return launch_status();
-    }
+    if (UB == 16 && s.tpr == kBlock) return one_row(ntl, nts, Bool<true>{});
     const unsigned gx = blocks_for(A, static_cast<size_t>(kRowsPerBlock) * s.rows_per_pass);
     if (s.tpr >= kWave)
       hipLaunchKernelGGL((moe_dispatch_by_expert_kernel<UB, decltype(ntl)::value, decltype(nts)::value, true>), dim3(gx, P),
@@ -914,14 +1110,16 @@ int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& exp
   return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
-    if (variant != SV_SCALAR && row_shape(row_elems * EB / 16).tpr == kBlock) {     // one row per workgroup
-      const uint32_t upr = static_cast<uint32_t>(row_elems * EB / 16);
-      return dispatch_hint(variant, [&](auto ntl, auto nts) {
+    const size_t row_bytes = row_elems * EB;
+    if (row_bytes / 16 > kBlock / 2) {     // one row per workgroup; on the element path with pieces at element-aligned addresses
+      const uint32_t upr = static_cast<uint32_t>(row_bytes / 16);
+      auto one_row = [&](auto ntl, auto nts, auto al) {
         auto launch = [&](auto ku, auto gc) {
-          hipLaunchKernelGGL((moe_combine_row_kernel<DT, 16, decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value,
-                                                     decltype(gc)::value>),
+          hipLaunchKernelGGL((moe_combine_row_kernel<DT, decltype(ku)::value, decltype(ntl)::value, decltype(nts)::value,
+                                                     decltype(gc)::value, decltype(al)::value>),
                              dim3(static_cast<unsigned>(T), P), dim3(kRowGatherBlock), 0, stream, out, expert_out, ids, slot, g,
-                             row_table, E, rank_magic(E, P), T, K, static_cast<uint64_t>(recv_rows), upr);
+                             row_table, E, rank_magic(E, P), T, K, static_cast<uint64_t>(recv_rows), row_bytes, upr,
+                             static_cast<uint32_t>((row_bytes % 16) / EB));
         };
         auto by_k = [&](auto gc) {
           if (K == 1) launch(Int<1>{}, gc);
@@ -931,7 +1129,9 @@ int launch_moe_combine_by_expert(mcr_ctx*, const PtrTab& out, const CPtrTab& exp
         if (gate) by_k(Bool<true>{});
         else by_k(Bool<false>{});
         return launch_status();
-      });
+      };
+      if (variant == SV_SCALAR) return one_row(Bool<true>{}, Bool<true>{}, Bool<false>{});   // nontemporal, as tuned for aligned rows
+      return dispatch_hint(variant, [&](auto ntl, auto nts) { return one_row(ntl, nts, Bool<true>{}); });
     }
     if (K > 1) {
       auto topk = [&](auto ub, auto ntl, auto nts) {

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstddef>
+#include <atomic>
 #include <cstdint>
 #include <map>
 #include <mutex>
@@ -49,9 +50,16 @@ struct TuneKey {
 
 }  // namespace mcr
 
+// Slots of the context's ring of displacement tables (mcr::PairSlot, 4 KiB each): a fused MoE
+// call takes the next one, so that many calls may be in flight on different streams before two of
+// them share a slot.
+constexpr unsigned kPairRingSlots = 64;
+
 struct mcr_ctx {
   int device = 0;
   int n_cu = 256;                                                     // compute units of the device
+  mcr::PairSlot* pair_ring = nullptr;                                 // device memory, kPairRingSlots entries, from mcr_init
+  std::atomic<unsigned> pair_next{0};
   std::mutex mu;                                                      // guards `tables`
   std::map<mcr::TuneKey, std::vector<std::pair<size_t, int>>> tables; // sorted by bytes
 };

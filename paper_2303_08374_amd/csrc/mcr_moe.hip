@@ -293,6 +293,22 @@ pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows,
   }
 }
 
+// pack for rows wider than half a workgroup: one row per workgroup, the slot through a scalar load.
+// AL = false: rows of any width and alignment (16-byte pieces at element-aligned addresses, then
+// `tail2` 2-byte units).
+template <bool NTL, bool NTS, bool AL>
+__global__ void __launch_bounds__(kBlock)
+pack_row_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t out_rows, size_t row_bytes, uint32_t pieces, uint32_t tail2) {
+  const unsigned rank = blockIdx.y;
+  const size_t t = blockIdx.x;
+  const int32_t s = static_cast<const int32_t*>(slot_tab.p[rank])[t];
+  if (s < 0 || static_cast<size_t>(s) >= out_rows) return;
+  const char* srow = static_cast<const char*>(in.p[rank]) + t * row_bytes;
+  char* drow = static_cast<char*>(out.p[rank]) + static_cast<size_t>(s) * row_bytes;
+  copy_row_pieces<kBlock, 1, NTL, NTS, AL>(drow, srow, pieces);
+  if (!AL && threadIdx.x < tail2) copy_tail2(drow, srow, pieces, threadIdx.x);
+}
+
 template <int DT> __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float g) {
   using E = Elem<DT>;
   float f[E::kPerVec];
@@ -349,38 +365,46 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
 // slot and the gate come through scalar loads), kRowGatherVecs units per thread in flight.  A
 // gather behind a lookup is bound by the rows a compute unit has in flight: the smaller workgroup
 // doubles them (6.1 against 5.8 TB/s in a plain gather of 4 KiB rows).
-template <int DT, bool NTL, bool NTS, bool GATE>
+template <int DT, bool NTL, bool NTS, bool GATE, bool AL>
 __global__ void __launch_bounds__(kRowGatherBlock)
-unpack_row_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t in_rows, uint32_t upr) {
+unpack_row_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t in_rows, size_t row_bytes, uint32_t upr,
+                  uint32_t tail) {
+  using E = Elem<DT>;
   constexpr int V = kRowGatherVecs;
   const unsigned rank = blockIdx.y;
   const size_t t = blockIdx.x;
   const int32_t s = static_cast<const int32_t*>(slot_tab.p[rank])[t];
   float g = 1.0f;
   if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[rank])[t];
-  const u32x4* src = static_cast<const u32x4*>(in.p[rank]);
-  u32x4* drow = static_cast<u32x4*>(out.p[rank]) + t * upr;
+  char* drow = static_cast<char*>(out.p[rank]) + t * row_bytes;
   const bool kept = s >= 0 && static_cast<size_t>(s) < in_rows;
+  const size_t first_tail = static_cast<size_t>(upr) * E::kPerVec;   // `tail` elements behind the whole pieces
   if (!kept) {
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) store16<NTS>(drow, c, z);
+    for (uint32_t c = threadIdx.x; c < upr; c += kRowGatherBlock) store_piece<NTS, AL>(drow, c, z);
+    if (!AL && threadIdx.x < tail) E::store1(drow, first_tail + threadIdx.x, typename E::acc_t(0));
     return;
   }
-  const u32x4* srow = src + static_cast<size_t>(s) * upr;
+  const char* srow = static_cast<const char*>(in.p[rank]) + static_cast<size_t>(s) * row_bytes;
   for (uint32_t c0 = threadIdx.x; c0 < upr; c0 += V * kRowGatherBlock) {
     u32x4 v[V];
 #pragma unroll
     for (int u = 0; u < V; ++u) {
       const uint32_t c = c0 + u * kRowGatherBlock;
-      if (c < upr) v[u] = load16<NTL>(srow, c);
+      if (c < upr) v[u] = load_piece<NTL, AL>(srow, c);
     }
 #pragma unroll
     for (int u = 0; u < V; ++u) {
       const uint32_t c = c0 + u * kRowGatherBlock;
       if (c >= upr) continue;
       if constexpr (GATE) v[u] = scale_vec<DT>(v[u], g);
-      store16<NTS>(drow, c, v[u]);
+      store_piece<NTS, AL>(drow, c, v[u]);
     }
+  }
+  if (!AL && threadIdx.x < tail) {
+    const size_t i = first_tail + threadIdx.x;
+    if constexpr (GATE) E::store1(drow, i, g * E::load1(srow, i));
+    else copy_elem<E::kBytes>(drow, srow, i);                        // a bit copy, whatever the pattern
   }
 }
 
@@ -467,6 +491,13 @@ int route_scratch_address(int device, int32_t** out) {
 int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& slot, size_t T, size_t out_rows,
                 size_t row_bytes, int elem_b, int P, int variant, hipStream_t stream) {
   if (T == 0 || row_bytes == 0) return MCR_OK;
+  if (variant == SV_SCALAR && row_bytes / 16 > kBlock / 2) {
+    // wide rows of any width and alignment: one row per workgroup, 16-byte pieces and a tail, nontemporal
+    // both ways (what the tuning suite picks for the aligned rows of the workloads)
+    hipLaunchKernelGGL((pack_row_kernel<true, true, false>), dim3(static_cast<unsigned>(T), P), dim3(kBlock), 0, stream, out, in, slot,
+                       out_rows, row_bytes, static_cast<uint32_t>(row_bytes / 16), static_cast<uint32_t>((row_bytes % 16) / 2));
+    return launch_status();
+  }
   if (variant == SV_SCALAR) {
     const RowShape s = row_shape(T, row_bytes / elem_b);
     if (elem_b == 4)
@@ -478,8 +509,8 @@ int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& s
   const RowShape s = row_shape(T, row_bytes / 16);
   return dispatch_hint(variant, [&](auto ntl, auto nts) {
     if (s.tpr == kBlock)
-      hipLaunchKernelGGL((pack_kernel<16, decltype(ntl)::value, decltype(nts)::value, true>), dim3(s.blocks, P), dim3(kBlock), 0,
-                         stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
+      hipLaunchKernelGGL((pack_row_kernel<decltype(ntl)::value, decltype(nts)::value, true>), dim3(static_cast<unsigned>(T), P),
+                         dim3(kBlock), 0, stream, out, in, slot, out_rows, row_bytes, s.upr, 0u);
     else
       hipLaunchKernelGGL((pack_kernel<16, decltype(ntl)::value, decltype(nts)::value, false>), dim3(s.blocks, P), dim3(kBlock), 0,
                          stream, out, in, slot, T, out_rows, s.upr, s.tpr, s.shift);
@@ -497,12 +528,20 @@ int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab&
   return dispatch_float_dtype(kernel_dtype, [&](auto dt) {
     constexpr int DT = decltype(dt)::value;
     constexpr int EB = Elem<DT>::kBytes;
+    const size_t row_bytes = row_elems * EB;
     auto go = [&](auto ub, auto ntl, auto nts, auto gc) {
       constexpr int UB = decltype(ub)::value;
       const RowShape s = row_shape(T, row_elems * EB / UB);
       if (UB == 16 && s.tpr == kBlock)
-        hipLaunchKernelGGL((unpack_row_kernel<DT, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
-                           dim3(static_cast<unsigned>(T), P), dim3(kRowGatherBlock), 0, stream, out, in, slot, g, in_rows, s.upr);
+        hipLaunchKernelGGL((unpack_row_kernel<DT, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value, true>),
+                           dim3(static_cast<unsigned>(T), P), dim3(kRowGatherBlock), 0, stream, out, in, slot, g, in_rows, row_bytes,
+                           s.upr, 0u);
+      else if (UB != 16 && row_bytes / 16 > kBlock / 2)
+        // the element path on wide rows: 16-byte pieces at element-aligned addresses and a tail (plain
+        // loads and stores: 291 us on the MoE workload with 4104-byte rows, 315-330 with nontemporal ones)
+        hipLaunchKernelGGL((unpack_row_kernel<DT, false, false, decltype(gc)::value, false>), dim3(static_cast<unsigned>(T), P),
+                           dim3(kRowGatherBlock), 0, stream, out, in, slot, g, in_rows, row_bytes,
+                           static_cast<uint32_t>(row_bytes / 16), static_cast<uint32_t>((row_bytes % 16) / EB));
       else
         hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
                            dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);

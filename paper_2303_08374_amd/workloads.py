@@ -72,7 +72,9 @@ def allreduce_small(ctx, reps: int = 50) -> Dict:
 
 # ---- workload 3 ---------------------------------------------------------------------------
 def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoEWorkload(),
-                         variants: Optional[Dict[str, int]] = None) -> Dict:
+                         variants: Optional[Dict[str, int]] = None, odd_hidden: int = 0) -> Dict:
+    """`odd_hidden`: a second hidden size (say 2052: rows of 4104 bytes, not a multiple of 16) to run
+    the row kernels on as well; their times are reported against the ones at w.H."""
     P, T, H, E, C = w.P, w.T, w.H, w.E, w.C
     row = H * 2
     d_ids = [torch.from_numpy(w.ids(p)).cuda() for p in range(P)]
@@ -209,6 +211,25 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
     rep["top2"]["kept_assignments"] = kept2
     rep["top2"]["tokens_with_a_kept_choice"] = tokens_sent
     rep["top2"]["kept_fraction"] = round(kept2 / (P * A), 4)
+    if odd_hidden:
+        import dataclasses
+        del d_tok, d_packed, d_recv, d_back, d_out, d_recv2
+        torch.cuda.empty_cache()
+        odd = moe_dispatch_combine(ctx, reps, dataclasses.replace(w, H=odd_hidden), variants)
+        pairs = [("pack", ("pack",)), ("alltoallv_dispatch", ("alltoallv_dispatch",)), ("unpack_combine", ("unpack_combine",)),
+                 ("moe_dispatch", ("fused", "moe_dispatch")), ("moe_combine", ("fused", "moe_combine")),
+                 ("moe_dispatch_by_expert", ("by_expert", "moe_dispatch_by_expert")),
+                 ("moe_combine_by_expert", ("by_expert", "moe_combine_by_expert")),
+                 ("top2 moe_dispatch_by_expert", ("top2", "moe_dispatch_by_expert")),
+                 ("top2 moe_combine_by_expert", ("top2", "moe_combine_by_expert"))]
+
+        def at(r, path):
+            for k in path:
+                r = r[k]
+            return r
+        rep["odd_rows"] = {"H": odd_hidden, "row_bytes": odd_hidden * 2, "stages": {
+            name: {"us": at(odd, path)["us"], "GBps": at(odd, path).get("GBps"),
+                   "vs_aligned": round(at(odd, path)["us"] / at(rep, path)["us"], 2)} for name, path in pairs}}
     return rep
 
 
@@ -446,7 +467,7 @@ def graph_replay(ctx, P: int = inputs.SWEEP_P, max_bytes: int = 1 << 20, reps: i
 def run_all(ctx) -> Dict:
     out = {"allreduce_small": allreduce_small(ctx)}
     torch.cuda.empty_cache()
-    out["moe_dispatch_combine"] = moe_dispatch_combine(ctx)
+    out["moe_dispatch_combine"] = moe_dispatch_combine(ctx, odd_hidden=2052)
     torch.cuda.empty_cache()
     out["dlrm_shuffle"] = dlrm_shuffle(ctx)
     torch.cuda.empty_cache()

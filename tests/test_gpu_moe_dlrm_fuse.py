@@ -100,7 +100,8 @@ def test_moe_route_zipf_workload():
 # ----------------------------------------------------------------- pack / unpack
 @pytest.mark.parametrize("dtype,w", [(mcr.F32, 1), (mcr.F32, 4), (mcr.F32, 128), (mcr.BF16, 5), (mcr.BF16, 8),
                                       (mcr.BF16, 2048), (mcr.BF16, 24), (mcr.F32, 1028), (mcr.BF16, 1040), (mcr.F32, 516),
-                                      (mcr.BF16, 8200)])
+                                      (mcr.BF16, 8200), (mcr.BF16, 2052), (mcr.BF16, 2049), (mcr.F32, 1027), (mcr.F32, 515),
+                                      (mcr.BF16, 1031)])
 def test_pack_unpack_combine(dtype, w):
     P, T, E = 3, 777, 12
     g = np.random.Generator(np.random.Philox(key=w))
@@ -230,6 +231,11 @@ def test_moe_pipeline_small():
         _moe_pipeline(inputs.MoEWorkload(P=4, T=300, H=1040, E=8, capacity_factor=0.8), permute=True, fused_variant=v)
     _moe_pipeline(inputs.MoEWorkload(P=16, T=90, H=4104, E=16, capacity_factor=0.5))
     _moe_pipeline(inputs.MoEWorkload(P=1, T=65, H=2048, E=3))
+    # wide rows that are not a multiple of 16 bytes (4104, 4098 and 2062 bytes): 16-byte pieces at
+    # element-aligned addresses and a tail, in every stage of the chain and in the fused pair
+    for H in (2052, 2049, 1031):
+        _moe_pipeline(inputs.MoEWorkload(P=4, T=300, H=H, E=8, capacity_factor=0.8), permute=True)
+    _moe_pipeline(inputs.MoEWorkload(P=16, T=90, H=2052, E=16, capacity_factor=0.5), fused_variant=0)
 
 
 def test_moe_pipeline_config3_full_size():
@@ -304,6 +310,15 @@ def test_moe_by_expert_small():
     for H, dt in ((1040, mcr.BF16), (2048, mcr.BF16), (1028, mcr.F32), (8200, mcr.BF16)):
         for v in (mcr.AUTO, 1, 6, 8, 11):
             _moe_by_expert(inputs.MoEWorkload(P=4, T=300, H=H, E=8, capacity_factor=0.8), variant=v, dtype=dt, permute=True)
+
+
+def test_moe_by_expert_wide_rows_of_any_width():
+    """Rows wider than half a workgroup whose width is not a multiple of 16 bytes: one row per
+    workgroup, 16-byte pieces at element-aligned addresses and a tail of single elements."""
+    for H, dt in ((2052, mcr.BF16), (2049, mcr.BF16), (1027, mcr.F32), (1031, mcr.BF16)):
+        for K in (1, 2, 3):
+            _moe_by_expert(inputs.MoEWorkload(P=4, T=300, H=H, E=8, capacity_factor=0.8), dtype=dt, K=K, permute=True)
+    _moe_by_expert(inputs.MoEWorkload(P=16, T=90, H=2052, E=16, capacity_factor=0.5), variant=0)
 
 
 @pytest.mark.parametrize("K", [2, 3, 4])
