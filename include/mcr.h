@@ -143,10 +143,10 @@ const char* mcr_strerror(int status);
  * number of bytes (the same view of a tensor on every rank) and the message reaches the next
  * 16-byte boundary; otherwise only the element path ("scalar") applies.  `count` may be any
  * number.
- * One variant beyond the common launch shapes (all_reduce, reduce, reduce_scatter): "pk8", a
+ * Two variants beyond the common launch shapes (all_reduce, reduce, reduce_scatter): "pk8", a
  * persistent form with one workgroup of 1024 threads per compute unit, each walking a contiguous
  * run of the message in rounds (read and reduce 8 steps of one vector per thread, then store
- * them). */
+ * them), and "w64", workgroups of one wavefront with two vectors per thread. */
 int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype,
                   mcr_redop op, int P, int variant, void* stream);
 
@@ -162,7 +162,11 @@ int mcr_allgather(mcr_ctx* ctx, void* const* out, const void* const* in, size_t 
 
 /* all_to_all_single (API listing; "shuffles the tensor elements themselves"),
  * equal split.  in[p], out[r]: `count` elements, P divides count, b = count/P:
- * out[r][p*b + k] = in[p][r*b + k].  Bit copy. */
+ * out[r][p*b + k] = in[p][r*b + k].  Bit copy.
+ * Variants beyond the common launch shapes: "flat" (threads numbered along the output of a
+ * destination, so that blocks shorter than a workgroup leave no lane idle), "w64" (the same with
+ * workgroups of one wavefront) and "lds" ("flat" with four vectors per thread staged through LDS
+ * between the workgroup's loads and its stores). */
 int mcr_alltoall(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
                  mcr_dtype dtype, int P, int variant, void* stream);
 

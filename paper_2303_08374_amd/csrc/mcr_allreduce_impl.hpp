@@ -43,10 +43,10 @@ __device__ __forceinline__ void allreduce_edges(const PtrTab& bufs, const CPtrTa
   }
 }
 
-template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
-__global__ void __launch_bounds__(kBlock)
+template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC, int BS = kBlock>
+__global__ void __launch_bounds__(BS)
 allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root, unsigned head) {
-  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
+  constexpr size_t kTile = static_cast<size_t>(U) * BS;
   CPtrTab in;
 #pragma unroll
   for (int p = 0; p < P; ++p) in.p[p] = bufs.p[p];
@@ -54,13 +54,13 @@ allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int r
   if (tile < nvec) {
     u32x4 out[U];
     const bool full = tile + kTile <= nvec;
-    if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, 0, tile, nvec, scale, op, out);
-    else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, 0, tile, nvec, scale, op, out);
+    if (full) reduce_tile<DT, P, U, NTL, true, GENERIC, BS>(in, 0, tile, nvec, scale, op, out);
+    else reduce_tile<DT, P, U, NTL, false, GENERIC, BS>(in, 0, tile, nvec, scale, op, out);
 #pragma unroll
     for (int p = 0; p < P; ++p) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+        const size_t idx = tile + static_cast<size_t>(u) * BS + threadIdx.x;
         if ((full || idx < nvec) && (root < 0 || root == p)) store16<NTS>(bufs.p[p], idx, out[u]);
       }
     }
@@ -165,6 +165,24 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
         if constexpr (all_shapes(DT)) {
           hipLaunchKernelGGL((allreduce_persist<DT, kP, kPersistU, kPersistK>), dim3(g), dim3(kPersistBlock), 0, stream, bufs, nvec,
                              count, scale, op, root, head);
+          return launch_status();
+        } else {
+          return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above
+        }
+      });
+    }
+  }
+  if (variant == SV_W64) {
+    if (op > MCR_AVG || !all_shapes(DT)) {
+      variant = SV_V2NT;                                  // the shape that stands in for it
+    } else {
+      const size_t per = 2 * kWave;
+      const unsigned g = static_cast<unsigned>(nvec ? (nvec + per - 1) / per : 1);
+      return dispatch_ranks(P, [&](auto pp) {
+        constexpr int kP = decltype(pp)::value;
+        if constexpr (all_shapes(DT)) {
+          hipLaunchKernelGGL((allreduce_vec<DT, kP, 2, true, true, false, kWave>), dim3(g), dim3(kWave), 0, stream, bufs, nvec, count,
+                             scale, op, root, head);
           return launch_status();
         } else {
           return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above

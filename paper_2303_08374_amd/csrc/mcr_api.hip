@@ -16,7 +16,8 @@ namespace mcr {
 const char* const kStreamVariantNames[AG_COUNT] = {"scalar", "v1", "v2", "v4", "v1nt", "v2nt", "v4nt", "v1ln", "v2ln", "v4ln",
                                                    "v1sn", "v2sn", "v4sn", "sc4", "sc8", "sc16"};
 
-const char* const kReduceVariantNames[RV_COUNT - SV_COUNT] = {"pk8"};
+const char* const kReduceVariantNames[RV_COUNT - SV_COUNT] = {"pk8", "w64"};
+const char* const kAlltoallVariantNames[A2A_COUNT - SV_COUNT] = {"flat", "w64", "lds"};
 
 namespace {
 
@@ -35,13 +36,15 @@ bool redop_fits(int o, int dtype) { return !(dtype == MCR_I32 && o == MCR_AVG); 
 bool valid_P(int P) { return P >= 1 && P <= MCR_MAX_RANKS; }
 bool is_reduction(int op) { return op == MCR_OP_ALLREDUCE || op == MCR_OP_REDUCE_SCATTER; }
 int n_variants(int op) {
-  return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : is_reduction(op) ? RV_COUNT : SV_COUNT;
+  return op == MCR_OP_MOE_ROUTE ? 1 : op == MCR_OP_ALLGATHER ? AG_COUNT : is_reduction(op) ? RV_COUNT
+         : op == MCR_OP_ALLTOALL ? A2A_COUNT : SV_COUNT;
 }
 // Name of variant `i` of `op`: the ids from SV_COUNT on belong to one op each (super-chunk forms of
 // all_gather, persistent forms of the reductions).
 const char* variant_name(int op, int i) {
   if (op == MCR_OP_MOE_ROUTE) return kRouteVariantNames[i];
   if (is_reduction(op) && i >= SV_COUNT) return kReduceVariantNames[i - SV_COUNT];
+  if (op == MCR_OP_ALLTOALL && i >= SV_COUNT) return kAlltoallVariantNames[i - SV_COUNT];
   return kStreamVariantNames[i];
 }
 

@@ -171,6 +171,42 @@ alltoall_kernel(PtrTab out, CPtrTab in, size_t b) {
                             static_cast<T*>(out.p[r]) + static_cast<size_t>(p) * b, b);
 }
 
+// "flat": blockIdx.y = destination r; the threads are numbered along out[r], U vectors each, and
+// every vector is fetched from the block of the source it belongs to (p = index / b).  A block
+// shorter than a workgroup then costs no idle lanes, and out[r] is written front to back.
+// BS = threads per workgroup.  LDS: the U vectors of every thread go through LDS between the
+// workgroup's loads and its stores (a read phase and a write phase per workgroup).
+template <int BS, int U, bool LDS>
+__global__ void __launch_bounds__(BS)
+alltoall_flat_kernel(PtrTab out, CPtrTab in, uint32_t b, uint32_t P) {
+  __shared__ u32x4 stage[LDS ? U * BS : 1];
+  const unsigned r = blockIdx.y;
+  const uint64_t n = static_cast<uint64_t>(b) * P;                       // vectors of one output
+  const uint64_t first = static_cast<uint64_t>(blockIdx.x) * (U * BS) + threadIdx.x;
+  u32x4 v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint64_t i = first + static_cast<uint64_t>(u) * BS;
+    if (i < n) {
+      const uint32_t p = static_cast<uint32_t>(i / b);
+      const uint64_t k = i - static_cast<uint64_t>(p) * b;
+      v[u] = load16<true>(in.p[p], static_cast<uint64_t>(r) * b + k);
+    }
+  }
+  if constexpr (LDS) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) stage[u * BS + threadIdx.x] = v[u];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = stage[u * BS + threadIdx.x];
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint64_t i = first + static_cast<uint64_t>(u) * BS;
+    if (i < n) store16<true>(out.p[r], i, v[u]);
+  }
+}
+
 // ---- all_to_allv -----------------------------------------------------------------
 // blockIdx.y = sender p, blockIdx.z = receiver r, blockIdx.x = tile of the pair's
 // rows.  With packed displacements the rows of one pair are contiguous on both
@@ -355,6 +391,23 @@ int launch_alltoall(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t count
     return launch_status();
   }
   const size_t bvec = b / per_vec(dtype);
+  // blocks too long for the 32-bit arithmetic of the flat forms run "v1nt" in their place
+  if ((variant == A2A_FLAT || variant == A2A_W64 || variant == A2A_LDS) && bvec * static_cast<size_t>(P) > (size_t(1) << 36))
+    variant = SV_V1NT;
+  if (variant == A2A_FLAT || variant == A2A_W64 || variant == A2A_LDS) {
+    const uint64_t n = static_cast<uint64_t>(bvec) * P;
+    const uint32_t b32 = static_cast<uint32_t>(bvec), P32 = static_cast<uint32_t>(P);
+    if (variant == A2A_FLAT)
+      hipLaunchKernelGGL((alltoall_flat_kernel<kBlock, 1, false>), dim3(static_cast<unsigned>((n + kBlock - 1) / kBlock), P), dim3(kBlock), 0,
+                         stream, out, in, b32, P32);
+    else if (variant == A2A_W64)
+      hipLaunchKernelGGL((alltoall_flat_kernel<kWave, 1, false>), dim3(static_cast<unsigned>((n + kWave - 1) / kWave), P), dim3(kWave), 0,
+                         stream, out, in, b32, P32);
+    else
+      hipLaunchKernelGGL((alltoall_flat_kernel<kBlock, 4, true>), dim3(static_cast<unsigned>((n + 4 * kBlock - 1) / (4 * kBlock)), P),
+                         dim3(kBlock), 0, stream, out, in, b32, P32);
+    return launch_status();
+  }
   const unsigned gx = grid_x(bvec, variant);
   return dispatch_shape(variant, [&](auto uu, auto ntl, auto nts) {
     constexpr int U = decltype(uu)::value;

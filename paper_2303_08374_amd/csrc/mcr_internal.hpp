@@ -37,7 +37,16 @@ enum AllgatherVariant { AG_SC4 = 13, AG_SC8 = 14, AG_SC16 = 15, AG_COUNT = 16 };
 // threads per compute unit walking a contiguous run of the message in rounds of 8 steps of one
 // vector per thread.  SUM / AVG on fp32 and bf16; other ReduceOps and element types run "v4nt" in
 // its place.
-enum ReduceVariant { SV_PK8 = 13, RV_COUNT = 14 };
+enum ReduceVariant { SV_PK8 = 13, SV_W64 = 14, RV_COUNT = 15 };
+// "w64" (the reductions and all_to_all_single): workgroups of one wavefront, two vectors per thread
+// (one for all_to_all), nontemporal: four times as many, smaller workgroups as "v2nt" for the
+// messages of a few MiB whose kernels last a few microseconds.
+// all_to_all_single only: "flat" numbers the threads along the output of a destination (thread i
+// writes vector i of out[r] and fetches it from the block it belongs to), so that blocks shorter
+// than a workgroup do not leave lanes idle; "lds" is "flat" with four vectors per thread staged
+// through LDS between a read phase and a write phase of the workgroup.
+enum AlltoallVariant { A2A_FLAT = 13, A2A_W64 = 14, A2A_LDS = 15, A2A_COUNT = 16 };
+extern const char* const kAlltoallVariantNames[A2A_COUNT - SV_COUNT];
 extern const char* const kStreamVariantNames[AG_COUNT];
 extern const char* const kReduceVariantNames[RV_COUNT - SV_COUNT];
 

@@ -10,10 +10,10 @@ namespace mcr {
 namespace {
 
 // blockIdx.y = destination rank r; slice r of every input is bvec vectors long.
-template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC>
-__global__ void __launch_bounds__(kBlock)
+template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC, int BS = kBlock>
+__global__ void __launch_bounds__(BS)
 reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
-  constexpr size_t kTile = static_cast<size_t>(U) * kBlock;
+  constexpr size_t kTile = static_cast<size_t>(U) * BS;
   const unsigned r = blockIdx.y;
   void* dst = out.p[r];
   const size_t off = static_cast<size_t>(r) * bvec;
@@ -21,11 +21,11 @@ reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
   if (tile >= bvec) return;
   u32x4 res[U];
   const bool full = tile + kTile <= bvec;
-  if (full) reduce_tile<DT, P, U, NTL, true, GENERIC>(in, off, tile, bvec, scale, op, res);
-  else reduce_tile<DT, P, U, NTL, false, GENERIC>(in, off, tile, bvec, scale, op, res);
+  if (full) reduce_tile<DT, P, U, NTL, true, GENERIC, BS>(in, off, tile, bvec, scale, op, res);
+  else reduce_tile<DT, P, U, NTL, false, GENERIC, BS>(in, off, tile, bvec, scale, op, res);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const size_t idx = tile + static_cast<size_t>(u) * kBlock + threadIdx.x;
+    const size_t idx = tile + static_cast<size_t>(u) * BS + threadIdx.x;
     if (full || idx < bvec) store16<NTS>(dst, idx, res[u]);
   }
 }
@@ -118,6 +118,24 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
         if constexpr (all_shapes(DT)) {
           hipLaunchKernelGGL((reduce_scatter_persist<DT, kP, kPersistU, kPersistK>), grid, dim3(kPersistBlock), 0, stream, out, in,
                              bvec, scale, op);
+          return launch_status();
+        } else {
+          return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above
+        }
+      });
+    }
+  }
+  if (variant == SV_W64) {
+    if (op > MCR_AVG || !all_shapes(DT)) {
+      variant = SV_V2NT;                                  // the shape that stands in for it
+    } else {
+      const size_t per = 2 * kWave;
+      const dim3 grid(static_cast<unsigned>(bvec ? (bvec + per - 1) / per : 1), P);
+      return dispatch_ranks(P, [&](auto pp) {
+        constexpr int kP = decltype(pp)::value;
+        if constexpr (all_shapes(DT)) {
+          hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, 2, true, true, false, kWave>), grid, dim3(kWave), 0, stream, out, in, bvec,
+                             scale, op);
           return launch_status();
         } else {
           return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above

@@ -126,12 +126,18 @@ TIMES_HEADER = ("# every variant's time, in microseconds per launch, behind each
                 "# (written by python -m paper_2303_08374_amd.tune --times-out): op dtype P bytes chosen | variant=us ...\n")
 
 
-def write_times(path: str, rows) -> None:
+def write_times(path: str, rows, coarse_vs_fine=None) -> None:
     dt = {mcr.F32: "f32", mcr.BF16: "bf16", mcr.F16: "f16", mcr.I32: "i32"}
     with open(path, "w") as f:
         f.write(TIMES_HEADER)
         for op, dtype, P, nbytes, best, us in rows:
             f.write(f"{op} {dt[dtype]} {P} {nbytes} {best} | " + " ".join(f"{k}={v}" for k, v in us.items()) + "\n")
+        if coarse_vs_fine:
+            f.write("# one variant per (op, dtype, scale) for every size (the paper's MCR-DL) against one per size (MCR-DL-T):\n"
+                    "# sum over the 17 sizes of the time per launch, in microseconds\n")
+            for key, v in coarse_vs_fine.items():
+                f.write(f"# {key}: best single variant {v['variant']} {v['sum_us']} us, per-size table {v['fine_sum_us']} us "
+                        f"(x{v['fine_gain']})\n")
 
 
 def read_times(path: str):
@@ -163,7 +169,7 @@ def run(out_path: str, report_path: str | None, scales, max_bytes: int, arena_gi
     os.makedirs(os.path.dirname(out_path) or ".", exist_ok=True)
     mcr.mcr_tune_save(ctx, out_path)
     if times_path:
-        write_times(times_path, rows)
+        write_times(times_path, rows, report["coarse_vs_fine"])
     if report_path:
         os.makedirs(os.path.dirname(report_path) or ".", exist_ok=True)
         with open(report_path, "w") as f:

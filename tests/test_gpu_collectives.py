@@ -211,7 +211,8 @@ def _variants_for(vec_ok, extra=()):
 def test_variant_lists_match_the_library():
     for op in range(10):
         names = mcr.mcr_get_variants(gu.ctx(), op)
-        extra = {mcr.OP_ALLGATHER: gu.ALLGATHER_EXTRA, mcr.OP_ALLREDUCE: gu.REDUCE_EXTRA, mcr.OP_REDUCE_SCATTER: gu.REDUCE_EXTRA}
+        extra = {mcr.OP_ALLGATHER: gu.ALLGATHER_EXTRA, mcr.OP_ALLREDUCE: gu.REDUCE_EXTRA, mcr.OP_REDUCE_SCATTER: gu.REDUCE_EXTRA,
+                 mcr.OP_ALLTOALL: gu.ALLTOALL_EXTRA}
         want = len(gu.ALL_VARIANTS) + len(extra.get(op, []))
         assert len(names) == want, (op, names)
 
@@ -289,7 +290,7 @@ def test_alltoall(dtype, P):
         n = P * b
         host = _make(P, n, dtype, seed=400 + P, dist="uniform")
         exp = oracle.alltoall(host, dtype)
-        for variant in _variants_for(b % W == 0):
+        for variant in _variants_for(b % W == 0, gu.ALLTOALL_EXTRA):
             dev_in = [gu.to_dev(h) for h in host]
             dev_out = [gu.dev_empty(n, dtype, 0) for _ in range(P)]
             mcr.mcr_alltoall(gu.ctx(), dev_out, dev_in, n, dtype, P, variant)
@@ -463,7 +464,7 @@ def test_max_min_prod(dtype, op):
         exp_rs = oracle.reduce_scatter(host, dtype, op)
         exp_red = [h.copy() for h in host]
         oracle.reduce(exp_red, dtype, op, 2)
-    for variant in (mcr.AUTO, 0, 2, 6, 13):
+    for variant in (mcr.AUTO, 0, 2, 6, 13, 14):
         dev = [gu.to_dev(h) for h in host]
         mcr.mcr_allreduce(gu.ctx(), dev, n, dtype, op, P, variant)
         d_in = [gu.to_dev(h) for h in host]

@@ -45,6 +45,11 @@ def _host(t, s, w, dtype):
     return a.cpu().numpy().copy()
 
 
+def _bits(t):
+    """A tensor as integers of its element size: equality of bit patterns, NaN and -0 included."""
+    return t.view(torch.int16 if t.element_size() == 2 else torch.int32)
+
+
 def _starts(n, rng, extra=()):
     """Window starts in [0, n - W]: both ends, boundaries of 4 KiB tiles and of 4/8/16 MiB super-chunks
     (in elements of either dtype), and random places."""
@@ -82,6 +87,10 @@ def test_sweep_ops_sampled(tuned_ctx, dtype, M):
             for st in _starts(b, rng)[::3]:
                 gu.assert_bits_equal(_host(outs[r], p * b + st, W, dtype), _host(ins[p], r * b + st, W, dtype),
                                      f"alltoall M={M} r={r} p={p} at {st}")
+    # and the whole output, on the device: every (r, p) block is a bit copy of its source block
+    for r in range(P):
+        for p in range(P):
+            assert torch.equal(_bits(outs[r][p * b:(p + 1) * b]), _bits(ins[p][r * b:(r + 1) * b])), f"alltoall M={M} block ({r}, {p})"
     del outs
 
     # all_gather: out[r][p*n + j] = in[p][j]  (P*M per output: 2 GiB each at the top size)
@@ -93,6 +102,10 @@ def test_sweep_ops_sampled(tuned_ctx, dtype, M):
             for st in _starts(n, rng)[::2]:
                 gu.assert_bits_equal(_host(outs[r], p * n + st, W, dtype), _host(ins[p], st, W, dtype),
                                      f"allgather M={M} r={r} p={p} at {st}")
+    # and the whole output, on the device: every (r, p) slice is a bit copy of rank p's input
+    for r in range(P):
+        for p in range(P):
+            assert torch.equal(_bits(outs[r][p * n:(p + 1) * n]), _bits(ins[p])), f"allgather M={M} slice ({r}, {p})"
     del outs
 
     # all_reduce, in place: download the windows first
@@ -109,6 +122,21 @@ def test_sweep_ops_sampled(tuned_ctx, dtype, M):
     for r in range(1, P):
         assert torch.equal(ins[r].view(torch.int16 if dtype == mcr.BF16 else torch.int32),
                            ins[0].view(torch.int16 if dtype == mcr.BF16 else torch.int32))
+
+
+@pytest.mark.parametrize("variant,mib", [(13, 9), (14, 20), (15, 40)])
+def test_allgather_superchunk_forms_with_several_superchunks(variant, mib):
+    """The super-chunk forms of all_gather (4, 8 and 16 MiB per source and super-chunk) on messages
+    of two super-chunks and a ragged third one, every element against the oracle."""
+    Pn = 2
+    n = ((mib << 20) + 4096 + 48) // 4                                  # fp32 elements: not a whole tile either
+    host = inputs.rank_buffers(Pn, n, seed=4400 + variant, dist="uniform")
+    exp = oracle.allgather(host, oracle.F32)
+    dev_out = [gu.dev_empty(Pn * n, mcr.F32, 0) for _ in range(Pn)]
+    mcr.mcr_allgather(gu.ctx(), dev_out, [gu.to_dev(h) for h in host], n, mcr.F32, Pn, variant)
+    gu.sync()
+    for r in range(Pn):
+        gu.assert_bits_equal(gu.to_host(dev_out[r], np.float32), exp[r], f"super-chunk form {variant}, {mib} MiB, r={r}")
 
 
 def test_gradient_buckets_full_size_sampled(tuned_ctx):
