@@ -30,7 +30,9 @@ __device__ __forceinline__ void store_unit(void* base, size_t i, T v) {
 // UB < 16 is the element path (addresses aligned to the element only, any length): still 16 bytes
 // per access, at whatever address the element falls on -- the hardware serves unaligned global
 // accesses, and 64 lanes x 2 bytes per instruction is what made this path 2-3 times slower than
-// the aligned one -- and the n mod (16 / UB) elements behind the last whole 16 bytes one by one.
+// the aligned one -- with the nontemporal hint both ways (what the tuning suite picks for the
+// aligned copies from a few MiB up), and the n mod (16 / UB) elements behind the last whole 16
+// bytes one by one.
 template <int UB, int U>
 __device__ constexpr uint64_t run_tile_units() {
   return static_cast<uint64_t>(U) * kBlock * (16 / UB);
@@ -64,12 +66,12 @@ __device__ __forceinline__ void copy_run(const typename Unit<UB>::type* src, typ
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-        if (idx < nv) __builtin_memcpy(&v[u], s + 16 * idx, 16);
+        if (idx < nv) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_elem_aligned*>(s + 16 * idx));
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint64_t idx = tile + static_cast<uint64_t>(u) * kBlock + threadIdx.x;
-        if (idx < nv) __builtin_memcpy(d + 16 * idx, &v[u], 16);
+        if (idx < nv) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4_elem_aligned*>(d + 16 * idx));
       }
     }
     const uint64_t e = nv * kPer + threadIdx.x;

@@ -12,6 +12,7 @@ import csv
 import glob
 import json
 import os
+import re
 import sys
 
 from . import inputs, sweep
@@ -154,16 +155,72 @@ def kernel_times(trace_dir: str, passes: int, cells_json: str | None) -> str:
     return "\n".join(out) + "\n"
 
 
+def _short_kernel(n: str) -> str:
+    n = n.replace("void ", "").replace("mcr::(anonymous namespace)::", "")
+    return re.sub(r"\(.*$", "", n)
+
+
+def kernel_stats(stats_dir: str, log_path: str, command: str, what: str) -> str:
+    """The library's kernels of a `rocprofv3 --kernel-trace --stats` run of bench.py (calls, average,
+    least and largest duration, share of the library's kernel time) and, from the JSON line bench.py
+    printed in that run, what its own events measured for the dominant kernel."""
+    files = sorted(glob.glob(os.path.join(stats_dir, "**", "*kernel_stats.csv"), recursive=True))
+    if not files:
+        raise SystemExit(f"no *_kernel_stats.csv under {stats_dir}")
+    with open(files[0]) as f:
+        rows = [r for r in csv.DictReader(f) if "mcr::" in r["Name"]]
+    line = None
+    with open(log_path) as f:
+        for l in f:
+            if l.startswith('{"metric"'):
+                line = json.loads(l)
+    out = [f"rocprofv3 kernel statistics of {what}, one MI355X.", "", "command (from /tmp, TMPDIR=/tmp):", f"  {command}", "",
+           f"{'kernel':84s} {'calls':>6s} {'avg_us':>10s} {'min_us':>9s} {'max_us':>10s} {'share%':>7s}"]
+    tot = sum(int(r["TotalDurationNs"]) for r in rows)
+    for r in rows:
+        share = 100.0 * int(r["TotalDurationNs"]) / tot
+        if share < 0.05:
+            continue
+        out.append(f"{_short_kernel(r['Name'])[:84]:84s} {r['Calls']:>6s} {float(r['AverageNs']) / 1e3:10.2f} {int(r['MinNs']) / 1e3:9.2f} "
+                   f"{int(r['MaxNs']) / 1e3:10.2f} {share:7.2f}")
+    if line:
+        rl = line["roofline"]
+        out += ["", f"bench.py in the same run (events on the launch stream, timed region only): dominant kernel {rl['kernel']}, "
+                    f"{rl['launches']} launches, average {rl['avg_launch_us']} us, {rl['avg_launch_alg_bytes']} algorithmic bytes per launch on "
+                    f"average => {rl['achieved']} GB/s = {rl['frac']} of 8000 GB/s.",
+                f"whole step: {line['ms_per_step']} ms for {line['config']['algorithmic_bytes_per_step']} algorithmic bytes => {line['value']} GB/s."]
+        st = line.get("stages")
+        if st:
+            m = st["moe_dispatch_combine"]
+            out += ["", "bench.py's own stage times in the same run (events around each call, us): "
+                        f"pack {m['pack']['us']}, all_to_allv {m['alltoallv_dispatch']['us']} / {m['alltoallv_return']['us']}, unpack + combine {m['unpack_combine']['us']}; "
+                        f"fused pair: dispatch {m['fused']['moe_dispatch']['us']}, combine {m['fused']['moe_combine']['us']}; "
+                        f"by expert: dispatch {m['by_expert']['moe_dispatch_by_expert']['us']}, combine {m['by_expert']['moe_combine_by_expert']['us']}; "
+                        f"top-2: dispatch {m['top2']['moe_dispatch_by_expert']['us']}, combine {m['top2']['moe_combine_by_expert']['us']}; "
+                        f"DLRM fused shuffle fwd {st['dlrm_shuffle']['fused']['fwd_dlrm_shuffle']['us']}, bwd {st['dlrm_shuffle']['fused']['bwd_dlrm_shuffle']['us']}; "
+                        f"allreduce_multi {st['grad_buckets']['allreduce_multi_one_launch']['us']}."]
+    return "\n".join(out) + "\n"
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
+    ks = sub.add_parser("kernel-stats")
+    ks.add_argument("stats_dir")
+    ks.add_argument("--log", required=True, help="stdout of the profiled bench.py run")
+    ks.add_argument("--command", required=True, help="the full profiling command, for the header")
+    ks.add_argument("--what", default="the op sweep (bench.py)")
+    ks.add_argument("--out", default=None)
     k = sub.add_parser("kernel-times")
     k.add_argument("trace_dir")
     k.add_argument("--passes", type=int, required=True)
     k.add_argument("--cells", default=None)
     k.add_argument("--out", default=None)
     a = ap.parse_args(argv)
-    text = kernel_times(a.trace_dir, a.passes, a.cells)
+    if a.cmd == "kernel-stats":
+        text = kernel_stats(a.stats_dir, a.log, a.command, a.what)
+    else:
+        text = kernel_times(a.trace_dir, a.passes, a.cells)
     if a.out:
         with open(a.out, "w") as f:
             f.write(text)
