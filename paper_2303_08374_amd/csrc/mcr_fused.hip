@@ -918,6 +918,37 @@ dlrm_shuffle_kernel(PtrTab dst_tab, CPtrTab src_tab, uint32_t n_tables, uint64_t
   for (uint32_t c = threadIdx.x & (tpr - 1); c < upr; c += tpr) stu<NTS, U>(d + c, ldu<NTL, U>(s + c));
 }
 
+// The same walk for rows that are not a multiple of 16 bytes wide or not 16-byte aligned: whole
+// 16-byte pieces at whatever address the elements fall on, then the `tail2` 2-byte units behind them
+// (one element per access, the form for rows under 64 bytes, is what this replaces).
+template <bool NTL, bool NTS, bool BWD>
+__global__ void __launch_bounds__(kBlock)
+dlrm_shuffle_pieces_kernel(PtrTab dst_tab, CPtrTab src_tab, uint32_t n_tables, uint64_t batch, uint32_t P, uint32_t row_bytes,
+                           uint32_t pieces, uint32_t tail2, uint32_t tpr, uint32_t tpr_shift) {
+  const uint32_t r = blockIdx.y;
+  const uint64_t bl = batch / P;
+  const uint64_t rows = bl * n_tables;
+  const uint32_t rows_per_pass = kBlock >> tpr_shift;
+  const uint64_t j = static_cast<uint64_t>(blockIdx.x) * rows_per_pass + (threadIdx.x >> tpr_shift);
+  if (j >= rows) return;
+  const uint64_t b = j / n_tables;
+  const uint32_t t = static_cast<uint32_t>(j - b * n_tables);
+  const uint32_t owner = t % P, local = t / P;
+  const uint64_t trow = static_cast<uint64_t>(local) * batch + static_cast<uint64_t>(r) * bl + b;
+  const char* s;
+  char* d;
+  if constexpr (BWD) {
+    s = static_cast<const char*>(src_tab.p[r]) + j * row_bytes;
+    d = static_cast<char*>(dst_tab.p[owner]) + trow * row_bytes;
+  } else {
+    s = static_cast<const char*>(src_tab.p[owner]) + trow * row_bytes;
+    d = static_cast<char*>(dst_tab.p[r]) + j * row_bytes;
+  }
+  const uint32_t lane = threadIdx.x & (tpr - 1);
+  for (uint32_t c = lane; c < pieces; c += tpr) store_piece<NTS, false>(d, c, load_piece<NTL, false>(s, c));
+  if (lane < tail2) copy_tail2(d, s, pieces, lane);
+}
+
 struct RowShape {
   uint32_t upr, tpr, shift, rows_per_pass;
 };
@@ -1198,6 +1229,18 @@ int launch_dlrm_shuffle(mcr_ctx*, const PtrTab& dst, const CPtrTab& src, int n_t
                          static_cast<uint32_t>(P), s.upr, s.tpr, s.shift);
     return launch_status();
   };
+  if (variant == SV_SCALAR && row_bytes >= 64) {
+    const uint32_t pieces = static_cast<uint32_t>(row_bytes / 16), tail2 = static_cast<uint32_t>(row_bytes % 16) / 2;
+    const RowShape s = row_shape(pieces);
+    const unsigned gx = blocks_for(rows, s.rows_per_pass);
+    auto odd = [&](auto bwd) {
+      hipLaunchKernelGGL((dlrm_shuffle_pieces_kernel<true, false, decltype(bwd)::value>), dim3(gx, P), dim3(kBlock), 0, stream, dst,
+                         src, static_cast<uint32_t>(n_tables), static_cast<uint64_t>(batch), static_cast<uint32_t>(P),
+                         static_cast<uint32_t>(row_bytes), pieces, tail2, s.tpr, s.shift);
+      return launch_status();
+    };
+    return backward ? odd(Bool<true>{}) : odd(Bool<false>{});
+  }
   if (variant == SV_SCALAR) return elem_b == 4 ? go(Int<4>{}, Bool<false>{}, Bool<false>{}) : go(Int<2>{}, Bool<false>{}, Bool<false>{});
   return dispatch_hint(variant, [&](auto ntl, auto nts) { return go(Int<16>{}, ntl, nts); });
 }

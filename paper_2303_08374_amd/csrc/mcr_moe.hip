@@ -293,6 +293,25 @@ pack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows,
   }
 }
 
+// pack_kernel for rows of any width and alignment from 64 bytes up: whole 16-byte pieces at the
+// address the elements fall on, then `tail2` 2-byte units.
+template <bool NTL, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+pack_pieces_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, size_t T, size_t out_rows, size_t row_bytes, uint32_t pieces,
+                   uint32_t tail2, uint32_t tpr, uint32_t tpr_shift) {
+  const unsigned rank = blockIdx.y;
+  size_t t;
+  uint32_t c0, step;
+  row_of_thread<false>(tpr, tpr_shift, &t, &c0, &step);
+  if (t >= T) return;
+  const int32_t s = static_cast<const int32_t*>(slot_tab.p[rank])[t];
+  if (s < 0 || static_cast<size_t>(s) >= out_rows) return;
+  const char* srow = static_cast<const char*>(in.p[rank]) + t * row_bytes;
+  char* drow = static_cast<char*>(out.p[rank]) + static_cast<size_t>(s) * row_bytes;
+  for (uint32_t c = c0; c < pieces; c += step) store_piece<NTS, false>(drow, c, load_piece<NTL, false>(srow, c));
+  if (c0 < tail2) copy_tail2(drow, srow, pieces, c0);
+}
+
 // pack for rows wider than half a workgroup: one row per workgroup, the slot through a scalar load.
 // AL = false: rows of any width and alignment (16-byte pieces at element-aligned addresses, then
 // `tail2` 2-byte units).
@@ -358,6 +377,46 @@ unpack_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t
       }
     }
     if constexpr (NTS) __builtin_nontemporal_store(v, drow + c); else drow[c] = v;
+  }
+}
+
+// unpack_kernel for rows of any width and alignment from 64 bytes up: 16-byte pieces, then the
+// `tail` elements behind them one by one.
+template <int DT, bool GATE>
+__global__ void __launch_bounds__(kBlock)
+unpack_pieces_kernel(PtrTab out, CPtrTab in, CPtrTab slot_tab, CPtrTab gate_tab, size_t T, size_t in_rows, size_t row_bytes,
+                     uint32_t pieces, uint32_t tail, uint32_t tpr, uint32_t tpr_shift) {
+  typedef Elem<DT> EL;
+  const unsigned rank = blockIdx.y;
+  size_t t;
+  uint32_t c0, step;
+  row_of_thread<false>(tpr, tpr_shift, &t, &c0, &step);
+  if (t >= T) return;
+  const int32_t s = static_cast<const int32_t*>(slot_tab.p[rank])[t];
+  const bool kept = s >= 0 && static_cast<size_t>(s) < in_rows;
+  char* drow = static_cast<char*>(out.p[rank]) + t * row_bytes;
+  const size_t first_tail = static_cast<size_t>(pieces) * (16 / EL::kBytes);
+  if (!kept) {
+    const u32x4 z = {};
+    for (uint32_t c = c0; c < pieces; c += step) store_piece<false, false>(drow, c, z);
+    if (c0 < tail) {
+      if constexpr (EL::kBytes == 4) reinterpret_cast<uint32_t*>(drow)[first_tail + c0] = 0u;
+      else reinterpret_cast<uint16_t*>(drow)[first_tail + c0] = 0;
+    }
+    return;
+  }
+  const char* srow = static_cast<const char*>(in.p[rank]) + static_cast<size_t>(s) * row_bytes;
+  float g = 1.0f;
+  if constexpr (GATE) g = static_cast<const float*>(gate_tab.p[rank])[t];
+  for (uint32_t c = c0; c < pieces; c += step) {
+    u32x4 v = load_piece<false, false>(srow, c);
+    if constexpr (GATE) v = scale_vec<DT>(v, g);
+    store_piece<false, false>(drow, c, v);
+  }
+  if (c0 < tail) {
+    const size_t i = first_tail + c0;
+    if constexpr (GATE) EL::store1(drow, i, g * EL::load1(srow, i));
+    else copy_elem<EL::kBytes>(drow, srow, i);
   }
 }
 
@@ -498,6 +557,12 @@ int launch_pack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab& s
                        out_rows, row_bytes, static_cast<uint32_t>(row_bytes / 16), static_cast<uint32_t>((row_bytes % 16) / 2));
     return launch_status();
   }
+  if (variant == SV_SCALAR && row_bytes >= 64) {
+    const RowShape s = row_shape(T, row_bytes / 16);
+    hipLaunchKernelGGL((pack_pieces_kernel<true, false>), dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, T, out_rows,
+                       row_bytes, s.upr, static_cast<uint32_t>((row_bytes % 16) / 2), s.tpr, s.shift);
+    return launch_status();
+  }
   if (variant == SV_SCALAR) {
     const RowShape s = row_shape(T, row_bytes / elem_b);
     if (elem_b == 4)
@@ -542,7 +607,11 @@ int launch_unpack(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const CPtrTab&
         hipLaunchKernelGGL((unpack_row_kernel<DT, false, false, decltype(gc)::value, false>), dim3(static_cast<unsigned>(T), P),
                            dim3(kRowGatherBlock), 0, stream, out, in, slot, g, in_rows, row_bytes,
                            static_cast<uint32_t>(row_bytes / 16), static_cast<uint32_t>((row_bytes % 16) / EB));
-      else
+      else if (UB != 16 && row_bytes >= 64) {
+        const RowShape sp = row_shape(T, row_bytes / 16);
+        hipLaunchKernelGGL((unpack_pieces_kernel<DT, decltype(gc)::value>), dim3(sp.blocks, P), dim3(kBlock), 0, stream, out, in, slot,
+                           g, T, in_rows, row_bytes, sp.upr, static_cast<uint32_t>((row_bytes % 16) / EB), sp.tpr, sp.shift);
+      } else
         hipLaunchKernelGGL((unpack_kernel<DT, UB, decltype(ntl)::value, decltype(nts)::value, decltype(gc)::value>),
                            dim3(s.blocks, P), dim3(kBlock), 0, stream, out, in, slot, g, T, in_rows, s.upr, s.tpr, s.shift);
       return launch_status();

@@ -97,6 +97,12 @@ def _stage_lines(st: dict):
         f"chain end to end {_sg(d['end_to_end'])}",
         f"  - fused single pass: fwd {_sg(d['fused']['fwd_dlrm_shuffle'])}; bwd {_sg(d['fused']['bwd_dlrm_shuffle'])}; end to end {_sg(d['fused']['end_to_end'])} "
         f"= {d['fused']['speedup_vs_chain']}x the chain",
+    ]
+    if "odd_rows" in d:
+        o = d["odd_rows"]
+        lines.append(f"  - the same workload with dim = {o['dim']} (rows of {o['row_bytes']} bytes, not a multiple of 16): " +
+                     "; ".join(f"{k} {_sg(v)} ({v['per_byte_vs_aligned']}x the time per byte of dim = 128)" for k, v in o["stages"].items()))
+    lines += [
         f"- gradient buckets ({g['tensors']} bf16 tensors, {g['elements_per_rank'] / 1e9:.3f} G elements per rank, P=8, {g['buckets']} buckets; minimum traffic "
         f"{g['fuse']['alg_bytes'] / 1e9:.1f} GB = {g['fuse']['alg_bytes'] / 8e6:.0f} us at 8 TB/s): fuse {_sg(g['fuse'])}; allreduce(flat, AVG) {_sg(g['allreduce_flat'])}; "
         f"unfuse {_sg(g['unfuse'])}; pipeline of {g['pipeline_fuse_allreduce_unfuse']['launches']} launches {g['pipeline_fuse_allreduce_unfuse']['us']} us; "

@@ -235,11 +235,13 @@ def moe_dispatch_combine(ctx, reps: int = 10, w: inputs.MoEWorkload = inputs.MoE
 
 # ---- workload 4 ---------------------------------------------------------------------------
 def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorkload(), sets: int = 3,
-                 variants: Optional[Dict[str, int]] = None) -> Dict:
+                 variants: Optional[Dict[str, int]] = None, odd_dim: int = 0) -> Dict:
     """Forward: pooled [T_p, B, D] -> destination-major send order (pack) -> alltoallv ->
     [B/P, n_tables, D] (unpack with the table permutation).  Backward: the inverse chain.
     `sets` independent buffer sets are used in rotation so that a stage does not find its
-    input in the last-level cache."""
+    input in the last-level cache.  `odd_dim`: a second embedding width (say 130: rows of 520
+    bytes, not a multiple of 16) to run the same stages on; their times per byte against the
+    first width's go under "odd_rows"."""
     P, NT, D, B = w.P, w.n_tables, w.dim, w.batch
     bl = B // P
     n_local = [len(w.tables_on(p)) for p in range(P)]
@@ -301,6 +303,21 @@ def dlrm_shuffle(ctx, reps: int = 10, w: inputs.DLRMWorkload = inputs.DLRMWorklo
     torch.cuda.synchronize()
     rep["fused"] = _stage_report(["fwd_dlrm_shuffle", "bwd_dlrm_shuffle"], [2 * data, 2 * data], rows)
     rep["fused"]["speedup_vs_chain"] = round(rep["end_to_end"]["us"] / rep["fused"]["end_to_end"]["us"], 2)
+    if odd_dim:
+        import dataclasses
+        del bufs
+        torch.cuda.empty_cache()
+        odd = dlrm_shuffle(ctx, reps, dataclasses.replace(w, dim=odd_dim), sets, variants)
+        names = [(k, (k,)) for k in ("fwd_pack_send_order", "fwd_alltoallv", "fwd_unpack_permute", "bwd_pack_permute", "bwd_alltoallv",
+                                     "bwd_unpack_table_order")] + [(k, ("fused", k)) for k in ("fwd_dlrm_shuffle", "bwd_dlrm_shuffle")]
+
+        def at(r, path):
+            for k in path:
+                r = r[k]
+            return r
+        rep["odd_rows"] = {"dim": odd_dim, "row_bytes": odd_dim * 4, "stages": {
+            name: {"us": at(odd, path)["us"], "GBps": at(odd, path).get("GBps"),
+                   "per_byte_vs_aligned": round(at(odd, path)["us"] / at(rep, path)["us"] * D / odd_dim, 2)} for name, path in names}}
     return rep
 
 
@@ -469,7 +486,7 @@ def run_all(ctx) -> Dict:
     torch.cuda.empty_cache()
     out["moe_dispatch_combine"] = moe_dispatch_combine(ctx, odd_hidden=2052)
     torch.cuda.empty_cache()
-    out["dlrm_shuffle"] = dlrm_shuffle(ctx)
+    out["dlrm_shuffle"] = dlrm_shuffle(ctx, odd_dim=130)
     torch.cuda.empty_cache()
     out["grad_buckets"] = grad_buckets(ctx)
     torch.cuda.empty_cache()

@@ -101,7 +101,8 @@ def test_moe_route_zipf_workload():
 @pytest.mark.parametrize("dtype,w", [(mcr.F32, 1), (mcr.F32, 4), (mcr.F32, 128), (mcr.BF16, 5), (mcr.BF16, 8),
                                       (mcr.BF16, 2048), (mcr.BF16, 24), (mcr.F32, 1028), (mcr.BF16, 1040), (mcr.F32, 516),
                                       (mcr.BF16, 8200), (mcr.BF16, 2052), (mcr.BF16, 2049), (mcr.F32, 1027), (mcr.F32, 515),
-                                      (mcr.BF16, 1031)])
+                                      (mcr.BF16, 1031), (mcr.BF16, 1), (mcr.BF16, 33), (mcr.F32, 17), (mcr.F32, 130),
+                                      (mcr.BF16, 1021), (mcr.BF16, 516)])
 def test_pack_unpack_combine(dtype, w):
     P, T, E = 3, 777, 12
     g = np.random.Generator(np.random.Philox(key=w))
@@ -222,6 +223,8 @@ def _moe_pipeline(w: inputs.MoEWorkload, permute=False, check_ranks=None, fused_
 def test_moe_pipeline_small():
     _moe_pipeline(inputs.MoEWorkload(P=4, T=1000, H=72, E=8))
     _moe_pipeline(inputs.MoEWorkload(P=2, T=333, H=7, E=6), permute=True)     # rows not a multiple of 16 bytes
+    _moe_pipeline(inputs.MoEWorkload(P=2, T=333, H=1, E=6), permute=True)     # one element per row
+    _moe_pipeline(inputs.MoEWorkload(P=3, T=200, H=33, E=6), permute=True)
     for v in (0, 1, 4, 7, 10):
         _moe_pipeline(inputs.MoEWorkload(P=4, T=1000, H=72, E=8), fused_variant=v)
     _moe_pipeline(inputs.MoEWorkload(P=16, T=100, H=8, E=16, capacity_factor=0.5))   # heavy dropping, one-vector rows
@@ -299,6 +302,7 @@ def test_moe_by_expert_small():
     _moe_by_expert(inputs.MoEWorkload(P=4, T=1000, H=72, E=8))
     _moe_by_expert(inputs.MoEWorkload(P=2, T=333, H=7, E=6), permute=True)        # rows not a multiple of 16 bytes
     _moe_by_expert(inputs.MoEWorkload(P=2, T=333, H=7, E=6), dtype=mcr.F32)
+    _moe_by_expert(inputs.MoEWorkload(P=2, T=333, H=1, E=6), permute=True)        # one element per row
     for v in (0, 1, 4, 7, 10):
         _moe_by_expert(inputs.MoEWorkload(P=4, T=1000, H=72, E=8), variant=v)
         _moe_by_expert(inputs.MoEWorkload(P=3, T=500, H=256, E=48), variant=v, dtype=mcr.F32)   # rows a wavefront wide
@@ -437,7 +441,9 @@ def test_dlrm_small_closed_form():
 
 def test_dlrm_fused_odd_shapes():
     """Fewer tables than ranks (some ranks own none), rows that are not a multiple of 16 bytes, bf16."""
-    for P, NT, D, B, dtype in ((4, 3, 5, 16, mcr.F32), (8, 26, 12, 64, mcr.BF16), (1, 2, 8, 7, mcr.F32), (3, 7, 128, 9, mcr.BF16)):
+    for P, NT, D, B, dtype in ((4, 3, 5, 16, mcr.F32), (8, 26, 12, 64, mcr.BF16), (1, 2, 8, 7, mcr.F32), (3, 7, 128, 9, mcr.BF16),
+                               (8, 26, 130, 64, mcr.F32), (4, 5, 65, 32, mcr.BF16), (2, 3, 1, 8, mcr.BF16), (3, 4, 1027, 9, mcr.BF16),
+                               (2, 3, 17, 10, mcr.F32), (4, 9, 2052, 8, mcr.BF16)):
         bf = dtype == mcr.BF16
         n_local = [len(range(p, NT, P)) for p in range(P)]
         src = [inputs.normal(max(n_local[p] * B * D, 0), 1300 + NT, p, bf16=bf) for p in range(P)]
