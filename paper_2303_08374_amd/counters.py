@@ -8,8 +8,8 @@
 
 `run` launches, over buffers the caches have not seen (a cursor walking a large arena), `reps`
 times each: first the plain copy of 1 GiB (all_to_all_single at P=1: the kernel of known size that
-every reading is compared with), then for every size of `--mibs` (MiB per rank) the `--ops`, fp32,
-through MCR_AUTO with the shipped tuning table: all_reduce, reduce_scatter, all_to_all_single and
+every reading is compared with), then for every size of `--mibs` (MiB per rank; or `--kibs`) the
+`--ops`, fp32 (`allgather_bf16`: all_gather on bf16), through MCR_AUTO with the shipped tuning table: all_reduce, reduce_scatter, all_to_all_single and
 all_gather at P=8, and two launches that bracket the read / write mix: reduce_scatter at P=16 on
 half the message (16 reads to 1 write) and bcast at P=8 (1 read to 7 writes).  Every launch is one
 kernel, so the dispatches of the library's kernels in a run are this list in this order;
@@ -31,25 +31,33 @@ import re
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-ALL_OPS = ("allreduce", "reduce_scatter", "alltoall", "allgather", "reduce_scatter_P16", "bcast")
+ALL_OPS = ("allreduce", "reduce_scatter", "alltoall", "allgather", "reduce_scatter_P16", "bcast")   # also: "allgather_bf16"
 N_XCD = 8            # GRBM_GUI_ACTIVE is summed over the accelerator dies of the MI355X
 P = 8
 GIB = 1 << 30
 
 
-def plan(ops, mibs, reps):
-    """[(label, algorithmic bytes)] in launch order."""
+def _human(nbytes: int) -> str:
+    return f"{nbytes >> 20} MiB" if nbytes % (1 << 20) == 0 else f"{nbytes >> 10} KiB"
+
+
+def _bytes_of(label: str) -> int:
+    _, n, unit = label.split()
+    return int(n) << (20 if unit == "MiB" else 10)
+
+
+def plan(ops, sizes, reps):
+    """[(label, algorithmic bytes)] in launch order; `sizes` in bytes per rank."""
     out = [("plain copy 1 GiB (all_to_all_single at P=1)", 2 * GIB)] * reps
-    for mib in mibs:
-        M = mib << 20
+    for M in sizes:
         alg = {"allreduce": 2 * P * M, "reduce_scatter": (P + 1) * M, "alltoall": 2 * P * M, "allgather": (P + P * P) * M,
-               "reduce_scatter_P16": 17 * (M // 2), "bcast": P * M}
+               "allgather_bf16": (P + P * P) * M, "reduce_scatter_P16": 17 * (M // 2), "bcast": P * M}
         for op in ops:
-            out += [(f"{op} {mib} MiB", alg[op])] * reps
+            out += [(f"{op} {_human(M)}", alg[op])] * reps
     return out
 
 
-def run(ops, mibs, reps: int) -> int:
+def run(ops, sizes, reps: int) -> int:
     import torch
     from . import inputs, mcr, sweep
     if not torch.cuda.is_available():
@@ -58,8 +66,8 @@ def run(ops, mibs, reps: int) -> int:
     torch.cuda.set_device(0)
     ctx = mcr.mcr_init(0)
     mcr.mcr_tune_load(ctx, mcr.SHIPPED_TABLE)
-    top = max(mibs) << 20
-    need = max(2 * GIB, 2 * P * top, (P + P * P) * top if "allgather" in ops else 0)
+    top = max(sizes)
+    need = max(2 * GIB, 2 * P * top, (P + P * P) * top if any(o.startswith("allgather") for o in ops) else 0)
     arena = sweep.Arena(need + 2 * GIB, seed=inputs.SWEEP_SEED)
     torch.cuda.synchronize()
 
@@ -69,8 +77,7 @@ def run(ops, mibs, reps: int) -> int:
     for _ in range(reps):
         base = arena.take(2 * GIB)
         mcr.mcr_alltoall(ctx, [base + GIB], [base], GIB // 4, mcr.F32, 1, 4)       # v1nt at P=1: a plain copy
-    for mib in mibs:
-        M = mib << 20
+    for M in sizes:
         n = M // 4
         for op in ops:
             for _ in range(reps):
@@ -85,6 +92,9 @@ def run(ops, mibs, reps: int) -> int:
                 elif op == "allgather":
                     base = arena.take(P * M + P * P * M)
                     mcr.mcr_allgather(ctx, ptrs(base + P * M, P, P * M), ptrs(base, P, M), n, mcr.F32, P)
+                elif op == "allgather_bf16":                                       # the table may choose differently per element type
+                    base = arena.take(P * M + P * P * M)
+                    mcr.mcr_allgather(ctx, ptrs(base + P * M, P, P * M), ptrs(base, P, M), M // 2, mcr.BF16, P)
                 elif op == "reduce_scatter_P16":
                     Mh = M // 2                                                    # 16 ranks of half the size: the same input bytes
                     base = arena.take(16 * Mh + Mh)
@@ -95,7 +105,7 @@ def run(ops, mibs, reps: int) -> int:
                     raise SystemExit(f"unknown op {op}")
     torch.cuda.synchronize()
     mcr.mcr_finalize(ctx)
-    print(f"counters run: plain copy + {len(ops)} kinds of launch x {len(mibs)} sizes x {reps}")
+    print(f"counters run: plain copy + {len(ops)} kinds of launch x {len(sizes)} sizes x {reps}")
     return 0
 
 
@@ -137,11 +147,10 @@ def _read(dirs, labels):
     return vals, groups
 
 
-def summarize(dirs, ops, mibs, reps, out_path, traffic_json):
-    labels = plan(ops, mibs, reps)
+def summarize(dirs, ops, sizes, reps, out_path, traffic_json, opts):
+    labels = plan(ops, sizes, reps)
     alg = dict(labels)
     vals, groups = _read(dirs, labels)
-    opts = f"--ops {','.join(ops)} --mibs {','.join(str(m) for m in mibs)} --reps {reps}"
     lines = ["Hardware counters of the library's kernels on one MI355X, fp32, MCR_AUTO with the shipped tuning table, cold buffers.",
              "Commands (from /tmp, TMPDIR=/tmp; rocprofv3 collects one group of counters per run):"]
     for i, g in enumerate(groups):
@@ -183,7 +192,8 @@ def summarize(dirs, ops, mibs, reps, out_path, traffic_json):
     if traffic_json:
         sys.path.insert(0, os.path.dirname(HERE))
         import bench
-        per_size = {str(int(label.split()[1]) << 20): t for label, t in traffic.items() if label.startswith("allgather ")}
+        per_size = {str(_bytes_of(label)): t for label, t in traffic.items()
+                    if label.startswith("allgather") and "superchunk" in vals[label]["kernel"]}
         with open(traffic_json, "w") as f:
             json.dump({"sources_digest": bench.kernel_sources_digest(), "scale": {c: round(s, 5) for c, s in scale.items()},
                        "kernels": {"allgather/superchunk": per_size}}, f, indent=1)
@@ -246,7 +256,8 @@ def main(argv=None) -> int:
     for name in ("run", "summarize"):
         s = sub.add_parser(name)
         s.add_argument("--ops", default=",".join(ALL_OPS))
-        s.add_argument("--mibs", default="256")
+        s.add_argument("--mibs", default="256", help="message sizes per rank in MiB")
+        s.add_argument("--kibs", default=None, help="message sizes per rank in KiB (instead of --mibs)")
         s.add_argument("--reps", type=int, default=3)
         if name == "summarize":
             s.add_argument("dirs", nargs="+")
@@ -255,10 +266,11 @@ def main(argv=None) -> int:
                            help="write the all_gather traffic per message size here, for bench.py's roofline.traffic")
     a = ap.parse_args(argv)
     ops = [o for o in a.ops.split(",") if o]
-    mibs = [int(x) for x in a.mibs.split(",")]
+    sizes = [int(x) << 10 for x in a.kibs.split(",")] if a.kibs else [int(x) << 20 for x in a.mibs.split(",")]
     if a.cmd == "run":
-        return run(ops, mibs, a.reps)
-    return summarize(a.dirs, ops, mibs, a.reps, a.out, a.traffic_json)
+        return run(ops, sizes, a.reps)
+    opts = f"--ops {','.join(ops)} " + (f"--kibs {a.kibs}" if a.kibs else f"--mibs {a.mibs}") + f" --reps {a.reps}"
+    return summarize(a.dirs, ops, sizes, a.reps, a.out, a.traffic_json, opts)
 
 
 if __name__ == "__main__":

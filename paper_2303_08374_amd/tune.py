@@ -25,20 +25,22 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 DEFAULT_TABLE = os.path.join(HERE, "tuning", "mi355x.tbl")
 
 
-def tie_window_us(floor_us: float) -> float:
+def tie_window_us(floor_us: float, graph_timed: bool = False) -> float:
     """Times within this many microseconds of the least one count as a tie (the lowest variant id
     then wins): 2 % of the least time while a launch is shorter than 100 us, 0.5 % from there on
     (where a batch mean repeats to a few tenths of a percent), and never less than half a
-    microsecond, which is what two batches of the same launch-bound kernel differ by."""
-    return max(0.5, floor_us * (0.02 if floor_us < 100.0 else 0.005))
+    microsecond, which is what two batches of the same launch-bound kernel issued from the host
+    differ by; a tenth of a microsecond for a batch replayed from a graph, which repeats to a few
+    hundredths."""
+    return max(0.1 if graph_timed else 0.5, floor_us * (0.02 if floor_us < 100.0 else 0.005))
 
 
-def pick(times_us: dict):
+def pick(times_us: dict, graph_timed: bool = False):
     """The table's choice among {variant: microseconds per launch}, the figures as they are
     recorded (two decimals): least time, ties to the variant listed first (the lowest id)."""
     floor = min(times_us.values())
     for v, t in times_us.items():
-        if t <= floor + tie_window_us(floor):
+        if t <= floor + tie_window_us(floor, graph_timed):
             return v
 
 
@@ -49,6 +51,30 @@ def variants_of(ctx, op_id: int):
     if op_id in (mcr.OP_ALLREDUCE, mcr.OP_REDUCE_SCATTER):
         return [v for v in range(1, n_var) if not 7 <= v <= 12]
     return list(range(1, n_var))
+
+
+GRAPH_BELOW_MS = 0.03
+
+
+def graph_batch_ms(launch, bases) -> float:
+    """Milliseconds per launch of `launch(base, stream)` over `bases`, captured once into a HIP
+    graph (the entry points only enqueue kernels) and replayed: the least of three replays."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        launch(bases[0], None)                                # nothing is loaded for the first time inside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stream = torch.cuda.current_stream().cuda_stream
+        for b in bases:
+            launch(b, stream)
+    graph.replay()
+    torch.cuda.synchronize()
+    ms = min(sweep.time_launches(graph.replay, 1) for _ in range(3)) / len(bases)
+    del graph
+    return ms
 
 
 def reps_for(alg_bytes: int) -> int:
@@ -123,15 +149,15 @@ def names_of(ctx, op_id: int):
 
 
 TIMES_HEADER = ("# every variant's time, in microseconds per launch, behind each row of the tuning table next to it\n"
-                "# (written by python -m paper_2303_08374_amd.tune --times-out): op dtype P bytes chosen | variant=us ...\n")
+                "# (written by python -m paper_2303_08374_amd.tune --times-out): op dtype P bytes chosen how-timed | variant=us ...\n")
 
 
 def write_times(path: str, rows, coarse_vs_fine=None) -> None:
     dt = {mcr.F32: "f32", mcr.BF16: "bf16", mcr.F16: "f16", mcr.I32: "i32"}
     with open(path, "w") as f:
         f.write(TIMES_HEADER)
-        for op, dtype, P, nbytes, best, us in rows:
-            f.write(f"{op} {dt[dtype]} {P} {nbytes} {best} | " + " ".join(f"{k}={v}" for k, v in us.items()) + "\n")
+        for op, dtype, P, nbytes, best, us, *how in rows:
+            f.write(f"{op} {dt[dtype]} {P} {nbytes} {best} {how[0] if how else 'batch'} | " + " ".join(f"{k}={v}" for k, v in us.items()) + "\n")
         if coarse_vs_fine:
             f.write("# one variant per (op, dtype, scale) for every size (the paper's MCR-DL) against one per size (MCR-DL-T):\n"
                     "# sum over the 17 sizes of the time per launch, in microseconds\n")
@@ -141,15 +167,17 @@ def write_times(path: str, rows, coarse_vs_fine=None) -> None:
 
 
 def read_times(path: str):
-    """[(op, dtype name, P, bytes, chosen, {variant name: us})] of a file written by write_times."""
+    """[(op, dtype name, P, bytes, chosen, {variant name: us}, "batch" | "graph")] of a file written by
+    write_times; the last field says how the row's launches were timed (back to back from the host,
+    or replayed from a captured graph)."""
     rows = []
     with open(path) as f:
         for line in f:
             if line.startswith("#") or not line.strip():
                 continue
             head, tail = line.split("|")
-            op, dt, P, nbytes, best = head.split()
-            rows.append((op, dt, int(P), int(nbytes), best, {k: float(v) for k, v in (kv.split("=") for kv in tail.split())}))
+            op, dt, P, nbytes, best, how = head.split()
+            rows.append((op, dt, int(P), int(nbytes), best, {k: float(v) for k, v in (kv.split("=") for kv in tail.split())}, how))
     return rows
 
 
@@ -188,11 +216,19 @@ def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbos
         variants = variants_of(ctx, sweep.OPS[cell.op])
         reps = reps_for(cell.alg_bytes)
         times = {}
+        graph_timed = None
         for v in variants:
             cell.launch(ctx, arena.take(cell.footprint), v)              # first-launch effects out of the way
             ms = sweep.time_launches(lambda: cell.launch(ctx, arena.take(cell.footprint), v), reps)
-            if ms < 0.1:
-                # launch-bound: the least of three batches, which is what the kernel costs when nothing else interferes
+            if graph_timed is None:
+                graph_timed = ms < GRAPH_BELOW_MS                         # one way of timing per cell, decided by its first variant
+            if graph_timed:
+                # the host's cost per call (10 us from Python) hides what a kernel this short takes: time the
+                # same batch replayed from a captured graph, where only the device's own launch floor is left
+                ms = graph_batch_ms(lambda base, stream: cell.launch(ctx, base, v, stream),
+                                    [arena.take(cell.footprint) for _ in range(reps)])
+            elif ms < 0.1:
+                # the least of three batches, which is what the kernel costs when nothing else interferes
                 for _ in range(2):
                     ms = min(ms, sweep.time_launches(lambda: cell.launch(ctx, arena.take(cell.footprint), v), reps))
             times[v] = ms
@@ -200,10 +236,10 @@ def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbos
         # is taken, so that launch-bound sizes do not pick a variant by noise
         names = names_of(ctx, sweep.OPS[cell.op])
         us = {v: round(times[v] * 1e3, 2) for v in variants}              # ascending ids
-        best = pick(us)
+        best = pick(us, graph_timed)
         mcr.mcr_tune_set(ctx, sweep.OPS[cell.op], sweep.DTYPES[cell.dtype], P, cell.M, best)
         full_report.setdefault("_rows", []).append((cell.op, sweep.DTYPES[cell.dtype], P, cell.M, names[best],
-                                                    {names[v]: t for v, t in us.items()}))
+                                                    {names[v]: t for v, t in us.items()}, "graph" if graph_timed else "batch"))
         report["cells"][cell.key] = {
             "alg_bytes": cell.alg_bytes, "best": names[best],
             "us": {names[v]: round(times[v] * 1e3, 3) for v in variants},
@@ -238,7 +274,7 @@ def main(argv=None) -> int:
     ap.add_argument("--report", default=None)
     ap.add_argument("--ranks", default="4,8,16", help="rank counts to tune the swept collectives for")
     ap.add_argument("--max-bytes", type=int, default=inputs.SWEEP_BYTES[-1])
-    ap.add_argument("--arena-gib", type=float, default=4.0)
+    ap.add_argument("--arena-gib", type=float, default=20.0)
     ap.add_argument("--times-out", default=None, help="write every variant's time behind every table row here")
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():

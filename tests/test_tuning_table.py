@@ -30,18 +30,23 @@ def test_tie_window():
     assert tune.pick({"v1": 6.2, "v2": 6.0, "v4": 7.1}) == "v1"
     assert tune.pick({"v1": 6.6, "v2": 6.0, "v4": 7.1}) == "v2"
     assert tune.pick({"v1": 1000.0, "v2": 990.0, "v4": 900.0}) == "v4"
+    assert tune.tie_window_us(4.0, graph_timed=True) == 0.1  # replayed from a graph: a tenth of a microsecond
+    assert tune.pick({"v1": 4.8, "v2": 4.5, "v4": 4.45}, graph_timed=True) == "v2"
+    assert tune.pick({"v1": 4.8, "v2": 4.5, "v4": 4.45}) == "v1"
 
 
 def test_every_table_row_is_the_least_time_of_its_recorded_timings():
     table = _table_rows()
     times = tune.read_times(TIMES)
     assert len(times) == len(table) >= 4 * 2 * 3 * 17           # collectives x dtypes x scales x sizes, plus the workload ops
-    for op, dt, P, nbytes, chosen, us in times:
+    for op, dt, P, nbytes, chosen, us, how in times:
+        assert how in ("batch", "graph")
+        graph_timed = how == "graph"
         key = (op, dt, P, nbytes)
         assert key in table, f"no table row for {key}"
         assert table[key] == chosen, f"{key}: table says {table[key]}, the timing record {chosen}"
         assert chosen in us
-        best = tune.pick(us)
+        best = tune.pick(us, graph_timed)
         assert best == chosen, f"{key}: {chosen} ({us[chosen]} us) is not the pick of {us}"
         floor = min(us.values())
-        assert us[chosen] <= floor + tune.tie_window_us(floor)
+        assert us[chosen] <= floor + tune.tie_window_us(floor, graph_timed)
