@@ -53,10 +53,12 @@ typedef struct mcr_fuse_plan mcr_fuse_plan; /* library-owned: bucket plan + devi
  * arithmetic that wraps (sums and products modulo 2^32; MAX and MIN compare as signed), which
  * does not depend on the order; MCR_AVG of int32 gives MCR_EOP, and the calls that scale rows by
  * a gate weight (mcr_unpack, mcr_moe_combine, mcr_moe_combine_by_expert with a gate or K > 1)
- * give MCR_EDTYPE for it.  The reductions (SUM / AVG) on MCR_F32 and MCR_BF16 are compiled for the
- * plain and the nontemporal shape of every unroll (their "ln" / "sn" variants run the nontemporal
- * one) and for the persistent shape; on MCR_F16 and MCR_I32, and for the other ReduceOps, every
- * vector variant runs the nontemporal shape of its unroll and the persistent one runs "v4nt". */
+ * give MCR_EDTYPE for it.  The reductions (SUM / AVG) on MCR_F32 and MCR_BF16 are compiled for
+ * "v1" with plain accesses, for the nontemporal shape of every unroll ("v2", "v4" and the "ln" /
+ * "sn" variants run the nontemporal kernel of their unroll: the other hint combinations won no row
+ * of the tuning table) and for "pk8" and "w64"; on MCR_F16 and MCR_I32, and for the other
+ * ReduceOps, every vector variant runs one shape ("v2nt").  mcr_allreduce_multi is compiled for
+ * plain and for nontemporal accesses; its "ln" / "sn" variants run the nontemporal kernel. */
 typedef enum { MCR_F32 = 0, MCR_BF16 = 1, MCR_F16 = 2, MCR_I32 = 3 } mcr_dtype;
 
 /* ReduceOp of the API listing; every op runs as a left-to-right chain in rank order in

@@ -194,11 +194,9 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
   return dispatch_ranks(P, [&](auto pp) {
     constexpr int kP = decltype(pp)::value;
     if (op > MCR_AVG || !all_shapes(DT)) {
-      return dispatch_unroll(variant, [&](auto uu) {
-        hipLaunchKernelGGL((allreduce_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx), dim3(kBlock), 0,
-                           stream, bufs, nvec, count, scale, op, root, head);
-        return launch_status();
-      });
+      hipLaunchKernelGGL((allreduce_vec<DT, kP, kGenericUnroll, true, true, true>), dim3(grid_x(nvec, kGenericShape)), dim3(kBlock), 0,
+                         stream, bufs, nvec, count, scale, op, root, head);
+      return launch_status();
     }
     if constexpr (all_shapes(DT)) {
       return dispatch_reduce_shape(variant, [&](auto uu, auto nt) {

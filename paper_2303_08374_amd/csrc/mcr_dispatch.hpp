@@ -42,7 +42,7 @@ inline int dispatch_float_dtype(int dtype, F&& f) {
 }
 
 // The reductions on the hot element types get every launch shape; on fp16 and int32 they are
-// compiled like the generic ReduceOps, for the variant's unroll with nontemporal loads and stores.
+// compiled like the generic ReduceOps: one shape, two vectors per thread, nontemporal loads and stores.
 constexpr bool all_shapes(int dtype) { return dtype == MCR_F32 || dtype == MCR_BF16; }
 
 // f(Int<U>, Bool<NT loads>, Bool<NT stores>) for the vector launch shapes
@@ -65,17 +65,17 @@ inline int dispatch_shape(int variant, F&& f) {
   return MCR_EVARIANT;
 }
 
-// The reductions are compiled for the plain and the fully nontemporal shape of each unroll; their
-// "ln" and "sn" variants (which won no cell of any tuning run) run the nontemporal one.
+// The reductions are compiled for one plain shape (one vector per thread, what short messages take)
+// and the fully nontemporal shape of each unroll; the ids of the other hint combinations ("v2", "v4",
+// "ln", "sn"), which won no row of the tuning table at any scale, run the nontemporal kernel of
+// their unroll.
 template <class F>
 inline int dispatch_reduce_shape(int variant, F&& f) {
   switch (variant) {
     case SV_V1: return f(Int<1>{}, Bool<false>{});
-    case SV_V2: return f(Int<2>{}, Bool<false>{});
-    case SV_V4: return f(Int<4>{}, Bool<false>{});
     case SV_V1NT: case SV_V1LN: case SV_V1SN: return f(Int<1>{}, Bool<true>{});
-    case SV_V2NT: case SV_V2LN: case SV_V2SN: return f(Int<2>{}, Bool<true>{});
-    case SV_V4NT: case SV_V4LN: case SV_V4SN: return f(Int<4>{}, Bool<true>{});
+    case SV_V2: case SV_V2NT: case SV_V2LN: case SV_V2SN: return f(Int<2>{}, Bool<true>{});
+    case SV_V4: case SV_V4NT: case SV_V4LN: case SV_V4SN: return f(Int<4>{}, Bool<true>{});
   }
   return MCR_EVARIANT;
 }

@@ -188,11 +188,14 @@ int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, 
           hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
           return launch_status();
         }
-        return dispatch_hint(variant, [&](auto ntl, auto nts) {
-          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, decltype(ntl)::value, decltype(nts)::value, false, false>), dim3(c1 - c0),
-                             dim3(kBlock), 0, stream, d, c0, scale, op);
-          return launch_status();
-        });
+        // plain or fully nontemporal: the ids with one-sided hints run the nontemporal kernel, as in the reductions
+        if (variant == SV_V1 || variant == SV_V2 || variant == SV_V4)
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, false, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0,
+                             scale, op);
+        else
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, true, false, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0,
+                             scale, op);
+        return launch_status();
       } else {
         return static_cast<int>(MCR_EVARIANT);          // not reached: taken by the branch above
       }

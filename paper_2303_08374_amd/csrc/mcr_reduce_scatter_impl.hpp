@@ -147,11 +147,9 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
   return dispatch_ranks(P, [&](auto pp) {
     constexpr int kP = decltype(pp)::value;
     if (op > MCR_AVG || !all_shapes(DT)) {
-      return dispatch_unroll(variant, [&](auto uu) {
-        hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, decltype(uu)::value, true, true, true>), dim3(gx, P), dim3(kBlock), 0,
-                           stream, out, in, bvec, scale, op);
-        return launch_status();
-      });
+      hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, kGenericUnroll, true, true, true>), dim3(grid_x(bvec, kGenericShape), P), dim3(kBlock),
+                         0, stream, out, in, bvec, scale, op);
+      return launch_status();
     }
     if constexpr (all_shapes(DT)) {
       return dispatch_reduce_shape(variant, [&](auto uu, auto nt) {

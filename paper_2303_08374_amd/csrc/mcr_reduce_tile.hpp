@@ -132,16 +132,10 @@ inline unsigned persistent_grid(int n_cu, int slices) {
   return static_cast<unsigned>(g < 1 ? 1 : g);
 }
 
-// The launch shapes the generic-op kernels are compiled for: the variant's unroll, nontemporal
-// loads and stores.  f(Int<U>)
-template <class F>
-inline int dispatch_unroll(int variant, F&& f) {
-  switch (shape_unroll(variant)) {
-    case 2: return f(Int<2>{});
-    case 4: return f(Int<4>{});
-  }
-  return f(Int<1>{});
-}
+// The one launch shape the generic-op kernels (MAX, MIN, PROD; fp16 and int32) are compiled for: two
+// vectors per thread, nontemporal loads and stores, whatever vector variant was asked for.
+constexpr int kGenericUnroll = 2;
+constexpr int kGenericShape = SV_V2NT;
 
 // 16-byte pieces each thread of an element-path reduction kernel works on at a time.
 constexpr int kScalarUnroll = 2;

@@ -46,10 +46,10 @@ def pick(times_us: dict, graph_timed: bool = False):
 
 def variants_of(ctx, op_id: int):
     """The variants worth timing for an op: every 128-bit shape (the element path is only the
-    fallback); for the reductions not the "ln" / "sn" ids, which run the "nt" kernels."""
+    fallback); for the reductions not the "v2", "v4", "ln" and "sn" ids, which run the "nt" kernels."""
     n_var = len(mcr.mcr_get_variants(ctx, op_id))
     if op_id in (mcr.OP_ALLREDUCE, mcr.OP_REDUCE_SCATTER):
-        return [v for v in range(1, n_var) if not 7 <= v <= 12]
+        return [v for v in range(1, n_var) if v not in (2, 3) and not 7 <= v <= 12]
     return list(range(1, n_var))
 
 
@@ -118,16 +118,19 @@ def tune_workload_ops(ctx, verbose: bool = True):
         for part in path.split("/"):
             rep = rep[part]
         return rep["us"]
+    # the multi-tensor all_reduce has two kernels, plain and nontemporal: the other ids run the second one
+    distinct = {mcr.OP_ALLREDUCE_MULTI: (1, 4)}
     report = {}
     for label, runner, ops, dtype, P, nbytes in plans:
         times = {op: {} for op in ops}
         for v in variants:
             rep = runner({key_of[op]: v for op in ops})
             for op, stages in ops.items():
-                times[op][v] = sum(stage_us(rep, st) for st in stages)
+                if v in distinct.get(op, variants):
+                    times[op][v] = sum(stage_us(rep, st) for st in stages)
             torch.cuda.empty_cache()
         for op in ops:
-            us = {v: round(times[op][v], 2) for v in variants}
+            us = {v: round(t, 2) for v, t in times[op].items()}
             best = pick(us)
             mcr.mcr_tune_set(ctx, op, dtype, P, nbytes, best)
             report.setdefault("_rows", []).append((mcr.OP_NAMES[op], dtype, P, nbytes, names[best],
