@@ -58,6 +58,45 @@ def _starts(n, rng, extra=()):
     return sorted({min(max(c, 0), n - W) for c in cand})
 
 
+@pytest.mark.parametrize("ranks", [8, 16, 6])
+@pytest.mark.parametrize("dtype", [mcr.F32, mcr.BF16])
+def test_rows_of_the_shipped_table_whole_outputs(tuned_ctx, dtype, ranks):
+    """MCR_AUTO with the shipped table at small and middle sizes, every element against the oracle:
+    the rows of a tuned scale (8, 16) and of a scale that borrows its neighbour's table (6); sizes
+    a little off the table's own so that tails are in play."""
+    bf = dtype == mcr.BF16
+    eb = 2 if bf else 4
+    for M in (4 << 10, 72 << 10, (1 << 20) + 4 * ranks * eb, 3 << 20, 8 << 20, (16 << 20) + 16 * ranks):
+        n = M // eb // ranks * ranks
+        host = [inputs.uniform_pm1(n, 4100 + ranks, p, bf16=bf) for p in range(ranks)]
+        names = {op: mcr.mcr_get_variants(tuned_ctx, op)[mcr.mcr_auto_variant(tuned_ctx, op, dtype, ranks, n * eb, True)]
+                 for op in (mcr.OP_ALLREDUCE, mcr.OP_REDUCE_SCATTER, mcr.OP_ALLGATHER, mcr.OP_ALLTOALL)}
+        what = f"P={ranks} M={n * eb} dtype={dtype} table picks {names}"
+        d_in = [gu.to_dev(h) for h in host]
+        d_out = [gu.dev_empty(n // ranks, dtype, 1) for _ in range(ranks)]
+        mcr.mcr_reduce_scatter(tuned_ctx, d_out, d_in, n, dtype, mcr.SUM, ranks)
+        exp = oracle.reduce_scatter(host, dtype)
+        for r in range(ranks):
+            gu.assert_reduced_equal(gu.to_host(d_out[r], gu.NPDT[dtype]), exp[r], dtype, "reduce_scatter " + what)
+        d_out = [gu.dev_empty(n, dtype, 1) for _ in range(ranks)]
+        mcr.mcr_alltoall(tuned_ctx, d_out, d_in, n, dtype, ranks)
+        exp = oracle.alltoall(host, dtype)
+        for r in range(ranks):
+            gu.assert_bits_equal(gu.to_host(d_out[r], gu.NPDT[dtype]), exp[r], "alltoall " + what)
+        if n * eb * ranks * ranks <= (1 << 30):
+            d_out = [gu.dev_empty(n * ranks, dtype, 1) for _ in range(ranks)]
+            mcr.mcr_allgather(tuned_ctx, d_out, d_in, n, dtype, ranks)
+            exp = oracle.allgather(host, dtype)
+            for r in range(ranks):
+                gu.assert_bits_equal(gu.to_host(d_out[r], gu.NPDT[dtype]), exp[r], "allgather " + what)
+            del d_out, exp
+        mcr.mcr_allreduce(tuned_ctx, d_in, n, dtype, mcr.SUM, ranks)
+        bufs = [h.copy() for h in host]
+        oracle.allreduce(bufs, dtype)
+        for r in range(ranks):
+            gu.assert_reduced_equal(gu.to_host(d_in[r], gu.NPDT[dtype]), bufs[r], dtype, "allreduce " + what)
+
+
 @pytest.mark.parametrize("M", [64 << 20, 256 << 20])
 @pytest.mark.parametrize("dtype", [mcr.F32, mcr.BF16])
 def test_sweep_ops_sampled(tuned_ctx, dtype, M):
