@@ -289,29 +289,26 @@ const char* mcr_strerror(int status) {
 
 int mcr_init(mcr_ctx** out, int device) {
   if (!out || device < MCR_NO_DEVICE) return MCR_EINVAL;
-  if (device != MCR_NO_DEVICE) {
-    int count = 0;
-    if (hipGetDeviceCount(&count) != hipSuccess) return MCR_EHIP;
-    if (device >= count) return MCR_EINVAL;
-    if (hipSetDevice(device) != hipSuccess) return MCR_EHIP;
-  }
-  if (device != MCR_NO_DEVICE) {
-    // the static scratch array of mcr_moe_route_static: its address on this device, looked up
-    // here so that the entry point itself does nothing but launch
-    int32_t* unused = nullptr;
-    const int rc = route_scratch_address(device, &unused);
-    if (rc != MCR_OK) return rc;
-  }
   mcr_ctx* ctx = new (std::nothrow) mcr_ctx;
   if (!ctx) return MCR_ENOMEM;
   ctx->device = device;
   if (device != MCR_NO_DEVICE) {
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess) { delete ctx; return MCR_EHIP; }
+    if (device >= count) { delete ctx; return MCR_EINVAL; }
+    DeviceScope on_device(ctx);                          // the caller's current device is put back on return
+    int rc = on_device.status();
+    // the static scratch array of mcr_moe_route_static: its address on this device, looked up
+    // here so that the entry point itself does nothing but launch
+    int32_t* unused = nullptr;
+    if (rc == MCR_OK) rc = route_scratch_address(device, &unused);
+    if (rc == MCR_OK && hipMalloc(reinterpret_cast<void**>(&ctx->pair_ring), kPairRingSlots * sizeof(PairSlot)) != hipSuccess) {
+      ctx->pair_ring = nullptr;
+      rc = MCR_EHIP;
+    }
+    if (rc != MCR_OK) { delete ctx; return rc; }
     int n_cu = 0;
     if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && n_cu > 0) ctx->n_cu = n_cu;
-    if (hipMalloc(reinterpret_cast<void**>(&ctx->pair_ring), kPairRingSlots * sizeof(PairSlot)) != hipSuccess) {
-      delete ctx;
-      return MCR_EHIP;
-    }
   }
   const char* path = std::getenv("MCR_TUNING_TABLE");
   if (path && *path) (void)mcr_tune_load(ctx, path);   // an unreadable file leaves the table empty

@@ -246,21 +246,25 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
   const int64_t* S = DEV ? ds : hs.s;
   // strides of the sender and the receiver index in the matrix as stored
   const int sp = (DEV && tr) ? 1 : P, sr = (DEV && tr) ? P : 1;
-  uint64_t rows = clamp_split(S[p * sp + r * sr], in_rows);
-  if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;      // the common early exit
-  uint64_t sdispl = 0, rdispl = 0;
+  uint64_t rows, sdispl = 0, rdispl = 0;
   if constexpr (DEV) {
-    // The two displacements: lane q of every wavefront loads the q-th entry of row p (counted when
-    // q < r) and of column r (counted when q < p), both loads go out together, and a butterfly over
-    // the 16 lanes adds them up.  (A loop of uniform loads costs one memory round trip per entry, up
-    // to 2 * (P - 1) of them in a row, before the first byte is copied.)
+    // One memory round trip for everything the workgroup needs from the matrix: lane q of every
+    // wavefront loads the q-th entry of row p and of column r, both loads go out together; the
+    // pair's own length is lane r's row entry, the two displacements are the sums over the lanes
+    // below r (row) and below p (column), added up by a butterfly over the 16 lanes.  (A loop of
+    // uniform loads costs one round trip per entry, up to 2 * (P - 1) of them in a row.)
     // same_src: every receiver gets the sender's rows from row 0 on (all_gatherv, bcast)
     const int lane = static_cast<int>(__lane_id());
-    uint64_t a = 0, b = 0;
+    uint64_t row_e = 0, col_e = 0;
     if (lane < P) {
-      if (!same_src && lane < r) a = clamp_split(ds[p * sp + lane * sr], in_rows);
-      if (lane < p) b = clamp_split(ds[lane * sp + r * sr], in_rows);
+      row_e = clamp_split(ds[p * sp + lane * sr], in_rows);
+      col_e = clamp_split(ds[lane * sp + r * sr], in_rows);
     }
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<uint32_t>(row_e), r);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<uint32_t>(row_e >> 32), r);
+    rows = (static_cast<uint64_t>(hi) << 32) | lo;
+    if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;    // the common early exit
+    uint64_t a = (!same_src && lane < r) ? row_e : 0, b = lane < p ? col_e : 0;
 #pragma unroll
     for (int d = MCR_MAX_RANKS / 2; d >= 1; d >>= 1) {
       a += __shfl_xor(static_cast<unsigned long long>(a), d);
@@ -273,6 +277,8 @@ alltoallv_kernel(PtrTab out, CPtrTab in, SplitArg hs, const int64_t* ds, int P, 
   } else {
     // a host matrix normally goes through the pair-table kernel; this is the fallback for pairs too
     // long for its 32-bit offsets
+    rows = clamp_split(S[p * P + r], in_rows);
+    if (static_cast<uint64_t>(blockIdx.x) * kTile >= rows * upr) return;
     if (!same_src)
       for (int q = 0; q < r; ++q) sdispl += clamp_split(S[p * P + q], in_rows);
     for (int q = 0; q < p; ++q) rdispl += clamp_split(S[q * P + r], in_rows);
