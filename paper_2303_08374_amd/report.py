@@ -113,6 +113,12 @@ def _stage_lines(st: dict):
         + "; ".join(f"{human(int(k))}: dispatch layer alone {v['dispatch_only_us']} us per call = "
                     f"{round(100 * v['dispatch_only_us'] / min(v['auto_us'], v['direct_us']), 2)} % of one operation; end to end through the entry point vs "
                     f"bare launches {v['auto_us']} vs {v['direct_us']} us" for k, v in st["dispatch_overhead_alltoall"].items()),
+    ]
+    rc = st.get("rooted_collectives")
+    if rc:
+        lines.append(f"- rooted and vector collectives (P={rc['P']}, fp32, {human(rc['bytes_per_rank'])} per rank, cold buffers): " +
+                     "; ".join(f"{k} {_sg(rc[k])}" for k in ("reduce", "bcast", "gather", "scatter", "allgatherv")))
+    lines += [
         f"- HIP graph: the {gr['launches']} sweep cells of at most 1 MiB per rank issued call by call from Python {gr['eager_us']} us "
         f"({gr['eager_us_per_launch']} us per launch), replayed from one captured graph {gr['graph_us']} us ({gr['graph_us_per_launch']} us per launch)",
     ]

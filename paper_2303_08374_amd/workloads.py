@@ -481,6 +481,43 @@ def graph_replay(ctx, P: int = inputs.SWEEP_P, max_bytes: int = 1 << 20, reps: i
             "graph_us_per_launch": round(graph_ms * 1e3 / len(cells), 2), "speedup": round(eager_ms / graph_ms, 2)}
 
 
+def rooted_collectives(ctx, P: int = inputs.SWEEP_P, M: int = 32 << 20, reps: int = 12) -> Dict:
+    """reduce, bcast, gather, scatter and all_gatherv (the rooted and vector collectives of the API
+    listing) on fp32 messages of `M` bytes per rank over cold buffers: a batch of `reps` launches
+    back to back, microseconds per launch and GB/s of the bytes the operation has to move."""
+    from . import sweep
+    n = M // 4
+    arena = sweep.Arena(max(20 * (P + P * P) * M // 8, 4 << 30), seed=inputs.SWEEP_SEED)
+
+    def ptrs(base, k, nbytes):
+        return [base + i * nbytes for i in range(k)]
+
+    def reduce_():
+        mcr.mcr_reduce(ctx, ptrs(arena.take(P * M), P, M), n, mcr.F32, mcr.SUM, 0, P)
+
+    def bcast():
+        mcr.mcr_bcast(ctx, ptrs(arena.take(P * M), P, M), n, mcr.F32, 0, P)
+
+    def gather():
+        base = arena.take(2 * P * M)
+        mcr.mcr_gather(ctx, base + P * M, ptrs(base, P, M), n, mcr.F32, P)
+
+    def scatter():
+        base = arena.take(2 * P * M)
+        mcr.mcr_scatter(ctx, ptrs(base + P * M, P, M), base, n, mcr.F32, P)
+
+    def allgatherv():
+        base = arena.take(P * M + P * P * M)
+        mcr.mcr_allgatherv(ctx, ptrs(base + P * M, P, P * M), ptrs(base, P, M), [n] * P, mcr.F32, P)
+    out = {"P": P, "bytes_per_rank": M}
+    for name, fn, alg in (("reduce", reduce_, (P + 1) * M), ("bcast", bcast, P * M), ("gather", gather, 2 * P * M),
+                          ("scatter", scatter, 2 * P * M), ("allgatherv", allgatherv, (P + P * P) * M)):
+        fn()
+        ms = sweep.time_launches(fn, reps)
+        out[name] = {"us": round(ms * 1e3, 2), "alg_bytes": alg, "GBps": round(alg / (ms * 1e-3) / 1e9, 1)}
+    return out
+
+
 def run_all(ctx) -> Dict:
     out = {"allreduce_small": allreduce_small(ctx)}
     torch.cuda.empty_cache()
@@ -495,6 +532,8 @@ def run_all(ctx) -> Dict:
     out["dispatch_overhead_alltoall"] = dispatch_overhead(ctx)
     torch.cuda.empty_cache()
     out["small_cells_graph_replay"] = graph_replay(ctx)
+    torch.cuda.empty_cache()
+    out["rooted_collectives"] = rooted_collectives(ctx)
     torch.cuda.empty_cache()
     torch.cuda.empty_cache()
     return out
