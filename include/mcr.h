@@ -339,7 +339,12 @@ int mcr_unpack(mcr_ctx* ctx, void* const* out, const void* const* in, const int3
  * p and token t with 0 <= slot[p][t] < T, the token row is written to row
  * rdispl[r][p] + (slot - sdispl[p][r]) of recv[r], r being the rank whose block of rank
  * p's packed order holds that slot.  Rows that would fall outside recv_rows are skipped;
- * other rows of recv are left untouched.  splits: DEVICE memory, P*P int64. */
+ * other rows of recv are left untouched.  splits: DEVICE memory, P*P int64.
+ * On rows wider than 2 KiB this call and mcr_moe_combine launch two kernels: a one-workgroup
+ * kernel turns `splits` into displacement tables in the next of the context's 64 table slots
+ * (device memory the context owns), and the row kernel reads them.  Both are ordered on
+ * `stream`; only more than 64 such calls in flight at once on different streams would meet in
+ * one slot.  A captured graph keeps the slot it was captured with. */
 int mcr_moe_dispatch(mcr_ctx* ctx, void* const* recv, const void* const* tokens,
                      const int32_t* const* slot, const int64_t* splits, size_t T, size_t recv_rows,
                      size_t row_elems, mcr_dtype dtype, int P, int variant, void* stream);
@@ -376,8 +381,8 @@ int mcr_moe_expert_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int
  * local expert, token order).  With S[p][r] = sum of counts[p][e] over the experts of rank r:
  *   row_table[p*E + e] = sum_{q<p} S[q][e/(E/P)] - sum_{r'<e/(E/P)} S[p][r'].
  * mcr_moe_dispatch_by_expert / mcr_moe_combine_by_expert fed this table move the same rows to the
- * same places as mcr_moe_dispatch / mcr_moe_combine, bit for bit, with the faster kernels of the
- * table-driven calls.  Arguments as for mcr_moe_expert_layout. */
+ * same places as mcr_moe_dispatch / mcr_moe_combine, bit for bit (for a caller that keeps the
+ * table over several calls).  Arguments as for mcr_moe_expert_layout. */
 int mcr_moe_source_layout(mcr_ctx* ctx, const int32_t* const* counts, int E, int P,
                           int64_t* row_table, void* stream);
 
