@@ -158,7 +158,11 @@ int mcr_reduce_scatter(mcr_ctx* ctx, void* const* out, const void* const* in, si
                        mcr_dtype dtype, mcr_redop op, int P, int variant, void* stream);
 
 /* all_gather (API listing; Table II is its tuning table).  in[p]: `count`
- * elements; out[r]: P*count elements, out[r][p*count + j] = in[p][j].  Bit copy. */
+ * elements; out[r]: P*count elements, out[r][p*count + j] = in[p][j].  Bit copy.
+ * Variants beyond the common launch shapes: "sc4", "sc8", "sc16" copy one super-chunk of 4, 8 or
+ * 16 MiB of a source to one destination after the other (one read and one write stream at a time,
+ * the re-reads served by the cache); "sc16x" is "sc16" with the tiles of a super-chunk dealt to the
+ * 8 XCDs in contiguous units of 512 KiB. */
 int mcr_allgather(mcr_ctx* ctx, void* const* out, const void* const* in, size_t count,
                   mcr_dtype dtype, int P, int variant, void* stream);
 

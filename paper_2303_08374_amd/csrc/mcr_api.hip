@@ -14,7 +14,7 @@
 namespace mcr {
 
 const char* const kStreamVariantNames[AG_COUNT] = {"scalar", "v1", "v2", "v4", "v1nt", "v2nt", "v4nt", "v1ln", "v2ln", "v4ln",
-                                                   "v1sn", "v2sn", "v4sn", "sc4", "sc8", "sc16"};
+                                                   "v1sn", "v2sn", "v4sn", "sc4", "sc8", "sc16", "sc16x"};
 
 const char* const kReduceVariantNames[RV_COUNT - SV_COUNT] = {"pk8", "w64"};
 const char* const kAlltoallVariantNames[A2A_COUNT - SV_COUNT] = {"flat", "w64", "lds"};

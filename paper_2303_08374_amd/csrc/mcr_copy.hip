@@ -147,12 +147,22 @@ allgather_kernel(PtrTab out, CPtrTab in, size_t m) {
 // served by the last-level cache (plain loads); the stores are nontemporal so they
 // do not push it out.  HBM traffic stays at one read and P writes per unit.
 __global__ void __launch_bounds__(kBlock)
-allgather_superchunk_kernel(PtrTab out, CPtrTab in, size_t mvec, unsigned bpc, unsigned P) {
+allgather_superchunk_kernel(PtrTab out, CPtrTab in, size_t mvec, unsigned bpc, unsigned P, unsigned unit_shift) {
   const unsigned p = blockIdx.y;
   const unsigned per_sc = P * bpc;
   const size_t sc = blockIdx.x / per_sc;
   const unsigned rem = blockIdx.x - static_cast<unsigned>(sc * per_sc);
-  const unsigned r = rem / bpc, j = rem - r * bpc;
+  const unsigned r = rem / bpc;
+  unsigned j = rem - r * bpc;
+  if (unit_shift) {
+    // Workgroups are dealt to the 8 XCDs in turn; within every group of 8 << unit_shift tiles, the
+    // tiles are renumbered so that the workgroups of one XCD cover one contiguous unit of
+    // 1 << unit_shift tiles instead of every eighth tile.  Still the same XCD for a tile whatever
+    // the destination (bpc is a multiple of the group), so the re-reads find it in that XCD's L2.
+    const unsigned span = 8u << unit_shift;
+    const unsigned within = j & (span - 1);
+    j = (j - within) + ((within & 7u) << unit_shift) + (within >> 3);
+  }
   const size_t idx = (sc * bpc + j) * static_cast<size_t>(kBlock) + threadIdx.x;
   if (idx >= mvec) return;
   const u32x4 v = load16<false>(in.p[p], idx);
@@ -327,12 +337,18 @@ struct SharedSegments {
 };
 
 __global__ void __launch_bounds__(kBlock)
-alltoallv_pairs_superchunk_kernel(SharedSegments a, unsigned bpc, unsigned R) {
+alltoallv_pairs_superchunk_kernel(SharedSegments a, unsigned bpc, unsigned R, unsigned unit_shift) {
   const unsigned y = blockIdx.y;
   const unsigned per_sc = R * bpc;                       // R: the most receivers any sender has
   const size_t sc = blockIdx.x / per_sc;
   const unsigned rem = blockIdx.x - static_cast<unsigned>(sc * per_sc);
-  const unsigned r = rem / bpc, j = rem - r * bpc;
+  const unsigned r = rem / bpc;
+  unsigned j = rem - r * bpc;
+  if (unit_shift) {                                      // contiguous units per XCD, as in all_gather's "sc16x"
+    const unsigned span = 8u << unit_shift;
+    const unsigned within = j & (span - 1);
+    j = (j - within) + ((within & 7u) << unit_shift) + (within >> 3);
+  }
   const u32x4* src = a.src[y];
   u32x4* dst = a.dst[y * MCR_MAX_RANKS + r];
   const size_t idx = (sc * bpc + j) * static_cast<size_t>(kBlock) + threadIdx.x;
@@ -366,7 +382,7 @@ int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t coun
     });
   }
   const size_t mvec = count / per_vec(dtype);
-  if (variant >= AG_SC4 && variant <= AG_SC16) {
+  if (variant >= AG_SC4 && variant <= AG_SC16X) {
     const size_t sc_bytes = (variant == AG_SC4 ? 4u : variant == AG_SC8 ? 8u : 16u) << 20;
     const size_t nblk = (mvec + kBlock - 1) / kBlock;                    // tiles of 4 KiB per source
     size_t bpc = sc_bytes / (kBlock * 16);
@@ -374,8 +390,12 @@ int launch_allgather(mcr_ctx*, const PtrTab& out, const CPtrTab& in, size_t coun
     const size_t nsc = (nblk + bpc - 1) / bpc;
     const size_t gx = nsc * bpc * static_cast<size_t>(P);
     if (gx > 0x7fffffffull) return MCR_EVARIANT;
+    // "sc16x": units of 512 KiB per XCD (2.92 against 3.01 ms at 256 MiB per rank, P=8; units of 64 or
+    // 128 KiB are a third slower, 1 MiB the same); needs super-chunks made of whole groups
+    unsigned unit_shift = variant == AG_SC16X ? 7u : 0u;
+    if (bpc % (8u << unit_shift) != 0) unit_shift = 0;
     hipLaunchKernelGGL(allgather_superchunk_kernel, dim3(static_cast<unsigned>(gx), P), dim3(kBlock), 0, stream, out, in,
-                       mvec, static_cast<unsigned>(bpc), static_cast<unsigned>(P));
+                       mvec, static_cast<unsigned>(bpc), static_cast<unsigned>(P), unit_shift);
     return launch_status();
   }
   const unsigned gx = grid_x(mvec, variant);
@@ -549,8 +569,9 @@ int launch_alltoallv_pairs(mcr_ctx*, const PtrTab& out, const CPtrTab& in, const
       const size_t nsc = (nblk + bpc - 1) / bpc;
       const size_t gx = nsc * bpc * static_cast<size_t>(most);
       if (gx <= 0x7fffffffull) {
+        const unsigned unit_shift = bpc % (8u << 7) == 0 ? 7u : 0u;
         hipLaunchKernelGGL(alltoallv_pairs_superchunk_kernel, dim3(static_cast<unsigned>(gx), n_senders), dim3(kBlock), 0,
-                           stream, seg, static_cast<unsigned>(bpc), most);
+                           stream, seg, static_cast<unsigned>(bpc), most, unit_shift);
         return launch_status();
       }
     }

@@ -31,8 +31,10 @@ enum StreamVariant {
 };
 // all_gather only: "scN" walks the message in super-chunks of N MiB per source and
 // copies each super-chunk to one destination after the other, so that at any
-// moment the chip streams from one source region into one destination region.
-enum AllgatherVariant { AG_SC4 = 13, AG_SC8 = 14, AG_SC16 = 15, AG_COUNT = 16 };
+// moment the chip streams from one source region into one destination region.  "sc16x" is "sc16"
+// with the tiles of a super-chunk renumbered so that each of the 8 XCDs works through contiguous
+// units of 512 KiB.
+enum AllgatherVariant { AG_SC4 = 13, AG_SC8 = 14, AG_SC16 = 15, AG_SC16X = 16, AG_COUNT = 17 };
 // all_reduce, reduce and reduce_scatter only: the persistent form "pk8", one workgroup of 1024
 // threads per compute unit walking a contiguous run of the message in rounds of 8 steps of one
 // vector per thread.  SUM / AVG on fp32 and bf16; other ReduceOps and element types run "v4nt" in

@@ -163,10 +163,12 @@ def test_sweep_ops_sampled(tuned_ctx, dtype, M):
                            ins[0].view(torch.int16 if dtype == mcr.BF16 else torch.int32))
 
 
-@pytest.mark.parametrize("variant,mib", [(13, 9), (14, 20), (15, 40)])
+@pytest.mark.parametrize("variant,mib", [(13, 9), (14, 20), (15, 40), (16, 40), (16, 7)])
 def test_allgather_superchunk_forms_with_several_superchunks(variant, mib):
-    """The super-chunk forms of all_gather (4, 8 and 16 MiB per source and super-chunk) on messages
-    of two super-chunks and a ragged third one, every element against the oracle."""
+    """The super-chunk forms of all_gather (4, 8 and 16 MiB per source and super-chunk; 16 MiB with
+    the tiles renumbered in units per XCD) on messages of two super-chunks and a ragged third one,
+    and the renumbering form on a message shorter than one group of units (where it must fall back),
+    every element against the oracle."""
     Pn = 2
     n = ((mib << 20) + 4096 + 48) // 4                                  # fp32 elements: not a whole tile either
     host = inputs.rank_buffers(Pn, n, seed=4400 + variant, dist="uniform")
