@@ -148,7 +148,10 @@ const char* mcr_strerror(int status);
  * Two variants beyond the common launch shapes (all_reduce, reduce, reduce_scatter): "pk8", a
  * persistent form with one workgroup of 1024 threads per compute unit, each walking a contiguous
  * run of the message in rounds (read and reduce 8 steps of one vector per thread, then store
- * them), and "w64", workgroups of one wavefront with two vectors per thread. */
+ * them), and "w64", workgroups of one wavefront with two vectors per thread.  The ids behind them,
+ * named "<shape>.x<KiB>" ("v1nt.x1024", "w64.x512", ...), run that shape with its tiles dealt to
+ * the 8 XCDs in contiguous units of that many KiB of every rank buffer instead of every eighth
+ * tile; which of them wins depends on the message size, and the tuning table chooses. */
 int mcr_allreduce(mcr_ctx* ctx, void* const* bufs, size_t count, mcr_dtype dtype,
                   mcr_redop op, int P, int variant, void* stream);
 

@@ -45,12 +45,12 @@ __device__ __forceinline__ void allreduce_edges(const PtrTab& bufs, const CPtrTa
 
 template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC, int BS = kBlock>
 __global__ void __launch_bounds__(BS)
-allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root, unsigned head) {
+allreduce_vec(PtrTab bufs, size_t nvec, size_t count, float scale, int op, int root, unsigned head, unsigned unit_shift) {
   constexpr size_t kTile = static_cast<size_t>(U) * BS;
   CPtrTab in;
 #pragma unroll
   for (int p = 0; p < P; ++p) in.p[p] = bufs.p[p];
-  const size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
+  const size_t tile = static_cast<size_t>(xcd_unit_tile(blockIdx.x, unit_shift)) * kTile;
   if (tile < nvec) {
     u32x4 out[U];
     const bool full = tile + kTile <= nvec;
@@ -145,6 +145,11 @@ template <int DT>
 int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op, int P, int root, int variant, int n_cu,
                         hipStream_t stream) {
   const float scale = 1.0f / static_cast<float>(P);
+  unsigned unit_kib = 0;
+  if (variant >= RV_XUNIT0) {
+    unit_kib = kReduceUnitVariants[variant - RV_XUNIT0].unit_kib;
+    variant = kReduceUnitVariants[variant - RV_XUNIT0].shape;
+  }
   if (variant == SV_SCALAR) {
     return dispatch_ranks(P, [&](auto pp) {
       hipLaunchKernelGGL((allreduce_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(count / Elem<DT>::kPerVec, kScalarUnroll)), dim3(kBlock), 0,
@@ -182,7 +187,7 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
         constexpr int kP = decltype(pp)::value;
         if constexpr (all_shapes(DT)) {
           hipLaunchKernelGGL((allreduce_vec<DT, kP, 2, true, true, false, kWave>), dim3(g), dim3(kWave), 0, stream, bufs, nvec, count,
-                             scale, op, root, head);
+                             scale, op, root, head, unit_kib ? xcd_unit_shift(unit_kib, per) : 0u);
           return launch_status();
         } else {
           return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above
@@ -195,14 +200,15 @@ int launch_allreduce_dt(const PtrTab& bufs, size_t count, unsigned head, int op,
     constexpr int kP = decltype(pp)::value;
     if (op > MCR_AVG || !all_shapes(DT)) {
       hipLaunchKernelGGL((allreduce_vec<DT, kP, kGenericUnroll, true, true, true>), dim3(grid_x(nvec, kGenericShape)), dim3(kBlock), 0,
-                         stream, bufs, nvec, count, scale, op, root, head);
+                         stream, bufs, nvec, count, scale, op, root, head, 0u);
       return launch_status();
     }
     if constexpr (all_shapes(DT)) {
       return dispatch_reduce_shape(variant, [&](auto uu, auto nt) {
         constexpr int U = decltype(uu)::value;
         hipLaunchKernelGGL((allreduce_vec<DT, kP, U, decltype(nt)::value, decltype(nt)::value, false>),
-                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root, head);
+                           dim3(gx), dim3(kBlock), 0, stream, bufs, nvec, count, scale, op, root, head,
+                           unit_kib ? xcd_unit_shift(unit_kib, static_cast<size_t>(U) * kBlock) : 0u);
         return launch_status();
       });
     } else {

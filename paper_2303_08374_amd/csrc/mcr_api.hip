@@ -16,7 +16,7 @@ namespace mcr {
 const char* const kStreamVariantNames[AG_COUNT] = {"scalar", "v1", "v2", "v4", "v1nt", "v2nt", "v4nt", "v1ln", "v2ln", "v4ln",
                                                    "v1sn", "v2sn", "v4sn", "sc4", "sc8", "sc16", "sc16x"};
 
-const char* const kReduceVariantNames[RV_COUNT - SV_COUNT] = {"pk8", "w64"};
+const char* const kReduceVariantNames[RV_XUNIT0 - SV_COUNT] = {"pk8", "w64"};
 const char* const kAlltoallVariantNames[A2A_COUNT - SV_COUNT] = {"flat", "w64", "lds"};
 
 namespace {
@@ -43,6 +43,7 @@ int n_variants(int op) {
 // all_gather, persistent forms of the reductions).
 const char* variant_name(int op, int i) {
   if (op == MCR_OP_MOE_ROUTE) return kRouteVariantNames[i];
+  if (is_reduction(op) && i >= RV_XUNIT0) return kReduceUnitVariants[i - RV_XUNIT0].name;
   if (is_reduction(op) && i >= SV_COUNT) return kReduceVariantNames[i - SV_COUNT];
   if (op == MCR_OP_ALLTOALL && i >= SV_COUNT) return kAlltoallVariantNames[i - SV_COUNT];
   return kStreamVariantNames[i];

@@ -12,12 +12,12 @@ namespace {
 // blockIdx.y = destination rank r; slice r of every input is bvec vectors long.
 template <int DT, int P, int U, bool NTL, bool NTS, bool GENERIC, int BS = kBlock>
 __global__ void __launch_bounds__(BS)
-reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op) {
+reduce_scatter_vec(PtrTab out, CPtrTab in, size_t bvec, float scale, int op, unsigned unit_shift) {
   constexpr size_t kTile = static_cast<size_t>(U) * BS;
   const unsigned r = blockIdx.y;
   void* dst = out.p[r];
   const size_t off = static_cast<size_t>(r) * bvec;
-  const size_t tile = static_cast<size_t>(blockIdx.x) * kTile;
+  const size_t tile = static_cast<size_t>(xcd_unit_tile(blockIdx.x, unit_shift)) * kTile;
   if (tile >= bvec) return;
   u32x4 res[U];
   const bool full = tile + kTile <= bvec;
@@ -100,6 +100,11 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
                              hipStream_t stream) {
   const float scale = 1.0f / static_cast<float>(P);
   const size_t b = count / static_cast<size_t>(P);
+  unsigned unit_kib = 0;
+  if (variant >= RV_XUNIT0) {
+    unit_kib = kReduceUnitVariants[variant - RV_XUNIT0].unit_kib;
+    variant = kReduceUnitVariants[variant - RV_XUNIT0].shape;
+  }
   if (variant == SV_SCALAR) {
     return dispatch_ranks(P, [&](auto pp) {
       hipLaunchKernelGGL((reduce_scatter_scalar<DT, decltype(pp)::value>), dim3(scalar_grid(b / Elem<DT>::kPerVec, kScalarUnroll), P), dim3(kBlock),
@@ -135,7 +140,7 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
         constexpr int kP = decltype(pp)::value;
         if constexpr (all_shapes(DT)) {
           hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, 2, true, true, false, kWave>), grid, dim3(kWave), 0, stream, out, in, bvec,
-                             scale, op);
+                             scale, op, unit_kib ? xcd_unit_shift(unit_kib, per) : 0u);
           return launch_status();
         } else {
           return static_cast<int>(MCR_EVARIANT);          // not reached: ruled out above
@@ -148,14 +153,15 @@ int launch_reduce_scatter_dt(const PtrTab& out, const CPtrTab& in, size_t count,
     constexpr int kP = decltype(pp)::value;
     if (op > MCR_AVG || !all_shapes(DT)) {
       hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, kGenericUnroll, true, true, true>), dim3(grid_x(bvec, kGenericShape), P), dim3(kBlock),
-                         0, stream, out, in, bvec, scale, op);
+                         0, stream, out, in, bvec, scale, op, 0u);
       return launch_status();
     }
     if constexpr (all_shapes(DT)) {
       return dispatch_reduce_shape(variant, [&](auto uu, auto nt) {
         constexpr int U = decltype(uu)::value;
         hipLaunchKernelGGL((reduce_scatter_vec<DT, kP, U, decltype(nt)::value, decltype(nt)::value, false>),
-                           dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, op);
+                           dim3(gx, P), dim3(kBlock), 0, stream, out, in, bvec, scale, op,
+                           unit_kib ? xcd_unit_shift(unit_kib, static_cast<size_t>(U) * kBlock) : 0u);
         return launch_status();
       });
     } else {
