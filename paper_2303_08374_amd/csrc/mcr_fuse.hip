@@ -62,11 +62,11 @@ fuse_kernel(PlanDev d, PtrTab flat, uint32_t first_chunk) {
 // All-reduce of one chunk of one tensor across the bound ranks, in place.
 template <int DT, int P, bool NTL, bool NTS, bool FORCE_SCALAR, bool GENERIC>
 __global__ void __launch_bounds__(kBlock)
-allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op) {
+allreduce_multi_kernel(PlanDev d, uint32_t first_chunk, float scale, int op, uint32_t unit_shift) {
   using E = Elem<DT>;
   constexpr int W = E::kPerVec;
   constexpr uint64_t CE = kChunkBytes / E::kBytes;
-  const uint32_t c = first_chunk + blockIdx.x;
+  const uint32_t c = first_chunk + xcd_unit_tile(blockIdx.x, unit_shift);
   const uint32_t i = d.chunk_tensor[c];
   const uint64_t e0 = static_cast<uint64_t>(c - d.chunk_start[i]) * CE;
   const uint64_t n = d.numel[i];
@@ -165,6 +165,11 @@ int launch_fuse(mcr_ctx*, const mcr_fuse_plan* plan, int bucket, const PtrTab& f
   return unfuse ? by_shape(Int<2>{}, Bool<true>{}) : by_shape(Int<2>{}, Bool<false>{});
 }
 
+// Chunks per XCD unit of the multi-tensor all_reduce, as a shift: consecutive chunks are consecutive
+// memory inside a tensor, and 64 of them (1 MiB of every rank's tensor) per XCD at a stretch take
+// the 292-tensor gradient list in 7.65 ms instead of 7.98 (units of 256 KiB to 2 MiB alike).
+constexpr uint32_t kMultiUnitShift = 6;
+
 int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, int op, int variant,
                            hipStream_t stream) {
   const uint32_t c0 = plan->chunk_start[t0], c1 = plan->chunk_start[t1];
@@ -178,23 +183,23 @@ int launch_allreduce_multi(mcr_ctx*, const mcr_fuse_plan* plan, int t0, int t1, 
       constexpr int kP = decltype(pp)::value;
       if (op > MCR_AVG || !all_shapes(DT)) {      // the other ReduceOps and element types: one nontemporal shape, or the element path
         if (variant == SV_SCALAR)
-          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op, 0u);
         else
-          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, true, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, true, false, true>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op, 0u);
         return launch_status();
       }
       if constexpr (all_shapes(DT)) {
         if (variant == SV_SCALAR) {
-          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op);
+          hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, true, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0, scale, op, 0u);
           return launch_status();
         }
         // plain or fully nontemporal: the ids with one-sided hints run the nontemporal kernel, as in the reductions
         if (variant == SV_V1 || variant == SV_V2 || variant == SV_V4)
           hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, false, false, false, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0,
-                             scale, op);
+                             scale, op, kMultiUnitShift);
         else
           hipLaunchKernelGGL((allreduce_multi_kernel<DT, kP, true, true, false, false>), dim3(c1 - c0), dim3(kBlock), 0, stream, d, c0,
-                             scale, op);
+                             scale, op, kMultiUnitShift);
         return launch_status();
       } else {
         return static_cast<int>(MCR_EVARIANT);          // not reached: taken by the branch above

@@ -132,19 +132,6 @@ inline unsigned persistent_grid(int n_cu, int slices) {
   return static_cast<unsigned>(g < 1 ? 1 : g);
 }
 
-// Workgroups are dealt to the 8 XCDs in turn.  With unit_shift != 0 the tiles of every whole group of
-// 8 << unit_shift workgroups are renumbered so that the workgroups of one XCD cover a contiguous
-// unit of 1 << unit_shift tiles (a partial group at the end of the grid keeps its numbering).
-__device__ __forceinline__ unsigned xcd_unit_tile(unsigned bx, unsigned unit_shift) {
-  if (unit_shift) {
-    const unsigned span = 8u << unit_shift;
-    if ((bx | (span - 1)) < gridDim.x) {
-      const unsigned within = bx & (span - 1);
-      bx = (bx - within) + ((within & 7u) << unit_shift) + (within >> 3);
-    }
-  }
-  return bx;
-}
 // log2 of the tiles per unit for units of `unit_kib` KiB and tiles of `tile_vecs` 16-byte vectors.
 inline unsigned xcd_unit_shift(unsigned unit_kib, size_t tile_vecs) {
   const size_t tiles = (static_cast<size_t>(unit_kib) << 10) / (tile_vecs * 16);
