@@ -154,15 +154,10 @@ allgather_superchunk_kernel(PtrTab out, CPtrTab in, size_t mvec, unsigned bpc, u
   const unsigned rem = blockIdx.x - static_cast<unsigned>(sc * per_sc);
   const unsigned r = rem / bpc;
   unsigned j = rem - r * bpc;
-  if (unit_shift) {
-    // Workgroups are dealt to the 8 XCDs in turn; within every group of 8 << unit_shift tiles, the
-    // tiles are renumbered so that the workgroups of one XCD cover one contiguous unit of
-    // 1 << unit_shift tiles instead of every eighth tile.  Still the same XCD for a tile whatever
-    // the destination (bpc is a multiple of the group), so the re-reads find it in that XCD's L2.
-    const unsigned span = 8u << unit_shift;
-    const unsigned within = j & (span - 1);
-    j = (j - within) + ((within & 7u) << unit_shift) + (within >> 3);
-  }
+  // "sc16x": the workgroups of one XCD cover contiguous units of 1 << unit_shift tiles instead of every
+  // eighth tile.  Still the same XCD for a tile whatever the destination (bpc is a multiple of the
+  // group of 8 units), so the re-reads find it in that XCD's L2.
+  if (unit_shift) j = xcd_unit_renumber(j, unit_shift);
   const size_t idx = (sc * bpc + j) * static_cast<size_t>(kBlock) + threadIdx.x;
   if (idx >= mvec) return;
   const u32x4 v = load16<false>(in.p[p], idx);
@@ -322,9 +317,9 @@ alltoallv_pairs_kernel(PtrTab out, CPtrTab in, PairArg a, int P) {
   copy_run<UB, U, NTL, NTS>(static_cast<const T*>(in.p[p]) + a.sd[i], static_cast<T*>(out.p[r]) + a.rd[i], n);
 }
 
-// Every sender hands the *same* segment to all of its receivers (bcast, all_gatherv) and the
-// segment is longer than the last-level cache keeps: pair by pair, each receiver's copy would fetch
-// the segment from memory again.  Super-chunk order as in all_gather: workgroups numbered
+// Every sender hands the *same* segment to all of its receivers (bcast, all_gatherv): pair by pair,
+// each receiver's copy of a segment longer than the caches keep would fetch it from memory again, and
+// with loads that bypass the cache a short one too.  Super-chunk order as in all_gather: workgroups numbered
 // [sender slot (y)] [super-chunk] [receiver] [tile], plain loads so that the re-reads of a
 // super-chunk hit the cache, nontemporal stores so that they do not push it out.  The host resolves
 // every address and lists, per sender that sends anything, its receivers without gaps, so that the
@@ -344,11 +339,7 @@ alltoallv_pairs_superchunk_kernel(SharedSegments a, unsigned bpc, unsigned R, un
   const unsigned rem = blockIdx.x - static_cast<unsigned>(sc * per_sc);
   const unsigned r = rem / bpc;
   unsigned j = rem - r * bpc;
-  if (unit_shift) {                                      // contiguous units per XCD, as in all_gather's "sc16x"
-    const unsigned span = 8u << unit_shift;
-    const unsigned within = j & (span - 1);
-    j = (j - within) + ((within & 7u) << unit_shift) + (within >> 3);
-  }
+  if (unit_shift) j = xcd_unit_renumber(j, unit_shift);   // contiguous units per XCD, as in all_gather's "sc16x"
   const u32x4* src = a.src[y];
   u32x4* dst = a.dst[y * MCR_MAX_RANKS + r];
   const size_t idx = (sc * bpc + j) * static_cast<size_t>(kBlock) + threadIdx.x;

@@ -41,17 +41,19 @@ struct CPtrTab {
 //   start[p][16] = min(all the rows p sends, 2^31 - 1): a slot is below 2^31 - 1, so the receiver of
 //                  a slot is found with 32-bit compares and no bound on r;
 //   delta[p][r] = rd[r] - sd[r]: slot s of sender p lands in row s + delta[p][r] of receiver r.
-// Workgroups are dealt to the 8 XCDs in turn.  With unit_shift != 0 the tiles of every whole group of
-// 8 << unit_shift workgroups are renumbered so that the workgroups of one XCD cover a contiguous
-// unit of 1 << unit_shift tiles (a partial group at the end of the grid keeps its numbering).
+// Workgroups are dealt to the 8 XCDs in turn.  Index `i` renumbered within its group of
+// 8 << unit_shift so that the eight residues mod 8 (the XCDs) each cover a contiguous unit of
+// 1 << unit_shift indices: a bijection of every whole group onto itself.
+__device__ __forceinline__ unsigned xcd_unit_renumber(unsigned i, unsigned unit_shift) {
+  const unsigned span = 8u << unit_shift;
+  const unsigned within = i & (span - 1);
+  return (i - within) + ((within & 7u) << unit_shift) + (within >> 3);
+}
+// The tile of workgroup `bx` of a one-dimensional walk: with unit_shift != 0 the tiles of every whole
+// group of 8 << unit_shift workgroups are renumbered in XCD units (a partial group at the end of the
+// grid keeps its numbering).
 __device__ __forceinline__ unsigned xcd_unit_tile(unsigned bx, unsigned unit_shift) {
-  if (unit_shift) {
-    const unsigned span = 8u << unit_shift;
-    if ((bx | (span - 1)) < gridDim.x) {
-      const unsigned within = bx & (span - 1);
-      bx = (bx - within) + ((within & 7u) << unit_shift) + (within >> 3);
-    }
-  }
+  if (unit_shift && (bx | ((8u << unit_shift) - 1)) < gridDim.x) return xcd_unit_renumber(bx, unit_shift);
   return bx;
 }
 struct PairSlot {
