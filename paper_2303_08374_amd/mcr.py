@@ -81,10 +81,24 @@ def _ptr_array(xs: Optional[Sequence[Ptr]], need: int = 0):
     return (ctypes.c_void_p * len(xs))(*[_addr(x) for x in xs])
 
 
+_raw_stream = None
+
+
+def _current_stream_handle() -> int:
+    """The calling thread's current torch stream as a raw handle.  torch's own accessor for the raw
+    handle costs 0.1 us where building a torch.cuda.Stream object costs 3 us, which is a third of what
+    a small collective takes from Python."""
+    global _raw_stream
+    import torch
+    if _raw_stream is None:
+        fast = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        _raw_stream = (lambda: fast(torch.cuda.current_device())) if fast else (lambda: torch.cuda.current_stream().cuda_stream)
+    return _raw_stream()
+
+
 def _stream(stream) -> ctypes.c_void_p:
     if stream is None:
-        import torch
-        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        return ctypes.c_void_p(_current_stream_handle())
     if isinstance(stream, int):
         return ctypes.c_void_p(stream)
     return ctypes.c_void_p(stream.cuda_stream)
