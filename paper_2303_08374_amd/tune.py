@@ -226,7 +226,7 @@ def _tune_sweep(ctx, P: int, sizes, arena_gib: float, names, full_report, verbos
             if graph_timed is None:
                 graph_timed = ms < GRAPH_BELOW_MS                         # one way of timing per cell, decided by its first variant
             if graph_timed:
-                # the host's cost per call (10 us from Python) hides what a kernel this short takes: time the
+                # the host's cost per call (8 to 10 us from Python) hides what a kernel this short takes: time the
                 # same batch replayed from a captured graph, where only the device's own launch floor is left
                 ms = graph_batch_ms(lambda base, stream: cell.launch(ctx, base, v, stream),
                                     [arena.take(cell.footprint) for _ in range(reps)])
