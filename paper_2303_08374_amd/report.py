@@ -1,8 +1,8 @@
 """Text summaries of bench.py's measurements (the tables kept under profiles/).
 
-    python3 bench.py --cells-md profiles/op_sweep_cells.md         # per-cell table + workloads
+    python3 bench.py --cells-out CELLS.json --cells-md profiles/op_sweep_cells.md   # per-cell table + workloads
     rocprofv3 --kernel-trace --output-format csv -d DIR -o trace -- python3 bench.py --trace-passes 5
-    python3 -m paper_2303_08374_amd.report kernel-times DIR --passes 5 --cells gpurun_out/bench_cells.json \\
+    python3 -m paper_2303_08374_amd.report kernel-times DIR --passes 5 --cells CELLS.json \\
         --out profiles/op_sweep_kernel_times.md                       # kernel-only durations per cell
 """
 from __future__ import annotations
@@ -147,7 +147,7 @@ def kernel_times(trace_dir: str, passes: int, cells_json: str | None) -> str:
     table = json.load(open(cells_json)) if cells_json else {}
     out = ["# Op sweep: kernel-only durations per cell (rocprofv3 kernel trace)", "",
            f"Commands: `rocprofv3 --kernel-trace --output-format csv -d DIR -o trace -- python3 bench.py --trace-passes {passes}`, then",
-           f"`python3 -m paper_2303_08374_amd.report kernel-times DIR --passes {passes} --cells gpurun_out/bench_cells.json`.",
+           f"`python3 -m paper_2303_08374_amd.report kernel-times DIR --passes {passes} --cells CELLS.json`.",
            "Median over the passes of the kernel's own begin-to-end time; \"events\" is the event-pair time of the same cell in",
            "`op_sweep_cells.md` (two events around one launch cost about 6 us by themselves, which is all a small cell shows there).",
            "GB/s and % of 8000 GB/s from the kernel-only time.", ""]
