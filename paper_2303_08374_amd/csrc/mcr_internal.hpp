@@ -39,19 +39,22 @@ enum AllgatherVariant { AG_SC4 = 13, AG_SC8 = 14, AG_SC16 = 15, AG_SC16X = 16, A
 // threads per compute unit walking a contiguous run of the message in rounds of 8 steps of one
 // vector per thread.  SUM / AVG on fp32 and bf16; other ReduceOps and element types run "v4nt" in
 // its place.
-enum ReduceVariant { SV_PK8 = 13, SV_W64 = 14, RV_XUNIT0 = 15, RV_COUNT = 26 };
+enum ReduceVariant { SV_PK8 = 13, SV_W64 = 14, RV_XUNIT0 = 15, RV_COUNT = 35 };
 // Ids from RV_XUNIT0 on: a launch shape of the list above with its tiles dealt to the 8 XCDs in
 // contiguous units ("<shape>.x<unit in KiB>": every XCD works through `unit` bytes of each rank
-// buffer at a stretch instead of every eighth tile).  Which (shape, unit) wins depends on the size.
+// buffer at a stretch instead of every eighth tile).  Which (shape, unit) wins depends on the size
+// and on the distance between the rank buffers; the unit is a kernel argument, so the 20 of them
+// cost no code.
 struct ReduceUnitVariant {
   int shape;            // SV_V1NT, SV_V2NT, SV_V4NT or SV_W64
   unsigned unit_kib;
   const char* name;
 };
 constexpr ReduceUnitVariant kReduceUnitVariants[RV_COUNT - RV_XUNIT0] = {
-    {SV_V1NT, 512, "v1nt.x512"},   {SV_V1NT, 1024, "v1nt.x1024"}, {SV_V1NT, 2048, "v1nt.x2048"}, {SV_V2NT, 128, "v2nt.x128"},
-    {SV_V2NT, 512, "v2nt.x512"},   {SV_V2NT, 1024, "v2nt.x1024"}, {SV_W64, 128, "w64.x128"},     {SV_W64, 512, "w64.x512"},
-    {SV_W64, 1024, "w64.x1024"},   {SV_V4NT, 128, "v4nt.x128"},   {SV_V4NT, 512, "v4nt.x512"}};
+    {SV_V1NT, 128, "v1nt.x128"}, {SV_V1NT, 256, "v1nt.x256"}, {SV_V1NT, 512, "v1nt.x512"}, {SV_V1NT, 1024, "v1nt.x1024"}, {SV_V1NT, 2048, "v1nt.x2048"},
+    {SV_V2NT, 128, "v2nt.x128"}, {SV_V2NT, 256, "v2nt.x256"}, {SV_V2NT, 512, "v2nt.x512"}, {SV_V2NT, 1024, "v2nt.x1024"}, {SV_V2NT, 2048, "v2nt.x2048"},
+    {SV_V4NT, 128, "v4nt.x128"}, {SV_V4NT, 256, "v4nt.x256"}, {SV_V4NT, 512, "v4nt.x512"}, {SV_V4NT, 1024, "v4nt.x1024"}, {SV_V4NT, 2048, "v4nt.x2048"},
+    {SV_W64, 128, "w64.x128"}, {SV_W64, 256, "w64.x256"}, {SV_W64, 512, "w64.x512"}, {SV_W64, 1024, "w64.x1024"}, {SV_W64, 2048, "w64.x2048"}};
 // "w64" (the reductions and all_to_all_single): workgroups of one wavefront, two vectors per thread
 // (one for all_to_all), nontemporal: four times as many, smaller workgroups as "v2nt" for the
 // messages of a few MiB whose kernels last a few microseconds.

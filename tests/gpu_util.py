@@ -69,7 +69,7 @@ def assert_reduced_equal(got: np.ndarray, exp: np.ndarray, dtype: int, what=""):
 VEC_VARIANTS = list(range(1, 13))          # every 128-bit launch shape
 ALL_VARIANTS = [0] + VEC_VARIANTS
 ALLGATHER_EXTRA = [13, 14, 15, 16]         # super-chunk forms of all_gather
-REDUCE_EXTRA = list(range(13, 26))         # persistent form, one-wavefront workgroups, XCD-unit forms
+REDUCE_EXTRA = list(range(13, 35))         # persistent form, one-wavefront workgroups, XCD-unit forms
 ALLTOALL_EXTRA = [13, 14, 15]              # flat, one-wavefront and LDS-staged forms of all_to_all_single of all_reduce / reduce / reduce_scatter
 NPDT = {mcr.F32: np.float32, mcr.BF16: np.uint16, mcr.F16: np.float16, mcr.I32: np.int32}
 EB = {mcr.F32: 4, mcr.BF16: 2, mcr.F16: 2, mcr.I32: 4}

@@ -48,7 +48,7 @@ def test_strerror_and_variants(ctx):
         assert mcr.strerror(code) not in ("ok", "unknown status")
     for op in range(10):
         v = mcr.mcr_get_variants(ctx, op)
-        assert v[0] == "scalar" and len(v) == len(set(v)) == {mcr.OP_ALLGATHER: 17, mcr.OP_ALLREDUCE: 26, mcr.OP_REDUCE_SCATTER: 26, mcr.OP_ALLTOALL: 16}.get(op, 13)
+        assert v[0] == "scalar" and len(v) == len(set(v)) == {mcr.OP_ALLGATHER: 17, mcr.OP_ALLREDUCE: 35, mcr.OP_REDUCE_SCATTER: 35, mcr.OP_ALLTOALL: 16}.get(op, 13)
     assert mcr.mcr_get_variants(ctx, mcr.OP_MOE_ROUTE) == ["wave_ballot"]
     with pytest.raises(mcr.McrError) as e:
         mcr.mcr_get_variants(ctx, 99)
