@@ -70,6 +70,9 @@ VEC_VARIANTS = list(range(1, 13))          # every 128-bit launch shape
 ALL_VARIANTS = [0] + VEC_VARIANTS
 ALLGATHER_EXTRA = [13, 14, 15, 16]         # super-chunk forms of all_gather
 REDUCE_EXTRA = list(range(13, 35))         # persistent form, one-wavefront workgroups, XCD-unit forms
+# for the tests on long messages: the persistent and one-wavefront forms and XCD-unit forms of every shape, from the
+# smallest to the largest unit (the unit is a run-time argument of one kernel per shape)
+REDUCE_LONG = [13, 14, 15, 19, 22, 26, 29, 30, 33, 34]
 ALLTOALL_EXTRA = [13, 14, 15]              # flat, one-wavefront and LDS-staged forms of all_to_all_single of all_reduce / reduce / reduce_scatter
 NPDT = {mcr.F32: np.float32, mcr.BF16: np.uint16, mcr.F16: np.float16, mcr.I32: np.int32}
 EB = {mcr.F32: 4, mcr.BF16: 2, mcr.F16: 2, mcr.I32: 4}

@@ -63,7 +63,7 @@ def test_persistent_reductions_over_several_rounds(dtype, P):
     exp_red = [h.copy() for h in host]
     oracle.reduce(exp_red, dtype, mcr.SUM, 1)
     exp_rs = oracle.reduce_scatter([h[:n] for h in host], dtype, mcr.SUM)
-    for variant in gu.REDUCE_EXTRA:
+    for variant in gu.REDUCE_LONG:
         dev = [gu.to_dev(h) for h in host]
         mcr.mcr_allreduce(gu.ctx(), dev, n + 3, dtype, mcr.AVG, P, variant)
         d_red = [gu.to_dev(h) for h in host]
